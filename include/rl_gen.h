@@ -1,0 +1,135 @@
+/*
+ * rl_gen.h -- C ABI of the MI355X (gfx950) library for the actor's batched autoregressive
+ * generation: prefill plus per-token decode of a LLaMA-architecture decoder with a KV cache.
+ *
+ * The operation is the "Generation" model function call of the paper (Section 2.1, RLHF workflow):
+ * a prefill forward pass over all prompt tokens yields the first generated token; the decode phase
+ * then feeds the single latest token of every sequence and yields the next one, repeatedly.
+ * The workload is fixed-length (Appendix A, experiment details): all sequences of a batch have the
+ * same prompt length and generation never stops early.  The weight inventory follows the paper's
+ * model-configuration table: untied input/output embeddings, bias-free projections, NumKVHeads may
+ * be smaller than NumAttentionHeads (grouped-query attention).
+ *
+ * Conventions
+ *   - Every pointer marked DEVICE is HIP device memory of the current device, allocated by the
+ *     caller (for example through torch) and BORROWED: it must stay valid while the handle lives.
+ *     The library allocates no device memory except bf16 copies of fp32 weights (weight_dtype 0).
+ *   - `hip_stream` is a hipStream_t passed as void*; NULL is the default stream.  Calls enqueue work
+ *     on that stream and return without synchronising; results are ready when the stream reaches
+ *     that point.  One handle must not be used from two streams or two host threads at once.
+ *   - Return value: RL_GEN_OK (0) or a negative rl_gen_status.  A failed call leaves the sequence
+ *     state (batch, length) unchanged.  No exception crosses this boundary.
+ *   - Matrices are row-major [out_features, in_features]; token ids are int32 in [0, vocab) --
+ *     ids outside that range are clamped on the device (no fault), the result is then unspecified.
+ */
+#ifndef RL_GEN_H
+#define RL_GEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rl_gen rl_gen_t; /* opaque, library-owned */
+
+typedef enum {
+    RL_GEN_OK = 0,
+    RL_GEN_E_NULL = -1,     /* a required pointer is NULL */
+    RL_GEN_E_SHAPE = -2,    /* inconsistent or unsupported model shape / argument value */
+    RL_GEN_E_CAPACITY = -3, /* batch, sequence length or an arena exceeds what was reserved */
+    RL_GEN_E_STATE = -4,    /* call order violated (decode before prefill, ...) */
+    RL_GEN_E_HIP = -5       /* a HIP runtime call failed; text in rl_gen_last_error() */
+} rl_gen_status;
+
+typedef struct {
+    int32_t n_layers, hidden, n_heads, n_kv_heads, head_dim, ffn, vocab;
+    float rope_base; /* rotary base, 10000 for the benchmark shapes */
+    float rms_eps;   /* added to the mean square inside the square root */
+    int32_t rope_style;   /* 0: pairs (2r, 2r+1) of a head rotate together; 1: pairs (r, r + head_dim/2) */
+    int32_t weight_dtype; /* 0: fp32 (converted once to bf16 at create), 1: bf16 */
+    int32_t max_batch;    /* KV capacity in sequences */
+    int32_t max_seq;      /* KV capacity in tokens per sequence (prompt + generated) */
+} rl_gen_shape;
+
+/* Supported shapes: hidden == n_heads*head_dim, n_heads % n_kv_heads == 0, n_heads/n_kv_heads <= 16,
+ * head_dim in {64, 128}, hidden % 8 == 0, ffn % 8 == 0, all counts positive (n_layers may be 0). */
+
+typedef struct {                 /* all DEVICE, borrowed, dtype given by weight_dtype */
+    const void *tok_emb;         /* [vocab, hidden] */
+    const void *const *attn_norm; /* HOST array of n_layers DEVICE pointers, each [hidden] */
+    const void *const *wq;       /* each [n_heads*head_dim, hidden] */
+    const void *const *wk;       /* each [n_kv_heads*head_dim, hidden] */
+    const void *const *wv;       /* each [n_kv_heads*head_dim, hidden] */
+    const void *const *wo;       /* each [hidden, n_heads*head_dim] */
+    const void *const *ffn_norm; /* each [hidden] */
+    const void *const *w_gate;   /* each [ffn, hidden] */
+    const void *const *w_up;     /* each [ffn, hidden] */
+    const void *const *w_down;   /* each [hidden, ffn] */
+    const void *final_norm;      /* [hidden] */
+    const void *lm_head;         /* [vocab, hidden] */
+} rl_gen_weights;
+
+/* Closed forms (host only, no GPU needed).  Return 0 / negative on an invalid shape. */
+int64_t rl_gen_param_count(const rl_gen_shape *shape); /* parameters of the model-configuration table's inventory */
+size_t rl_gen_kv_bytes(const rl_gen_shape *shape);     /* bytes of the KV arena: 2*L*max_batch*Hkv*max_seq*head_dim*2 */
+size_t rl_gen_work_bytes(const rl_gen_shape *shape);   /* bytes of the activation workspace arena */
+int rl_gen_validate_shape(const rl_gen_shape *shape);  /* RL_GEN_OK or RL_GEN_E_SHAPE */
+
+/* Creates a handle.  kv_arena / work_arena: DEVICE, 256-byte aligned, at least rl_gen_kv_bytes /
+ * rl_gen_work_bytes long (else RL_GEN_E_CAPACITY), contents need not be initialised.  The host
+ * arrays inside `weights` are copied; the device tensors they point to are borrowed.
+ * KV layout inside the arena: [layer][K|V][sequence][kv_head][position][head_dim] bf16. */
+int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void *kv_arena, size_t kv_bytes,
+                  void *work_arena, size_t work_bytes, rl_gen_t **out);
+
+/* Prefill (Section 2.1: one forward pass that consumes all prompt tokens and yields the first
+ * generated token).  tokens: DEVICE int32 [B, T] row-major, 1 <= B <= max_batch, 1 <= T <= max_seq.
+ * logits: DEVICE fp32 [B, vocab] of the LAST prompt position, or NULL.  next: DEVICE int32 [B],
+ * greedy token = lowest index of the largest logit.  Replaces any previous sequence state:
+ * afterwards every sequence has length T. */
+int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logits, int32_t *next,
+                   void *hip_stream);
+
+/* One decode step (Section 2.1: input the single latest token of each sequence, produce the next).
+ * tokens: DEVICE int32 [B] with B as given to the last prefill -- the caller chooses what to feed
+ * (the previous `next` buffer for free-running greedy generation, or reference tokens for teacher
+ * forcing).  logits: DEVICE fp32 [B, vocab] or NULL.  next: DEVICE int32 [B].  tokens and next may
+ * be the same buffer.  Appends one position to every sequence; RL_GEN_E_CAPACITY once length
+ * would exceed max_seq, RL_GEN_E_STATE before a prefill. */
+int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_t *next, void *hip_stream);
+
+/* Whether decode steps are replayed as one captured HIP graph (1, default) or launched kernel by
+ * kernel (0).  Both produce identical results. */
+int rl_gen_set_graph(rl_gen_t *h, int32_t enabled);
+
+/* Forgets all sequences (weights and arenas stay).  Host-side only. */
+int rl_gen_reset(rl_gen_t *h);
+/* Current state: number of sequences and tokens per sequence (0, 0 before a prefill). */
+int rl_gen_state(const rl_gen_t *h, int32_t *batch, int32_t *length);
+/* Waits for the handle's pending work and releases library-owned memory.  NULL is accepted. */
+void rl_gen_destroy(rl_gen_t *h);
+/* Text of the last error of this handle (or of the last failed create when h is NULL).
+ * Static storage, not thread-safe. */
+const char *rl_gen_last_error(const rl_gen_t *h);
+
+/* ---- per-kernel timing (used by the benchmark to report the roofline of single kernels) --------
+ * While profiling is on, every kernel launch of prefill/decode is bracketed by HIP events on the
+ * caller's stream and decode steps are not graph-replayed.  rl_gen_profile_read synchronises the
+ * stream, then fills, for each kernel class id < RL_GEN_N_KERNEL_CLASSES, the number of launches
+ * and the summed duration in milliseconds since profiling was switched on, and clears the sums. */
+enum {
+    RL_GEN_K_EMBED = 0, RL_GEN_K_ADD_RMSNORM, RL_GEN_K_GEMM_QKV, RL_GEN_K_ROPE_APPEND, RL_GEN_K_DECODE_ATTN,
+    RL_GEN_K_ATTN_MERGE, RL_GEN_K_PREFILL_ATTN, RL_GEN_K_GEMM_O, RL_GEN_K_GEMM_GATE_UP, RL_GEN_K_GEMM_DOWN,
+    RL_GEN_K_GEMM_LM_HEAD, RL_GEN_K_ARGMAX, RL_GEN_K_MISC, RL_GEN_N_KERNEL_CLASSES
+};
+int rl_gen_profile(rl_gen_t *h, int32_t enabled);
+int rl_gen_profile_read(rl_gen_t *h, int32_t *launches /*HOST [N_KERNEL_CLASSES]*/,
+                        float *milliseconds /*HOST [N_KERNEL_CLASSES]*/, void *hip_stream);
+const char *rl_gen_kernel_class_name(int32_t id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RL_GEN_H */

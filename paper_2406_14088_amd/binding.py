@@ -1,0 +1,290 @@
+"""ctypes binding of librl_gen.so: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory (arenas, I/O tensors) and for the current stream; every step of the
+generation path runs inside the library's HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librl_gen.so")
+_LIB = None
+
+STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_CAPACITY", -4: "E_STATE", -5: "E_HIP"}
+KERNEL_CLASSES = ("embed", "add_rmsnorm", "gemm_qkv", "rope_append", "decode_attention", "attention_merge",
+                  "prefill_attention", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax", "misc")
+LAYER_NAMES = ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")
+
+
+class RlGenError(RuntimeError):
+    def __init__(self, code: int, where: str, text: str = ""):
+        super().__init__(f"{where}: {STATUS.get(code, code)} {text}".strip())
+        self.code = code
+
+
+class RlGenShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + [
+        ("rope_base", C.c_float), ("rms_eps", C.c_float), ("rope_style", C.c_int32), ("weight_dtype", C.c_int32),
+        ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+
+    @classmethod
+    def from_model(cls, shape, max_batch: int, max_seq: int, weight_dtype: int = 1) -> "RlGenShape":
+        return cls(shape.n_layers, shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab,
+                   shape.rope_base, shape.rms_eps, shape.rope_style, weight_dtype, max_batch, max_seq)
+
+
+class RlGenWeights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p)] + [(n, C.POINTER(C.c_void_p)) for n in LAYER_NAMES] + [
+        ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)]
+
+
+def lib():
+    """Loads the built library; raises if it is missing (there is no fallback path)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2406_14088_amd.build` "
+                           "(or __graft_entry__.build()) first; this package has no fallback path")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    sp = C.POINTER(RlGenShape)
+    sig = {
+        "rl_gen_validate_shape": (C.c_int, [sp]),
+        "rl_gen_param_count": (i64, [sp]),
+        "rl_gen_kv_bytes": (sz, [sp]),
+        "rl_gen_work_bytes": (sz, [sp]),
+        "rl_gen_create": (C.c_int, [sp, C.POINTER(RlGenWeights), vp, sz, vp, sz, C.POINTER(vp)]),
+        "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
+        "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
+        "rl_gen_set_graph": (C.c_int, [vp, i32]),
+        "rl_gen_reset": (C.c_int, [vp]),
+        "rl_gen_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
+        "rl_gen_destroy": (None, [vp]),
+        "rl_gen_last_error": (C.c_char_p, [vp]),
+        "rl_gen_profile": (C.c_int, [vp, i32]),
+        "rl_gen_profile_read": (C.c_int, [vp, C.POINTER(i32), C.POINTER(f32), vp]),
+        "rl_gen_kernel_class_name": (C.c_char_p, [i32]),
+        "rl_op_embed": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
+        "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, i32, i32, vp]),
+        "rl_op_gemm": (C.c_int, [vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
+        "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
+        "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
+        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
+        "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    L._signatures = sig
+    _LIB = L
+    return L
+
+
+EXPORTED_SYMBOLS = (
+    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_prefill",
+    "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
+    "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
+    "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats",
+    "rl_op_prefill_attention", "rl_op_argmax")
+
+
+def _shape_of(shape, max_batch=1, max_seq=1, weight_dtype=1) -> RlGenShape:
+    return shape if isinstance(shape, RlGenShape) else RlGenShape.from_model(shape, max_batch, max_seq, weight_dtype)
+
+
+def validate_shape(shape, max_batch=1, max_seq=1) -> int:
+    return int(lib().rl_gen_validate_shape(C.byref(_shape_of(shape, max_batch, max_seq))))
+
+
+def param_count(shape) -> int:
+    return int(lib().rl_gen_param_count(C.byref(_shape_of(shape))))
+
+
+def kv_bytes(shape, max_batch=1, max_seq=1) -> int:
+    return int(lib().rl_gen_kv_bytes(C.byref(_shape_of(shape, max_batch, max_seq))))
+
+
+def work_bytes(shape, max_batch=1, max_seq=1) -> int:
+    return int(lib().rl_gen_work_bytes(C.byref(_shape_of(shape, max_batch, max_seq))))
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Generator:
+    """rl_gen handle plus the torch tensors (weights, arenas) it borrows.
+
+    weights: dict as produced by workload.make_weights, tensors on the GPU, all bf16 or all fp32.
+    """
+
+    def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int):
+        import torch
+        self._h = None
+        any_w = weights["tok_emb"]
+        wd = 1 if any_w.dtype == torch.bfloat16 else 0
+        if wd == 0 and any_w.dtype != torch.float32:
+            raise TypeError("weights must be bf16 or fp32")
+        self.shape = shape
+        self.cshape = RlGenShape.from_model(shape, max_batch, max_seq, wd)
+        self._keep: List[object] = []
+
+        def hold(t):
+            if not t.is_cuda or not t.is_contiguous() or t.dtype != any_w.dtype:
+                raise TypeError("weights must be contiguous GPU tensors of one dtype")
+            self._keep.append(t)
+            return t.data_ptr()
+
+        w = RlGenWeights()
+        w.tok_emb, w.final_norm, w.lm_head = hold(weights["tok_emb"]), hold(weights["final_norm"]), hold(weights["lm_head"])
+        self._arrays = []
+        for name in LAYER_NAMES:
+            arr = (C.c_void_p * max(shape.n_layers, 1))()
+            lst = weights[name]
+            if len(lst) != shape.n_layers:
+                raise ValueError(f"{name}: expected {shape.n_layers} tensors")
+            for l, t in enumerate(lst):
+                arr[l] = hold(t)
+            self._arrays.append(arr)
+            setattr(w, name, C.cast(arr, C.POINTER(C.c_void_p)))
+        L = lib()
+        rc = L.rl_gen_validate_shape(C.byref(self.cshape))
+        if rc != 0:
+            raise RlGenError(rc, "rl_gen_validate_shape")
+        nkv, nwork = L.rl_gen_kv_bytes(C.byref(self.cshape)), L.rl_gen_work_bytes(C.byref(self.cshape))
+        dev = any_w.device
+        self.kv_arena = torch.empty(max(nkv, 256), dtype=torch.uint8, device=dev)
+        self.work_arena = torch.empty(nwork, dtype=torch.uint8, device=dev)
+        h = C.c_void_p()
+        rc = L.rl_gen_create(C.byref(self.cshape), C.byref(w), self.kv_arena.data_ptr(), nkv, self.work_arena.data_ptr(),
+                             nwork, C.byref(h))
+        if rc != 0:
+            raise RlGenError(rc, "rl_gen_create", L.rl_gen_last_error(None).decode())
+        self._h = h
+        self.max_batch, self.max_seq = max_batch, max_seq
+
+    def _check(self, rc: int, where: str):
+        if rc != 0:
+            raise RlGenError(rc, where, lib().rl_gen_last_error(self._h).decode())
+
+    def prefill(self, tokens, logits=None, next_tokens=None):
+        """tokens: int32 GPU tensor [B, T].  Returns (logits fp32 [B, V], next int32 [B])."""
+        import torch
+        B, T = tokens.shape
+        assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        if logits is None:
+            logits = torch.empty((B, self.shape.vocab), dtype=torch.float32, device=tokens.device)
+        if next_tokens is None:
+            next_tokens = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+        self._check(lib().rl_gen_prefill(self._h, tokens.data_ptr(), B, T, _ptr(logits), _ptr(next_tokens), _stream()),
+                    "rl_gen_prefill")
+        return logits, next_tokens
+
+    def decode_step(self, tokens, logits=None, next_tokens=None, want_logits=True):
+        """tokens: int32 GPU tensor [B].  Returns (logits or None, next)."""
+        import torch
+        assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        B = tokens.shape[0]
+        if logits is None and want_logits:
+            logits = torch.empty((B, self.shape.vocab), dtype=torch.float32, device=tokens.device)
+        if next_tokens is None:
+            next_tokens = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+        self._check(lib().rl_gen_decode_step(self._h, tokens.data_ptr(), _ptr(logits), _ptr(next_tokens), _stream()),
+                    "rl_gen_decode_step")
+        return logits, next_tokens
+
+    def set_graph(self, enabled: bool):
+        self._check(lib().rl_gen_set_graph(self._h, int(enabled)), "rl_gen_set_graph")
+
+    def reset(self):
+        self._check(lib().rl_gen_reset(self._h), "rl_gen_reset")
+
+    def state(self):
+        b, n = C.c_int32(), C.c_int32()
+        self._check(lib().rl_gen_state(self._h, C.byref(b), C.byref(n)), "rl_gen_state")
+        return b.value, n.value
+
+    def profile(self, enabled: bool):
+        self._check(lib().rl_gen_profile(self._h, int(enabled)), "rl_gen_profile")
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        n = len(KERNEL_CLASSES)
+        launches, ms = (C.c_int32 * n)(), (C.c_float * n)()
+        self._check(lib().rl_gen_profile_read(self._h, launches, ms, _stream()), "rl_gen_profile_read")
+        return {KERNEL_CLASSES[i]: {"launches": int(launches[i]), "ms": float(ms[i])} for i in range(n)}
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().rl_gen_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class _Ops:
+    """Single-kernel entry points (rl_op_*), tensors in, status checked."""
+
+    @staticmethod
+    def _ck(rc, name):
+        if rc != 0:
+            raise RlGenError(rc, name)
+
+    def embed(self, tokens, emb, x):
+        self._ck(lib().rl_op_embed(tokens.data_ptr(), emb.data_ptr(), x.data_ptr(), tokens.numel(), emb.shape[1], emb.shape[0],
+                                   _stream()), "rl_op_embed")
+
+    def add_rmsnorm(self, x, part, nsplit, part_stride, gain, eps, h):
+        M, d = x.shape
+        self._ck(lib().rl_op_add_rmsnorm(x.data_ptr(), _ptr(part), nsplit, part_stride, gain.data_ptr(), eps, h.data_ptr(), M, d,
+                                         _stream()), "rl_op_add_rmsnorm")
+
+    def gemm(self, A, Ws, out, ldc, M=None, lda=None, split_stride=0, splits=1, epilogue=0, kernel=0):
+        K = Ws[0].shape[1]
+        ptrs = [w.data_ptr() for w in Ws] + [None] * (3 - len(Ws))
+        rows = [w.shape[0] for w in Ws] + [0] * (3 - len(Ws))
+        M = A.shape[0] if M is None else M
+        lda = A.stride(0) if lda is None else lda
+        self._ck(lib().rl_op_gemm(A.data_ptr(), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K, out.data_ptr(),
+                                  ldc, split_stride, splits, epilogue, kernel, _stream()), "rl_op_gemm")
+
+    def build_rope_table(self, tab, max_seq, head_dim, base):
+        self._ck(lib().rl_op_build_rope_table(tab.data_ptr(), max_seq, head_dim, base), "rl_op_build_rope_table")
+
+    def rope_append(self, qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_bf16, kc, vc):
+        self._ck(lib().rl_op_rope_append(qkv.data_ptr(), nsplit, split_stride, M, T, b0, d_pos0.data_ptr(), rope_tab.data_ptr(),
+                                         rope_style, Hq, Hkv, hd, S, _ptr(q_f32), _ptr(q_bf16), kc.data_ptr(), vc.data_ptr(),
+                                         _stream()), "rl_op_rope_append")
+
+    def decode_attention_ws_floats(self, B, Hq, hd, nsplit):
+        return int(lib().rl_op_decode_attention_ws_floats(B, Hq, hd, nsplit))
+
+    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit):
+        self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), out.data_ptr(),
+                                              _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention")
+
+    def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):
+        self._ck(lib().rl_op_prefill_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), nb, b0, T, Hq, Hkv,
+                                               hd, S, _stream()), "rl_op_prefill_attention")
+
+    def argmax(self, logits, nxt):
+        B, V = logits.shape
+        self._ck(lib().rl_op_argmax(logits.data_ptr(), B, V, nxt.data_ptr(), _stream()), "rl_op_argmax")
+
+
+ops = _Ops()

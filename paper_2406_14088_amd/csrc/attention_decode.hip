@@ -1,0 +1,235 @@
+// Decode attention: one new query per (sequence, query head) against the KV cache.
+//
+// Every decode step re-reads the whole cache (the paper, Section 8.4, calls this iterative KV-cache
+// loading the irreducible overhead of generation), so this kernel is a pure HBM stream: each cache
+// element is used once per query head that shares it.  Design for gfx950:
+//   * one WAVEFRONT per (sequence, kv head, group of GT query heads, sequence split); no LDS and no
+//     barriers on the streaming path;
+//   * the cache slab of one (sequence, kv head) is contiguous [position][head_dim], so a wavefront
+//     load instruction fetches 1 KB of consecutive bytes (64 lanes x 16 B = 4 rows of head_dim 128);
+//   * a lane owns 8 consecutive head_dim elements; q.k is finished by a 16-lane DPP reduction;
+//   * each of the 64/LPR lane groups runs its own online softmax (running max / sum / weighted V) over
+//     the rows it sees; groups are merged once at the end by wavefront shuffles;
+//   * grouped-query attention: the GT query heads that share a kv head are processed by the same
+//     wavefront, so K and V are read once for all of them;
+//   * optional split over the sequence axis (more wavefronts for long contexts / small batches):
+//     splits write (max, sum, unnormalised output) partials that a small merge kernel combines.
+// All arithmetic is fp32; only the cache elements and the output are bf16.
+#include "kernels.h"
+
+#define DA_THREADS 256
+#define DA_U 4  // cache rows-per-lane-group in flight per iteration (x2 for K and V)
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// sum over the LPR lanes that share a cache row; every lane of the group receives the total
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+    v += dpp_f<0xB1>(v);               // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E>(v);               // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);              // row_half_mirror: joins the two quads of 8 lanes
+    if (LPR == 16) v += dpp_f<0x140>(v);  // row_mirror: joins the two halves of 16 lanes
+    return v;
+}
+
+template <int HD, int GT>
+__global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
+    const float *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
+    const int32_t *__restrict__ d_len, bf16_t *__restrict__ out, float *__restrict__ ws, int n_items, int Hq, int Hkv,
+    int S, int nsplit) {
+    constexpr int LPR = HD / 8;     // lanes per cache row
+    constexpr int RPW = 64 / LPR;   // rows per wavefront load instruction
+    const int lane = threadIdx.x & 63;
+    const int item = blockIdx.x * (DA_THREADS / 64) + (threadIdx.x >> 6);
+    if (item >= n_items) return;
+    const int g = Hq / Hkv, hgs = g / GT;
+    int split = item % nsplit;
+    int rest = item / nsplit;
+    int hg = rest % hgs; rest /= hgs;
+    int kvh = rest % Hkv;
+    int b = rest / Hkv;
+    const int head0 = kvh * g + hg * GT;  // first query head of this wavefront
+
+    int n = d_len[0] + 1;  // visible cache rows: positions 0 .. len
+    if (n > S) n = S;
+    const int chunk = (n + nsplit - 1) / nsplit;
+    const int j0 = split * chunk;
+    const int j1 = j0 + chunk < n ? j0 + chunk : n;
+
+    const int c = lane % LPR, r = lane / LPR;
+    float qr[GT][8];
+#pragma unroll
+    for (int gh = 0; gh < GT; ++gh) {
+        const f32x4_t *qp = reinterpret_cast<const f32x4_t *>(q + ((size_t)b * Hq + head0 + gh) * HD + c * 8);
+        f32x4_t a = qp[0], bb = qp[1];
+        qr[gh][0] = a.x; qr[gh][1] = a.y; qr[gh][2] = a.z; qr[gh][3] = a.w;
+        qr[gh][4] = bb.x; qr[gh][5] = bb.y; qr[gh][6] = bb.z; qr[gh][7] = bb.w;
+    }
+    const float scale = rsqrtf((float)HD);
+    const bf16_t *kb = kc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
+    const bf16_t *vb = vc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
+
+    float mx[GT], den[GT], acc[GT][8];
+#pragma unroll
+    for (int gh = 0; gh < GT; ++gh) {
+        mx[gh] = -INFINITY; den[gh] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[gh][i] = 0.f;
+    }
+
+    for (int base = j0; base < j1; base += RPW * DA_U) {
+        u32x4_t kr[DA_U], vr[DA_U];
+        int jj[DA_U];
+#pragma unroll
+        for (int u = 0; u < DA_U; ++u) {
+            int j = base + u * RPW + r;
+            jj[u] = j;
+            int jc = j < j1 ? j : j1 - 1;  // rows past the end re-read the last valid row; their weight is 0
+            kr[u] = *reinterpret_cast<const u32x4_t *>(kb + (size_t)jc * HD);
+            vr[u] = *reinterpret_cast<const u32x4_t *>(vb + (size_t)jc * HD);
+        }
+        float kf[DA_U][8];
+#pragma unroll
+        for (int u = 0; u < DA_U; ++u) {
+            kf[u][0] = bf16lo_to_f32(kr[u].x); kf[u][1] = bf16hi_to_f32(kr[u].x);
+            kf[u][2] = bf16lo_to_f32(kr[u].y); kf[u][3] = bf16hi_to_f32(kr[u].y);
+            kf[u][4] = bf16lo_to_f32(kr[u].z); kf[u][5] = bf16hi_to_f32(kr[u].z);
+            kf[u][6] = bf16lo_to_f32(kr[u].w); kf[u][7] = bf16hi_to_f32(kr[u].w);
+        }
+        float sc[GT][DA_U];
+#pragma unroll
+        for (int gh = 0; gh < GT; ++gh)
+#pragma unroll
+            for (int u = 0; u < DA_U; ++u) {
+                float d = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) d = fmaf(qr[gh][i], kf[u][i], d);
+                d = group_sum<LPR>(d) * scale;
+                sc[gh][u] = jj[u] < j1 ? d : -INFINITY;
+            }
+        float vf[DA_U][8];
+#pragma unroll
+        for (int u = 0; u < DA_U; ++u) {
+            vf[u][0] = bf16lo_to_f32(vr[u].x); vf[u][1] = bf16hi_to_f32(vr[u].x);
+            vf[u][2] = bf16lo_to_f32(vr[u].y); vf[u][3] = bf16hi_to_f32(vr[u].y);
+            vf[u][4] = bf16lo_to_f32(vr[u].z); vf[u][5] = bf16hi_to_f32(vr[u].z);
+            vf[u][6] = bf16lo_to_f32(vr[u].w); vf[u][7] = bf16hi_to_f32(vr[u].w);
+        }
+#pragma unroll
+        for (int gh = 0; gh < GT; ++gh) {
+            float mnew = mx[gh];
+#pragma unroll
+            for (int u = 0; u < DA_U; ++u) mnew = fmaxf(mnew, sc[gh][u]);
+            if (mnew == -INFINITY) continue;  // this lane group has seen no valid row yet
+            float alpha = mx[gh] == -INFINITY ? 0.f : __expf(mx[gh] - mnew);
+            mx[gh] = mnew;
+            den[gh] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[gh][i] *= alpha;
+#pragma unroll
+            for (int u = 0; u < DA_U; ++u) {
+                float p = __expf(sc[gh][u] - mnew);  // exp(-inf) = 0 for rows past the end
+                den[gh] += p;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[gh][i] = fmaf(p, vf[u][i], acc[gh][i]);
+            }
+        }
+    }
+
+    // ---- merge the RPW lane groups (lanes with equal c) of the wavefront
+#pragma unroll
+    for (int gh = 0; gh < GT; ++gh) {
+        float m = mx[gh];
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        float wgt = mx[gh] == -INFINITY ? 0.f : __expf(mx[gh] - m);
+        float l = den[gh] * wgt;
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) l += __shfl_xor(l, o, 64);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float a = acc[gh][i] * wgt;
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) a += __shfl_xor(a, o, 64);
+            acc[gh][i] = a;
+        }
+        if (r == 0) {
+            int head = head0 + gh;
+            if (nsplit == 1) {
+                float inv = 1.0f / l;
+                u32x4_t o4;
+                o4.x = pack_bf16x2(acc[gh][0] * inv, acc[gh][1] * inv);
+                o4.y = pack_bf16x2(acc[gh][2] * inv, acc[gh][3] * inv);
+                o4.z = pack_bf16x2(acc[gh][4] * inv, acc[gh][5] * inv);
+                o4.w = pack_bf16x2(acc[gh][6] * inv, acc[gh][7] * inv);
+                *reinterpret_cast<u32x4_t *>(out + ((size_t)b * Hq + head) * HD + c * 8) = o4;
+            } else {
+                float *p = ws + (((size_t)b * Hq + head) * nsplit + split) * (HD + 2);
+                if (c == 0) { p[0] = m; p[1] = l; }
+                float *ps = p + 2 + c * 8;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) ps[i] = acc[gh][i];
+            }
+        }
+    }
+}
+
+// Combines the split partials: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M)
+__global__ __launch_bounds__(128) void decode_attention_merge_kernel(const float *__restrict__ ws, bf16_t *__restrict__ out,
+                                                                     int hd, int nsplit) {
+    int bh = blockIdx.x, e = threadIdx.x;
+    if (e >= hd) return;
+    const float *p = ws + (size_t)bh * nsplit * (hd + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[s * (hd + 2)]);
+    float L = 0.f, o = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        float m = p[s * (hd + 2)];
+        float wgt = m == -INFINITY ? 0.f : __expf(m - M);
+        L += p[s * (hd + 2) + 1] * wgt;
+        o += p[s * (hd + 2) + 2 + e] * wgt;
+    }
+    out[(size_t)bh * hd + e] = f32_to_bf16(o / L);
+}
+
+size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit) {
+    return nsplit > 1 ? (size_t)B * Hq * nsplit * (hd + 2) : 0;
+}
+
+int decode_attention_default_splits(int B, int Hkv, int S) {
+    long items = (long)B * Hkv;
+    int s = (int)((4096 + items - 1) / items);  // aim at >= 4 wavefronts per SIMD over 256 compute units
+    int cap = S / 128;                          // but keep >= 128 positions per split at full length
+    if (s > cap) s = cap;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    return s;
+}
+
+template <int HD, int GT>
+static void launch_da(const float *q, const bf16_t *kc, const bf16_t *vc, const int32_t *d_len, bf16_t *out, float *ws, int B,
+                      int Hq, int Hkv, int S, int nsplit, hipStream_t st) {
+    int g = Hq / Hkv;
+    int n_items = B * Hkv * (g / GT) * nsplit;
+    int blocks = ceil_div(n_items, DA_THREADS / 64);
+    decode_attention_kernel<HD, GT><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S, nsplit);
+}
+
+void launch_decode_attention(const float *q, const bf16_t *kc, const bf16_t *vc, const int32_t *d_len, bf16_t *out,
+                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st) {
+    if (B <= 0) return;
+    int g = Hq / Hkv;
+    int gt = g % 8 == 0 ? 8 : (g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1));
+#define DA_CASE(HDV, GTV) \
+    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, out, ws, B, Hq, Hkv, S, nsplit, st); }
+    DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4) DA_CASE(128, 8)
+    DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4) DA_CASE(64, 8)
+#undef DA_CASE
+    if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, hd, nsplit, st);
+}
+
+void launch_decode_attention_merge(const float *ws, bf16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {
+    decode_attention_merge_kernel<<<B * Hq, 128, 0, st>>>(ws, out, hd, nsplit);
+}

@@ -1,0 +1,196 @@
+// Bandwidth-trivial steps of the generation path: embedding gather, residual add + RMSNorm, rotary
+// embedding + KV-cache append, greedy argmax.  fp32 VALU arithmetic, wavefront (64-lane) reductions.
+#include "kernels.h"
+
+// ------------------------------------------------------------------------------------------------
+// Embedding gather: the first step of a forward pass (paper Section 2.1: prompt tokens, or the latest
+// generated token, enter the model).  One workgroup per token row.
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t *__restrict__ tokens, const bf16_t *__restrict__ emb,
+                                                    float *__restrict__ x, int d, int vocab) {
+    int m = blockIdx.x;
+    int tok = tokens[m];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+    const u32x4_t *src = reinterpret_cast<const u32x4_t *>(emb + (size_t)tok * d);
+    f32x4_t *dst = reinterpret_cast<f32x4_t *>(x + (size_t)m * d);
+    for (int i = threadIdx.x; i < d / 8; i += blockDim.x) {
+        u32x4_t v = src[i];
+        f32x4_t a = {bf16lo_to_f32(v.x), bf16hi_to_f32(v.x), bf16lo_to_f32(v.y), bf16hi_to_f32(v.y)};
+        f32x4_t b = {bf16lo_to_f32(v.z), bf16hi_to_f32(v.z), bf16lo_to_f32(v.w), bf16hi_to_f32(v.w)};
+        dst[2 * i] = a;
+        dst[2 * i + 1] = b;
+    }
+}
+
+void launch_embed(const int32_t *tokens, const bf16_t *emb, float *x, int M, int d, int vocab, hipStream_t st) {
+    if (M <= 0) return;
+    embed_kernel<<<M, 256, 0, st>>>(tokens, emb, x, d, vocab);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Residual add of split-K partial sums, then RMSNorm: y = g * x / sqrt(mean(x^2) + eps).
+// The residual stream stays fp32; only the normalised copy that feeds the next projection is bf16.
+// One workgroup per row; each thread keeps its slice of the row in registers (hidden <= 8192).
+#define RN_THREADS 256
+#define RN_MAXV 8
+__global__ __launch_bounds__(RN_THREADS) void add_rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part,
+                                                                 int nsplit, size_t part_stride,
+                                                                 const bf16_t *__restrict__ gain, float eps,
+                                                                 bf16_t *__restrict__ h, int d) {
+    __shared__ float red[RN_THREADS / RL_WAVE];
+    int m = blockIdx.x, t = threadIdx.x;
+    f32x4_t v[RN_MAXV];
+    float ss = 0.f;
+    f32x4_t *xr = reinterpret_cast<f32x4_t *>(x + (size_t)m * d);
+#pragma unroll
+    for (int i = 0; i < RN_MAXV; ++i) {
+        int e4 = t + i * RN_THREADS;
+        if (e4 * 4 < d) {
+            f32x4_t a = xr[e4];
+            for (int s = 0; s < nsplit; ++s) {
+                const f32x4_t *pr = reinterpret_cast<const f32x4_t *>(part + (size_t)s * part_stride + (size_t)m * d);
+                a += pr[e4];
+            }
+            if (nsplit > 0) xr[e4] = a;
+            v[i] = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((t & 63) == 0) red[t >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < RN_THREADS / RL_WAVE; ++w) tot += red[w];
+    float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    u32x2_t *hr = reinterpret_cast<u32x2_t *>(h + (size_t)m * d);
+    const u32x2_t *gr = reinterpret_cast<const u32x2_t *>(gain);
+#pragma unroll
+    for (int i = 0; i < RN_MAXV; ++i) {
+        int e4 = t + i * RN_THREADS;
+        if (e4 * 4 < d) {
+            u32x2_t g = gr[e4];
+            u32x2_t o;
+            o.x = pack_bf16x2(bf16lo_to_f32(g.x) * v[i].x * inv, bf16hi_to_f32(g.x) * v[i].y * inv);
+            o.y = pack_bf16x2(bf16lo_to_f32(g.y) * v[i].z * inv, bf16hi_to_f32(g.y) * v[i].w * inv);
+            hr[e4] = o;
+        }
+    }
+}
+
+void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_stride, const bf16_t *gain, float eps,
+                        bf16_t *h, int M, int d, hipStream_t st) {
+    if (M <= 0) return;
+    add_rmsnorm_kernel<<<M, RN_THREADS, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Rotary embedding of q and k at the token's absolute position, and KV-cache append.
+// Pair r of a head turns by the angle pos * base^(-2r/hd); cos/sin come from a table built in fp64.
+// One workgroup per token row; a thread handles one (head, pair) item at a time.
+__global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ qkv, int nsplit, size_t split_stride,
+                                                          int T, int b0, const int32_t *__restrict__ d_pos0,
+                                                          const float *__restrict__ rope_tab, int rope_style, int Hq,
+                                                          int Hkv, int hd, int S, float *__restrict__ q_f32,
+                                                          bf16_t *__restrict__ q_bf16, bf16_t *__restrict__ kc,
+                                                          bf16_t *__restrict__ vc) {
+    int m = blockIdx.x;
+    int b = b0 + m / T;
+    int pos = d_pos0[0] + m % T;
+    if (pos >= S) return;  // capacity is checked on the host; never write outside the cache
+    int half = hd >> 1;
+    int nq = Hq * half, nk = Hkv * half;
+    int ld = (Hq + 2 * Hkv) * hd;
+    const float *row = qkv + (size_t)m * ld;
+    const float *tab = rope_tab + (size_t)pos * hd;  // [half][2]
+    for (int it = threadIdx.x; it < nq + 2 * nk; it += blockDim.x) {
+        int kind = it < nq ? 0 : (it < nq + nk ? 1 : 2);
+        int local = kind == 0 ? it : (kind == 1 ? it - nq : it - nq - nk);
+        int head = local / half, r = local % half;
+        int col0 = (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd)) + head * hd;
+        int ia, ib;
+        if (kind == 2 || rope_style == 0) { ia = 2 * r; ib = 2 * r + 1; } else { ia = r; ib = r + half; }
+        float a = 0.f, c = 0.f;
+        for (int s = 0; s < nsplit; ++s) {
+            a += row[(size_t)s * split_stride + col0 + ia];
+            c += row[(size_t)s * split_stride + col0 + ib];
+        }
+        if (kind != 2) {
+            float cs = tab[2 * r], sn = tab[2 * r + 1];
+            float ra = a * cs - c * sn, rb = a * sn + c * cs;
+            a = ra; c = rb;
+        }
+        if (kind == 0) {
+            size_t o = (size_t)m * Hq * hd + (size_t)head * hd;
+            if (q_f32) { q_f32[o + ia] = a; q_f32[o + ib] = c; }
+            if (q_bf16) { q_bf16[o + ia] = f32_to_bf16(a); q_bf16[o + ib] = f32_to_bf16(c); }
+        } else {
+            bf16_t *dst = (kind == 1 ? kc : vc) + (((size_t)b * Hkv + head) * S + pos) * hd;
+            dst[ia] = f32_to_bf16(a);
+            dst[ib] = f32_to_bf16(c);
+        }
+    }
+}
+
+void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
+                        const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
+                        bf16_t *q_bf16, bf16_t *kc, bf16_t *vc, hipStream_t st) {
+    if (M <= 0) return;
+    rope_append_kernel<<<M, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S,
+                                          q_f32, q_bf16, kc, vc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Greedy token: index of the largest logit, lowest index on ties; -1 if the row holds a NaN.
+#define AM_THREADS 1024
+__global__ __launch_bounds__(AM_THREADS) void argmax_kernel(const float *__restrict__ logits, int V,
+                                                            int32_t *__restrict__ next, int32_t *inc_len) {
+    __shared__ float sv[AM_THREADS / RL_WAVE];
+    __shared__ int si[AM_THREADS / RL_WAVE];
+    __shared__ int snan;
+    int b = blockIdx.x, t = threadIdx.x;
+    if (t == 0) snan = 0;
+    __syncthreads();
+    const float *row = logits + (size_t)b * V;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    bool nan = false;
+    for (int i = t; i < V; i += AM_THREADS) {
+        float v = row[i];
+        nan |= (v != v);
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        float ov = __shfl_xor(bv, o, 64);
+        int oi = __shfl_xor(bi, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (nan) snan = 1;
+    if ((t & 63) == 0) { sv[t >> 6] = bv; si[t >> 6] = bi; }
+    __syncthreads();
+    if (t == 0) {
+        for (int w = 1; w < AM_THREADS / RL_WAVE; ++w)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        next[b] = (snan || bi == 0x7fffffff) ? -1 : bi;
+        if (inc_len && b == 0) inc_len[0] += 1;
+    }
+}
+
+void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *inc_len, hipStream_t st) {
+    if (B <= 0) return;
+    argmax_kernel<<<B, AM_THREADS, 0, st>>>(logits, V, next, inc_len);
+}
+
+__global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }
+void launch_set_i32(int32_t *p, int32_t v, hipStream_t st) { set_i32_kernel<<<1, 1, 0, st>>>(p, v); }
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = f32_to_bf16(src[i]);
+}
+void launch_f32_to_bf16(const float *src, bf16_t *dst, size_t n, hipStream_t st) {
+    if (n == 0) return;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    f32_to_bf16_kernel<<<(unsigned)blocks, 256, 0, st>>>(src, dst, n);
+}

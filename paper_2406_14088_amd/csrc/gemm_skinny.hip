@@ -1,0 +1,245 @@
+// Skinny-M bf16 GEMM for the decode step: C[M, N] = A[M, K] * W[N, K]^T with M <= 256.
+//
+// A decode step multiplies a few rows of activations (one per sequence) with every weight matrix, so
+// the step is bound by streaming the weights from HBM exactly once.  Design for gfx950:
+//   * one workgroup = 4 wavefronts; wavefront w owns 32 output columns and all (<= 256) rows;
+//   * weights go global -> VGPR directly in MFMA operand layout (lane = (row of W, 8 consecutive k)),
+//     double-buffered one K-chunk (128) ahead, never touching LDS;
+//   * the activation chunk [M, 128] is staged once per workgroup in LDS (padded rows, conflict-free
+//     ds_read_b128) and shared by the four wavefronts;
+//   * v_mfma_f32_32x32x16_bf16, fp32 accumulators;
+//   * split-K over workgroups (grid.y) gives enough workgroups to fill 256 CUs; each split writes its
+//     fp32 partial tile and the consumer kernel adds the partials in a fixed order (deterministic).
+// Buffer loads with a range-checked descriptor return 0 outside a matrix, so ragged N and K need no
+// per-load branches; the activation tile is zero-filled beyond K.
+#include "kernels.h"
+
+#define SK_BK 128            // K elements per chunk
+#define SK_LDS_STRIDE 136    // bf16 elements per LDS row (128 + 8 pad -> 272 B, conflict-free b128 reads)
+#define SK_THREADS 256
+
+struct SkinnyParams {
+    const bf16_t *A;
+    const bf16_t *W[3];
+    int rows[3];
+    int tile_begin[4];  // first n-tile of each matrix (prefix sums), tile_begin[3] = total
+    int col_off[3];
+    int lda_bytes;      // row stride of A in bytes
+    uint32_t a_bytes;   // size of A in bytes (range check)
+    int M, K, chunks, splits, epilogue;
+    void *out;
+    int64_t ldc;
+    size_t split_stride;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <int MT>
+__global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_kernel(SkinnyParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *xs = reinterpret_cast<bf16_t *>(smem);  // [2][MT*32][SK_LDS_STRIDE]
+    constexpr int BM = MT * 32;
+    constexpr int XLOADS = MT * 2;  // 16-byte loads per thread per chunk: BM*128*2 B / (256 thr * 16 B)
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int K = p.K;
+
+    // ---- which weight rows does this wavefront own?
+    int tile = blockIdx.x;
+    int seg = tile >= p.tile_begin[2] ? 2 : (tile >= p.tile_begin[1] ? 1 : 0);
+    int n_base, out_col;  // first W row of this wavefront / first output column
+    if (p.epilogue == EPI_SWIGLU) {
+        seg = w >> 1;                        // wavefronts 0,1: gate; 2,3: up
+        n_base = tile * 64 + (w & 1) * 32;
+        out_col = n_base;
+    } else {
+        n_base = (tile - p.tile_begin[seg]) * 128 + w * 32;
+        out_col = p.col_off[seg] + n_base;
+    }
+    const int rows = p.rows[seg];
+    const bf16_t *Wp = p.W[seg];
+    __amdgpu_buffer_rsrc_t wr = make_rsrc(Wp, (uint32_t)((size_t)rows * K * 2));
+    __amdgpu_buffer_rsrc_t ar = make_rsrc(p.A, p.a_bytes);
+    int wrow = n_base + (lane & 31);
+    // rows past the matrix read row 0 instead (always in bounds); their columns are never stored
+    uint32_t w_off = (uint32_t)(wrow < rows ? wrow : 0) * (uint32_t)K * 2u + (uint32_t)(lane >> 5) * 16u;
+
+    // ---- K range of this split
+    const int c0 = (int)(((int64_t)blockIdx.y * p.chunks) / p.splits);
+    const int c1 = (int)(((int64_t)(blockIdx.y + 1) * p.chunks) / p.splits);
+
+    // activation loader: thread -> (row r0 + 16*i, 16-byte column group c16)
+    const int c16 = t & 15, r0 = t >> 4;
+    u32x4_t xr[XLOADS];
+    bf16x8_t wq[2][8];
+    f32x16_t acc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+
+    auto load_x = [&](int c) {
+        int k = c * SK_BK + c16 * 8;
+#pragma unroll
+        for (int i = 0; i < XLOADS; ++i) {
+            int row = r0 + 16 * i;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (row < p.M && k < K)
+                v = __builtin_amdgcn_raw_buffer_load_b128(ar, row * p.lda_bytes + k * 2, 0, 0);
+            xr[i] = v;
+        }
+    };
+    auto store_x = [&](int buf) {
+        bf16_t *dst = xs + (size_t)buf * BM * SK_LDS_STRIDE;
+#pragma unroll
+        for (int i = 0; i < XLOADS; ++i) {
+            int row = r0 + 16 * i;
+            *reinterpret_cast<u32x4_t *>(dst + row * SK_LDS_STRIDE + c16 * 8) = xr[i];
+        }
+    };
+    auto load_w = [&](int c, int slot) {
+        int kb = c * SK_BK * 2;  // uniform byte offset of the chunk inside a row
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(w_off + (uint32_t)(s * 32)), kb, 0);
+            wq[slot][s] = __builtin_bit_cast(bf16x8_t, v);
+        }
+    };
+    auto compute = [&](int buf, int slot) {
+        const bf16_t *src = xs + (size_t)buf * BM * SK_LDS_STRIDE + (lane & 31) * SK_LDS_STRIDE + (lane >> 5) * 8;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(src + mt * 32 * SK_LDS_STRIDE + s * 16);
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wq[slot][s], acc[mt], 0, 0, 0);
+            }
+        }
+    };
+
+    if (c0 < c1) {
+        load_w(c0, 0);
+        load_x(c0);
+        store_x(0);
+        int c = c0;
+        // two chunks per trip so that the register double-buffer index is a compile-time constant
+        while (c < c1) {
+            bool more = c + 1 < c1;
+            if (more) { load_w(c + 1, 1); load_x(c + 1); }
+            __syncthreads();
+            compute(0, 0);
+            if (more) store_x(1);
+            ++c;
+            if (c >= c1) break;
+            more = c + 1 < c1;
+            if (more) { load_w(c + 1, 0); load_x(c + 1); }
+            __syncthreads();
+            compute(1, 1);
+            if (more) store_x(0);
+            ++c;
+        }
+    }
+
+    // ---- epilogue.  Lane holds column (lane & 31); register j of tile mt is row
+    //      mt*32 + (j/4)*8 + (lane>>5)*4 + (j%4).
+    const int col_local = lane & 31;
+    if (p.epilogue != EPI_SWIGLU) {
+        float *out = reinterpret_cast<float *>(p.out) + (size_t)blockIdx.y * p.split_stride;
+        const bool accumulate = p.epilogue == EPI_F32_ACC;
+        if (n_base + col_local < rows) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    int m = mt * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+                    if (m < p.M) {
+                        float *dst = out + (size_t)m * p.ldc + out_col + col_local;
+                        *dst = accumulate ? *dst + acc[mt][j] : acc[mt][j];
+                    }
+                }
+        }
+    } else {
+        // SwiGLU: wavefronts 2,3 (up) hand their accumulators to wavefronts 0,1 (gate) through LDS.
+        float *ex = reinterpret_cast<float *>(smem);  // [2][MT*16][64]
+        __syncthreads();                              // every wavefront is done reading the activation tiles
+        if (w >= 2) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) ex[((w - 2) * MT * 16 + mt * 16 + j) * 64 + lane] = acc[mt][j];
+        }
+        __syncthreads();
+        if (w < 2 && n_base + col_local < rows) {
+            bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    int m = mt * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
+                    float g = acc[mt][j], u = ex[(w * MT * 16 + mt * 16 + j) * 64 + lane];
+                    float a = g / (1.0f + expf(-g)) * u;
+                    if (m < p.M) out[(size_t)m * p.ldc + out_col + col_local] = f32_to_bf16(a);
+                }
+        }
+    }
+}
+
+int gemm_skinny_default_splits(int M, int N, int K) {
+    (void)M;
+    int tiles = ceil_div(N, 128);
+    int chunks = ceil_div(K, SK_BK);
+    int s = 512 / (tiles > 0 ? tiles : 1);  // aim at two workgroups per compute unit
+    if (s < 1) s = 1;
+    if (s > chunks / 4) s = chunks / 4 > 0 ? chunks / 4 : 1;  // keep at least 4 chunks per split
+    if (s > 16) s = 16;
+    return s;
+}
+
+template <int MT>
+static void launch_mt(const SkinnyParams &p, int tiles, hipStream_t st) {
+    size_t lds = (size_t)2 * MT * 32 * SK_LDS_STRIDE * sizeof(bf16_t);
+    size_t ex = (size_t)2 * MT * 16 * 64 * sizeof(float);
+    if (p.epilogue == EPI_SWIGLU && ex > lds) lds = ex;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_skinny_kernel<MT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    gemm_skinny_kernel<MT><<<dim3(tiles, p.splits), SK_THREADS, lds, st>>>(p);
+}
+
+void launch_gemm_skinny(const GemmArgs &a, hipStream_t st) {
+    if (a.M <= 0) return;
+    SkinnyParams p;
+    p.A = a.A;
+    p.lda_bytes = (int)(a.lda * 2);
+    p.a_bytes = (uint32_t)((((size_t)a.M - 1) * a.lda + a.K) * 2);
+    p.M = a.M;
+    p.K = a.K;
+    p.chunks = ceil_div(a.K, SK_BK);
+    p.epilogue = a.epilogue;
+    p.splits = a.epilogue != EPI_F32 ? 1 : (a.splits < 1 ? 1 : a.splits);
+    if (p.splits > p.chunks) p.splits = p.chunks;
+    p.out = a.out;
+    p.ldc = a.ldc;
+    p.split_stride = a.split_stride;
+    int tiles = 0, col = 0;
+    for (int i = 0; i < 3; ++i) {
+        p.W[i] = a.W[i] ? a.W[i] : a.W[0];
+        p.rows[i] = a.W[i] ? a.rows[i] : 0;
+        p.tile_begin[i] = tiles;
+        p.col_off[i] = col;
+        if (a.epilogue == EPI_SWIGLU) continue;
+        tiles += ceil_div(p.rows[i], 128);
+        col += p.rows[i];
+    }
+    if (a.epilogue == EPI_SWIGLU) tiles = ceil_div(a.rows[0], 64);
+    p.tile_begin[3] = tiles;
+    if (tiles <= 0) return;
+    if (a.M <= 32) launch_mt<1>(p, tiles, st);
+    else if (a.M <= 64) launch_mt<2>(p, tiles, st);
+    else if (a.M <= 128) launch_mt<4>(p, tiles, st);
+    else launch_mt<8>(p, tiles, st);
+}

@@ -1,0 +1,253 @@
+// Large-M bf16 GEMM for prefill: C[M, N] = A[M, K] * W[N, K]^T, both operands tiled through LDS,
+// v_mfma_f32_32x32x16_bf16 with fp32 accumulators.
+//
+// Prefill multiplies all prompt tokens of a chunk of sequences (thousands of rows) with every weight
+// matrix: a dense contraction, bound by the matrix cores.  Design for gfx950:
+//   * workgroup = 4 wavefronts in a 2 x 2 grid; each wavefront owns (WM*32) x (WN*32) of the tile
+//     (WM = WN = 4: a 256 x 256 tile, 128 x 128 per wavefront, 256 accumulator registers), so that
+//     each 1 KB LDS fragment read feeds four MFMAs;
+//   * K chunks of 64, register-staged global -> LDS copies, double-buffered LDS (one barrier per chunk);
+//   * LDS rows padded to 72 elements: ds_read_b128 of MFMA fragments is bank-conflict free;
+//   * workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8)
+//     work on neighbouring tiles and share their operand panels in that XCD's L2;
+//   * fused epilogues: fp32 store, fp32 accumulate (residual add), SwiGLU (wavefront column 0 holds
+//     the gate tile, column 1 the up tile of the same outputs; exchanged through LDS).
+#include "kernels.h"
+
+#define TG_BK 64
+#define TG_LDS_STRIDE 72
+#define TG_THREADS 256
+
+struct TiledParams {
+    const bf16_t *A;
+    const bf16_t *W[3];
+    int rows[3];
+    int tile_begin[4];
+    int col_off[3];
+    int64_t lda;
+    int M, K, chunks, epilogue;
+    int tiles_m, tiles_n;
+    void *out;
+    int64_t ldc;
+};
+
+template <int WM, int WN>
+__global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, HALF_N = WN * 32;
+    constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;  // 16-byte loads per thread per chunk
+    bf16_t *as = reinterpret_cast<bf16_t *>(smem);                  // [2][BM][72]
+    bf16_t *bs = as + 2 * BM * TG_LDS_STRIDE;                        // [2][BN][72]
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
+    const int K = p.K;
+
+    // ---- XCD-aware tile order: consecutive logical ids live on one XCD; walk tiles in groups of 8 rows
+    int nwg = p.tiles_m * p.tiles_n;
+    int bid = blockIdx.x;
+    int per_xcd = (nwg + 7) / 8;
+    int logical = (bid % 8) * per_xcd + bid / 8;
+    if (nwg % 8 != 0) logical = bid;  // ragged grids keep the plain order
+    constexpr int GROUP_M = 8;
+    int group = logical / (GROUP_M * p.tiles_n);
+    int first_m = group * GROUP_M;
+    int gsize = p.tiles_m - first_m < GROUP_M ? p.tiles_m - first_m : GROUP_M;
+    int in_group = logical % (GROUP_M * p.tiles_n);
+    int tile_m = first_m + in_group % gsize;
+    int tile_n = in_group / gsize;
+
+    // ---- weight rows of each half of the B tile (half h belongs to wavefront column h)
+    int seg_h[2], nbase_h[2], ocol_h[2];
+    if (p.epilogue == EPI_SWIGLU) {
+        for (int h = 0; h < 2; ++h) { seg_h[h] = h; nbase_h[h] = tile_n * HALF_N; ocol_h[h] = tile_n * HALF_N; }
+    } else {
+        int seg = tile_n >= p.tile_begin[2] ? 2 : (tile_n >= p.tile_begin[1] ? 1 : 0);
+        for (int h = 0; h < 2; ++h) {
+            seg_h[h] = seg;
+            nbase_h[h] = (tile_n - p.tile_begin[seg]) * BN + h * HALF_N;
+            ocol_h[h] = p.col_off[seg] + nbase_h[h];
+        }
+    }
+    const int m0 = tile_m * BM;
+
+    // loader mapping: thread -> (row t/8 + 32*i, 16-byte group t%8)
+    const int lc = t & 7, lr = t >> 3;
+    const bf16_t *a_ptr[A_LOADS];
+    bool a_ok[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        int row = m0 + lr + 32 * i;
+        a_ok[i] = row < p.M;
+        a_ptr[i] = p.A + (size_t)(a_ok[i] ? row : 0) * p.lda + lc * 8;
+    }
+    const bf16_t *b_ptr[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+        int r = lr + 32 * i;
+        int h = r / HALF_N;
+        int row = nbase_h[h] + (r - h * HALF_N);
+        int rows = p.rows[seg_h[h]];
+        b_ptr[i] = p.W[seg_h[h]] + (size_t)(row < rows ? row : 0) * K + lc * 8;  // clamped rows are never stored
+    }
+    u32x4_t ar[A_LOADS], br[B_LOADS];
+    f32x16_t acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    auto load_g = [&](int c) {
+        int k = c * TG_BK;
+        bool kok = k + lc * 8 < K;
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (a_ok[i] && kok) v = *reinterpret_cast<const u32x4_t *>(a_ptr[i] + k);
+            ar[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (kok) v = *reinterpret_cast<const u32x4_t *>(b_ptr[i] + k);
+            br[i] = v;
+        }
+    };
+    auto store_s = [&](int buf) {
+        bf16_t *ad = as + buf * BM * TG_LDS_STRIDE, *bd = bs + buf * BN * TG_LDS_STRIDE;
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i)
+            *reinterpret_cast<u32x4_t *>(ad + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = ar[i];
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i)
+            *reinterpret_cast<u32x4_t *>(bd + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = br[i];
+    };
+    auto compute = [&](int buf) {
+        const bf16_t *ap = as + buf * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        const bf16_t *bp = bs + buf * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+#pragma unroll
+        for (int s = 0; s < TG_BK / 16; ++s) {
+            bf16x8_t af[WM], bf[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const bf16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + s * 16);
+#pragma unroll
+            for (int j = 0; j < WN; ++j) bf[j] = *reinterpret_cast<const bf16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + s * 16);
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    load_g(0);
+    store_s(0);
+    for (int c = 0; c < p.chunks; ++c) {
+        bool more = c + 1 < p.chunks;
+        if (more) load_g(c + 1);
+        __syncthreads();
+        compute(c & 1);
+        if (more) store_s((c + 1) & 1);
+    }
+
+    // ---- epilogue.  Lane holds column (lane & 31) of each 32x32 tile; register e is row
+    //      (e/4)*8 + (lane>>5)*4 + (e%4).
+    const int rows_w = p.rows[seg_h[wn]];
+    const int nb = nbase_h[wn], oc = ocol_h[wn];
+    if (p.epilogue != EPI_SWIGLU) {
+        float *out = reinterpret_cast<float *>(p.out);
+        const bool accumulate = p.epilogue == EPI_F32_ACC;
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            int n = j * 32 + (lane & 31);
+            if (nb + n >= rows_w) continue;
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    int m = m0 + (wm * WM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    if (m < p.M) {
+                        float *dst = out + (size_t)m * p.ldc + oc + n;
+                        *dst = accumulate ? *dst + acc[i][j][e] : acc[i][j][e];
+                    }
+                }
+        }
+    } else {
+        // wavefront column 1 (up) -> LDS -> wavefront column 0 (gate), one 32-column strip at a time
+        float *ex = reinterpret_cast<float *>(smem);  // [2 (wm)][WM*16][64] floats per strip
+        bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            __syncthreads();
+            if (wn == 1) {
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) ex[((wm * WM + i) * 16 + e) * 64 + lane] = acc[i][j][e];
+            }
+            __syncthreads();
+            int n = j * 32 + (lane & 31);
+            if (wn == 0 && nb + n < rows_w) {
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        int m = m0 + (wm * WM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                        float g = acc[i][j][e], u = ex[((wm * WM + i) * 16 + e) * 64 + lane];
+                        float a = g / (1.0f + expf(-g)) * u;
+                        if (m < p.M) out[(size_t)m * p.ldc + oc + n] = f32_to_bf16(a);
+                    }
+            }
+        }
+    }
+}
+
+template <int WM, int WN>
+static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
+    constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
+    int tiles = 0, col = 0;
+    for (int i = 0; i < 3; ++i) {
+        p.tile_begin[i] = tiles;
+        p.col_off[i] = col;
+        if (a.epilogue == EPI_SWIGLU) continue;
+        tiles += ceil_div(p.rows[i], BN);
+        col += p.rows[i];
+    }
+    if (a.epilogue == EPI_SWIGLU) tiles = ceil_div(a.rows[0], BN / 2);
+    p.tile_begin[3] = tiles;
+    p.tiles_n = tiles;
+    p.tiles_m = ceil_div(a.M, BM);
+    if (tiles <= 0 || p.tiles_m <= 0) return;
+    size_t lds = (size_t)2 * (BM + BN) * TG_LDS_STRIDE * sizeof(bf16_t);
+    size_t ex = (size_t)2 * WM * 16 * 64 * sizeof(float);
+    if (ex > lds) lds = ex;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tiled_kernel<WM, WN>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    gemm_tiled_kernel<WM, WN><<<p.tiles_m * p.tiles_n, TG_THREADS, lds, st>>>(p);
+}
+
+void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
+    if (a.M <= 0) return;
+    TiledParams p;
+    p.A = a.A;
+    p.lda = a.lda;
+    p.M = a.M;
+    p.K = a.K;
+    p.chunks = ceil_div(a.K, TG_BK);
+    p.epilogue = a.epilogue;
+    p.out = a.out;
+    p.ldc = a.ldc;
+    int n_total = 0;
+    for (int i = 0; i < 3; ++i) {
+        p.W[i] = a.W[i] ? a.W[i] : a.W[0];
+        p.rows[i] = a.W[i] ? a.rows[i] : 0;
+        n_total += p.rows[i];
+    }
+    // big tiles only when they still give every compute unit work
+    long big_tiles = (long)ceil_div(a.M, 256) * ceil_div(n_total, 256);
+    if (a.M >= 1024 && big_tiles >= 256) launch_t<4, 4>(p, a, st);
+    else launch_t<2, 2>(p, a, st);
+}

@@ -1,0 +1,647 @@
+// Host side of the C ABI (include/rl_gen.h, include/rl_gen_ops.h): argument validation, arena
+// carving, kernel sequencing of prefill / decode steps, HIP-graph replay of decode steps and
+// per-kernel event timing.  All arithmetic of the method runs in the kernels this file launches.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/rl_gen.h"
+#include "../../include/rl_gen_ops.h"
+#include "kernels.h"
+
+namespace {
+
+char g_create_error[512] = "";
+
+constexpr int kPrefillChunkTokens = 16384;  // prompt tokens pushed through the layers at once
+constexpr int kSkinnyMaxM = 256;
+constexpr int kMaxSplits = 16;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct WorkPlan {
+    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, rope, state, total;
+    int rows;  // activation rows the workspace can hold
+};
+
+int validate(const rl_gen_shape *s) {
+    if (!s) return RL_GEN_E_NULL;
+    if (s->n_layers < 0 || s->hidden <= 0 || s->n_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0 || s->ffn <= 0 ||
+        s->vocab <= 0 || s->max_batch <= 0 || s->max_seq <= 0)
+        return RL_GEN_E_SHAPE;
+    if ((int64_t)s->n_heads * s->head_dim != s->hidden) return RL_GEN_E_SHAPE;
+    if (s->n_heads % s->n_kv_heads != 0 || s->n_heads / s->n_kv_heads > 16) return RL_GEN_E_SHAPE;
+    if (s->head_dim != 64 && s->head_dim != 128) return RL_GEN_E_SHAPE;
+    if (s->hidden % 8 != 0 || s->ffn % 8 != 0 || s->hidden > 8192) return RL_GEN_E_SHAPE;
+    if (s->rope_style != 0 && s->rope_style != 1) return RL_GEN_E_SHAPE;
+    if (s->weight_dtype != 0 && s->weight_dtype != 1) return RL_GEN_E_SHAPE;
+    if (!(s->rope_base > 0.f) || !(s->rms_eps >= 0.f)) return RL_GEN_E_SHAPE;
+    // every weight matrix is addressed through a 32-bit range-checked buffer descriptor
+    const uint64_t lim = 0xffffffffull;
+    if ((uint64_t)s->vocab * s->hidden * 2 > lim || (uint64_t)s->ffn * s->hidden * 2 > lim) return RL_GEN_E_SHAPE;
+    return RL_GEN_OK;
+}
+
+int attn_splits(const rl_gen_shape *s) {
+    int g = s->n_heads / s->n_kv_heads;
+    int gt = g % 8 == 0 ? 8 : (g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1));
+    return decode_attention_default_splits(s->max_batch, s->n_kv_heads * (g / gt), s->max_seq);
+}
+
+WorkPlan plan_work(const rl_gen_shape *s) {
+    WorkPlan p;
+    int64_t all = (int64_t)s->max_batch * s->max_seq;
+    int64_t chunk = s->max_seq > kPrefillChunkTokens ? s->max_seq : kPrefillChunkTokens;
+    if (chunk > all) chunk = all;
+    int64_t rows = chunk > s->max_batch ? chunk : s->max_batch;
+    p.rows = (int)rows;
+    size_t d = s->hidden, qd = (size_t)s->n_heads * s->head_dim, kvd = (size_t)s->n_kv_heads * s->head_dim;
+    size_t nqkv = qd + 2 * kvd, nmax = nqkv > d ? nqkv : d;
+    size_t skinny_rows = rows < kSkinnyMaxM ? (size_t)rows : (size_t)kSkinnyMaxM;
+    size_t part_elems = (size_t)rows * nqkv;
+    if ((size_t)kMaxSplits * skinny_rows * nmax > part_elems) part_elems = (size_t)kMaxSplits * skinny_rows * nmax;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    p.x = take((size_t)rows * d * 4);
+    p.h = take((size_t)rows * d * 2);
+    p.part = take(part_elems * 4);
+    p.qf32 = take((size_t)s->max_batch * qd * 4);
+    p.qbf = take((size_t)rows * qd * 2);
+    p.attn = take((size_t)rows * qd * 2);
+    p.act = take((size_t)rows * s->ffn * 2);
+    p.attn_ws = take(decode_attention_ws_floats(s->max_batch, s->n_heads, s->head_dim, attn_splits(s)) * 4 + 16);
+    p.logits = take((size_t)s->max_batch * s->vocab * 4);
+    p.next = take((size_t)s->max_batch * 4);
+    p.rope = take((size_t)s->max_seq * s->head_dim * 4);
+    p.state = take(64);
+    p.total = off;
+    return p;
+}
+
+struct GraphEntry {
+    const void *tokens, *logits, *next;
+    int B;
+    hipStream_t stream;
+    int calls;
+    hipGraphExec_t exec;
+};
+
+struct ProfEvent {
+    hipEvent_t a, b;
+    int cls;
+};
+
+}  // namespace
+
+struct rl_gen {
+    rl_gen_shape s;
+    std::vector<const bf16_t *> lw[9];
+    const bf16_t *tok_emb, *final_norm, *lm_head;
+    std::vector<void *> owned;
+    bf16_t *kv;
+    unsigned char *work;
+    WorkPlan wp;
+    int nsplit_attn;
+    int B, len;
+    bool graph_on, prof_on;
+    std::vector<GraphEntry> graphs;
+    std::vector<ProfEvent> prof_events;
+    std::vector<ProfEvent> prof_pool;
+    int prof_launches[RL_GEN_N_KERNEL_CLASSES];
+    float prof_ms[RL_GEN_N_KERNEL_CLASSES];
+    char err[512];
+
+    float *x() const { return reinterpret_cast<float *>(work + wp.x); }
+    bf16_t *h() const { return reinterpret_cast<bf16_t *>(work + wp.h); }
+    float *part() const { return reinterpret_cast<float *>(work + wp.part); }
+    float *qf32() const { return reinterpret_cast<float *>(work + wp.qf32); }
+    bf16_t *qbf() const { return reinterpret_cast<bf16_t *>(work + wp.qbf); }
+    bf16_t *attn() const { return reinterpret_cast<bf16_t *>(work + wp.attn); }
+    bf16_t *act() const { return reinterpret_cast<bf16_t *>(work + wp.act); }
+    float *attn_ws() const { return reinterpret_cast<float *>(work + wp.attn_ws); }
+    float *logits_ws() const { return reinterpret_cast<float *>(work + wp.logits); }
+    int32_t *next_ws() const { return reinterpret_cast<int32_t *>(work + wp.next); }
+    float *rope() const { return reinterpret_cast<float *>(work + wp.rope); }
+    int32_t *d_len() const { return reinterpret_cast<int32_t *>(work + wp.state); }
+    int32_t *d_zero() const { return reinterpret_cast<int32_t *>(work + wp.state) + 1; }
+    bf16_t *kslab(int l) const {
+        return kv + (size_t)(2 * l) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
+    }
+    bf16_t *vslab(int l) const {
+        return kv + (size_t)(2 * l + 1) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
+    }
+};
+
+namespace {
+
+enum { W_ATTN_NORM = 0, W_Q, W_K, W_V, W_O, W_FFN_NORM, W_GATE, W_UP, W_DOWN };
+
+void set_err(rl_gen *h, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(h ? h->err : g_create_error, 512, fmt, ap);
+    va_end(ap);
+}
+
+// brackets one kernel launch with events when per-kernel timing is on
+struct Scope {
+    rl_gen *h;
+    hipStream_t st;
+    ProfEvent ev;
+    bool on;
+    Scope(rl_gen *h_, int cls, hipStream_t st_) : h(h_), st(st_), on(h_->prof_on) {
+        if (!on) return;
+        if (!h->prof_pool.empty()) {
+            ev = h->prof_pool.back();
+            h->prof_pool.pop_back();
+        } else {
+            (void)hipEventCreate(&ev.a);
+            (void)hipEventCreate(&ev.b);
+        }
+        ev.cls = cls;
+        (void)hipEventRecord(ev.a, st);
+    }
+    ~Scope() {
+        if (!on) return;
+        (void)hipEventRecord(ev.b, st);
+        h->prof_events.push_back(ev);
+    }
+};
+
+// One projection.  Returns the number of fp32 partials written to h->part() (0 when the result was
+// accumulated straight into `acc_out`).
+int project(rl_gen *h, int cls, const bf16_t *A, int64_t lda, int M, int K, const bf16_t *W0, int r0, const bf16_t *W1,
+            int r1, const bf16_t *W2, int r2, float *acc_out, int64_t ld_acc, hipStream_t st) {
+    GemmArgs a;
+    a.A = A; a.lda = lda; a.M = M; a.K = K;
+    a.W[0] = W0; a.W[1] = W1; a.W[2] = W2;
+    a.rows[0] = r0; a.rows[1] = r1; a.rows[2] = r2;
+    int N = r0 + r1 + r2;
+    Scope sc(h, cls, st);
+    if (M <= kSkinnyMaxM) {
+        int splits = gemm_skinny_default_splits(M, N, K);
+        if (splits > kMaxSplits) splits = kMaxSplits;
+        a.out = h->part(); a.ldc = N; a.split_stride = (size_t)M * N; a.splits = splits; a.epilogue = EPI_F32;
+        launch_gemm_skinny(a, st);
+        return splits;
+    }
+    if (acc_out) {
+        a.out = acc_out; a.ldc = ld_acc; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32_ACC;
+        launch_gemm_tiled(a, st);
+        return 0;
+    }
+    a.out = h->part(); a.ldc = N; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
+    launch_gemm_tiled(a, st);
+    return 1;
+}
+
+void swiglu_project(rl_gen *h, const bf16_t *A, int M, int l, hipStream_t st) {
+    GemmArgs a;
+    a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
+    a.W[0] = h->lw[W_GATE][l]; a.W[1] = h->lw[W_UP][l]; a.W[2] = nullptr;
+    a.rows[0] = h->s.ffn; a.rows[1] = h->s.ffn; a.rows[2] = 0;
+    a.out = h->act(); a.ldc = h->s.ffn; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
+    Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
+    if (M <= kSkinnyMaxM) launch_gemm_skinny(a, st);
+    else launch_gemm_tiled(a, st);
+}
+
+// All layers for M = nb*T rows (sequences b0 .. b0+nb-1, T new positions each starting at *d_pos0),
+// then final norm; leaves the normalised rows in h->h().  decode == (T == 1 and attention over the cache).
+void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool decode, hipStream_t st) {
+    const rl_gen_shape &s = h->s;
+    const int M = nb * T, d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
+    const int L = s.n_layers;
+    {
+        Scope sc(h, RL_GEN_K_EMBED, st);
+        launch_embed(tokens, h->tok_emb, h->x(), M, d, s.vocab, st);
+    }
+    {
+        Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
+        launch_add_rmsnorm(h->x(), nullptr, 0, 0, L > 0 ? h->lw[W_ATTN_NORM][0] : h->final_norm, s.rms_eps, h->h(), M, d, st);
+    }
+    for (int l = 0; l < L; ++l) {
+        int ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
+                         nullptr, 0, st);
+        {
+            Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
+            launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_len() : h->d_zero(),
+                               h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
+                               decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st);
+        }
+        if (decode) {
+            Scope sc(h, RL_GEN_K_DECODE_ATTN, st);
+            launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_len(), h->attn(), h->attn_ws(), nb,
+                                    s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st);
+        } else {
+            Scope sc(h, RL_GEN_K_PREFILL_ATTN, st);
+            launch_prefill_attention(h->qbf(), h->kslab(l), h->vslab(l), h->attn(), nb, b0, T, s.n_heads, s.n_kv_heads,
+                                     s.head_dim, s.max_seq, st);
+        }
+        ns = project(h, RL_GEN_K_GEMM_O, h->attn(), qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
+        {
+            Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
+            launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), M, d, st);
+        }
+        swiglu_project(h, h->h(), M, l, st);
+        ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d,
+                     st);
+        {
+            Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
+            launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, l + 1 < L ? h->lw[W_ATTN_NORM][l + 1] : h->final_norm,
+                               s.rms_eps, h->h(), M, d, st);
+        }
+    }
+}
+
+// logits[b0 + i, :] = lm_head * h[row i*T + T-1]  for i < nb
+void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st) {
+    const rl_gen_shape &s = h->s;
+    GemmArgs a;
+    a.A = h->h() + (size_t)(T - 1) * s.hidden; a.lda = (int64_t)T * s.hidden; a.M = nb; a.K = s.hidden;
+    a.W[0] = h->lm_head; a.W[1] = nullptr; a.W[2] = nullptr;
+    a.rows[0] = s.vocab; a.rows[1] = 0; a.rows[2] = 0;
+    a.out = logits + (size_t)b0 * s.vocab; a.ldc = s.vocab; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
+    Scope sc(h, RL_GEN_K_GEMM_LM_HEAD, st);
+    if (nb <= kSkinnyMaxM) launch_gemm_skinny(a, st);
+    else launch_gemm_tiled(a, st);
+}
+
+void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, int32_t *next, hipStream_t st) {
+    run_layers(h, tokens, h->B, 1, 0, true, st);
+    lm_head(h, h->B, 1, 0, logits, st);
+    Scope sc(h, RL_GEN_K_ARGMAX, st);
+    launch_argmax(logits, h->B, h->s.vocab, next, h->d_len(), st);
+}
+
+int check_hip(rl_gen *h, const char *where) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_err(h, "%s: %s", where, hipGetErrorString(e));
+        return RL_GEN_E_HIP;
+    }
+    return RL_GEN_OK;
+}
+
+void drop_graphs(rl_gen *h) {
+    for (auto &g : h->graphs)
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    h->graphs.clear();
+}
+
+}  // namespace
+
+extern "C" {
+
+int rl_gen_validate_shape(const rl_gen_shape *shape) { return validate(shape); }
+
+int64_t rl_gen_param_count(const rl_gen_shape *s) {
+    if (!s) return RL_GEN_E_NULL;
+    if (s->n_layers < 0 || s->hidden <= 0 || s->n_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0 || s->ffn <= 0 ||
+        s->vocab <= 0)
+        return RL_GEN_E_SHAPE;
+    int64_t d = s->hidden, qd = (int64_t)s->n_heads * s->head_dim, kvd = (int64_t)s->n_kv_heads * s->head_dim;
+    int64_t emb = 2 * (int64_t)s->vocab * d;                      // input and output embeddings, untied
+    int64_t attn = qd * d + 2 * kvd * d + d * qd;                 // Wq, Wk, Wv, Wo
+    int64_t ffn = 3 * d * (int64_t)s->ffn;                        // gate, up, down
+    return emb + (int64_t)s->n_layers * (attn + ffn + 2 * d) + d;  // + two gains per layer + final gain
+}
+
+size_t rl_gen_kv_bytes(const rl_gen_shape *s) {
+    if (validate(s) != RL_GEN_OK) return 0;
+    return (size_t)2 * s->n_layers * s->max_batch * s->n_kv_heads * s->max_seq * s->head_dim * sizeof(bf16_t);
+}
+
+size_t rl_gen_work_bytes(const rl_gen_shape *s) {
+    if (validate(s) != RL_GEN_OK) return 0;
+    return plan_work(s).total;
+}
+
+int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_arena, size_t kv_bytes, void *work_arena,
+                  size_t work_bytes, rl_gen_t **out) {
+    if (!shape || !w || !out) { set_err(nullptr, "rl_gen_create: NULL argument"); return RL_GEN_E_NULL; }
+    *out = nullptr;
+    int rc = validate(shape);
+    if (rc != RL_GEN_OK) { set_err(nullptr, "rl_gen_create: unsupported shape"); return rc; }
+    const int L = shape->n_layers;
+    const void *const *arrs[9] = {w->attn_norm, w->wq, w->wk, w->wv, w->wo, w->ffn_norm, w->w_gate, w->w_up, w->w_down};
+    if (!w->tok_emb || !w->final_norm || !w->lm_head) { set_err(nullptr, "rl_gen_create: NULL weight"); return RL_GEN_E_NULL; }
+    for (int a = 0; a < 9; ++a) {
+        if (L > 0 && !arrs[a]) { set_err(nullptr, "rl_gen_create: NULL weight array"); return RL_GEN_E_NULL; }
+        for (int l = 0; l < L; ++l)
+            if (!arrs[a][l]) { set_err(nullptr, "rl_gen_create: NULL layer weight"); return RL_GEN_E_NULL; }
+    }
+    size_t need_kv = rl_gen_kv_bytes(shape);
+    WorkPlan wp = plan_work(shape);
+    if ((need_kv > 0 && !kv_arena) || !work_arena) { set_err(nullptr, "rl_gen_create: NULL arena"); return RL_GEN_E_NULL; }
+    if (kv_bytes < need_kv || work_bytes < wp.total) {
+        set_err(nullptr, "rl_gen_create: arena too small (kv %zu < %zu or work %zu < %zu)", kv_bytes, need_kv, work_bytes, wp.total);
+        return RL_GEN_E_CAPACITY;
+    }
+    if (((uintptr_t)kv_arena | (uintptr_t)work_arena) % kAlign) { set_err(nullptr, "rl_gen_create: arena not 256-byte aligned"); return RL_GEN_E_SHAPE; }
+
+    rl_gen *h = new rl_gen();
+    h->s = *shape;
+    h->kv = reinterpret_cast<bf16_t *>(kv_arena);
+    h->work = reinterpret_cast<unsigned char *>(work_arena);
+    h->wp = wp;
+    h->nsplit_attn = attn_splits(shape);
+    h->B = 0; h->len = 0;
+    h->graph_on = true; h->prof_on = false;
+    h->err[0] = 0;
+    memset(h->prof_launches, 0, sizeof h->prof_launches);
+    memset(h->prof_ms, 0, sizeof h->prof_ms);
+
+    // weights: borrow bf16, convert fp32 once
+    const size_t d = shape->hidden, qd = (size_t)shape->n_heads * shape->head_dim, kvd = (size_t)shape->n_kv_heads * shape->head_dim;
+    const size_t elems[9] = {d, qd * d, kvd * d, kvd * d, d * qd, d, (size_t)shape->ffn * d, (size_t)shape->ffn * d, d * (size_t)shape->ffn};
+    bool fail = false;
+    auto adopt = [&](const void *p, size_t n) -> const bf16_t * {
+        if (shape->weight_dtype == 1) return reinterpret_cast<const bf16_t *>(p);
+        void *dst = nullptr;
+        if (hipMalloc(&dst, n * sizeof(bf16_t)) != hipSuccess) { fail = true; return nullptr; }
+        h->owned.push_back(dst);
+        launch_f32_to_bf16(reinterpret_cast<const float *>(p), reinterpret_cast<bf16_t *>(dst), n, nullptr);
+        return reinterpret_cast<const bf16_t *>(dst);
+    };
+    h->tok_emb = adopt(w->tok_emb, (size_t)shape->vocab * d);
+    h->final_norm = adopt(w->final_norm, d);
+    h->lm_head = adopt(w->lm_head, (size_t)shape->vocab * d);
+    for (int a = 0; a < 9 && !fail; ++a) {
+        h->lw[a].resize(L);
+        for (int l = 0; l < L && !fail; ++l) h->lw[a][l] = adopt(arrs[a][l], elems[a]);
+    }
+    // rotary table (fp64 on the host) and the device-side state words
+    if (!fail) {
+        std::vector<float> tab((size_t)shape->max_seq * shape->head_dim);
+        int half = shape->head_dim / 2;
+        for (int pos = 0; pos < shape->max_seq; ++pos)
+            for (int r = 0; r < half; ++r) {
+                double ang = (double)pos * pow((double)shape->rope_base, -2.0 * r / (double)shape->head_dim);
+                tab[((size_t)pos * half + r) * 2] = (float)cos(ang);
+                tab[((size_t)pos * half + r) * 2 + 1] = (float)sin(ang);
+            }
+        int32_t zeros[16] = {0};
+        if (hipMemcpy(h->rope(), tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(h->d_len(), zeros, sizeof zeros, hipMemcpyHostToDevice) != hipSuccess)
+            fail = true;
+    }
+    if (!fail && hipDeviceSynchronize() != hipSuccess) fail = true;
+    if (fail || hipGetLastError() != hipSuccess) {
+        set_err(nullptr, "rl_gen_create: HIP failure while preparing weights/tables");
+        for (void *p : h->owned) (void)hipFree(p);
+        delete h;
+        return RL_GEN_E_HIP;
+    }
+    *out = h;
+    return RL_GEN_OK;
+}
+
+int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logits, int32_t *next, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!tokens) { set_err(h, "rl_gen_prefill: NULL tokens"); return RL_GEN_E_NULL; }
+    if (B <= 0 || T <= 0) { set_err(h, "rl_gen_prefill: B and T must be positive"); return RL_GEN_E_SHAPE; }
+    if (B > h->s.max_batch || T > h->s.max_seq) {
+        set_err(h, "rl_gen_prefill: B=%d T=%d exceed capacity %d x %d", B, T, h->s.max_batch, h->s.max_seq);
+        return RL_GEN_E_CAPACITY;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    float *lg = logits ? logits : h->logits_ws();
+    int32_t *nx = next ? next : h->next_ws();
+    int per_chunk = h->wp.rows / T;  // whole sequences per pass through the layers
+    if (per_chunk < 1) per_chunk = 1;
+    for (int b0 = 0; b0 < B; b0 += per_chunk) {
+        int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
+        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
+        lm_head(h, nb, T, b0, lg, st);
+    }
+    {
+        Scope sc(h, RL_GEN_K_ARGMAX, st);
+        launch_argmax(lg, B, h->s.vocab, nx, nullptr, st);
+    }
+    {
+        Scope sc(h, RL_GEN_K_MISC, st);
+        launch_set_i32(h->d_len(), T, st);
+    }
+    int rc = check_hip(h, "rl_gen_prefill");
+    if (rc != RL_GEN_OK) return rc;
+    h->B = B; h->len = T;
+    return RL_GEN_OK;
+}
+
+int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_t *next, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!tokens) { set_err(h, "rl_gen_decode_step: NULL tokens"); return RL_GEN_E_NULL; }
+    if (h->B <= 0) { set_err(h, "rl_gen_decode_step: no prefill yet"); return RL_GEN_E_STATE; }
+    if (h->len + 1 > h->s.max_seq) { set_err(h, "rl_gen_decode_step: sequence capacity %d reached", h->s.max_seq); return RL_GEN_E_CAPACITY; }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    float *lg = logits ? logits : h->logits_ws();
+    int32_t *nx = next ? next : h->next_ws();
+    bool use_graph = h->graph_on && !h->prof_on;
+    if (!use_graph) {
+        enqueue_decode(h, tokens, lg, nx, st);
+    } else {
+        GraphEntry *g = nullptr;
+        for (auto &e : h->graphs)
+            if (e.tokens == tokens && e.logits == lg && e.next == nx && e.B == h->B && e.stream == st) g = &e;
+        if (!g) {
+            if (h->graphs.size() >= 8) drop_graphs(h);
+            h->graphs.push_back(GraphEntry{tokens, lg, nx, h->B, st, 0, nullptr});
+            g = &h->graphs.back();
+        }
+        g->calls++;
+        if (g->exec) {
+            if (hipGraphLaunch(g->exec, st) != hipSuccess) { set_err(h, "rl_gen_decode_step: hipGraphLaunch failed"); return RL_GEN_E_HIP; }
+        } else if (g->calls == 1) {
+            enqueue_decode(h, tokens, lg, nx, st);  // first use: plain launches (also warms up lazy kernel attributes)
+        } else {
+            hipGraph_t graph = nullptr;
+            if (hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed) != hipSuccess) {
+                (void)hipGetLastError();
+                enqueue_decode(h, tokens, lg, nx, st);
+            } else {
+                enqueue_decode(h, tokens, lg, nx, st);
+                hipError_t e = hipStreamEndCapture(st, &graph);
+                if (e != hipSuccess || !graph) { set_err(h, "rl_gen_decode_step: stream capture failed: %s", hipGetErrorString(e)); return RL_GEN_E_HIP; }
+                e = hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0);
+                (void)hipGraphDestroy(graph);
+                if (e != hipSuccess) { g->exec = nullptr; set_err(h, "rl_gen_decode_step: hipGraphInstantiate failed: %s", hipGetErrorString(e)); return RL_GEN_E_HIP; }
+                if (hipGraphLaunch(g->exec, st) != hipSuccess) { set_err(h, "rl_gen_decode_step: hipGraphLaunch failed"); return RL_GEN_E_HIP; }
+            }
+        }
+    }
+    int rc = check_hip(h, "rl_gen_decode_step");
+    if (rc != RL_GEN_OK) return rc;
+    h->len += 1;
+    return RL_GEN_OK;
+}
+
+int rl_gen_set_graph(rl_gen_t *h, int32_t enabled) {
+    if (!h) return RL_GEN_E_NULL;
+    h->graph_on = enabled != 0;
+    return RL_GEN_OK;
+}
+
+int rl_gen_reset(rl_gen_t *h) {
+    if (!h) return RL_GEN_E_NULL;
+    h->B = 0; h->len = 0;
+    return RL_GEN_OK;
+}
+
+int rl_gen_state(const rl_gen_t *h, int32_t *batch, int32_t *length) {
+    if (!h) return RL_GEN_E_NULL;
+    if (batch) *batch = h->B;
+    if (length) *length = h->len;
+    return RL_GEN_OK;
+}
+
+void rl_gen_destroy(rl_gen_t *h) {
+    if (!h) return;
+    (void)hipDeviceSynchronize();
+    drop_graphs(h);
+    for (auto &e : h->prof_events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    for (auto &e : h->prof_pool) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    for (void *p : h->owned) (void)hipFree(p);
+    delete h;
+}
+
+const char *rl_gen_last_error(const rl_gen_t *h) { return h ? h->err : g_create_error; }
+
+int rl_gen_profile(rl_gen_t *h, int32_t enabled) {
+    if (!h) return RL_GEN_E_NULL;
+    h->prof_on = enabled != 0;
+    return RL_GEN_OK;
+}
+
+int rl_gen_profile_read(rl_gen_t *h, int32_t *launches, float *milliseconds, void *hip_stream) {
+    if (!h || !launches || !milliseconds) return RL_GEN_E_NULL;
+    if (hipStreamSynchronize(reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess) { set_err(h, "rl_gen_profile_read: sync failed"); return RL_GEN_E_HIP; }
+    for (auto &e : h->prof_events) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) {
+            h->prof_launches[e.cls] += 1;
+            h->prof_ms[e.cls] += ms;
+        }
+        h->prof_pool.push_back(e);
+    }
+    h->prof_events.clear();
+    for (int i = 0; i < RL_GEN_N_KERNEL_CLASSES; ++i) {
+        launches[i] = h->prof_launches[i];
+        milliseconds[i] = h->prof_ms[i];
+        h->prof_launches[i] = 0;
+        h->prof_ms[i] = 0.f;
+    }
+    (void)hipGetLastError();
+    return RL_GEN_OK;
+}
+
+const char *rl_gen_kernel_class_name(int32_t id) {
+    static const char *names[RL_GEN_N_KERNEL_CLASSES] = {"embed", "add_rmsnorm", "gemm_qkv", "rope_append", "decode_attention",
+                                                         "attention_merge", "prefill_attention", "gemm_o", "gemm_gate_up",
+                                                         "gemm_down", "gemm_lm_head", "argmax", "misc"};
+    return id >= 0 && id < RL_GEN_N_KERNEL_CLASSES ? names[id] : "?";
+}
+
+// ------------------------------------------------------------------ single-kernel entry points
+
+#define RL_OP_RETURN()                                         \
+    do {                                                       \
+        return hipGetLastError() == hipSuccess ? RL_GEN_OK : RL_GEN_E_HIP; \
+    } while (0)
+
+int rl_op_embed(const int32_t *tokens, const uint16_t *emb, float *x, int32_t M, int32_t d, int32_t vocab, void *st) {
+    if (!tokens || !emb || !x) return RL_GEN_E_NULL;
+    if (M < 0 || d <= 0 || d % 8 || vocab <= 0) return RL_GEN_E_SHAPE;
+    launch_embed(tokens, emb, x, M, d, vocab, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_stride, const uint16_t *gain, float eps,
+                      uint16_t *h, int32_t M, int32_t d, void *st) {
+    if (!x || !gain || !h || (nsplit > 0 && !part)) return RL_GEN_E_NULL;
+    if (M < 0 || d <= 0 || d % 4 || d > 8192 || nsplit < 0) return RL_GEN_E_SHAPE;
+    launch_add_rmsnorm(x, part, nsplit, part_stride, gain, eps, h, M, d, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_gemm(const uint16_t *A, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2, int32_t rows0,
+               int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
+               int32_t splits, int32_t epilogue, int32_t kernel, void *st) {
+    if (!A || !W0 || !out) return RL_GEN_E_NULL;
+    if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
+    if (epilogue < 0 || epilogue > 2 || kernel < 0 || kernel > 2 || splits < 1) return RL_GEN_E_SHAPE;
+    if (epilogue == EPI_SWIGLU && (!W1 || rows1 != rows0 || W2)) return RL_GEN_E_SHAPE;
+    if (epilogue != EPI_F32 && splits != 1) return RL_GEN_E_SHAPE;
+    if (kernel == 1 && M > kSkinnyMaxM) return RL_GEN_E_SHAPE;
+    if (kernel == 2 && splits != 1) return RL_GEN_E_SHAPE;
+    if ((uint64_t)rows0 * K * 2 > 0xffffffffull || (uint64_t)rows1 * K * 2 > 0xffffffffull || (uint64_t)rows2 * K * 2 > 0xffffffffull)
+        return RL_GEN_E_SHAPE;
+    GemmArgs a;
+    a.A = A; a.lda = lda; a.M = M; a.K = K;
+    a.W[0] = W0; a.W[1] = rows1 > 0 ? W1 : nullptr; a.W[2] = rows2 > 0 ? W2 : nullptr;
+    a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
+    a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue;
+    bool skinny = kernel == 1 || (kernel == 0 && M <= kSkinnyMaxM);
+    if (skinny) launch_gemm_skinny(a, reinterpret_cast<hipStream_t>(st));
+    else launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float base) {
+    if (!tab) return RL_GEN_E_NULL;
+    if (max_seq <= 0 || head_dim <= 0 || head_dim % 2 || !(base > 0.f)) return RL_GEN_E_SHAPE;
+    std::vector<float> t((size_t)max_seq * head_dim);
+    int half = head_dim / 2;
+    for (int pos = 0; pos < max_seq; ++pos)
+        for (int r = 0; r < half; ++r) {
+            double ang = (double)pos * pow((double)base, -2.0 * r / (double)head_dim);
+            t[((size_t)pos * half + r) * 2] = (float)cos(ang);
+            t[((size_t)pos * half + r) * 2 + 1] = (float)sin(ang);
+        }
+    return hipMemcpy(tab, t.data(), t.size() * sizeof(float), hipMemcpyHostToDevice) == hipSuccess ? RL_GEN_OK : RL_GEN_E_HIP;
+}
+
+int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
+                      const int32_t *d_pos0, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv, int32_t hd,
+                      int32_t S, float *q_f32, uint16_t *q_bf16, uint16_t *kc, uint16_t *vc, void *st) {
+    if (!qkv || !d_pos0 || !rope_tab || !kc || !vc) return RL_GEN_E_NULL;
+    if (nsplit < 1 || M < 0 || T <= 0 || b0 < 0 || Hq <= 0 || Hkv <= 0 || hd <= 0 || hd % 2 || S <= 0 || (rope_style != 0 && rope_style != 1))
+        return RL_GEN_E_SHAPE;
+    launch_rope_append(qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_bf16, kc, vc,
+                       reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit) {
+    return decode_attention_ws_floats(B, Hq, hd, nsplit);
+}
+
+int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, uint16_t *out, float *ws,
+                           int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
+    if (!q || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
+    launch_decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_t *vc, uint16_t *out, int32_t nb, int32_t b0,
+                            int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, void *st) {
+    if (!q || !kc || !vc || !out) return RL_GEN_E_NULL;
+    if (nb < 0 || b0 < 0 || T <= 0 || T > S || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || nb > 65535)
+        return RL_GEN_E_SHAPE;
+    launch_prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *st) {
+    if (!logits || !next) return RL_GEN_E_NULL;
+    if (B < 0 || V <= 0) return RL_GEN_E_SHAPE;
+    launch_argmax(logits, B, V, next, nullptr, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+}  // extern "C"

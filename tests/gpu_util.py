@@ -1,0 +1,29 @@
+"""Helpers shared by the GPU parity tests (no arithmetic of the method)."""
+import numpy as np
+import torch
+
+DEV = "cuda:0"
+BF16_EPS = 2.0 ** -8      # one bf16 ulp relative to the value (half of it is the rounding error bound)
+
+
+def randn_bf16(shape, seed, std=1.0, device=DEV):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return (torch.randn(shape, generator=g) * std).to(torch.bfloat16).to(device)
+
+
+def randn_f32(shape, seed, std=1.0, device=DEV):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return (torch.randn(shape, generator=g) * std).to(device)
+
+
+def np64(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def bits(t):
+    """bf16 tensor -> uint16 numpy bit patterns (what the oracle borrows)"""
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def step(msg):
+    print(msg, flush=True)

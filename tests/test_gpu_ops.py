@@ -1,0 +1,212 @@
+"""GPU parity of every single kernel (rl_op_* entry points of the C ABI) against the CPU oracle's
+sub-functions on the same seeded inputs.  Sizes span several tiles and ragged tails.
+
+Tolerances (derived from the arithmetic): inputs are bf16-valued and identical on both sides; the
+kernels accumulate in fp32 (relative error ~1e-6 per term, growing like sqrt(K)), and outputs stored
+as bf16 carry one rounding (relative 2^-9).  Attention additionally uses a fast exponential
+(relative ~2e-6) and, in prefill, probabilities rounded to bf16 for the matrix cores (relative 2^-9
+per term of a convex combination).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import orc
+from tests.gpu_util import BF16_EPS, DEV, bits, np64, randn_bf16, randn_f32, step
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ops():
+    from paper_2406_14088_amd import ops as o
+    return o
+
+
+def test_embed_exact(ops):
+    emb = randn_bf16((1000, 264), 1)
+    tok = torch.tensor([0, 999, 5, 5, 123, 77], dtype=torch.int32, device=DEV)
+    x = torch.empty((6, 264), dtype=torch.float32, device=DEV)
+    ops.embed(tok, emb, x)
+    torch.cuda.synchronize()
+    assert torch.equal(x, emb[tok.long()].float())
+
+
+@pytest.mark.parametrize("d", [256, 4096, 5120, 8192])
+@pytest.mark.parametrize("nsplit", [0, 3])
+def test_add_rmsnorm(ops, d, nsplit):
+    M = 5
+    x = randn_f32((M, d), 10 + d, std=2.0)
+    part = randn_f32((max(nsplit, 1), M, d), 11 + d)
+    gain = (1.0 + 0.3 * randn_f32((d,), 12)).to(torch.bfloat16)
+    h = torch.empty((M, d), dtype=torch.bfloat16, device=DEV)
+    x0 = x.clone()
+    ops.add_rmsnorm(x, part, nsplit, M * d, gain, 1e-5, h)
+    torch.cuda.synchronize()
+    xs = np64(x0) + (np64(part[:nsplit]).sum(0) if nsplit else 0.0)
+    assert np.abs(np64(x) - xs).max() <= 1e-6 * (1 + np.abs(xs).max())
+    ref = orc.rmsnorm(xs, bits(gain), float(np.float32(1e-5)))
+    err = np.abs(np64(h) - ref)
+    assert (err <= 0.5 * BF16_EPS * np.abs(ref) * 1.01 + 1e-6).all()
+
+
+GEMM_CASES = [
+    # M, K, rows of up to three matrices, splits, kernel (1 skinny / 2 tiled)
+    (1, 256, (256,), 1, 1), (4, 688, (256,), 2, 1), (4, 256, (256, 256, 256), 1, 1), (33, 688, (1000, 72), 3, 1),
+    (128, 4096, (512, 128, 128), 4, 1), (200, 1024, (688,), 2, 1), (256, 512, (300,), 1, 1), (64, 256, (1024,), 1, 1),
+    (64, 688, (256,), 1, 2), (300, 256, (688, 256), 1, 2), (130, 1000, (1000,), 1, 2), (1024, 256, (16384,), 1, 2),
+    (1100, 136, (16400,), 1, 2),
+]
+
+
+@pytest.mark.parametrize("M,K,rows,splits,kernel", GEMM_CASES)
+def test_gemm_f32(ops, M, K, rows, splits, kernel):
+    step(f"gemm M={M} K={K} rows={rows} splits={splits} kernel={kernel}")
+    A = randn_bf16((M, K), 20 + M)
+    Ws = [randn_bf16((r, K), 30 + i + r, std=0.05) for i, r in enumerate(rows)]
+    N = sum(rows)
+    out = torch.full((splits, M, N), float("nan"), dtype=torch.float32, device=DEV)
+    ops.gemm(A, Ws, out, N, split_stride=M * N, splits=splits, epilogue=0, kernel=kernel)
+    torch.cuda.synchronize()
+    got = np64(out).sum(0)
+    ref = np.concatenate([orc.linear(bits(w), np64(A)) for w in Ws], axis=1)
+    tol = 2e-6 * np.sqrt(K) * (np.abs(ref).max() + 1.0)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= tol, (np.abs(got - ref).max(), tol)
+
+
+@pytest.mark.parametrize("M,kernel", [(4, 1), (128, 1), (70, 2), (600, 2)])
+def test_gemm_row_stride_and_accumulate(ops, M, kernel):
+    # A with a row stride (the LM head reads the last prompt position of every sequence) and the residual-add epilogue
+    K, N, T = 256, 264, 3
+    buf = randn_bf16((M * T, K), 40)
+    A = buf[T - 1::T]
+    assert A.stride(0) == T * K
+    W = randn_bf16((N, K), 41, std=0.05)
+    out = randn_f32((M, N), 42)
+    base = np64(out)
+    ops.gemm(A, [W], out, N, M=M, lda=T * K, epilogue=2, kernel=kernel)
+    torch.cuda.synchronize()
+    ref = base + orc.linear(bits(W), np64(A))
+    assert np.abs(np64(out) - ref).max() <= 1e-4
+
+
+@pytest.mark.parametrize("M,K,F,kernel", [(4, 256, 688, 1), (128, 512, 1000, 1), (256, 256, 72, 1), (100, 256, 688, 2),
+                                          (1024, 128, 8200, 2)])
+def test_gemm_swiglu(ops, M, K, F, kernel):
+    step(f"swiglu M={M} K={K} F={F} kernel={kernel}")
+    A = randn_bf16((M, K), 50)
+    Wg, Wu = randn_bf16((F, K), 51, std=0.1), randn_bf16((F, K), 52, std=0.1)
+    out = torch.zeros((M, F), dtype=torch.bfloat16, device=DEV)
+    ops.gemm(A, [Wg, Wu], out, F, epilogue=1, kernel=kernel)
+    torch.cuda.synchronize()
+    g, u = orc.linear(bits(Wg), np64(A)), orc.linear(bits(Wu), np64(A))
+    ref = g / (1.0 + np.exp(-g)) * u
+    err = np.abs(np64(out) - ref)
+    assert (err <= 0.5 * BF16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), err.max()
+
+
+@pytest.mark.parametrize("style", [0, 1])
+@pytest.mark.parametrize("hd,Hq,Hkv", [(64, 4, 4), (128, 8, 2)])
+def test_rope_append(ops, style, hd, Hq, Hkv):
+    S, nseq, nsplit = 40, 3, 2
+    tab = torch.empty((S, hd // 2, 2), dtype=torch.float32, device=DEV)
+    ops.build_rope_table(tab, S, hd, 10000.0)
+    ld = (Hq + 2 * Hkv) * hd
+    for (T, b0, pos0, nb) in [(7, 1, 0, 2), (1, 0, 23, 3)]:     # a prefill-like and a decode-like call
+        M = nb * T
+        qkv = randn_f32((nsplit, M, ld), 60 + T)
+        kc = torch.zeros((nseq, Hkv, S, hd), dtype=torch.bfloat16, device=DEV)
+        vc = torch.zeros_like(kc)
+        qf = torch.empty((M, Hq * hd), dtype=torch.float32, device=DEV)
+        qb = torch.empty((M, Hq * hd), dtype=torch.bfloat16, device=DEV)
+        d_pos = torch.tensor([pos0], dtype=torch.int32, device=DEV)
+        ops.rope_append(qkv, nsplit, M * ld, M, T, b0, d_pos, tab, style, Hq, Hkv, hd, S, qf, qb, kc, vc)
+        torch.cuda.synchronize()
+        tot = np64(qkv).sum(0)
+        kcn, vcn = np64(kc), np64(vc)
+        seen = np.zeros((nseq, S), bool)
+        for m in range(M):
+            b, pos = b0 + m // T, pos0 + m % T
+            seen[b, pos] = True
+            q = orc.rope(tot[m, : Hq * hd].reshape(Hq, hd), pos, 10000.0, style)
+            k = orc.rope(tot[m, Hq * hd: (Hq + Hkv) * hd].reshape(Hkv, hd), pos, 10000.0, style)
+            v = tot[m, (Hq + Hkv) * hd:].reshape(Hkv, hd)
+            assert np.abs(np64(qf[m]).reshape(Hq, hd) - q).max() <= 2e-6 * (1 + np.abs(q).max())
+            assert (np.abs(np64(qb[m]).reshape(Hq, hd) - q) <= 0.5 * BF16_EPS * np.abs(q) * 1.01 + 1e-6).all()
+            assert (np.abs(kcn[b, :, pos] - k) <= 0.5 * BF16_EPS * np.abs(k) * 1.01 + 1e-6).all()
+            assert (np.abs(vcn[b, :, pos] - v) <= 0.5 * BF16_EPS * np.abs(v) * 1.01 + 1e-6).all()
+        assert (kcn[~seen] == 0).all() and (vcn[~seen] == 0).all()      # nothing else was touched
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv", [(128, 8, 8), (128, 8, 2), (128, 16, 1), (64, 4, 4), (64, 6, 2), (128, 8, 1)])
+@pytest.mark.parametrize("length,nsplit", [(0, 1), (5, 1), (130, 1), (130, 3), (1000, 8), (2, 4)])
+def test_decode_attention(ops, hd, Hq, Hkv, length, nsplit):
+    step(f"decode attention hd={hd} Hq={Hq} Hkv={Hkv} len={length} nsplit={nsplit}")
+    B, S = 3, 1024
+    q = randn_f32((B, Hq * hd), 70, std=1.5)
+    kc = randn_bf16((B, Hkv, S, hd), 71)
+    vc = randn_bf16((B, Hkv, S, hd), 72)
+    # rows past the visible range must never be used: poison them
+    kc[:, :, length + 1:] = float("nan")
+    vc[:, :, length + 1:] = float("nan")
+    d_len = torch.tensor([length], dtype=torch.int32, device=DEV)
+    out = torch.zeros((B, Hq * hd), dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit)
+    torch.cuda.synchronize()
+    qn, kn, vn, on = np64(q).reshape(B, Hq, hd), np64(kc), np64(vc), np64(out).reshape(B, Hq, hd)
+    g = Hq // Hkv
+    for b in range(B):
+        for u in range(Hq):
+            ref = orc.attend(qn[b, u], kn[b, u // g, : length + 1], vn[b, u // g, : length + 1])
+            err = np.abs(on[b, u] - ref)
+            assert (err <= 0.5 * BF16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), (b, u, err.max())
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv", [(128, 4, 4), (128, 8, 2), (64, 4, 1)])
+@pytest.mark.parametrize("T", [1, 16, 100, 300])
+def test_prefill_attention(ops, hd, Hq, Hkv, T):
+    step(f"prefill attention hd={hd} Hq={Hq} Hkv={Hkv} T={T}")
+    nb, b0, S, nseq = 2, 1, 320, 3
+    q = randn_bf16((nb * T, Hq * hd), 80, std=1.5)
+    kc = randn_bf16((nseq, Hkv, S, hd), 81)
+    vc = randn_bf16((nseq, Hkv, S, hd), 82)
+    kc[:, :, T:] = float("nan")
+    vc[:, :, T:] = float("nan")
+    out = torch.zeros((nb * T, Hq * hd), dtype=torch.bfloat16, device=DEV)
+    ops.prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S)
+    torch.cuda.synchronize()
+    qn, kn, vn = np64(q).reshape(nb, T, Hq, hd), np64(kc), np64(vc)
+    on = np64(out).reshape(nb, T, Hq, hd)
+    g = Hq // Hkv
+    worst = 0.0
+    for b in range(nb):
+        for u in range(Hq):
+            for i in sorted(set([0, 1, T // 2, T - 1] + list(range(0, T, 7)))):
+                ref = orc.attend(qn[b, i, u], kn[b0 + b, u // g, : i + 1], vn[b0 + b, u // g, : i + 1])
+                err = np.abs(on[b, i, u] - ref)
+                worst = max(worst, err.max())
+                # probabilities are rounded to bf16 (2^-9 relative each) before the second product
+                bound = 0.5 * BF16_EPS * np.abs(ref) * 1.02 + 2.0 ** -9 * np.abs(vn[b0 + b, u // g, : i + 1]).max() + 1e-4
+                assert (err <= bound).all(), (b, u, i, err.max())
+    step(f"  worst abs error {worst:.2e}")
+
+
+@pytest.mark.parametrize("V", [1024, 32000, 128256])
+def test_argmax(ops, V):
+    B = 6
+    lg = randn_f32((B, V), 90)
+    lg[1, 17] = 50.0
+    lg[1, 4000 % V] = 50.0                     # tie: lowest index wins
+    lg[2, :] = -3.0                            # all equal
+    lg[3, V - 1] = 99.0
+    lg[4, 5] = float("nan")
+    lg[5, :] = -torch.abs(lg[5, :]) - 1.0      # all negative
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ops.argmax(lg, nxt)
+    torch.cuda.synchronize()
+    ln = np64(lg)
+    for b in range(B):
+        assert int(nxt[b]) == orc.argmax(ln[b]), b
+    assert int(nxt[1]) == min(17, 4000 % V) and int(nxt[2]) == 0 and int(nxt[3]) == V - 1 and int(nxt[4]) == -1

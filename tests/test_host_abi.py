@@ -1,0 +1,83 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and its host logic
+(shape validation, closed forms, argument errors) behaves as include/rl_gen.h states.  No GPU compute."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from workload import LLAMA3_TABLE_SHAPES, PRESETS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2406_14088_amd import binding as b
+    b.lib()
+    return b
+
+
+def declared_symbols():
+    names = set()
+    for hdr in ("rl_gen.h", "rl_gen_ops.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(rl_(?:gen|op)_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_every_declared_symbol_is_exported_and_bound(binding):
+    L = binding.lib()
+    decl = declared_symbols()
+    assert decl == set(binding.EXPORTED_SYMBOLS)
+    for name in decl:
+        assert getattr(L, name) is not None
+
+
+def test_param_count_matches_paper_table_and_presets(binding):
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "llama3_param_counts.txt"))
+            if l.strip() and not l.startswith("#")]
+    for name, *_cfg, total, _ in rows:
+        assert binding.param_count(LLAMA3_TABLE_SHAPES[name]) == int(total)
+    # benchmark shapes: counted tensor by tensor
+    for wl in PRESETS.values():
+        s = wl.shape
+        qd, kvd, d = s.n_heads * s.head_dim, s.n_kv_heads * s.head_dim, s.hidden
+        per_layer = qd * d + 2 * kvd * d + d * qd + 3 * d * s.ffn + 2 * d
+        assert binding.param_count(s) == 2 * s.vocab * d + s.n_layers * per_layer + d
+
+
+def test_kv_bytes_closed_form(binding):
+    s = PRESETS["llama7b"].shape
+    assert binding.kv_bytes(s, 1, 1) == 524288                      # 0.5 MiB per token and sequence in bf16
+    assert binding.kv_bytes(s, 128, 384) == 524288 * 128 * 384
+    assert binding.kv_bytes(PRESETS["llama70b"].shape, 64, 384) == 2 * 80 * 8 * 128 * 2 * 64 * 384
+    assert binding.work_bytes(s, 128, 384) > 0
+
+
+def test_shape_validation(binding):
+    from dataclasses import replace
+    s = PRESETS["tiny"].shape
+    assert binding.validate_shape(s, 4, 32) == 0
+    assert binding.validate_shape(replace(s, n_kv_heads=3), 4, 32) == -2      # heads not divisible
+    assert binding.validate_shape(replace(s, head_dim=32), 4, 32) == -2       # hidden != heads * head_dim
+    assert binding.validate_shape(replace(s, ffn=690), 4, 32) == -2           # ffn % 8
+    assert binding.validate_shape(replace(s, rope_style=2), 4, 32) == -2
+    assert binding.validate_shape(s, 0, 32) == -2
+    assert binding.kv_bytes(replace(s, n_kv_heads=3), 4, 32) == 0
+
+
+def test_null_arguments_are_rejected_without_a_gpu(binding):
+    L = binding.lib()
+    cs = binding.RlGenShape.from_model(PRESETS["tiny"].shape, 4, 32)
+    out = C.c_void_p()
+    assert L.rl_gen_create(C.byref(cs), None, None, 0, None, 0, C.byref(out)) == -1
+    assert L.rl_gen_prefill(None, None, 1, 1, None, None, None) == -1
+    assert L.rl_gen_decode_step(None, None, None, None, None) == -1
+    assert L.rl_gen_reset(None) == -1
+    L.rl_gen_destroy(None)
+    assert L.rl_op_argmax(None, 1, 1, None, None) == -1
+    assert L.rl_op_gemm(None, 8, None, None, None, 1, 0, 0, 1, 8, None, 1, 0, 1, 0, 0, None) == -1
+    assert L.rl_gen_kernel_class_name(4) == b"decode_attention"
+    assert len(binding.KERNEL_CLASSES) == 13
