@@ -3,7 +3,7 @@ import numpy as np
 import torch
 
 DEV = "cuda:0"
-BF16_EPS = 2.0 ** -8      # one bf16 ulp relative to the value (half of it is the rounding error bound)
+BF16_EPS = 2.0 ** -7      # bf16 spacing relative to the value (8 significant bits); rounding error <= half of it
 
 
 def randn_bf16(shape, seed, std=1.0, device=DEV):

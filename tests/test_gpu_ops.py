@@ -3,8 +3,8 @@ sub-functions on the same seeded inputs.  Sizes span several tiles and ragged ta
 
 Tolerances (derived from the arithmetic): inputs are bf16-valued and identical on both sides; the
 kernels accumulate in fp32 (relative error ~1e-6 per term, growing like sqrt(K)), and outputs stored
-as bf16 carry one rounding (relative 2^-9).  Attention additionally uses a fast exponential
-(relative ~2e-6) and, in prefill, probabilities rounded to bf16 for the matrix cores (relative 2^-9
+as bf16 carry one rounding (relative 2^-8).  Attention additionally uses a fast exponential
+(relative ~2e-6) and, in prefill, probabilities rounded to bf16 for the matrix cores (relative 2^-8
 per term of a convex combination).
 """
 import numpy as np
@@ -136,7 +136,8 @@ def test_rope_append(ops, style, hd, Hq, Hkv):
             assert (np.abs(np64(qb[m]).reshape(Hq, hd) - q) <= 0.5 * BF16_EPS * np.abs(q) * 1.01 + 1e-6).all()
             assert (np.abs(kcn[b, :, pos] - k) <= 0.5 * BF16_EPS * np.abs(k) * 1.01 + 1e-6).all()
             assert (np.abs(vcn[b, :, pos] - v) <= 0.5 * BF16_EPS * np.abs(v) * 1.01 + 1e-6).all()
-        assert (kcn[~seen] == 0).all() and (vcn[~seen] == 0).all()      # nothing else was touched
+        untouched = ~seen[:, None, :, None]                              # nothing else was touched
+        assert (np.where(untouched, kcn, 0) == 0).all() and (np.where(untouched, vcn, 0) == 0).all()
 
 
 @pytest.mark.parametrize("hd,Hq,Hkv", [(128, 8, 8), (128, 8, 2), (128, 16, 1), (64, 4, 4), (64, 6, 2), (128, 8, 1)])
@@ -183,12 +184,12 @@ def test_prefill_attention(ops, hd, Hq, Hkv, T):
     worst = 0.0
     for b in range(nb):
         for u in range(Hq):
-            for i in sorted(set([0, 1, T // 2, T - 1] + list(range(0, T, 7)))):
+            for i in sorted(set(min(i, T - 1) for i in [0, 1, T // 2, T - 1] + list(range(0, T, 7)))):
                 ref = orc.attend(qn[b, i, u], kn[b0 + b, u // g, : i + 1], vn[b0 + b, u // g, : i + 1])
                 err = np.abs(on[b, i, u] - ref)
                 worst = max(worst, err.max())
-                # probabilities are rounded to bf16 (2^-9 relative each) before the second product
-                bound = 0.5 * BF16_EPS * np.abs(ref) * 1.02 + 2.0 ** -9 * np.abs(vn[b0 + b, u // g, : i + 1]).max() + 1e-4
+                # probabilities are rounded to bf16 (2^-8 relative each) before the second product
+                bound = 0.5 * BF16_EPS * np.abs(ref) * 1.02 + 2.0 ** -8 * np.abs(vn[b0 + b, u // g, : i + 1]).max() + 1e-4
                 assert (err <= bound).all(), (b, u, i, err.max())
     step(f"  worst abs error {worst:.2e}")
 
