@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the generation hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input: prefill of B prompts
+of P tokens plus G-1 decode steps (B*G generated tokens), free-running greedy generation with on-device
+token feedback.  Prints ONE JSON line; see the design doc for the definition of every field.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--no-cpu-baseline] [--no-roofline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense 16-bit matrix cores (bf16 and fp16), published
+
+
+def decode_bytes(shape, B, t):
+    """Algorithmic HBM bytes of one decode step at position t (the new token attends to t+1 cache rows):
+    every weight once, the KV cache rows read, the appended K/V rows, the fp32 logits, the embedding rows."""
+    d, hd, Hq, Hkv, F, V, L = shape.hidden, shape.head_dim, shape.n_heads, shape.n_kv_heads, shape.ffn, shape.vocab, shape.n_layers
+    w = 2 * (L * ((Hq + 2 * Hkv) * hd * d + Hq * hd * d + 3 * d * F + 2 * d) + d + V * d)
+    kv_row = 2 * L * Hkv * hd * 2
+    return w + B * (t + 1) * kv_row + B * kv_row + B * V * 4 + B * d * 2
+
+
+def attention_bytes(shape, B, t):
+    """Algorithmic bytes of ONE decode-attention launch (one layer) at position t: K and V rows 0..t of every
+    (sequence, kv head), the fp32 queries and the 16-bit outputs."""
+    hd, Hq, Hkv = shape.head_dim, shape.n_heads, shape.n_kv_heads
+    return B * (t + 1) * 2 * Hkv * hd * 2 + B * Hq * hd * (4 + 2)
+
+
+def prefill_flops(shape, B, P):
+    d, hd, Hq, Hkv, F, V, L = shape.hidden, shape.head_dim, shape.n_heads, shape.n_kv_heads, shape.ffn, shape.vocab, shape.n_layers
+    return 2 * B * P * L * ((Hq + 2 * Hkv) * hd * d + Hq * hd * d + 3 * d * F) + 2 * B * V * d + 4 * L * B * Hq * hd * P * (P + 1) // 2
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--layers", type=int, default=0, help="debug: truncate the model depth (the result is then not the benchmark)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the data-parallel hot path of one GPU's share); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_14088_amd import Generator
+    from workload import PRESETS, make_prompts, make_weights
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    wl = PRESETS[args.workload]
+    shape = wl.shape.with_layers(args.layers) if args.layers else wl.shape
+    B, P, G = wl.batch, wl.prompt_len, wl.gen_len
+
+    t0 = time.perf_counter()
+    W = make_weights(shape, wl.index, device=dev)
+    prompts = make_prompts(wl, device=dev)
+    gen = Generator(shape, W, B, P + G)
+    gen.set_graph(not args.no_graph)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t0
+
+    buf = [torch.empty((B,), dtype=torch.int32, device=dev) for _ in range(2)]
+
+    def generate(timing=None):
+        """prefill + (G-1) decode steps; tokens stay on the device"""
+        if timing is not None:
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+        gen.prefill(prompts, next_tokens=buf[0])
+        if timing is not None:
+            torch.cuda.synchronize()
+            tb = time.perf_counter()
+        cur = 0
+        for _ in range(G - 1):
+            gen.decode_step(buf[cur], next_tokens=buf[1 - cur], want_logits=False)
+            cur = 1 - cur
+        if timing is not None:
+            torch.cuda.synchronize()
+            tc = time.perf_counter()
+            timing["prefill_s"] = timing.get("prefill_s", 0.0) + tb - ta
+            timing["decode_s"] = timing.get("decode_s", 0.0) + tc - tb
+        return buf[cur]
+
+    for _ in range(args.warmup):
+        generate()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        last = generate()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    tokens = B * G * args.steps
+    value = tokens / elapsed
+    last_tokens = last.clone()
+
+    # split of one generation into prefill and decode (separate, synchronised pass; not part of `value`)
+    split = {}
+    generate(split)
+    dec_bytes = sum(decode_bytes(shape, B, t) for t in range(P, P + G - 1))
+    pf = prefill_flops(shape, B, P)
+    phases = {
+        "prefill_ms": split["prefill_s"] * 1e3,
+        "prefill_tflops": pf / split["prefill_s"] / 1e12,
+        "prefill_frac_of_mfma_peak": pf / split["prefill_s"] / 1e12 / MFMA_PEAK_TFLOPS,
+        "decode_ms_per_step": split["decode_s"] * 1e3 / max(G - 1, 1),
+        "decode_algorithmic_GBs": dec_bytes / split["decode_s"] / 1e9,
+        "decode_frac_of_hbm_peak": dec_bytes / split["decode_s"] / 1e9 / HBM_PEAK_GBS,
+        "decode_tokens_per_s": B * (G - 1) / split["decode_s"],
+    }
+
+    out = {
+        "metric": "generated tokens/sec on 1 GPU (prefill + decode, greedy, LLaMA-7B shape)" if args.workload == "llama7b"
+        else f"generated tokens/sec on 1 GPU ({args.workload})",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: L{shape.n_layers} d{shape.hidden} H{shape.n_heads}/{shape.n_kv_heads} F{shape.ffn} "
+                               f"V{shape.vocab}, batch {B}, prompt {P}, generate {G}",
+                   "global_batch": B, "prompt_len": P, "gen_len": G, "hip_graph": not args.no_graph},
+        "phases": phases, "setup_s": setup_s,
+    }
+
+    if not args.no_roofline:
+        # per-kernel durations, measured with HIP events on the launch stream during one more generation
+        gen.profile(True)
+        gen.profile_read()
+        generate()
+        prof = gen.profile_read()
+        gen.profile(False)
+        att = prof["decode_attention"]
+        att_bytes = sum(attention_bytes(shape, B, t) for t in range(P, P + G - 1)) * shape.n_layers
+        if att["launches"] > 0 and att["ms"] > 0:
+            achieved = att_bytes / (att["ms"] * 1e-3) / 1e9
+            out["roofline"] = {"kernel": "decode_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                               "launches": att["launches"], "avg_launch_us": att["ms"] * 1e3 / att["launches"],
+                               "bytes_per_launch_mean": att_bytes / att["launches"]}
+        out["kernels"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 3)} for k, v in prof.items() if v["launches"]}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, wl, W)
+
+    out["checksum_last_tokens"] = int(last_tokens.to(torch.int64).sum().item())
+    gen.close()
+    print(json.dumps(out))
+
+
+def cpu_baseline(shape, wl, W):
+    """The CPU oracle as it stands, timed on this machine's host cores on a bounded sample of the same model shape."""
+    import numpy as np
+    from oracle import orc
+    from workload import make_prompts
+    Bs, Ps, Gs = 2, 16, 3
+    Wn = orc.weights_to_numpy(W)            # device -> host copy of the same bf16 values
+    om = orc.OracleModel(shape, Wn, Bs, Ps + Gs)
+    prompts = make_prompts(wl, batch=Bs, prompt_len=Ps).numpy()
+    t0 = time.perf_counter()
+    _, nxt = om.prefill(prompts)
+    for _ in range(Gs - 1):
+        _, nxt = om.decode_step(nxt)
+    dt = time.perf_counter() - t0
+    om.close()
+    return {"value": Bs * Gs / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"same model and weights, batch {Bs}, prompt {Ps}, generate {Gs} tokens (fp64 CPU oracle, {dt:.1f} s)"}
+
+
+if __name__ == "__main__":
+    main()

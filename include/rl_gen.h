@@ -19,6 +19,10 @@
  *     that point.  One handle must not be used from two streams or two host threads at once.
  *   - Return value: RL_GEN_OK (0) or a negative rl_gen_status.  A failed call leaves the sequence
  *     state (batch, length) unchanged.  No exception crosses this boundary.
+ *   - Number formats: weights are bf16 (as given) and are widened to IEEE half inside the kernels;
+ *     activations that feed a projection and the KV cache are IEEE half (same size as bf16, 11
+ *     instead of 8 significant bits); the residual stream, normalisation statistics, softmax,
+ *     accumulators and logits are fp32.
  *   - Matrices are row-major [out_features, in_features]; token ids are int32 in [0, vocab) --
  *     ids outside that range are clamped on the device (no fault), the result is then unspecified.
  */
@@ -80,7 +84,7 @@ int rl_gen_validate_shape(const rl_gen_shape *shape);  /* RL_GEN_OK or RL_GEN_E_
 /* Creates a handle.  kv_arena / work_arena: DEVICE, 256-byte aligned, at least rl_gen_kv_bytes /
  * rl_gen_work_bytes long (else RL_GEN_E_CAPACITY), contents need not be initialised.  The host
  * arrays inside `weights` are copied; the device tensors they point to are borrowed.
- * KV layout inside the arena: [layer][K|V][sequence][kv_head][position][head_dim] bf16. */
+ * KV layout inside the arena: [layer][K|V][sequence][kv_head][position][head_dim], IEEE half. */
 int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void *kv_arena, size_t kv_bytes,
                   void *work_arena, size_t work_bytes, rl_gen_t **out);
 

@@ -5,7 +5,9 @@
  * "Generation" function call -- Section 2.1 -- runs for every prompt / generated token) on the
  * given stream, so that every kernel can be checked against the CPU oracle in isolation and be
  * timed on its own.  All pointers are DEVICE pointers borrowed for the duration of the enqueued
- * work; bf16 tensors are passed as uint16_t bit patterns; `hip_stream` is a hipStream_t (NULL =
+ * work; 16-bit tensors are passed as uint16_t bit patterns -- weights (emb, gain, W_i) are bf16,
+ * activations and cache slabs (h, A, q_f16, kc, vc, attention outputs) are IEEE half, called "f16"
+ * below; `hip_stream` is a hipStream_t (NULL =
  * default stream).  Return: 0, or a negative rl_gen_status (rl_gen.h); nothing is enqueued on error.
  */
 #ifndef RL_GEN_OPS_H
@@ -25,17 +27,18 @@ int rl_op_embed(const int32_t *tokens, const uint16_t *emb, float *x, int32_t M,
 
 /* Residual add + RMSNorm: x[m,:] += sum_{s<nsplit} part[s*part_stride + m*d + :] (x is updated in
  * place when nsplit > 0; part may be NULL when nsplit == 0), then
- * h[m,:] = bf16(gain * x / sqrt(mean(x^2) + eps)).  x fp32 [M, d], gain bf16 [d], h bf16 [M, d];
+ * h[m,:] = f16(gain * x / sqrt(mean(x^2) + eps)).  x fp32 [M, d], gain bf16 [d], h f16 [M, d];
  * d % 4 == 0 and d <= 8192. */
 int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_stride, const uint16_t *gain, float eps,
                       uint16_t *h, int32_t M, int32_t d, void *hip_stream);
 
 /* Projection: out[m, off_i + n] = sum_k A[m,k] * W_i[n,k] for up to three bf16 matrices W_i
  * [rows_i, K] placed side by side along the output columns (unused: NULL / 0 rows).
- * A bf16 [M, K] with row stride lda; K % 8 == 0, lda % 8 == 0.
+ * A f16 [M, K] with row stride lda; K % 8 == 0, lda % 8 == 0.  Weights are widened bf16 -> f16 in the
+ * kernel (exact for |w| >= 2^-14) and multiplied on the f16 matrix cores with fp32 accumulation.
  * epilogue 0: fp32 out, row stride ldc; split s (0 <= s < splits) writes its partial sum at
  *             out + s*split_stride (the consumer adds the partials);
- * epilogue 1: SwiGLU, W_0 = gate, W_1 = up (equal shapes): out bf16 [m*ldc + n] = silu(gate)*up;
+ * epilogue 1: SwiGLU, W_0 = gate, W_1 = up (equal shapes): out f16 [m*ldc + n] = silu(gate)*up;
  * epilogue 2: fp32 out[m*ldc + col] += result (residual add).
  * splits applies to the skinny kernel with epilogue 0 only.  kernel: 0 = choose by M, 1 = skinny
  * (weights streamed once through registers; M <= 256), 2 = tiled (both operands through LDS). */
@@ -49,14 +52,14 @@ int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float 
 
 /* Rotary embedding + KV-cache append.  qkv fp32: nsplit partials, each [M, (Hq+2Hkv)*hd] laid out
  * q | k | v per row, split_stride elements apart.  Row m is sequence b0 + m / T at position
- * d_pos0[0] + m % T (d_pos0: DEVICE int32).  Writes q_f32 and/or q_bf16 ([M, Hq*hd], either may
- * be NULL) and the cache rows of kc / vc (bf16 [n_seq][Hkv][S][hd]).  Positions >= S are skipped. */
+ * d_pos0[0] + m % T (d_pos0: DEVICE int32).  Writes q_f32 and/or q_f16 ([M, Hq*hd], either may
+ * be NULL) and the cache rows of kc / vc (f16 [n_seq][Hkv][S][hd]).  Positions >= S are skipped. */
 int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
                       const int32_t *d_pos0, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv,
-                      int32_t hd, int32_t S, float *q_f32, uint16_t *q_bf16, uint16_t *kc, uint16_t *vc, void *hip_stream);
+                      int32_t hd, int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *hip_stream);
 
 /* Decode attention: for each sequence b < B and query head u, softmax(q_u . k_j / sqrt(hd)) v_j over
- * cache rows j = 0 .. d_len[0] of kv head u / (Hq/Hkv).  q fp32 [B, Hq*hd]; out bf16 [B, Hq*hd].
+ * cache rows j = 0 .. d_len[0] of kv head u / (Hq/Hkv).  q fp32 [B, Hq*hd]; kc, vc f16; out f16 [B, Hq*hd].
  * nsplit >= 1 splits the rows over wavefronts; ws must then hold rl_op_decode_attention_ws_floats
  * floats (may be NULL for nsplit == 1).  hd in {64, 128}. */
 int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, uint16_t *out,
@@ -65,7 +68,7 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
 /* Prefill attention: causal attention of positions 0..T-1 of nb sequences; sequence i reads cache
- * sequence b0 + i.  q bf16 [nb*T, Hq*hd] (rotated), out bf16 [nb*T, Hq*hd].  hd in {64, 128}. */
+ * sequence b0 + i.  q f16 [nb*T, Hq*hd] (rotated), kc, vc f16, out f16 [nb*T, Hq*hd].  hd in {64, 128}. */
 int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_t *vc, uint16_t *out, int32_t nb,
                             int32_t b0, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, void *hip_stream);
 

@@ -14,7 +14,7 @@
 //     wavefront, so K and V are read once for all of them;
 //   * optional split over the sequence axis (more wavefronts for long contexts / small batches):
 //     splits write (max, sum, unnormalised output) partials that a small merge kernel combines.
-// All arithmetic is fp32; only the cache elements and the output are bf16.
+// All arithmetic is fp32; only the cache elements and the output are half.
 #include "kernels.h"
 
 #define DA_THREADS 256
@@ -36,8 +36,8 @@ __device__ __forceinline__ float group_sum(float v) {
 
 template <int HD, int GT>
 __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
-    const float *__restrict__ q, const bf16_t *__restrict__ kc, const bf16_t *__restrict__ vc,
-    const int32_t *__restrict__ d_len, bf16_t *__restrict__ out, float *__restrict__ ws, int n_items, int Hq, int Hkv,
+    const float *__restrict__ q, const f16_t *__restrict__ kc, const f16_t *__restrict__ vc,
+    const int32_t *__restrict__ d_len, f16_t *__restrict__ out, float *__restrict__ ws, int n_items, int Hq, int Hkv,
     int S, int nsplit) {
     constexpr int LPR = HD / 8;     // lanes per cache row
     constexpr int RPW = 64 / LPR;   // rows per wavefront load instruction
@@ -68,8 +68,8 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
         qr[gh][4] = bb.x; qr[gh][5] = bb.y; qr[gh][6] = bb.z; qr[gh][7] = bb.w;
     }
     const float scale = rsqrtf((float)HD);
-    const bf16_t *kb = kc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
-    const bf16_t *vb = vc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
+    const f16_t *kb = kc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
+    const f16_t *vb = vc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
 
     float mx[GT], den[GT], acc[GT][8];
 #pragma unroll
@@ -93,10 +93,10 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
         float kf[DA_U][8];
 #pragma unroll
         for (int u = 0; u < DA_U; ++u) {
-            kf[u][0] = bf16lo_to_f32(kr[u].x); kf[u][1] = bf16hi_to_f32(kr[u].x);
-            kf[u][2] = bf16lo_to_f32(kr[u].y); kf[u][3] = bf16hi_to_f32(kr[u].y);
-            kf[u][4] = bf16lo_to_f32(kr[u].z); kf[u][5] = bf16hi_to_f32(kr[u].z);
-            kf[u][6] = bf16lo_to_f32(kr[u].w); kf[u][7] = bf16hi_to_f32(kr[u].w);
+            kf[u][0] = f16lo_to_f32(kr[u].x); kf[u][1] = f16hi_to_f32(kr[u].x);
+            kf[u][2] = f16lo_to_f32(kr[u].y); kf[u][3] = f16hi_to_f32(kr[u].y);
+            kf[u][4] = f16lo_to_f32(kr[u].z); kf[u][5] = f16hi_to_f32(kr[u].z);
+            kf[u][6] = f16lo_to_f32(kr[u].w); kf[u][7] = f16hi_to_f32(kr[u].w);
         }
         float sc[GT][DA_U];
 #pragma unroll
@@ -112,10 +112,10 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
         float vf[DA_U][8];
 #pragma unroll
         for (int u = 0; u < DA_U; ++u) {
-            vf[u][0] = bf16lo_to_f32(vr[u].x); vf[u][1] = bf16hi_to_f32(vr[u].x);
-            vf[u][2] = bf16lo_to_f32(vr[u].y); vf[u][3] = bf16hi_to_f32(vr[u].y);
-            vf[u][4] = bf16lo_to_f32(vr[u].z); vf[u][5] = bf16hi_to_f32(vr[u].z);
-            vf[u][6] = bf16lo_to_f32(vr[u].w); vf[u][7] = bf16hi_to_f32(vr[u].w);
+            vf[u][0] = f16lo_to_f32(vr[u].x); vf[u][1] = f16hi_to_f32(vr[u].x);
+            vf[u][2] = f16lo_to_f32(vr[u].y); vf[u][3] = f16hi_to_f32(vr[u].y);
+            vf[u][4] = f16lo_to_f32(vr[u].z); vf[u][5] = f16hi_to_f32(vr[u].z);
+            vf[u][6] = f16lo_to_f32(vr[u].w); vf[u][7] = f16hi_to_f32(vr[u].w);
         }
 #pragma unroll
         for (int gh = 0; gh < GT; ++gh) {
@@ -160,10 +160,10 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
             if (nsplit == 1) {
                 float inv = 1.0f / l;
                 u32x4_t o4;
-                o4.x = pack_bf16x2(acc[gh][0] * inv, acc[gh][1] * inv);
-                o4.y = pack_bf16x2(acc[gh][2] * inv, acc[gh][3] * inv);
-                o4.z = pack_bf16x2(acc[gh][4] * inv, acc[gh][5] * inv);
-                o4.w = pack_bf16x2(acc[gh][6] * inv, acc[gh][7] * inv);
+                o4.x = pack_f16x2(acc[gh][0] * inv, acc[gh][1] * inv);
+                o4.y = pack_f16x2(acc[gh][2] * inv, acc[gh][3] * inv);
+                o4.z = pack_f16x2(acc[gh][4] * inv, acc[gh][5] * inv);
+                o4.w = pack_f16x2(acc[gh][6] * inv, acc[gh][7] * inv);
                 *reinterpret_cast<u32x4_t *>(out + ((size_t)b * Hq + head) * HD + c * 8) = o4;
             } else {
                 float *p = ws + (((size_t)b * Hq + head) * nsplit + split) * (HD + 2);
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
 }
 
 // Combines the split partials: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M)
-__global__ __launch_bounds__(128) void decode_attention_merge_kernel(const float *__restrict__ ws, bf16_t *__restrict__ out,
+__global__ __launch_bounds__(128) void decode_attention_merge_kernel(const float *__restrict__ ws, f16_t *__restrict__ out,
                                                                      int hd, int nsplit) {
     int bh = blockIdx.x, e = threadIdx.x;
     if (e >= hd) return;
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(128) void decode_attention_merge_kernel(const float
         L += p[s * (hd + 2) + 1] * wgt;
         o += p[s * (hd + 2) + 2 + e] * wgt;
     }
-    out[(size_t)bh * hd + e] = f32_to_bf16(o / L);
+    out[(size_t)bh * hd + e] = f32_to_f16(o / L);
 }
 
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit) {
@@ -209,7 +209,7 @@ int decode_attention_default_splits(int B, int Hkv, int S) {
 }
 
 template <int HD, int GT>
-static void launch_da(const float *q, const bf16_t *kc, const bf16_t *vc, const int32_t *d_len, bf16_t *out, float *ws, int B,
+static void launch_da(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B,
                       int Hq, int Hkv, int S, int nsplit, hipStream_t st) {
     int g = Hq / Hkv;
     int n_items = B * Hkv * (g / GT) * nsplit;
@@ -217,7 +217,7 @@ static void launch_da(const float *q, const bf16_t *kc, const bf16_t *vc, const 
     decode_attention_kernel<HD, GT><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S, nsplit);
 }
 
-void launch_decode_attention(const float *q, const bf16_t *kc, const bf16_t *vc, const int32_t *d_len, bf16_t *out,
+void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st) {
     if (B <= 0) return;
     int g = Hq / Hkv;
@@ -230,6 +230,6 @@ void launch_decode_attention(const float *q, const bf16_t *kc, const bf16_t *vc,
     if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, hd, nsplit, st);
 }
 
-void launch_decode_attention_merge(const float *ws, bf16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {
+void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {
     decode_attention_merge_kernel<<<B * Hq, 128, 0, st>>>(ws, out, hd, nsplit);
 }

@@ -1,7 +1,7 @@
 // Prefill attention: causal attention of all prompt positions of a sequence against the K/V rows that
-// the same prefill pass has just written into the cache (tiled, online softmax, bf16 MFMA).
+// the same prefill pass has just written into the cache (tiled, online softmax, f16 MFMA).
 //
-// Layout of the computation for gfx950 (wavefront = 64 lanes, v_mfma_f32_32x32x16_bf16):
+// Layout of the computation for gfx950 (wavefront = 64 lanes, v_mfma_f32_32x32x16_f16):
 //   * workgroup = 4 wavefronts = 128 consecutive query positions of one (sequence, query head);
 //     wavefront w owns 32 of them and keeps its Q fragments in registers for the whole kernel;
 //   * key tiles of 32 positions are staged once per workgroup in LDS (K and V, padded rows);
@@ -10,7 +10,7 @@
 //     joins the two half-wavefronts), and the probabilities already sit in the register layout of the
 //     B operand of the second product O^T += V^T P^T -- no shuffle or LDS round trip for P;
 //   * V^T fragments are gathered from the LDS tile with 16-bit reads (the transpose happens there).
-// Softmax and accumulation are fp32; probabilities are rounded to bf16 for the matrix cores.
+// Softmax and accumulation are fp32; probabilities are rounded to half for the matrix cores.
 #include "kernels.h"
 
 #define PA_THREADS 256
@@ -18,16 +18,16 @@
 #define PA_STRIDE(HD) ((HD) + 8)
 
 template <int HD>
-__global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const bf16_t *__restrict__ q,
-                                                                      const bf16_t *__restrict__ kc,
-                                                                      const bf16_t *__restrict__ vc,
-                                                                      bf16_t *__restrict__ out, int b0, int T, int Hq,
+__global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const f16_t *__restrict__ q,
+                                                                      const f16_t *__restrict__ kc,
+                                                                      const f16_t *__restrict__ vc,
+                                                                      f16_t *__restrict__ out, int b0, int T, int Hq,
                                                                       int Hkv, int S) {
     constexpr int KS = HD / 16;   // k16 steps of the QK product
     constexpr int ET = HD / 32;   // 32-row tiles of O^T
     constexpr int STR = PA_STRIDE(HD);
-    __shared__ __attribute__((aligned(16))) bf16_t ks[PA_KT * STR];
-    __shared__ __attribute__((aligned(16))) bf16_t vs[PA_KT * STR];
+    __shared__ __attribute__((aligned(16))) f16_t ks[PA_KT * STR];
+    __shared__ __attribute__((aligned(16))) f16_t vs[PA_KT * STR];
     const int t = threadIdx.x, lane = t & 63, w = t >> 6, half = lane >> 5, l32 = lane & 31;
     const int qt = blockIdx.x;          // query tile (128 positions)
     const int u = blockIdx.y;           // query head
@@ -38,15 +38,15 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const bf1
     const size_t ldq = (size_t)Hq * HD;
 
     // Q fragments (B operand of S^T = K Q^T): lane = (query column l32, hd slice half*8 + 16*s)
-    bf16x8_t qf[KS];
+    f16x8_t qf[KS];
     {
         int qrow = qpos < T ? qpos : T - 1;
-        const bf16_t *qp = q + ((size_t)bl * T + qrow) * ldq + (size_t)u * HD + half * 8;
+        const f16_t *qp = q + ((size_t)bl * T + qrow) * ldq + (size_t)u * HD + half * 8;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const bf16x8_t *>(qp + s * 16);
+        for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const f16x8_t *>(qp + s * 16);
     }
-    const bf16_t *kbase = kc + ((size_t)(b0 + bl) * Hkv + kvh) * S * HD;
-    const bf16_t *vbase = vc + ((size_t)(b0 + bl) * Hkv + kvh) * S * HD;
+    const f16_t *kbase = kc + ((size_t)(b0 + bl) * Hkv + kvh) * S * HD;
+    const f16_t *vbase = vc + ((size_t)(b0 + bl) * Hkv + kvh) * S * HD;
 
     f32x16_t oacc[ET];
 #pragma unroll
@@ -82,8 +82,8 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const bf1
         for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(ks + l32 * STR + half * 8 + s * 16);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc, 0, 0, 0);
+            f16x8_t kf = *reinterpret_cast<const f16x8_t *>(ks + l32 * STR + half * 8 + s * 16);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[s], sacc, 0, 0, 0);
         }
         // register i holds key row (i/4)*8 + half*4 + (i%4) of the tile, query column l32
         float tmax = -INFINITY;
@@ -103,12 +103,12 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const bf1
         for (int e = 0; e < ET; ++e)
 #pragma unroll
             for (int i = 0; i < 16; ++i) oacc[e][i] *= alpha;
-        bf16x8_t pf[2];
+        f16x8_t pf[2];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             float p = __expf(sacc[i] - mnew);
             lrun += p;
-            pf[i >> 3][i & 7] = (__bf16)p;
+            pf[i >> 3][i & 7] = (_Float16)p;
         }
         // O^T += V^T P^T.  Slot j of k-step s in lane-half h stands for key (2s + j/4)*8 + h*4 + j%4 -- the
         // key that accumulator register s*8 + j already holds, so P needs no data movement.
@@ -116,13 +116,13 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const bf1
         for (int s = 0; s < 2; ++s) {
 #pragma unroll
             for (int e = 0; e < ET; ++e) {
-                bf16x8_t vf;
+                f16x8_t vf;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     int krow = (2 * s + (j >> 2)) * 8 + half * 4 + (j & 3);
-                    vf[j] = __builtin_bit_cast(__bf16, vs[krow * STR + e * 32 + l32]);
+                    vf[j] = __builtin_bit_cast(_Float16, vs[krow * STR + e * 32 + l32]);
                 }
-                oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s], oacc[e], 0, 0, 0);
+                oacc[e] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[s], oacc[e], 0, 0, 0);
             }
         }
     }
@@ -131,20 +131,20 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const bf1
     float ltot = lrun + __shfl_xor(lrun, 32, 64);
     if (qpos < T) {
         float inv = 1.0f / ltot;
-        bf16_t *op = out + ((size_t)bl * T + qpos) * ldq + (size_t)u * HD;
+        f16_t *op = out + ((size_t)bl * T + qpos) * ldq + (size_t)u * HD;
 #pragma unroll
         for (int e = 0; e < ET; ++e)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
                 u32x2_t o2;
-                o2.x = pack_bf16x2(oacc[e][i4 * 4 + 0] * inv, oacc[e][i4 * 4 + 1] * inv);
-                o2.y = pack_bf16x2(oacc[e][i4 * 4 + 2] * inv, oacc[e][i4 * 4 + 3] * inv);
+                o2.x = pack_f16x2(oacc[e][i4 * 4 + 0] * inv, oacc[e][i4 * 4 + 1] * inv);
+                o2.y = pack_f16x2(oacc[e][i4 * 4 + 2] * inv, oacc[e][i4 * 4 + 3] * inv);
                 *reinterpret_cast<u32x2_t *>(op + e * 32 + i4 * 8 + half * 4) = o2;
             }
     }
 }
 
-void launch_prefill_attention(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, bf16_t *out, int nb, int b0, int T,
+void launch_prefill_attention(const f16_t *q, const f16_t *kc, const f16_t *vc, f16_t *out, int nb, int b0, int T,
                               int Hq, int Hkv, int hd, int S, hipStream_t st) {
     if (nb <= 0 || T <= 0) return;
     dim3 grid(ceil_div(T, 128), Hq, nb);

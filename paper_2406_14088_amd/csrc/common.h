@@ -3,13 +3,15 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-typedef uint16_t bf16_t;  // storage type of a bf16 value (bit pattern)
+typedef uint16_t bf16_t;  // storage type of a bf16 value (bit pattern): weights
+typedef uint16_t f16_t;   // storage type of an IEEE half value (bit pattern): activations and KV cache
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 #define RL_WAVE 64
 
@@ -27,6 +29,29 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 }
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Activations and the KV cache are IEEE half: 11 significant bits instead of bf16's 8, at the same
+// size.  fp32 -> half rounds to nearest even and saturates at the largest finite half.
+__device__ __forceinline__ f16_t f32_to_f16(float f) {
+    _Float16 h = (_Float16)__builtin_amdgcn_fmed3f(f, -65504.f, 65504.f);
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    f16x2_t v = {(_Float16)__builtin_amdgcn_fmed3f(lo, -65504.f, 65504.f), (_Float16)__builtin_amdgcn_fmed3f(hi, -65504.f, 65504.f)};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float f16_to_f32(f16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ __forceinline__ float f16lo_to_f32(uint32_t pair) { return (float)__builtin_bit_cast(f16x2_t, pair).x; }
+__device__ __forceinline__ float f16hi_to_f32(uint32_t pair) { return (float)__builtin_bit_cast(f16x2_t, pair).y; }
+// Two bf16 weights -> two halves.  Exact for every bf16 value whose magnitude is a normal half
+// (2^-14 <= |w| <= 65504); smaller weights land on the half subnormal grid (absolute error < 2^-24).
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16lo_to_f32(w), bf16hi_to_f32(w)));
+}
+__device__ __forceinline__ u32x4_t bf16x8_to_f16x8(u32x4_t w) {
+    u32x4_t r = {bf16x2_to_f16x2(w.x), bf16x2_to_f16x2(w.y), bf16x2_to_f16x2(w.z), bf16x2_to_f16x2(w.w)};
+    return r;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -28,14 +28,14 @@ void launch_embed(const int32_t *tokens, const bf16_t *emb, float *x, int M, int
 
 // ------------------------------------------------------------------------------------------------
 // Residual add of split-K partial sums, then RMSNorm: y = g * x / sqrt(mean(x^2) + eps).
-// The residual stream stays fp32; only the normalised copy that feeds the next projection is bf16.
+// The residual stream stays fp32; only the normalised copy that feeds the next projection is half.
 // One workgroup per row; each thread keeps its slice of the row in registers (hidden <= 8192).
 #define RN_THREADS 256
 #define RN_MAXV 8
 __global__ __launch_bounds__(RN_THREADS) void add_rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part,
                                                                  int nsplit, size_t part_stride,
                                                                  const bf16_t *__restrict__ gain, float eps,
-                                                                 bf16_t *__restrict__ h, int d) {
+                                                                 f16_t *__restrict__ h, int d) {
     __shared__ float red[RN_THREADS / RL_WAVE];
     int m = blockIdx.x, t = threadIdx.x;
     f32x4_t v[RN_MAXV];
@@ -70,15 +70,15 @@ __global__ __launch_bounds__(RN_THREADS) void add_rmsnorm_kernel(float *__restri
         if (e4 * 4 < d) {
             u32x2_t g = gr[e4];
             u32x2_t o;
-            o.x = pack_bf16x2(bf16lo_to_f32(g.x) * v[i].x * inv, bf16hi_to_f32(g.x) * v[i].y * inv);
-            o.y = pack_bf16x2(bf16lo_to_f32(g.y) * v[i].z * inv, bf16hi_to_f32(g.y) * v[i].w * inv);
+            o.x = pack_f16x2(bf16lo_to_f32(g.x) * v[i].x * inv, bf16hi_to_f32(g.x) * v[i].y * inv);
+            o.y = pack_f16x2(bf16lo_to_f32(g.y) * v[i].z * inv, bf16hi_to_f32(g.y) * v[i].w * inv);
             hr[e4] = o;
         }
     }
 }
 
 void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_stride, const bf16_t *gain, float eps,
-                        bf16_t *h, int M, int d, hipStream_t st) {
+                        f16_t *h, int M, int d, hipStream_t st) {
     if (M <= 0) return;
     add_rmsnorm_kernel<<<M, RN_THREADS, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
 }
@@ -91,8 +91,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
                                                           int T, int b0, const int32_t *__restrict__ d_pos0,
                                                           const float *__restrict__ rope_tab, int rope_style, int Hq,
                                                           int Hkv, int hd, int S, float *__restrict__ q_f32,
-                                                          bf16_t *__restrict__ q_bf16, bf16_t *__restrict__ kc,
-                                                          bf16_t *__restrict__ vc) {
+                                                          f16_t *__restrict__ q_f16, f16_t *__restrict__ kc,
+                                                          f16_t *__restrict__ vc) {
     int m = blockIdx.x;
     int b = b0 + m / T;
     int pos = d_pos0[0] + m % T;
@@ -122,21 +122,21 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
         if (kind == 0) {
             size_t o = (size_t)m * Hq * hd + (size_t)head * hd;
             if (q_f32) { q_f32[o + ia] = a; q_f32[o + ib] = c; }
-            if (q_bf16) { q_bf16[o + ia] = f32_to_bf16(a); q_bf16[o + ib] = f32_to_bf16(c); }
+            if (q_f16) { q_f16[o + ia] = f32_to_f16(a); q_f16[o + ib] = f32_to_f16(c); }
         } else {
-            bf16_t *dst = (kind == 1 ? kc : vc) + (((size_t)b * Hkv + head) * S + pos) * hd;
-            dst[ia] = f32_to_bf16(a);
-            dst[ib] = f32_to_bf16(c);
+            f16_t *dst = (kind == 1 ? kc : vc) + (((size_t)b * Hkv + head) * S + pos) * hd;
+            dst[ia] = f32_to_f16(a);
+            dst[ib] = f32_to_f16(c);
         }
     }
 }
 
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
                         const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
-                        bf16_t *q_bf16, bf16_t *kc, bf16_t *vc, hipStream_t st) {
+                        f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st) {
     if (M <= 0) return;
     rope_append_kernel<<<M, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S,
-                                          q_f32, q_bf16, kc, vc);
+                                          q_f32, q_f16, kc, vc);
 }
 
 // ------------------------------------------------------------------------------------------------

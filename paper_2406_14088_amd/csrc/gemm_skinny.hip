@@ -1,4 +1,4 @@
-// Skinny-M bf16 GEMM for the decode step: C[M, N] = A[M, K] * W[N, K]^T with M <= 256.
+// Skinny-M GEMM for the decode step: C[M, N] = A[M, K] * W[N, K]^T with M <= 256 (A half, W bf16).
 //
 // A decode step multiplies a few rows of activations (one per sequence) with every weight matrix, so
 // the step is bound by streaming the weights from HBM exactly once.  Design for gfx950:
@@ -7,7 +7,9 @@
 //     double-buffered one K-chunk (128) ahead, never touching LDS;
 //   * the activation chunk [M, 128] is staged once per workgroup in LDS (padded rows, conflict-free
 //     ds_read_b128) and shared by the four wavefronts;
-//   * v_mfma_f32_32x32x16_bf16, fp32 accumulators;
+//   * each weight fragment is widened bf16 -> half in registers (3 VALU ops per pair, exact for normal
+//     halves) and fed to v_mfma_f32_32x32x16_f16 with fp32 accumulators: half activations keep 11
+//     significant bits where bf16 would keep 8, at the same matrix-core rate;
 //   * split-K over workgroups (grid.y) gives enough workgroups to fill 256 CUs; each split writes its
 //     fp32 partial tile and the consumer kernel adds the partials in a fixed order (deterministic).
 // Buffer loads with a range-checked descriptor return 0 outside a matrix, so ragged N and K need no
@@ -15,11 +17,11 @@
 #include "kernels.h"
 
 #define SK_BK 128            // K elements per chunk
-#define SK_LDS_STRIDE 136    // bf16 elements per LDS row (128 + 8 pad -> 272 B, conflict-free b128 reads)
+#define SK_LDS_STRIDE 136    // half elements per LDS row (128 + 8 pad -> 272 B, conflict-free b128 reads)
 #define SK_THREADS 256
 
 struct SkinnyParams {
-    const bf16_t *A;
+    const f16_t *A;
     const bf16_t *W[3];
     int rows[3];
     int tile_begin[4];  // first n-tile of each matrix (prefix sums), tile_begin[3] = total
@@ -39,7 +41,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
 template <int MT>
 __global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_kernel(SkinnyParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t *xs = reinterpret_cast<bf16_t *>(smem);  // [2][MT*32][SK_LDS_STRIDE]
+    f16_t *xs = reinterpret_cast<f16_t *>(smem);  // [2][MT*32][SK_LDS_STRIDE]
     constexpr int BM = MT * 32;
     constexpr int XLOADS = MT * 2;  // 16-byte loads per thread per chunk: BM*128*2 B / (256 thr * 16 B)
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_ker
     // activation loader: thread -> (row r0 + 16*i, 16-byte column group c16)
     const int c16 = t & 15, r0 = t >> 4;
     u32x4_t xr[XLOADS];
-    bf16x8_t wq[2][8];
+    u32x4_t wq[2][8];  // raw bf16 weight fragments, double-buffered
     f32x16_t acc[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_ker
         }
     };
     auto store_x = [&](int buf) {
-        bf16_t *dst = xs + (size_t)buf * BM * SK_LDS_STRIDE;
+        f16_t *dst = xs + (size_t)buf * BM * SK_LDS_STRIDE;
 #pragma unroll
         for (int i = 0; i < XLOADS; ++i) {
             int row = r0 + 16 * i;
@@ -102,18 +104,18 @@ __global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_ker
         int kb = c * SK_BK * 2;  // uniform byte offset of the chunk inside a row
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(w_off + (uint32_t)(s * 32)), kb, 0);
-            wq[slot][s] = __builtin_bit_cast(bf16x8_t, v);
+            wq[slot][s] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(w_off + (uint32_t)(s * 32)), kb, 0);
         }
     };
     auto compute = [&](int buf, int slot) {
-        const bf16_t *src = xs + (size_t)buf * BM * SK_LDS_STRIDE + (lane & 31) * SK_LDS_STRIDE + (lane >> 5) * 8;
+        const f16_t *src = xs + (size_t)buf * BM * SK_LDS_STRIDE + (lane & 31) * SK_LDS_STRIDE + (lane >> 5) * 8;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
+            f16x8_t wf = __builtin_bit_cast(f16x8_t, bf16x8_to_f16x8(wq[slot][s]));
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(src + mt * 32 * SK_LDS_STRIDE + s * 16);
-                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, wq[slot][s], acc[mt], 0, 0, 0);
+                f16x8_t a = *reinterpret_cast<const f16x8_t *>(src + mt * 32 * SK_LDS_STRIDE + s * 16);
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, wf, acc[mt], 0, 0, 0);
             }
         }
     };
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_ker
         }
         __syncthreads();
         if (w < 2 && n_base + col_local < rows) {
-            bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+            f16_t *out = reinterpret_cast<f16_t *>(p.out);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(SK_THREADS, (MT <= 4 ? 2 : 1)) void gemm_skinny_ker
                     int m = mt * 32 + (j >> 2) * 8 + (lane >> 5) * 4 + (j & 3);
                     float g = acc[mt][j], u = ex[(w * MT * 16 + mt * 16 + j) * 64 + lane];
                     float a = g / (1.0f + expf(-g)) * u;
-                    if (m < p.M) out[(size_t)m * p.ldc + out_col + col_local] = f32_to_bf16(a);
+                    if (m < p.M) out[(size_t)m * p.ldc + out_col + col_local] = f32_to_f16(a);
                 }
         }
     }
@@ -198,7 +200,7 @@ int gemm_skinny_default_splits(int M, int N, int K) {
 
 template <int MT>
 static void launch_mt(const SkinnyParams &p, int tiles, hipStream_t st) {
-    size_t lds = (size_t)2 * MT * 32 * SK_LDS_STRIDE * sizeof(bf16_t);
+    size_t lds = (size_t)2 * MT * 32 * SK_LDS_STRIDE * sizeof(f16_t);
     size_t ex = (size_t)2 * MT * 16 * 64 * sizeof(float);
     if (p.epilogue == EPI_SWIGLU && ex > lds) lds = ex;
     static bool attr_set = false;

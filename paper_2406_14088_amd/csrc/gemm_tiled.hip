@@ -1,5 +1,6 @@
-// Large-M bf16 GEMM for prefill: C[M, N] = A[M, K] * W[N, K]^T, both operands tiled through LDS,
-// v_mfma_f32_32x32x16_bf16 with fp32 accumulators.
+// Large-M GEMM for prefill: C[M, N] = A[M, K] * W[N, K]^T (A half, W bf16), both operands tiled
+// through LDS, v_mfma_f32_32x32x16_f16 with fp32 accumulators.  Weights are widened bf16 -> half
+// (exact for normal halves) once, on their way from registers into LDS.
 //
 // Prefill multiplies all prompt tokens of a chunk of sequences (thousands of rows) with every weight
 // matrix: a dense contraction, bound by the matrix cores.  Design for gfx950:
@@ -19,7 +20,7 @@
 #define TG_THREADS 256
 
 struct TiledParams {
-    const bf16_t *A;
+    const f16_t *A;
     const bf16_t *W[3];
     int rows[3];
     int tile_begin[4];
@@ -36,8 +37,8 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, HALF_N = WN * 32;
     constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;  // 16-byte loads per thread per chunk
-    bf16_t *as = reinterpret_cast<bf16_t *>(smem);                  // [2][BM][72]
-    bf16_t *bs = as + 2 * BM * TG_LDS_STRIDE;                        // [2][BN][72]
+    f16_t *as = reinterpret_cast<f16_t *>(smem);                    // [2][BM][72]
+    f16_t *bs = as + 2 * BM * TG_LDS_STRIDE;                         // [2][BN][72]
     const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
     const int K = p.K;
 
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 
     // loader mapping: thread -> (row t/8 + 32*i, 16-byte group t%8)
     const int lc = t & 7, lr = t >> 3;
-    const bf16_t *a_ptr[A_LOADS];
+    const f16_t *a_ptr[A_LOADS];
     bool a_ok[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
@@ -114,28 +115,28 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
         }
     };
     auto store_s = [&](int buf) {
-        bf16_t *ad = as + buf * BM * TG_LDS_STRIDE, *bd = bs + buf * BN * TG_LDS_STRIDE;
+        f16_t *ad = as + buf * BM * TG_LDS_STRIDE, *bd = bs + buf * BN * TG_LDS_STRIDE;
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i)
             *reinterpret_cast<u32x4_t *>(ad + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = ar[i];
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i)
-            *reinterpret_cast<u32x4_t *>(bd + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = br[i];
+            *reinterpret_cast<u32x4_t *>(bd + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = bf16x8_to_f16x8(br[i]);
     };
     auto compute = [&](int buf) {
-        const bf16_t *ap = as + buf * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
-        const bf16_t *bp = bs + buf * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        const f16_t *ap = as + buf * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        const f16_t *bp = bs + buf * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
 #pragma unroll
         for (int s = 0; s < TG_BK / 16; ++s) {
-            bf16x8_t af[WM], bf[WN];
+            f16x8_t af[WM], bf[WN];
 #pragma unroll
-            for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const bf16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + s * 16);
+            for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + s * 16);
 #pragma unroll
-            for (int j = 0; j < WN; ++j) bf[j] = *reinterpret_cast<const bf16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + s * 16);
+            for (int j = 0; j < WN; ++j) bf[j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + s * 16);
 #pragma unroll
             for (int i = 0; i < WM; ++i)
 #pragma unroll
-                for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
         }
     };
 
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     } else {
         // wavefront column 1 (up) -> LDS -> wavefront column 0 (gate), one 32-column strip at a time
         float *ex = reinterpret_cast<float *>(smem);  // [2 (wm)][WM*16][64] floats per strip
-        bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+        f16_t *out = reinterpret_cast<f16_t *>(p.out);
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             __syncthreads();
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
                         int m = m0 + (wm * WM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
                         float g = acc[i][j][e], u = ex[((wm * WM + i) * 16 + e) * 64 + lane];
                         float a = g / (1.0f + expf(-g)) * u;
-                        if (m < p.M) out[(size_t)m * p.ldc + oc + n] = f32_to_bf16(a);
+                        if (m < p.M) out[(size_t)m * p.ldc + oc + n] = f32_to_f16(a);
                     }
             }
         }
@@ -217,7 +218,7 @@ static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
     p.tiles_n = tiles;
     p.tiles_m = ceil_div(a.M, BM);
     if (tiles <= 0 || p.tiles_m <= 0) return;
-    size_t lds = (size_t)2 * (BM + BN) * TG_LDS_STRIDE * sizeof(bf16_t);
+    size_t lds = (size_t)2 * (BM + BN) * TG_LDS_STRIDE * sizeof(f16_t);
     size_t ex = (size_t)2 * WM * 16 * 64 * sizeof(float);
     if (ex > lds) lds = ex;
     static bool attr_set = false;

@@ -6,16 +6,16 @@
 // ---- elementwise.hip -------------------------------------------------------------------------
 // x[m, :] = widen(emb[clamp(tokens[m]), :])                      tokens int32 [M], emb bf16 [vocab, d], x fp32 [M, d]
 void launch_embed(const int32_t *tokens, const bf16_t *emb, float *x, int M, int d, int vocab, hipStream_t st);
-// x[m, :] += sum_s part[s*part_stride + m*d + :]  (nsplit may be 0);  h[m, :] = bf16(gain * x / sqrt(mean(x^2) + eps))
+// x[m, :] += sum_s part[s*part_stride + m*d + :]  (nsplit may be 0);  h[m, :] = half(gain * x / sqrt(mean(x^2) + eps))
 void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_stride, const bf16_t *gain, float eps,
-                        bf16_t *h, int M, int d, hipStream_t st);
+                        f16_t *h, int M, int d, hipStream_t st);
 // Sums the split partials of the fused QKV projection, rotates q and k heads at their positions and
-// writes q (fp32 and/or bf16, [M, Hq*hd]) and the cache rows.  Row m is sequence b0 + m / T at
+// writes q (fp32 and/or half, [M, Hq*hd]) and the cache rows.  Row m is sequence b0 + m / T at
 // position *d_pos0 + m % T.  rope_tab: fp32 [max_seq, hd/2, 2] (cos, sin).
-// kc / vc: this layer's K and V slabs, bf16 [max_batch][Hkv][S][hd].
+// kc / vc: this layer's K and V slabs, half [max_batch][Hkv][S][hd].
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
                         const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
-                        bf16_t *q_bf16, bf16_t *kc, bf16_t *vc, hipStream_t st);
+                        f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st);
 // next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN); optionally *inc_len += 1.
 void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *inc_len, hipStream_t st);
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
@@ -25,13 +25,15 @@ void launch_f32_to_bf16(const float *src, bf16_t *dst, size_t n, hipStream_t st)
 // ---- gemm_skinny.hip / gemm_tiled.hip ----------------------------------------------------------
 // C[m, off_i + n] = sum_k A[m, k] * W_i[n, k]  for up to three weight matrices W_i ([rows_i, K] bf16,
 // row-major) laid side by side along the output columns (off_0 = 0, off_1 = rows_0, ...).
+// Activations A are half; weights are widened bf16 -> half inside the kernels (exact for normal halves)
+// and multiplied on the f16 matrix cores with fp32 accumulation.
 enum GemmEpilogue {
     EPI_F32 = 0,    // out fp32: split s writes out + s*split_stride, element [m*ldc + col]
-    EPI_SWIGLU = 1, // W_0 = gate, W_1 = up (same shape): out bf16 [m*ldc + n] = silu(gate) * up; splits must be 1
+    EPI_SWIGLU = 1, // W_0 = gate, W_1 = up (same shape): out half [m*ldc + n] = silu(gate) * up; splits must be 1
     EPI_F32_ACC = 2 // out fp32 [m*ldc + col] += result (residual add); splits must be 1
 };
 struct GemmArgs {
-    const bf16_t *A;      // [M, K] bf16, row stride lda (elements)
+    const f16_t *A;       // [M, K] half, row stride lda (elements)
     int64_t lda;
     const bf16_t *W[3];
     int rows[3];          // rows of each W_i (0 for unused)
@@ -50,16 +52,16 @@ int gemm_skinny_default_splits(int M, int N, int K);
 
 // ---- attention_decode.hip ------------------------------------------------------------------------
 // One new query per (sequence, query head) against cache rows 0 .. *d_len (inclusive).
-// q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's slabs; out bf16 [B, Hq*hd].
+// q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's slabs (half); out half [B, Hq*hd].
 // ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
-void launch_decode_attention(const float *q, const bf16_t *kc, const bf16_t *vc, const int32_t *d_len, bf16_t *out,
+void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st);
-void launch_decode_attention_merge(const float *ws, bf16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
+void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);
 
 // ---- attention_prefill.hip -----------------------------------------------------------------------
 // Causal attention over the T prompt positions of nb sequences whose K/V already sit in the cache.
-// q bf16 [nb*T, Hq*hd] (rotated); sequence i of the chunk is cache sequence b0 + i; out bf16 [nb*T, Hq*hd].
-void launch_prefill_attention(const bf16_t *q, const bf16_t *kc, const bf16_t *vc, bf16_t *out, int nb, int b0, int T,
+// q half [nb*T, Hq*hd] (rotated); sequence i of the chunk is cache sequence b0 + i; out half [nb*T, Hq*hd].
+void launch_prefill_attention(const f16_t *q, const f16_t *kc, const f16_t *vc, f16_t *out, int nb, int b0, int T,
                               int Hq, int Hkv, int hd, int S, hipStream_t st);

@@ -102,7 +102,7 @@ struct rl_gen {
     std::vector<const bf16_t *> lw[9];
     const bf16_t *tok_emb, *final_norm, *lm_head;
     std::vector<void *> owned;
-    bf16_t *kv;
+    f16_t *kv;
     unsigned char *work;
     WorkPlan wp;
     int nsplit_attn;
@@ -116,22 +116,22 @@ struct rl_gen {
     char err[512];
 
     float *x() const { return reinterpret_cast<float *>(work + wp.x); }
-    bf16_t *h() const { return reinterpret_cast<bf16_t *>(work + wp.h); }
+    f16_t *h() const { return reinterpret_cast<f16_t *>(work + wp.h); }
     float *part() const { return reinterpret_cast<float *>(work + wp.part); }
     float *qf32() const { return reinterpret_cast<float *>(work + wp.qf32); }
-    bf16_t *qbf() const { return reinterpret_cast<bf16_t *>(work + wp.qbf); }
-    bf16_t *attn() const { return reinterpret_cast<bf16_t *>(work + wp.attn); }
-    bf16_t *act() const { return reinterpret_cast<bf16_t *>(work + wp.act); }
+    f16_t *qbf() const { return reinterpret_cast<f16_t *>(work + wp.qbf); }
+    f16_t *attn() const { return reinterpret_cast<f16_t *>(work + wp.attn); }
+    f16_t *act() const { return reinterpret_cast<f16_t *>(work + wp.act); }
     float *attn_ws() const { return reinterpret_cast<float *>(work + wp.attn_ws); }
     float *logits_ws() const { return reinterpret_cast<float *>(work + wp.logits); }
     int32_t *next_ws() const { return reinterpret_cast<int32_t *>(work + wp.next); }
     float *rope() const { return reinterpret_cast<float *>(work + wp.rope); }
     int32_t *d_len() const { return reinterpret_cast<int32_t *>(work + wp.state); }
     int32_t *d_zero() const { return reinterpret_cast<int32_t *>(work + wp.state) + 1; }
-    bf16_t *kslab(int l) const {
+    f16_t *kslab(int l) const {
         return kv + (size_t)(2 * l) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
     }
-    bf16_t *vslab(int l) const {
+    f16_t *vslab(int l) const {
         return kv + (size_t)(2 * l + 1) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
     }
 };
@@ -174,7 +174,7 @@ struct Scope {
 
 // One projection.  Returns the number of fp32 partials written to h->part() (0 when the result was
 // accumulated straight into `acc_out`).
-int project(rl_gen *h, int cls, const bf16_t *A, int64_t lda, int M, int K, const bf16_t *W0, int r0, const bf16_t *W1,
+int project(rl_gen *h, int cls, const f16_t *A, int64_t lda, int M, int K, const bf16_t *W0, int r0, const bf16_t *W1,
             int r1, const bf16_t *W2, int r2, float *acc_out, int64_t ld_acc, hipStream_t st) {
     GemmArgs a;
     a.A = A; a.lda = lda; a.M = M; a.K = K;
@@ -199,7 +199,7 @@ int project(rl_gen *h, int cls, const bf16_t *A, int64_t lda, int M, int K, cons
     return 1;
 }
 
-void swiglu_project(rl_gen *h, const bf16_t *A, int M, int l, hipStream_t st) {
+void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
     GemmArgs a;
     a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
     a.W[0] = h->lw[W_GATE][l]; a.W[1] = h->lw[W_UP][l]; a.W[2] = nullptr;
@@ -346,7 +346,7 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
 
     rl_gen *h = new rl_gen();
     h->s = *shape;
-    h->kv = reinterpret_cast<bf16_t *>(kv_arena);
+    h->kv = reinterpret_cast<f16_t *>(kv_arena);
     h->work = reinterpret_cast<unsigned char *>(work_arena);
     h->wp = wp;
     h->nsplit_attn = attn_splits(shape);
@@ -607,11 +607,11 @@ int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float 
 
 int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
                       const int32_t *d_pos0, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv, int32_t hd,
-                      int32_t S, float *q_f32, uint16_t *q_bf16, uint16_t *kc, uint16_t *vc, void *st) {
+                      int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *st) {
     if (!qkv || !d_pos0 || !rope_tab || !kc || !vc) return RL_GEN_E_NULL;
     if (nsplit < 1 || M < 0 || T <= 0 || b0 < 0 || Hq <= 0 || Hkv <= 0 || hd <= 0 || hd % 2 || S <= 0 || (rope_style != 0 && rope_style != 1))
         return RL_GEN_E_SHAPE;
-    launch_rope_append(qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_bf16, kc, vc,
+    launch_rope_append(qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_f16, kc, vc,
                        reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }

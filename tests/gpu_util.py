@@ -4,11 +4,17 @@ import torch
 
 DEV = "cuda:0"
 BF16_EPS = 2.0 ** -7      # bf16 spacing relative to the value (8 significant bits); rounding error <= half of it
+F16_EPS = 2.0 ** -10      # IEEE half spacing relative to the value (11 significant bits)
 
 
 def randn_bf16(shape, seed, std=1.0, device=DEV):
     g = torch.Generator(device="cpu").manual_seed(seed)
     return (torch.randn(shape, generator=g) * std).to(torch.bfloat16).to(device)
+
+
+def randn_f16(shape, seed, std=1.0, device=DEV):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return (torch.randn(shape, generator=g) * std).to(torch.float16).to(device)
 
 
 def randn_f32(shape, seed, std=1.0, device=DEV):
