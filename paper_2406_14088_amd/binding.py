@@ -46,6 +46,9 @@ def lib():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # torch first: the library must bind to the same HIP runtime instance that owns the device memory
+    # and streams it is handed (two runtimes in one process do not share allocations)
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2406_14088_amd.build` "
                            "(or __graft_entry__.build()) first; this package has no fallback path")
