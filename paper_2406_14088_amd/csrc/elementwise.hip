@@ -30,26 +30,32 @@ void launch_embed(const int32_t *tokens, const bf16_t *emb, float *x, int M, int
 // Residual add of split-K partial sums, then RMSNorm: y = g * x / sqrt(mean(x^2) + eps).
 // The residual stream stays fp32; only the normalised copy that feeds the next projection is half.
 // One workgroup per row; each thread keeps its slice of the row in registers (hidden <= 8192).
-#define RN_THREADS 256
-#define RN_MAXV 8
-__global__ __launch_bounds__(RN_THREADS) void add_rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part,
-                                                                 int nsplit, size_t part_stride,
-                                                                 const bf16_t *__restrict__ gain, float eps,
-                                                                 f16_t *__restrict__ h, int d) {
-    __shared__ float red[RN_THREADS / RL_WAVE];
+#define RN_MAX_SPLITS 16
+template <int THREADS, int MAXV>
+__global__ __launch_bounds__(THREADS) void add_rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part,
+                                                              int nsplit, size_t part_stride,
+                                                              const bf16_t *__restrict__ gain, float eps,
+                                                              f16_t *__restrict__ h, int d) {
+    __shared__ float red[THREADS / RL_WAVE];
     int m = blockIdx.x, t = threadIdx.x;
-    f32x4_t v[RN_MAXV];
+    f32x4_t v[MAXV];
     float ss = 0.f;
     f32x4_t *xr = reinterpret_cast<f32x4_t *>(x + (size_t)m * d);
+    const f32x4_t *pr = reinterpret_cast<const f32x4_t *>(part + (size_t)m * d);
+    const size_t ps4 = part_stride / 4;
 #pragma unroll
-    for (int i = 0; i < RN_MAXV; ++i) {
-        int e4 = t + i * RN_THREADS;
+    for (int i = 0; i < MAXV; ++i) {
+        int e4 = t + i * THREADS;
         if (e4 * 4 < d) {
             f32x4_t a = xr[e4];
-            for (int s = 0; s < nsplit; ++s) {
-                const f32x4_t *pr = reinterpret_cast<const f32x4_t *>(part + (size_t)s * part_stride + (size_t)m * d);
-                a += pr[e4];
+            // partials are added in split order (fixed, so results are reproducible); four loads in flight
+            int s = 0;
+            for (; s + 4 <= nsplit; s += 4) {
+                f32x4_t p0 = pr[(size_t)s * ps4 + e4], p1 = pr[(size_t)(s + 1) * ps4 + e4];
+                f32x4_t p2 = pr[(size_t)(s + 2) * ps4 + e4], p3 = pr[(size_t)(s + 3) * ps4 + e4];
+                a += p0; a += p1; a += p2; a += p3;
             }
+            for (; s < nsplit; ++s) a += pr[(size_t)s * ps4 + e4];
             if (nsplit > 0) xr[e4] = a;
             v[i] = a;
             ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
@@ -60,13 +66,13 @@ __global__ __launch_bounds__(RN_THREADS) void add_rmsnorm_kernel(float *__restri
     __syncthreads();
     float tot = 0.f;
 #pragma unroll
-    for (int w = 0; w < RN_THREADS / RL_WAVE; ++w) tot += red[w];
+    for (int w = 0; w < THREADS / RL_WAVE; ++w) tot += red[w];
     float inv = 1.0f / sqrtf(tot / (float)d + eps);
     u32x2_t *hr = reinterpret_cast<u32x2_t *>(h + (size_t)m * d);
     const u32x2_t *gr = reinterpret_cast<const u32x2_t *>(gain);
 #pragma unroll
-    for (int i = 0; i < RN_MAXV; ++i) {
-        int e4 = t + i * RN_THREADS;
+    for (int i = 0; i < MAXV; ++i) {
+        int e4 = t + i * THREADS;
         if (e4 * 4 < d) {
             u32x2_t g = gr[e4];
             u32x2_t o;
@@ -80,13 +86,18 @@ __global__ __launch_bounds__(RN_THREADS) void add_rmsnorm_kernel(float *__restri
 void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_stride, const bf16_t *gain, float eps,
                         f16_t *h, int M, int d, hipStream_t st) {
     if (M <= 0) return;
-    add_rmsnorm_kernel<<<M, RN_THREADS, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
+    // few rows (decode): many threads per row so that every row streams with many loads in flight;
+    // many rows (prefill): fewer threads per row, more rows per compute unit
+    if (M <= 1024 && d > 1024)
+        add_rmsnorm_kernel<1024, 2><<<M, 1024, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
+    else
+        add_rmsnorm_kernel<256, 8><<<M, 256, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Rotary embedding of q and k at the token's absolute position, and KV-cache append.
 // Pair r of a head turns by the angle pos * base^(-2r/hd); cos/sin come from a table built in fp64.
-// One workgroup per token row; a thread handles one (head, pair) item at a time.
+// One thread per (token row, head, pair) item.
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ qkv, int nsplit, size_t split_stride,
                                                           int T, int b0, const int32_t *__restrict__ d_pos0,
                                                           const float *__restrict__ rope_tab, int rope_style, int Hq,
@@ -102,7 +113,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     int ld = (Hq + 2 * Hkv) * hd;
     const float *row = qkv + (size_t)m * ld;
     const float *tab = rope_tab + (size_t)pos * hd;  // [half][2]
-    for (int it = threadIdx.x; it < nq + 2 * nk; it += blockDim.x) {
+    int it = blockIdx.y * blockDim.x + threadIdx.x;
+    if (it < nq + 2 * nk) {
         int kind = it < nq ? 0 : (it < nq + nk ? 1 : 2);
         int local = kind == 0 ? it : (kind == 1 ? it - nq : it - nq - nk);
         int head = local / half, r = local % half;
@@ -135,7 +147,9 @@ void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M
                         const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
                         f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st) {
     if (M <= 0) return;
-    rope_append_kernel<<<M, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S,
+    int items = (Hq + 2 * Hkv) * (hd / 2);
+    dim3 grid(M, ceil_div(items, 256));
+    rope_append_kernel<<<grid, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S,
                                           q_f32, q_f16, kc, vc);
 }
 
