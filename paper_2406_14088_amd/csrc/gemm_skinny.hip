@@ -110,8 +110,8 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
         int row = r0 + 32 * i;
         x_off[i] = (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)c16 * 16u;
     }
-    u32x4_t xr[MT];
-    u32x4_t wq[8];  // raw bf16 weight pieces in flight: slots (i & 1) * 4 .. + 3 belong to chunk c0 + i
+    u32x4_t xr[2][MT];  // activation pieces in flight: xr[i & 1] belongs to chunk c0 + i
+    u32x4_t wq[8];      // raw bf16 weight pieces in flight: slots (i & 1) * 4 .. + 3 belong to chunk c0 + i
     f32x16_t acc[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -121,37 +121,35 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
     // Loads that are not needed (past the K range of this split) get an offset outside the descriptor's
     // range: the hardware answers with zeros and touches no memory, and the number of outstanding loads
     // stays the same on every trip, so the compiler's wait counters stay exact.
-    auto load_x = [&](int c, bool wanted) {
-        bool ok = wanted && (c * SK_BK + c16 * 8 < K);
+    auto load_x = [&](int c, int set) {
+        bool ok = c < c1 && (c * SK_BK + c16 * 8 < K);
         uint32_t cb = (uint32_t)c * (SK_BK * 2);
 #pragma unroll
         for (int i = 0; i < MT; ++i)
-            xr[i] = __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok && r0 + 32 * i < Mloc ? x_off[i] + cb : SK_OOB), 0, 0);
+            xr[set][i] = __builtin_amdgcn_raw_buffer_load_b128(ar, (int)(ok && r0 + 32 * i < Mloc ? x_off[i] + cb : SK_OOB), 0, 0);
     };
-    auto store_x = [&](int buf) {
+    auto store_x1 = [&](int set, int buf, int i) {
         f16_t *dst = xs + (size_t)buf * BM * SK_LDS_STRIDE;
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-            *reinterpret_cast<u32x4_t *>(dst + (r0 + 32 * i) * SK_LDS_STRIDE + c16 * 8) = xr[i];
+        *reinterpret_cast<u32x4_t *>(dst + (r0 + 32 * i) * SK_LDS_STRIDE + c16 * 8) = xr[set][i];
     };
-    auto load_w = [&](int c, int slot0) {  // chunk c -> ring slots slot0 .. slot0 + 3
-        bool ok = c < c1;
+    auto load_w1 = [&](int c, int slot, int i) {  // piece i of chunk c -> ring slot
         uint32_t cb = (uint32_t)c * (SK_BK * 2);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            wq[slot0 + i] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(ok ? w_off[i] + cb : SK_OOB), 0, 0);
+        wq[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(c < c1 ? w_off[i] + cb : SK_OOB), 0, 0);
     };
-    auto stage_w = [&](int slot0, int buf) {  // ring slots -> half -> LDS strip `buf`
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4_t *>(wl + buf * 4096 + i * 1024 + wst) = bf16x8_to_f16x8(wq[slot0 + i]);
+    auto stage_w1 = [&](int slot, int buf, int i) {  // ring slot -> half -> LDS strip `buf`
+        *reinterpret_cast<u32x4_t *>(wl + buf * 4096 + i * 1024 + wst) = bf16x8_to_f16x8(wq[slot]);
     };
 
-    // One chunk (index i relative to c0, PAR = i & 1): MFMAs on the strip/tile staged one chunk ago,
-    // while the next chunk's weights move ring -> LDS and the ring is refilled three chunks ahead.
+    // One chunk (index i relative to c0, PAR = i & 1): MFMAs on the strip/tile staged one chunk ago.
+    // Interleaved with its four k-steps, piece by piece: the next chunk's activations move registers ->
+    // LDS tile, the next chunk's weights move ring -> half -> LDS strip, and the ring is refilled three
+    // chunks ahead, so that the matrix cores, the LDS and the memory pipeline work at the same time.
+    // The hardware counts outstanding loads in issue order: all (short-latency, L2) activation loads of a
+    // trip are issued before its weight loads, so waiting for them never waits for young weight loads.
     auto body = [&](int c, auto par_tag) {
         constexpr int PAR = decltype(par_tag)::value;
         __syncthreads();  // activation tile of chunk c is in LDS buffer PAR; buffer PAR^1 is free
+        load_x(c + 2, PAR);
         const f16_t *src = xs + (size_t)PAR * BM * SK_LDS_STRIDE + (lane & 31) * SK_LDS_STRIDE + (lane >> 5) * 8 + kg * 64;
         const unsigned char *wsrc = wl + PAR * 4096;
         f16x8_t a[2][MT];
@@ -159,35 +157,37 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) a[0][mt] = *reinterpret_cast<const f16x8_t *>(src + mt * 32 * SK_LDS_STRIDE);
         wf[0] = *reinterpret_cast<const f16x8_t *>(wsrc + wld[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            if (s + 1 < 4) {  // operands of step s+1 are requested before the MFMAs of step s are issued ...
+            if (s + 1 < 4) {  // operands of step s+1 are requested before the MFMAs of step s are issued
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     a[(s + 1) & 1][mt] = *reinterpret_cast<const f16x8_t *>(src + mt * 32 * SK_LDS_STRIDE + (s + 1) * 16);
                 wf[(s + 1) & 1] = *reinterpret_cast<const f16x8_t *>(wsrc + wld[s + 1]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            // ... so that the LDS latency hides behind MT matrix instructions
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[s & 1][mt], wf[s & 1], acc[mt], 0, 0, 0);
+            store_x1(PAR ^ 1, PAR ^ 1, s);               // activation piece s of chunk c+1 (loaded one chunk ago)
+            stage_w1((PAR ^ 1) * 4 + s, PAR ^ 1, s);     // weight piece s of chunk c+1: ring -> strip
+            load_w1(c + 3, (PAR ^ 1) * 4 + s, s);        // and refill its ring slot
             __builtin_amdgcn_sched_barrier(0);
         }
-        stage_w((PAR ^ 1) * 4, PAR ^ 1);   // chunk c+1: ring -> strip (last read one chunk ago by this wavefront)
-        load_w(c + 3, (PAR ^ 1) * 4);      // and refill its ring slots
-        store_x(PAR ^ 1);                  // activation tile of chunk c+1 (loaded one chunk ago; zeros past the end)
-        load_x(c + 2, c + 2 < c1);
-        __builtin_amdgcn_sched_barrier(0);
     };
 
     if (c0 < c1) {
-        load_x(c0, true);
-        load_w(c0, 0);
-        load_w(c0 + 1, 4);
-        store_x(0);
-        load_x(c0 + 1, c0 + 1 < c1);
-        stage_w(0, 0);
-        load_w(c0 + 2, 0);
+        load_x(c0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_w1(c0, i, i);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) store_x1(0, 0, i);
+        load_x(c0 + 1, 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_w1(c0 + 1, 4 + i, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) stage_w1(i, 0, i);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_w1(c0 + 2, i, i);
         __builtin_amdgcn_sched_barrier(0);
         for (int c = c0; c < c1; c += 2) {
             body(c, std::integral_constant<int, 0>{});
