@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (copy_kernel: a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the data-parallel hot path of one GPU's share); "
@@ -80,6 +82,14 @@ def main():
     setup_s = time.perf_counter() - t0
 
     buf = [torch.empty((B,), dtype=torch.int32, device=dev) for _ in range(2)]
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        from paper_2406_14088_amd import ops
+        for _ in range(3):
+            ops.copy(src, dst)            # copy_kernel of the library: 16 bytes per lane, like the hot kernels
+        torch.cuda.synchronize()
+        del src, dst
 
     def generate(timing=None):
         """prefill + (G-1) decode steps; tokens stay on the device"""

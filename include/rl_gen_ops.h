@@ -75,6 +75,11 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
 /* Greedy token: next[b] = lowest index of the largest of logits[b, 0..V-1]; -1 if the row has a NaN. */
 int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *hip_stream);
 
+/* Plain device-to-device copy of `bytes` bytes (multiple of 16; 16-byte aligned pointers), 16 bytes per
+ * lane.  Not a step of the method: a kernel of exactly known traffic that the benchmark profiles next
+ * to the real kernels to scale hardware byte counters. */
+int rl_op_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -80,6 +80,7 @@ def lib():
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
+        "rl_op_copy": (C.c_int, [vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -95,7 +96,7 @@ EXPORTED_SYMBOLS = (
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats",
-    "rl_op_prefill_attention", "rl_op_argmax")
+    "rl_op_prefill_attention", "rl_op_argmax", "rl_op_copy")
 
 
 def _shape_of(shape, max_batch=1, max_seq=1, weight_dtype=1) -> RlGenShape:
@@ -284,6 +285,9 @@ class _Ops:
     def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):
         self._ck(lib().rl_op_prefill_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), nb, b0, T, Hq, Hkv,
                                                hd, S, _stream()), "rl_op_prefill_attention")
+
+    def copy(self, src, dst):
+        self._ck(lib().rl_op_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream()), "rl_op_copy")
 
     def argmax(self, logits, nxt):
         B, V = logits.shape

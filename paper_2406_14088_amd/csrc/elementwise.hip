@@ -208,3 +208,16 @@ void launch_f32_to_bf16(const float *src, bf16_t *dst, size_t n, hipStream_t st)
     if (blocks > 65536) blocks = 65536;
     f32_to_bf16_kernel<<<(unsigned)blocks, 256, 0, st>>>(src, dst, n);
 }
+
+// Plain device copy, 16 bytes per lane: a kernel of exactly known traffic (n bytes read, n written) that the
+// benchmark runs next to the real kernels so that profiler byte counters can be scaled.
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
+    size_t n16 = bytes / 16;
+    if (n16 == 0) return;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    copy_kernel<<<(unsigned)blocks, 256, 0, st>>>(reinterpret_cast<const u32x4_t *>(src), reinterpret_cast<u32x4_t *>(dst), n16);
+}

@@ -22,6 +22,9 @@ void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
 // dst[i] = bf16(src[i])  (round to nearest even)
 void launch_f32_to_bf16(const float *src, bf16_t *dst, size_t n, hipStream_t st);
 
+// dst[0 .. bytes) = src[0 .. bytes)  (bytes rounded down to a multiple of 16)
+void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+
 // ---- gemm_skinny.hip / gemm_tiled.hip ----------------------------------------------------------
 // C[m, off_i + n] = sum_k A[m, k] * W_i[n, k]  for up to three weight matrices W_i ([rows_i, K] bf16,
 // row-major) laid side by side along the output columns (off_0 = 0, off_1 = rows_0, ...).

@@ -637,6 +637,13 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
     RL_OP_RETURN();
 }
 
+int rl_op_copy(const void *src, void *dst, size_t bytes, void *st) {
+    if (!src || !dst) return RL_GEN_E_NULL;
+    if (bytes % 16 || ((uintptr_t)src | (uintptr_t)dst) % 16) return RL_GEN_E_SHAPE;
+    launch_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
 int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *st) {
     if (!logits || !next) return RL_GEN_E_NULL;
     if (B < 0 || V <= 0) return RL_GEN_E_SHAPE;
