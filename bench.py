@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense 16-bit matrix cores (bf16 and fp16), published
+# HBM bytes per decode-attention launch (mean over the launches of one generation) measured with rocprofv3 counters:
+# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the library's 1 GiB copy_kernel
+# (profiles/decode_attention_llama7b_hbm_traffic.md).  Only valid for the unmodified llama7b workload.
+MEASURED_TRAFFIC_BYTES = {"llama7b": 527427 * 1024}
 
 
 def decode_bytes(shape, B, t):
@@ -139,8 +143,8 @@ def main():
     }
 
     out = {
-        "metric": "generated tokens/sec on 1 GPU (prefill + decode, greedy, LLaMA-7B shape)" if args.workload == "llama7b"
-        else f"generated tokens/sec on 1 GPU ({args.workload})",
+        "metric": "generated tokens/sec on 1 GPU + decode-step HBM GB/s (% peak), LLaMA-7B shape" if args.workload == "llama7b"
+        else f"generated tokens/sec on 1 GPU + decode-step HBM GB/s (% peak), {args.workload}",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
@@ -162,7 +166,8 @@ def main():
         if att["launches"] > 0 and att["ms"] > 0:
             achieved = att_bytes / (att["ms"] * 1e-3) / 1e9
             out["roofline"] = {"kernel": "decode_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                               "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                               "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                               "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if not args.layers else None,
                                "launches": att["launches"], "avg_launch_us": att["ms"] * 1e3 / att["launches"],
                                "bytes_per_launch_mean": att_bytes / att["launches"]}
         out["kernels"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 3)} for k, v in prof.items() if v["launches"]}
