@@ -108,6 +108,12 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
  * kernel (0).  Both produce identical results. */
 int rl_gen_set_graph(rl_gen_t *h, int32_t enabled);
 
+/* Number of half-precision terms in which the normalised activations reach the QKV projection: 2 (default;
+ * the projection runs on the stacked rows [h; h - half(h)] and k, v, q carry ~22-bit activations) or 1 (faster,
+ * less accurate: the projection that feeds the KV cache is the rounding the logits are most sensitive to).
+ * Takes effect from the next prefill / decode step. */
+int rl_gen_set_qkv_terms(rl_gen_t *h, int32_t terms);
+
 /* Forgets all sequences (weights and arenas stay).  Host-side only. */
 int rl_gen_reset(rl_gen_t *h);
 /* Current state: number of sequences and tokens per sequence (0, 0 before a prefill). */

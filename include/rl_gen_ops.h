@@ -27,10 +27,12 @@ int rl_op_embed(const int32_t *tokens, const uint16_t *emb, float *x, int32_t M,
 
 /* Residual add + RMSNorm: x[m,:] += sum_{s<nsplit} part[s*part_stride + m*d + :] (x is updated in
  * place when nsplit > 0; part may be NULL when nsplit == 0), then
- * h[m,:] = f16(gain * x / sqrt(mean(x^2) + eps)).  x fp32 [M, d], gain bf16 [d], h f16 [M, d];
- * d % 4 == 0 and d <= 8192. */
+ * y = gain * x / sqrt(mean(x^2) + eps), h[m,:] = f16(y).  x fp32 [M, d], gain bf16 [d], h f16 [M, d];
+ * d % 4 == 0 and d <= 8192.  If h_lo is not NULL it receives the second term of a two-term split,
+ * h_lo[m,:] = f16(y - h[m,:]) (f16 [M, d]): a projection fed with the stacked rows [h; h_lo] and summed
+ * over the two row blocks sees the activation with ~22 instead of 11 significant bits. */
 int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_stride, const uint16_t *gain, float eps,
-                      uint16_t *h, int32_t M, int32_t d, void *hip_stream);
+                      uint16_t *h, uint16_t *h_lo, int32_t M, int32_t d, void *hip_stream);
 
 /* Projection: out[m, off_i + n] = sum_k A[m,k] * W_i[n,k] for up to three bf16 matrices W_i
  * [rows_i, K] placed side by side along the output columns (unused: NULL / 0 rows).

@@ -64,6 +64,7 @@ def lib():
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "rl_gen_set_graph": (C.c_int, [vp, i32]),
+        "rl_gen_set_qkv_terms": (C.c_int, [vp, i32]),
         "rl_gen_reset": (C.c_int, [vp]),
         "rl_gen_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "rl_gen_destroy": (None, [vp]),
@@ -72,7 +73,7 @@ def lib():
         "rl_gen_profile_read": (C.c_int, [vp, C.POINTER(i32), C.POINTER(f32), vp]),
         "rl_gen_kernel_class_name": (C.c_char_p, [i32]),
         "rl_op_embed": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
-        "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, i32, i32, vp]),
+        "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, vp, i32, i32, vp]),
         "rl_op_gemm": (C.c_int, [vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
@@ -93,7 +94,7 @@ def lib():
 
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_prefill",
-    "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
+    "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_copy")
@@ -212,6 +213,9 @@ class Generator:
     def set_graph(self, enabled: bool):
         self._check(lib().rl_gen_set_graph(self._h, int(enabled)), "rl_gen_set_graph")
 
+    def set_qkv_terms(self, terms: int):
+        self._check(lib().rl_gen_set_qkv_terms(self._h, int(terms)), "rl_gen_set_qkv_terms")
+
     def reset(self):
         self._check(lib().rl_gen_reset(self._h), "rl_gen_reset")
 
@@ -253,9 +257,9 @@ class _Ops:
         self._ck(lib().rl_op_embed(tokens.data_ptr(), emb.data_ptr(), x.data_ptr(), tokens.numel(), emb.shape[1], emb.shape[0],
                                    _stream()), "rl_op_embed")
 
-    def add_rmsnorm(self, x, part, nsplit, part_stride, gain, eps, h):
+    def add_rmsnorm(self, x, part, nsplit, part_stride, gain, eps, h, h_lo=None):
         M, d = x.shape
-        self._ck(lib().rl_op_add_rmsnorm(x.data_ptr(), _ptr(part), nsplit, part_stride, gain.data_ptr(), eps, h.data_ptr(), M, d,
+        self._ck(lib().rl_op_add_rmsnorm(x.data_ptr(), _ptr(part), nsplit, part_stride, gain.data_ptr(), eps, h.data_ptr(), _ptr(h_lo), M, d,
                                          _stream()), "rl_op_add_rmsnorm")
 
     def gemm(self, A, Ws, out, ldc, M=None, lda=None, split_stride=0, splits=1, epilogue=0, kernel=0):

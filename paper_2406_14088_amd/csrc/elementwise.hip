@@ -35,7 +35,7 @@ template <int THREADS, int MAXV>
 __global__ __launch_bounds__(THREADS) void add_rmsnorm_kernel(float *__restrict__ x, const float *__restrict__ part,
                                                               int nsplit, size_t part_stride,
                                                               const bf16_t *__restrict__ gain, float eps,
-                                                              f16_t *__restrict__ h, int d) {
+                                                              f16_t *__restrict__ h, f16_t *__restrict__ h_lo, int d) {
     __shared__ float red[THREADS / RL_WAVE];
     int m = blockIdx.x, t = threadIdx.x;
     f32x4_t v[MAXV];
@@ -69,29 +69,38 @@ __global__ __launch_bounds__(THREADS) void add_rmsnorm_kernel(float *__restrict_
     for (int w = 0; w < THREADS / RL_WAVE; ++w) tot += red[w];
     float inv = 1.0f / sqrtf(tot / (float)d + eps);
     u32x2_t *hr = reinterpret_cast<u32x2_t *>(h + (size_t)m * d);
+    u32x2_t *lr = h_lo ? reinterpret_cast<u32x2_t *>(h_lo + (size_t)m * d) : nullptr;
     const u32x2_t *gr = reinterpret_cast<const u32x2_t *>(gain);
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
         int e4 = t + i * THREADS;
         if (e4 * 4 < d) {
             u32x2_t g = gr[e4];
+            float y0 = bf16lo_to_f32(g.x) * v[i].x * inv, y1 = bf16hi_to_f32(g.x) * v[i].y * inv;
+            float y2 = bf16lo_to_f32(g.y) * v[i].z * inv, y3 = bf16hi_to_f32(g.y) * v[i].w * inv;
             u32x2_t o;
-            o.x = pack_f16x2(bf16lo_to_f32(g.x) * v[i].x * inv, bf16hi_to_f32(g.x) * v[i].y * inv);
-            o.y = pack_f16x2(bf16lo_to_f32(g.y) * v[i].z * inv, bf16hi_to_f32(g.y) * v[i].w * inv);
+            o.x = pack_f16x2(y0, y1);
+            o.y = pack_f16x2(y2, y3);
             hr[e4] = o;
+            if (lr) {  // second half-precision term: what the first rounding lost (y = hi + lo up to 2^-22 relative)
+                u32x2_t r;
+                r.x = pack_f16x2(y0 - f16lo_to_f32(o.x), y1 - f16hi_to_f32(o.x));
+                r.y = pack_f16x2(y2 - f16lo_to_f32(o.y), y3 - f16hi_to_f32(o.y));
+                lr[e4] = r;
+            }
         }
     }
 }
 
 void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_stride, const bf16_t *gain, float eps,
-                        f16_t *h, int M, int d, hipStream_t st) {
+                        f16_t *h, f16_t *h_lo, int M, int d, hipStream_t st) {
     if (M <= 0) return;
     // few rows (decode): many threads per row so that every row streams with many loads in flight;
     // many rows (prefill): fewer threads per row, more rows per compute unit
     if (M <= 1024 && d > 1024)
-        add_rmsnorm_kernel<1024, 2><<<M, 1024, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
+        add_rmsnorm_kernel<1024, 2><<<M, 1024, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, h_lo, d);
     else
-        add_rmsnorm_kernel<256, 8><<<M, 256, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, d);
+        add_rmsnorm_kernel<256, 8><<<M, 256, 0, st>>>(x, part, nsplit, part_stride, gain, eps, h, h_lo, d);
 }
 
 // ------------------------------------------------------------------------------------------------

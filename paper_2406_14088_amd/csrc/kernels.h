@@ -6,9 +6,10 @@
 // ---- elementwise.hip -------------------------------------------------------------------------
 // x[m, :] = widen(emb[clamp(tokens[m]), :])                      tokens int32 [M], emb bf16 [vocab, d], x fp32 [M, d]
 void launch_embed(const int32_t *tokens, const bf16_t *emb, float *x, int M, int d, int vocab, hipStream_t st);
-// x[m, :] += sum_s part[s*part_stride + m*d + :]  (nsplit may be 0);  h[m, :] = half(gain * x / sqrt(mean(x^2) + eps))
+// x[m, :] += sum_s part[s*part_stride + m*d + :]  (nsplit may be 0);  y = gain * x / sqrt(mean(x^2) + eps);
+// h[m, :] = half(y); if h_lo is given, h_lo[m, :] = half(y - h[m, :]) (two-term split: h + h_lo carries ~22 bits of y)
 void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_stride, const bf16_t *gain, float eps,
-                        f16_t *h, int M, int d, hipStream_t st);
+                        f16_t *h, f16_t *h_lo, int M, int d, hipStream_t st);
 // Sums the split partials of the fused QKV projection, rotates q and k heads at their positions and
 // writes q (fp32 and/or half, [M, Hq*hd]) and the cache rows.  Row m is sequence b0 + m / T at
 // position *d_pos0 + m % T.  rope_tab: fp32 [max_seq, hd/2, 2] (cos, sin).

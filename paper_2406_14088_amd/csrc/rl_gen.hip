@@ -61,13 +61,14 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.rows = (int)rows;
     size_t d = s->hidden, qd = (size_t)s->n_heads * s->head_dim, kvd = (size_t)s->n_kv_heads * s->head_dim;
     size_t nqkv = qd + 2 * kvd, nmax = nqkv > d ? nqkv : d;
-    size_t skinny_rows = rows < kSkinnyMaxM ? (size_t)rows : (size_t)kSkinnyMaxM;
-    size_t part_elems = (size_t)rows * nqkv;
+    // the QKV projection may be fed the stacked two-term rows [h; h_lo]: twice the rows, twice the partials
+    size_t skinny_rows = 2 * rows < kSkinnyMaxM ? (size_t)(2 * rows) : (size_t)kSkinnyMaxM;
+    size_t part_elems = (size_t)2 * rows * nqkv;
     if ((size_t)kMaxSplits * skinny_rows * nmax > part_elems) part_elems = (size_t)kMaxSplits * skinny_rows * nmax;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
     p.x = take((size_t)rows * d * 4);
-    p.h = take((size_t)rows * d * 2);
+    p.h = take((size_t)2 * rows * d * 2);
     p.part = take(part_elems * 4);
     p.qf32 = take((size_t)s->max_batch * qd * 4);
     p.qbf = take((size_t)rows * qd * 2);
@@ -107,7 +108,7 @@ struct rl_gen {
     WorkPlan wp;
     int nsplit_attn;
     int B, len;
-    bool graph_on, prof_on;
+    bool graph_on, prof_on, qkv_two_term;
     std::vector<GraphEntry> graphs;
     std::vector<ProfEvent> prof_events;
     std::vector<ProfEvent> prof_pool;
@@ -220,16 +221,23 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         Scope sc(h, RL_GEN_K_EMBED, st);
         launch_embed(tokens, h->tok_emb, h->x(), M, d, s.vocab, st);
     }
+    // The normalised activations that feed the QKV projection are kept as a two-term half split [h; h_lo]
+    // (rows M..2M-1 hold what the first rounding lost): q, k and v errors are what the logits are most
+    // sensitive to, because k and v stay in the cache for every later token.  The projection then runs on 2M
+    // rows and its consumer adds the two row blocks like two more split-K partials.
+    const int terms = h->qkv_two_term ? 2 : 1;
+    f16_t *h_lo = terms == 2 ? h->h() + (size_t)M * d : nullptr;
     {
         Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
-        launch_add_rmsnorm(h->x(), nullptr, 0, 0, L > 0 ? h->lw[W_ATTN_NORM][0] : h->final_norm, s.rms_eps, h->h(), M, d, st);
+        launch_add_rmsnorm(h->x(), nullptr, 0, 0, L > 0 ? h->lw[W_ATTN_NORM][0] : h->final_norm, s.rms_eps, h->h(),
+                           L > 0 ? h_lo : nullptr, M, d, st);
     }
     for (int l = 0; l < L; ++l) {
-        int ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
-                         nullptr, 0, st);
+        int ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l],
+                         kvd, nullptr, 0, st);
         {
             Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
-            launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_len() : h->d_zero(),
+            launch_rope_append(h->part(), ns * terms, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_len() : h->d_zero(),
                                h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
                                decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st);
         }
@@ -245,7 +253,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         ns = project(h, RL_GEN_K_GEMM_O, h->attn(), qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
-            launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), M, d, st);
+            launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), nullptr, M, d, st);
         }
         swiglu_project(h, h->h(), M, l, st);
         ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d,
@@ -253,7 +261,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, l + 1 < L ? h->lw[W_ATTN_NORM][l + 1] : h->final_norm,
-                               s.rms_eps, h->h(), M, d, st);
+                               s.rms_eps, h->h(), l + 1 < L ? h_lo : nullptr, M, d, st);
         }
     }
 }
@@ -351,7 +359,7 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     h->wp = wp;
     h->nsplit_attn = attn_splits(shape);
     h->B = 0; h->len = 0;
-    h->graph_on = true; h->prof_on = false;
+    h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
     h->err[0] = 0;
     memset(h->prof_launches, 0, sizeof h->prof_launches);
     memset(h->prof_ms, 0, sizeof h->prof_ms);
@@ -486,6 +494,14 @@ int rl_gen_set_graph(rl_gen_t *h, int32_t enabled) {
     return RL_GEN_OK;
 }
 
+int rl_gen_set_qkv_terms(rl_gen_t *h, int32_t terms) {
+    if (!h) return RL_GEN_E_NULL;
+    if (terms != 1 && terms != 2) { set_err(h, "rl_gen_set_qkv_terms: terms must be 1 or 2"); return RL_GEN_E_SHAPE; }
+    if ((terms == 2) != h->qkv_two_term) drop_graphs(h);
+    h->qkv_two_term = terms == 2;
+    return RL_GEN_OK;
+}
+
 int rl_gen_reset(rl_gen_t *h) {
     if (!h) return RL_GEN_E_NULL;
     h->B = 0; h->len = 0;
@@ -561,10 +577,10 @@ int rl_op_embed(const int32_t *tokens, const uint16_t *emb, float *x, int32_t M,
 }
 
 int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_stride, const uint16_t *gain, float eps,
-                      uint16_t *h, int32_t M, int32_t d, void *st) {
+                      uint16_t *h, uint16_t *h_lo, int32_t M, int32_t d, void *st) {
     if (!x || !gain || !h || (nsplit > 0 && !part)) return RL_GEN_E_NULL;
     if (M < 0 || d <= 0 || d % 4 || d > 8192 || nsplit < 0) return RL_GEN_E_SHAPE;
-    launch_add_rmsnorm(x, part, nsplit, part_stride, gain, eps, h, M, d, reinterpret_cast<hipStream_t>(st));
+    launch_add_rmsnorm(x, part, nsplit, part_stride, gain, eps, h, h_lo, M, d, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

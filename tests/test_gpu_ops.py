@@ -41,14 +41,18 @@ def test_add_rmsnorm(ops, d, nsplit):
     part = randn_f32((max(nsplit, 1), M, d), 11 + d)
     gain = (1.0 + 0.3 * randn_f32((d,), 12)).to(torch.bfloat16)
     h = torch.empty((M, d), dtype=torch.float16, device=DEV)
+    h_lo = torch.empty((M, d), dtype=torch.float16, device=DEV) if nsplit else None
     x0 = x.clone()
-    ops.add_rmsnorm(x, part, nsplit, M * d, gain, 1e-5, h)
+    ops.add_rmsnorm(x, part, nsplit, M * d, gain, 1e-5, h, h_lo)
     torch.cuda.synchronize()
     xs = np64(x0) + (np64(part[:nsplit]).sum(0) if nsplit else 0.0)
     assert np.abs(np64(x) - xs).max() <= 1e-6 * (1 + np.abs(xs).max())
     ref = orc.rmsnorm(xs, bits(gain), float(np.float32(1e-5)))
     err = np.abs(np64(h) - ref)
     assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.01 + 1e-6).all()
+    if h_lo is not None:     # two-term split: h + h_lo reproduces the fp32 value (fp32 arithmetic: ~1e-6 relative)
+        err2 = np.abs(np64(h) + np64(h_lo) - ref)
+        assert (err2 <= 2e-6 * np.abs(ref) + 1e-7).all(), err2.max()
 
 
 GEMM_CASES = [
