@@ -185,7 +185,7 @@ def cpu_baseline(shape, wl, W):
     import numpy as np
     from oracle import orc
     from workload import make_prompts
-    Bs, Ps, Gs = 2, 16, 3
+    Bs, Ps, Gs = 4, 64, 4      # about 10-20 s of host work at the 7B shape
     Wn = orc.weights_to_numpy(W)            # device -> host copy of the same bf16 values
     om = orc.OracleModel(shape, Wn, Bs, Ps + Gs)
     prompts = make_prompts(wl, batch=Bs, prompt_len=Ps).numpy()
