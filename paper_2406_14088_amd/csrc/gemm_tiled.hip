@@ -13,6 +13,8 @@
 //     work on neighbouring tiles and share their operand panels in that XCD's L2;
 //   * fused epilogues: fp32 store, fp32 accumulate (residual add), SwiGLU (wavefront column 0 holds
 //     the gate tile, column 1 the up tile of the same outputs; exchanged through LDS).
+#include <type_traits>
+
 #include "kernels.h"
 
 #define TG_BK 64
@@ -26,6 +28,7 @@ struct TiledParams {
     int tile_begin[4];
     int col_off[3];
     int64_t lda;
+    uint32_t a_bytes;  // size of A in bytes (range check)
     int M, K, chunks, epilogue;
     int tiles_m, tiles_n;
     void *out;
@@ -70,24 +73,32 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     }
     const int m0 = tile_m * BM;
 
-    // loader mapping: thread -> (row t/8 + 32*i, 16-byte group t%8)
+    // loader mapping: thread -> (row t/8 + 32*i, 16-byte group t%8).  Range-checked buffer loads: rows past
+    // the matrix and K columns past the end get an offset outside the descriptor and come back as zeros,
+    // so the loop needs no branches and the count of outstanding loads is the same on every trip.
     const int lc = t & 7, lr = t >> 3;
-    const f16_t *a_ptr[A_LOADS];
-    bool a_ok[A_LOADS];
+    constexpr uint32_t OOB = 0xFFFFFF00u;
+    __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<f16_t *>(p.A), 0, (int)p.a_bytes, 0x00020000);
+    uint32_t a_off[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
         int row = m0 + lr + 32 * i;
-        a_ok[i] = row < p.M;
-        a_ptr[i] = p.A + (size_t)(a_ok[i] ? row : 0) * p.lda + lc * 8;
+        a_off[i] = row < p.M ? (uint32_t)((size_t)row * p.lda * 2) + (uint32_t)lc * 16u : OOB;
     }
-    const bf16_t *b_ptr[B_LOADS];
+    // B rows of the two halves may come from different matrices: one descriptor per half
+    __amdgpu_buffer_rsrc_t b_rs[2];
+    uint32_t b_off[B_LOADS];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+        b_rs[hh] = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg_h[hh]]), 0,
+                                                      (int)(uint32_t)((size_t)p.rows[seg_h[hh]] * K * 2), 0x00020000);
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
         int r = lr + 32 * i;
-        int h = r / HALF_N;
-        int row = nbase_h[h] + (r - h * HALF_N);
-        int rows = p.rows[seg_h[h]];
-        b_ptr[i] = p.W[seg_h[h]] + (size_t)(row < rows ? row : 0) * K + lc * 8;  // clamped rows are never stored
+        int hh = r / HALF_N;
+        int row = nbase_h[hh] + (r - hh * HALF_N);
+        int rows = p.rows[seg_h[hh]];
+        b_off[i] = (uint32_t)(row < rows ? row : 0) * (uint32_t)K * 2u + (uint32_t)lc * 16u;  // clamped rows are never stored
     }
     u32x4_t ar[A_LOADS], br[B_LOADS];
     f32x16_t acc[WM][WN];
@@ -98,56 +109,74 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    auto load_g = [&](int c) {
-        int k = c * TG_BK;
-        bool kok = k + lc * 8 < K;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (a_ok[i] && kok) v = *reinterpret_cast<const u32x4_t *>(a_ptr[i] + k);
-            ar[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (kok) v = *reinterpret_cast<const u32x4_t *>(b_ptr[i] + k);
-            br[i] = v;
-        }
+    auto load_a1 = [&](int c, int i) {
+        uint32_t kb = (uint32_t)c * (TG_BK * 2);
+        bool kok = c * TG_BK + lc * 8 < K;
+        ar[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)(kok && a_off[i] != OOB ? a_off[i] + kb : OOB), 0, 0);
     };
-    auto store_s = [&](int buf) {
-        f16_t *ad = as + buf * BM * TG_LDS_STRIDE, *bd = bs + buf * BN * TG_LDS_STRIDE;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i)
-            *reinterpret_cast<u32x4_t *>(ad + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = ar[i];
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i)
-            *reinterpret_cast<u32x4_t *>(bd + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = bf16x8_to_f16x8(br[i]);
+    auto load_b1 = [&](int c, int i) {
+        uint32_t kb = (uint32_t)c * (TG_BK * 2);
+        bool kok = c * TG_BK + lc * 8 < K;
+        // piece i belongs to half (32 i) / HALF_N: a compile-time choice of descriptor
+        br[i] = __builtin_amdgcn_raw_buffer_load_b128((32 * i) / HALF_N == 0 ? b_rs[0] : b_rs[1], (int)(kok ? b_off[i] + kb : OOB), 0, 0);
     };
-    auto compute = [&](int buf) {
-        const f16_t *ap = as + buf * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
-        const f16_t *bp = bs + buf * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+    auto store_a1 = [&](int buf, int i) {
+        *reinterpret_cast<u32x4_t *>(as + buf * BM * TG_LDS_STRIDE + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = ar[i];
+    };
+    auto store_b1 = [&](int buf, int i) {
+        *reinterpret_cast<u32x4_t *>(bs + buf * BN * TG_LDS_STRIDE + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = bf16x8_to_f16x8(br[i]);
+    };
+
+    // One K chunk: 4 k-steps of WM*WN MFMAs on the tiles staged one chunk ago.  Interleaved with them, piece by
+    // piece: LDS fragments of the next k-step, the next chunk's operands registers -> LDS (weights widened on the
+    // way), and the loads of the chunk after next into the registers just freed -- so the matrix cores, the LDS
+    // and the memory pipeline overlap although only one wavefront runs per SIMD.
+    constexpr int APS = A_LOADS / 4, BPS = B_LOADS / 4;  // pieces staged per k-step
+    auto body = [&](int c, auto par_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        __syncthreads();  // tiles of chunk c are in LDS buffer PAR; buffer PAR^1 is free
+        const f16_t *ap = as + PAR * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        const f16_t *bp = bs + PAR * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        f16x8_t af[2][WM], bf[2][WN];
 #pragma unroll
-        for (int s = 0; s < TG_BK / 16; ++s) {
-            f16x8_t af[WM], bf[WN];
+        for (int i = 0; i < WM; ++i) af[0][i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE);
 #pragma unroll
-            for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + s * 16);
+        for (int j = 0; j < WN; ++j) bf[0][j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE);
 #pragma unroll
-            for (int j = 0; j < WN; ++j) bf[j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + s * 16);
+        for (int s = 0; s < 4; ++s) {
+            if (s + 1 < 4) {
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+                    af[(s + 1) & 1][i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + (s + 1) * 16);
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    bf[(s + 1) & 1][j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + (s + 1) * 16);
+            }
 #pragma unroll
             for (int i = 0; i < WM; ++i)
 #pragma unroll
-                for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s & 1][i], bf[s & 1][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < APS; ++q) { store_a1(PAR ^ 1, s * APS + q); load_a1(c + 2, s * APS + q); }
+#pragma unroll
+            for (int q = 0; q < BPS; ++q) { store_b1(PAR ^ 1, s * BPS + q); load_b1(c + 2, s * BPS + q); }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    load_g(0);
-    store_s(0);
-    for (int c = 0; c < p.chunks; ++c) {
-        bool more = c + 1 < p.chunks;
-        if (more) load_g(c + 1);
-        __syncthreads();
-        compute(c & 1);
-        if (more) store_s((c + 1) & 1);
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) load_a1(0, i);
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) load_b1(0, i);
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) { store_a1(0, i); load_a1(1, i); }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) { store_b1(0, i); load_b1(1, i); }
+    __builtin_amdgcn_sched_barrier(0);
+    for (int c = 0; c < p.chunks; c += 2) {
+        body(c, std::integral_constant<int, 0>{});
+        body(c + 1, std::integral_constant<int, 1>{});  // past the end: multiplies zero tiles
     }
 
     // ---- epilogue.  Lane holds column (lane & 31) of each 32x32 tile; register e is row
@@ -230,11 +259,11 @@ static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
     gemm_tiled_kernel<WM, WN><<<p.tiles_m * p.tiles_n, TG_THREADS, lds, st>>>(p);
 }
 
-void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
-    if (a.M <= 0) return;
+static void launch_one(const GemmArgs &a, hipStream_t st) {
     TiledParams p;
     p.A = a.A;
     p.lda = a.lda;
+    p.a_bytes = (uint32_t)((((size_t)a.M - 1) * a.lda + a.K) * 2);
     p.M = a.M;
     p.K = a.K;
     p.chunks = ceil_div(a.K, TG_BK);
@@ -251,4 +280,56 @@ void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
     long big_tiles = (long)ceil_div(a.M, 256) * ceil_div(n_total, 256);
     if (a.M >= 1024 && big_tiles >= 256) launch_t<4, 4>(p, a, st);
     else launch_t<2, 2>(p, a, st);
+}
+
+// The kernel addresses each operand through a buffer descriptor with 32-bit byte offsets: operands of
+// TG_MAX_BYTES or more are cut into row blocks (of A) or into per-matrix row blocks (of W) here.
+#define TG_MAX_BYTES 0xF0000000ull
+
+void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
+    if (a.M <= 0) return;
+    const size_t out_elem = a.epilogue == EPI_SWIGLU ? sizeof(f16_t) : sizeof(float);
+    size_t a_bytes = (((size_t)a.M - 1) * a.lda + a.K) * 2;
+    if (a_bytes >= TG_MAX_BYTES) {
+        int rows_max = (int)((TG_MAX_BYTES / ((size_t)a.lda * 2)) / 256 * 256);
+        for (int m = 0; m < a.M; m += rows_max) {
+            GemmArgs s = a;
+            s.A = a.A + (size_t)m * a.lda;
+            s.M = a.M - m < rows_max ? a.M - m : rows_max;
+            s.out = static_cast<char *>(a.out) + (size_t)m * a.ldc * out_elem;
+            launch_gemm_tiled(s, st);
+        }
+        return;
+    }
+    bool w_big = false;
+    for (int i = 0; i < 3; ++i)
+        if (a.W[i] && (size_t)a.rows[i] * a.K * 2 >= TG_MAX_BYTES) w_big = true;
+    if (!w_big) { launch_one(a, st); return; }
+    int rows_max = (int)((TG_MAX_BYTES / ((size_t)a.K * 2)) / 256 * 256);
+    if (a.epilogue == EPI_SWIGLU) {  // gate and up blocks of the same output columns go together
+        for (int n = 0; n < a.rows[0]; n += rows_max) {
+            GemmArgs s = a;
+            int r = a.rows[0] - n < rows_max ? a.rows[0] - n : rows_max;
+            s.W[0] = a.W[0] + (size_t)n * a.K;
+            s.W[1] = a.W[1] + (size_t)n * a.K;
+            s.rows[0] = s.rows[1] = r;
+            s.out = static_cast<char *>(a.out) + (size_t)n * out_elem;
+            launch_one(s, st);
+        }
+        return;
+    }
+    int col = 0;
+    for (int i = 0; i < 3; ++i) {
+        if (!a.W[i] || a.rows[i] <= 0) continue;
+        for (int n = 0; n < a.rows[i]; n += rows_max) {
+            GemmArgs s = a;
+            s.W[0] = a.W[i] + (size_t)n * a.K;
+            s.rows[0] = a.rows[i] - n < rows_max ? a.rows[i] - n : rows_max;
+            s.W[1] = s.W[2] = nullptr;
+            s.rows[1] = s.rows[2] = 0;
+            s.out = static_cast<char *>(a.out) + (size_t)(col + n) * out_elem;
+            launch_one(s, st);
+        }
+        col += a.rows[i];
+    }
 }
