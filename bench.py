@@ -96,10 +96,16 @@ def main():
         del src, dst
 
     def generate(timing=None):
-        """prefill + (G-1) decode steps; tokens stay on the device"""
+        """weight re-layout + prefill + (G-1) decode steps; tokens stay on the device.  The fragment-order weight copies
+        are rebuilt inside every step: in the RLHF loop each generation phase starts from freshly trained weights."""
+        if timing is not None:
+            torch.cuda.synchronize()
+            tp = time.perf_counter()
+        gen.pack_weights()
         if timing is not None:
             torch.cuda.synchronize()
             ta = time.perf_counter()
+            timing["pack_s"] = timing.get("pack_s", 0.0) + ta - tp
         gen.prefill(prompts, next_tokens=buf[0])
         if timing is not None:
             torch.cuda.synchronize()
@@ -133,6 +139,7 @@ def main():
     dec_bytes = sum(decode_bytes(shape, B, t) for t in range(P, P + G - 1))
     pf = prefill_flops(shape, B, P)
     phases = {
+        "pack_weights_ms": split["pack_s"] * 1e3,
         "prefill_ms": split["prefill_s"] * 1e3,
         "prefill_tflops": pf / split["prefill_s"] / 1e12,
         "prefill_frac_of_mfma_peak": pf / split["prefill_s"] / 1e12 / MFMA_PEAK_TFLOPS,

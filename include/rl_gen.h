@@ -88,6 +88,19 @@ int rl_gen_validate_shape(const rl_gen_shape *shape);  /* RL_GEN_OK or RL_GEN_E_
 int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void *kv_arena, size_t kv_bytes,
                   void *work_arena, size_t work_bytes, rl_gen_t **out);
 
+/* Fragment-order copies of the projection matrices for the decode step.  A decode step multiplies only one
+ * row per sequence with every weight matrix, so it lives off streaming the weights once; rl_gen_pack_weights
+ * re-lays the borrowed matrices Wq, Wk, Wv, Wo, gate, up, down of every layer and the LM head into
+ * packed_arena (DEVICE, 256-byte aligned, at least rl_gen_packed_bytes long, caller-owned, borrowed while the
+ * handle lives) in the order the matrix cores read them (IEEE half; layout in rl_gen_ops.h), enqueued on
+ * hip_stream.  Afterwards steps of at most 256 rows (decode, short prefills) read only the copies; longer
+ * prefills keep reading the row-major weights.  Call it again after the weights changed (a training step
+ * between two generation phases); packed_arena == NULL detaches the copies.  Results are the same to fp32
+ * summation order with and without the copies.  Use the same stream as for the following steps, or
+ * synchronise in between. */
+size_t rl_gen_packed_bytes(const rl_gen_shape *shape);
+int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, void *hip_stream);
+
 /* Prefill (Section 2.1: one forward pass that consumes all prompt tokens and yields the first
  * generated token).  tokens: DEVICE int32 [B, T] row-major, 1 <= B <= max_batch, 1 <= T <= max_seq.
  * logits: DEVICE fp32 [B, vocab] of the LAST prompt position, or NULL.  next: DEVICE int32 [B],

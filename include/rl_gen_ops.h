@@ -48,6 +48,23 @@ int rl_op_gemm(const uint16_t *A, int64_t lda, const uint16_t *W0, const uint16_
                int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
                int32_t splits, int32_t epilogue, int32_t kernel, void *hip_stream);
 
+/* Weights in matrix-core fragment order.  rl_op_pack_weights converts W bf16 [N, K] row-major (K % 8 == 0)
+ * into P, rl_op_packed_weight_bytes(N, K) bytes of f16: P[ceil(N/32)][ceil(K/16)][64][8], where element e of
+ * lane l of fragment (nb, ks) is W[32 nb + (l & 31), 16 ks + 8 (l >> 5) + e], widened bf16 -> f16 (exact for
+ * |w| >= 2^-14), zero outside W.  A fragment is the B operand of one 32x32x16 f16 MFMA and 1 KB of consecutive
+ * memory, so the projection below fetches weights straight into the registers the matrix cores read. */
+size_t rl_op_packed_weight_bytes(int32_t N, int32_t K);
+int rl_op_pack_weights(const uint16_t *W, uint16_t *P, int32_t N, int32_t K, void *hip_stream);
+
+/* Projection over packed weights (the decode step's form of rl_op_gemm; same meaning of rows_i, M, K, lda,
+ * out, ldc, split_stride, splits and epilogue).  A_lo: optional second term of the activations (f16 [M, K],
+ * same stride, or NULL): out = (A + A_lo) W^T with both products accumulated in fp32, which is how the
+ * two-term split of rl_op_add_rmsnorm reaches the QKV projection.  nb: 32-column blocks per wavefront,
+ * 1 or 2 (0: chosen from the number of columns); epilogue 1 (SwiGLU) always uses gate block + up block. */
+int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P0, const uint16_t *P1,
+                      const uint16_t *P2, int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out,
+                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, void *hip_stream);
+
 /* Builds the rotary table the library uses: tab fp32 [max_seq, head_dim/2, 2] = (cos, sin) of
  * pos * base^(-2r/head_dim), evaluated in fp64 on the host and copied (synchronously) to `tab`. */
 int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float base);

@@ -61,6 +61,8 @@ def lib():
         "rl_gen_kv_bytes": (sz, [sp]),
         "rl_gen_work_bytes": (sz, [sp]),
         "rl_gen_create": (C.c_int, [sp, C.POINTER(RlGenWeights), vp, sz, vp, sz, C.POINTER(vp)]),
+        "rl_gen_packed_bytes": (sz, [sp]),
+        "rl_gen_pack_weights": (C.c_int, [vp, vp, sz, vp]),
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "rl_gen_set_graph": (C.c_int, [vp, i32]),
@@ -75,6 +77,9 @@ def lib():
         "rl_op_embed": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
         "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, vp, i32, i32, vp]),
         "rl_op_gemm": (C.c_int, [vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
+        "rl_op_packed_weight_bytes": (sz, [i32, i32]),
+        "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
+        "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
@@ -93,10 +98,11 @@ def lib():
 
 
 EXPORTED_SYMBOLS = (
-    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_prefill",
+    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_packed_bytes",
+    "rl_gen_pack_weights", "rl_gen_prefill",
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats",
+    "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_copy")
 
 
@@ -133,9 +139,11 @@ class Generator:
     """rl_gen handle plus the torch tensors (weights, arenas) it borrows.
 
     weights: dict as produced by workload.make_weights, tensors on the GPU, all bf16 or all fp32.
+    packed: also hold fragment-order copies of the projection matrices (what the decode step streams);
+    call pack_weights() again after the weight tensors were updated in place.
     """
 
-    def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int):
+    def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int, packed: bool = True):
         import torch
         self._h = None
         any_w = weights["tok_emb"]
@@ -179,6 +187,22 @@ class Generator:
             raise RlGenError(rc, "rl_gen_create", L.rl_gen_last_error(None).decode())
         self._h = h
         self.max_batch, self.max_seq = max_batch, max_seq
+        self.packed_arena = None
+        if packed:
+            self.pack_weights()
+
+    def pack_weights(self):
+        """(Re)builds the fragment-order weight copies from the current contents of the weight tensors."""
+        import torch
+        if self.packed_arena is None:
+            n = lib().rl_gen_packed_bytes(C.byref(self.cshape))
+            self.packed_arena = torch.empty(max(n, 256), dtype=torch.uint8, device=self.kv_arena.device)
+        self._check(lib().rl_gen_pack_weights(self._h, self.packed_arena.data_ptr(), self.packed_arena.numel(), _stream()),
+                    "rl_gen_pack_weights")
+
+    def unpack_weights(self):
+        """Back to the row-major weights for every projection."""
+        self._check(lib().rl_gen_pack_weights(self._h, None, 0, _stream()), "rl_gen_pack_weights")
 
     def _check(self, rc: int, where: str):
         if rc != 0:
@@ -270,6 +294,21 @@ class _Ops:
         lda = A.stride(0) if lda is None else lda
         self._ck(lib().rl_op_gemm(A.data_ptr(), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K, out.data_ptr(),
                                   ldc, split_stride, splits, epilogue, kernel, _stream()), "rl_op_gemm")
+
+    def packed_weight_bytes(self, N, K):
+        return int(lib().rl_op_packed_weight_bytes(N, K))
+
+    def pack_weights(self, W, P):
+        N, K = W.shape
+        self._ck(lib().rl_op_pack_weights(W.data_ptr(), P.data_ptr(), N, K, _stream()), "rl_op_pack_weights")
+
+    def gemm_packed(self, A, Ps, rows, K, out, ldc, A_lo=None, M=None, lda=None, split_stride=0, splits=1, epilogue=0, nb=0):
+        ptrs = [q.data_ptr() for q in Ps] + [None] * (3 - len(Ps))
+        rows = list(rows) + [0] * (3 - len(rows))
+        M = A.shape[0] if M is None else M
+        lda = A.stride(0) if lda is None else lda
+        self._ck(lib().rl_op_gemm_packed(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K,
+                                         out.data_ptr(), ldc, split_stride, splits, epilogue, nb, _stream()), "rl_op_gemm_packed")
 
     def build_rope_table(self, tab, max_seq, head_dim, base):
         self._ck(lib().rl_op_build_rope_table(tab.data_ptr(), max_seq, head_dim, base), "rl_op_build_rope_table")

@@ -1,0 +1,415 @@
+// Skinny-M GEMM over weights re-laid-out once in matrix-core fragment order (the decode step).
+//
+// A decode step multiplies one row of activations per sequence with every weight matrix: each weight
+// is used for only M (<= 128 per workgroup) multiply-adds, so the step lives off streaming the weights
+// from HBM exactly once, and whatever a compute unit has to do per weight byte besides the multiply
+// (widening bf16, transposing row-major rows into the lane = row layout the matrix cores want) costs
+// throughput.  The weights of a generation phase do not change, so that work is done once:
+//
+//   pack:   W [N, K] bf16 row-major  ->  P [ceil(N/32)][ceil(K/16)][64 lanes][8] IEEE half, where lane l of
+//           fragment (nb, ks) holds W[32 nb + (l & 31), 16 ks + 8 (l >> 5) + 0..7] (zero outside W).
+//           One fragment is exactly the B operand of one v_mfma_f32_32x32x16_f16 and is 1 KB of
+//           consecutive memory; the fragments of one 32-row block follow each other along K.
+//
+//   gemm:   a wavefront owns NB 32-row blocks (= 32 NB output columns) and walks along K: one
+//           16-byte-per-lane load (a whole, contiguous KB) fetches a fragment straight into the
+//           registers the MFMA reads -- no LDS, no conversion, no shuffle on the weight side.  Loads
+//           run two K chunks (2 x 4 NB fragments) ahead in a register ring.
+//           The activation chunk [128 rows, 64 k] is shared by the four wavefronts of a workgroup: it is
+//           copied global -> LDS by the load unit itself (buffer loads with the LDS bit: no registers,
+//           no ds_write), in an XOR-swizzled layout whose fragment reads are bank-conflict free, two
+//           chunks ahead in a three-deep buffer ring.
+//           TERMS = 2 multiplies the same weight fragment with two activation tiles (the two-term split
+//           of the normalised activations) into the same accumulators.
+//           Split-K over workgroups (grid.y) fills the chip; every split writes its own fp32 partial tile
+//           and the consumer adds the partials in a fixed order (deterministic).
+//           Epilogues: fp32 partials / fp32 accumulate through an LDS tile (whole 512-byte rows per
+//           store instruction); SwiGLU with gate block and up block of the same columns held by the same
+//           wavefront, so the nonlinearity needs no exchange.
+#include <type_traits>
+
+#include "kernels.h"
+
+#define PK_BK 64             // K elements per chunk (4 MFMA k-steps)
+#define PK_THREADS 256
+#define PK_BM 128            // activation rows per workgroup (grid.z walks taller batches)
+#define PK_MT 4              // 32-row MFMA tiles along M
+#define PK_OOB 0xFFFFFF00u   // byte offset beyond every descriptor: such a load returns zeros, touches no memory
+#define PK_XTILE (PK_BM * PK_BK * 2)  // bytes of one activation tile in LDS (16 KB)
+#define PK_CT_STRIDE 132     // floats per row of the fp32 output tile in LDS
+#define PK_HT_STRIDE 136     // halves per row of the SwiGLU output tile in LDS
+#define PK_MAX_BYTES 0xF0000000ull
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+// ---------------------------------------------------------------------------------------------------
+// pack
+// ---------------------------------------------------------------------------------------------------
+// One workgroup converts one (32-row block, 64-wide K chunk) = 4 fragments: rows are read as whole
+// 128-byte lines (8 lanes x 16 B per row), widened, transposed through LDS, written as 4 contiguous KB.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *W, f16_t *P, int N, int K, int ksteps) {
+    __shared__ __attribute__((aligned(16))) uint32_t tile[32][36];  // 32 rows x 64 halves (+ pad)
+    const int t = threadIdx.x;
+    const int nb = blockIdx.y, kc = blockIdx.x;
+    const int r = t >> 3, g = t & 7;  // row of the block, 16-byte piece of the 128-byte chunk
+    const int n = nb * 32 + r, k = kc * 64 + g * 8;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (n < N && k < K) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t *>(W + (size_t)n * K + k));  // K % 8 == 0
+    *reinterpret_cast<u32x4_t *>(&tile[r][g * 4]) = v;
+    __syncthreads();
+    // thread t writes lane (t & 63) of fragment ks = 4 kc + t / 64
+    const int s = t >> 6, l = t & 63;
+    const int ks = kc * 4 + s;
+    if (ks < ksteps) {
+        u32x4_t o = *reinterpret_cast<const u32x4_t *>(&tile[l & 31][s * 8 + (l >> 5) * 4]);
+        *reinterpret_cast<u32x4_t *>(P + (((size_t)nb * ksteps + ks) * 64 + l) * 8) = o;
+    }
+}
+
+size_t packed_weight_bytes(int N, int K) { return (size_t)ceil_div(N, 32) * ceil_div(K, 16) * 1024; }
+
+void launch_pack_weights(const bf16_t *W, f16_t *P, int N, int K, hipStream_t st) {
+    if (N <= 0 || K <= 0) return;
+    int ksteps = ceil_div(K, 16);
+    // grid.y is limited to 65535 blocks: walk taller matrices in slabs
+    const int max_nb = 65535;
+    int nblocks = ceil_div(N, 32);
+    for (int b0 = 0; b0 < nblocks; b0 += max_nb) {
+        int nbl = nblocks - b0 < max_nb ? nblocks - b0 : max_nb;
+        int rows_left = N - b0 * 32;
+        pack_weights_kernel<<<dim3(ceil_div(K, 64), nbl), 256, 0, st>>>(W + (size_t)b0 * 32 * K, P + (size_t)b0 * ksteps * 512,
+                                                                     rows_left, K, ksteps);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// gemm
+// ---------------------------------------------------------------------------------------------------
+struct PackedParams {
+    const f16_t *A;     // first-term activations [M, K], row stride lda
+    const f16_t *A_lo;  // second-term activations (TERMS == 2), same shape and stride
+    const f16_t *P[3];  // packed matrices
+    int rows[3];
+    int tile_begin[4];  // first n-tile of each matrix (prefix sums), tile_begin[3] = total
+    int col_off[3];
+    int lda_bytes;
+    uint32_t a_bytes;   // size of each activation matrix in bytes (range check)
+    int M, K, ksteps, chunks, splits, epilogue;
+    void *out;
+    int64_t ldc;
+    size_t split_stride;
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t pk_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <int NB, int TERMS>
+__global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int MT = PK_MT, BM = PK_BM;
+    constexpr int NBUF = TERMS == 1 ? 3 : 2;  // activation buffers: the copy of chunk c + NBUF - 1 runs during chunk c
+    constexpr int NBF = 4 * NB;               // weight fragments per chunk and wavefront
+    constexpr int HS = 4 * TERMS;             // (k-step, term) pairs per chunk
+    constexpr int XBUF = TERMS * PK_XTILE;    // bytes of one activation buffer
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int K = p.K;
+    const int m0 = blockIdx.z * BM;
+    const int Mloc = p.M - m0 < BM ? p.M - m0 : BM;
+
+    // ---- which 32-row blocks does this wavefront own?  Slot j of wavefront w:
+    //      fp32 epilogues: block 4 NB tile + 4 j + w of its matrix (pass j of the epilogue covers 128 adjacent columns);
+    //      SwiGLU:         j = 0 gate block, j = 1 up block, both number 4 tile + w.
+    const int tile = blockIdx.x;
+    int seg = tile >= p.tile_begin[2] ? 2 : (tile >= p.tile_begin[1] ? 1 : 0);
+    const bool swiglu = p.epilogue == EPI_SWIGLU;
+    if (swiglu) seg = 0;
+    const int ltile = tile - p.tile_begin[seg];
+    const int rows = seg == 0 ? p.rows[0] : (seg == 1 ? p.rows[1] : p.rows[2]);
+    const int nblocks = (rows + 31) >> 5;
+    __amdgpu_buffer_rsrc_t wr[NB];
+    uint32_t w_off[NB];
+    bool w_ok[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        int nb = swiglu ? ltile * 4 + w : (ltile * NB + j) * 4 + w;
+        const f16_t *P = swiglu ? (j == 0 ? p.P[0] : p.P[1]) : (seg == 0 ? p.P[0] : (seg == 1 ? p.P[1] : p.P[2]));
+        wr[j] = pk_rsrc(P, (uint32_t)((size_t)nblocks * p.ksteps * 1024));
+        w_ok[j] = nb < nblocks;
+        w_off[j] = ((uint32_t)nb * (uint32_t)p.ksteps * 64u + (uint32_t)lane) * 16u;
+    }
+
+    // ---- K range of this split
+    const int c0 = (int)(((int64_t)blockIdx.y * p.chunks) / p.splits);
+    const int c1 = (int)(((int64_t)(blockIdx.y + 1) * p.chunks) / p.splits);
+    const int ks_end = c1 * 4 < p.ksteps ? c1 * 4 : p.ksteps;
+
+    // ---- activation copy global -> LDS.  Instruction i of wavefront w fills the 1 KB block of rows
+    //      32 w + 8 i .. + 7 of a tile: lane l lands at byte 16 l of the block, i.e. row l / 8, slot l % 8, and
+    //      fetches piece (l % 8) ^ (l / 8) of that row, so that piece g of row r sits in slot g ^ (r & 7).
+    __amdgpu_buffer_rsrc_t ar[TERMS];
+    ar[0] = pk_rsrc(p.A, p.a_bytes);
+    if (TERMS == 2) ar[TERMS - 1] = pk_rsrc(p.A_lo, p.a_bytes);
+    const int xg = (lane & 7) ^ (lane >> 3);
+    uint32_t x_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int row = w * 32 + 8 * i + (lane >> 3);
+        x_off[i] = row < Mloc ? (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)xg * 16u : PK_OOB;
+    }
+    auto copy_x = [&](int c, int buf) {
+        bool ok = c < c1 && (c * PK_BK + xg * 8 < K);
+        uint32_t cb = (uint32_t)c * (PK_BK * 2);
+#pragma unroll
+        for (int tm = 0; tm < TERMS; ++tm)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                unsigned char *dst = smem + buf * XBUF + tm * PK_XTILE + (w * 32 + 8 * i) * 128;
+                uint32_t off = ok && x_off[i] != PK_OOB ? x_off[i] + cb : PK_OOB;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(ar[tm], LDS_PTR(dst), 16, (int)off, 0, 0, 0);
+#else
+                (void)dst; (void)off;
+#endif
+            }
+    };
+    // fragment of k-step s, tile mt: row 32 mt + (lane & 31), pieces 2 s + (lane >> 5)
+    int xld[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) xld[s] = (lane & 31) * 128 + (((2 * s + (lane >> 5)) ^ (lane & 7)) << 4);
+
+    u32x4_t ring[2 * NBF];  // weight fragments in flight: slots (i & 1) * NBF + s * NB + j belong to chunk c0 + i
+    auto load_w = [&](int c, int s, int j, int slot) {
+        int ks = c * 4 + s;
+        uint32_t off = (ks < ks_end && w_ok[j]) ? w_off[j] + (uint32_t)ks * 1024u : PK_OOB;
+        ring[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr[j], (int)off, 0, 0);
+    };
+
+    f32x16_t acc[NB][MT];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+    // One chunk (PAR = parity of its index relative to c0): all activation copies of a trip are issued
+    // before its weight loads -- the hardware retires loads in issue order, so waiting for the (short, L2)
+    // activation copy never waits for younger weight loads.
+    auto body = [&](int c, int buf, auto par_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        __syncthreads();  // the tile of chunk c has landed for every wavefront; buffer of chunk c-1 is free
+        int nbuf = buf + NBUF - 1;
+        if (nbuf >= NBUF) nbuf -= NBUF;
+        copy_x(c + NBUF - 1, nbuf);
+        const unsigned char *xb = smem + buf * XBUF;
+        f16x8_t a[2][MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a[0][mt] = *reinterpret_cast<const f16x8_t *>(xb + xld[0] + mt * 4096);
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
+            const int s = hs / TERMS, tm = hs % TERMS;
+            if (hs + 1 < HS) {
+                const int s2 = (hs + 1) / TERMS, tm2 = (hs + 1) % TERMS;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    a[(hs + 1) & 1][mt] = *reinterpret_cast<const f16x8_t *>(xb + tm2 * PK_XTILE + xld[s2] + mt * 4096);
+            }
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[j][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[hs & 1][mt], __builtin_bit_cast(f16x8_t, ring[PAR * NBF + s * NB + j]),
+                                                                      acc[j][mt], 0, 0, 0);
+            if (tm == TERMS - 1) {
+#pragma unroll
+                for (int j = 0; j < NB; ++j) load_w(c + 2, s, j, PAR * NBF + s * NB + j);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    if (c0 < c1) {
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i) copy_x(c0 + i, i);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int j = 0; j < NB; ++j) load_w(c0 + i, s, j, i * NBF + s * NB + j);
+        __builtin_amdgcn_sched_barrier(0);
+        int buf = 0;
+        for (int c = c0; c < c1; c += 2) {
+            body(c, buf, std::integral_constant<int, 0>{});
+            buf = buf + 1 == NBUF ? 0 : buf + 1;
+            body(c + 1, buf, std::integral_constant<int, 1>{});  // past the end: multiplies zero tiles
+            buf = buf + 1 == NBUF ? 0 : buf + 1;
+        }
+    }
+    // The copies issued for chunks past the end write zeros into the buffers: they must have landed before
+    // the epilogue reuses that memory.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();  // every wavefront is done reading the activation buffers
+
+    // ---- epilogues.  Lane holds column (lane & 31) of its block; register e of tile mt is row
+    //      32 mt + 8 (e / 4) + 4 (lane >> 5) + (e % 4).
+    if (!swiglu) {
+        float *ct = reinterpret_cast<float *>(smem);  // [BM][PK_CT_STRIDE]
+        float *out = reinterpret_cast<float *>(p.out) + (size_t)blockIdx.y * p.split_stride;
+        const bool accumulate = p.epilogue == EPI_F32_ACC;
+        const int c4 = (t & 31) * 4, rr = t >> 5;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (j > 0) __syncthreads();
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    int m = mt * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    ct[m * PK_CT_STRIDE + w * 32 + (lane & 31)] = acc[j][mt][e];
+                }
+            __syncthreads();
+            const int n_first = (ltile * NB + j) * 128;  // first weight row of this pass inside its matrix
+            const int ncols = rows - n_first;             // valid columns (may exceed 128, may be <= 0)
+            // 32 lanes x float4 = one 512-byte output row; 8 rows per pass
+#pragma unroll
+            for (int i = 0; i < BM / 8; ++i) {
+                int m = rr + 8 * i;
+                if (m < Mloc && c4 < ncols) {
+                    f32x4_t v = *reinterpret_cast<const f32x4_t *>(ct + m * PK_CT_STRIDE + c4);
+                    float *dst = out + (size_t)(m0 + m) * p.ldc + p.col_off[seg] + n_first + c4;
+                    if (c4 + 4 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+                        if (accumulate) v += *reinterpret_cast<const f32x4_t *>(dst);
+                        *reinterpret_cast<f32x4_t *>(dst) = v;
+                    } else {
+                        for (int e = 0; e < 4 && c4 + e < ncols; ++e) dst[e] = accumulate ? dst[e] + v[e] : v[e];
+                    }
+                }
+            }
+        }
+    } else if (NB == 2) {
+        f16_t *ht = reinterpret_cast<f16_t *>(smem);  // [BM][PK_HT_STRIDE]
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int m = mt * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                float g = acc[0][mt][e], u = acc[NB - 1][mt][e];
+                ht[m * PK_HT_STRIDE + w * 32 + (lane & 31)] = f32_to_f16(g / (1.0f + expf(-g)) * u);
+            }
+        __syncthreads();
+        f16_t *out = reinterpret_cast<f16_t *>(p.out);
+        const int c8 = (t & 15) * 8, rr = t >> 4;  // 16 lanes x 16 B = one 256-byte output row; 16 rows per pass
+        const int ncols = rows - ltile * 128;
+#pragma unroll
+        for (int i = 0; i < BM / 16; ++i) {
+            int m = rr + 16 * i;
+            if (m < Mloc && c8 < ncols) {
+                f16_t *dst = out + (size_t)(m0 + m) * p.ldc + ltile * 128 + c8;
+                const f16_t *srcp = ht + m * PK_HT_STRIDE + c8;
+                if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+                    *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
+                } else {
+                    for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+                }
+            }
+        }
+    }
+}
+
+template <int NB, int TERMS>
+static void launch_p(PackedParams &p, int tiles, hipStream_t st) {
+    constexpr int NBUF = TERMS == 1 ? 3 : 2;
+    size_t lds = (size_t)NBUF * TERMS * PK_XTILE;
+    size_t epi = (size_t)PK_BM * PK_CT_STRIDE * sizeof(float);
+    if (epi > lds) lds = epi;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_kernel<NB, TERMS>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    gemm_packed_kernel<NB, TERMS><<<dim3(tiles, p.splits, ceil_div(p.M, PK_BM)), PK_THREADS, lds, st>>>(p);
+}
+
+// columns per workgroup: 128 NB (fp32 epilogues), 128 (SwiGLU)
+int gemm_packed_default_nb(int N) { (void)N; return 1; }
+
+int gemm_packed_default_splits(int N, int K, int nb, int M) {
+    int tiles = ceil_div(N, 128 * nb) * ceil_div(M, PK_BM);
+    int chunks = ceil_div(K, PK_BK);
+    int s = 256 / (tiles > 0 ? tiles : 1);  // aim at one 4-wavefront workgroup per compute unit
+    if (s < 1) s = 1;
+    if (s > chunks / 8) s = chunks / 8 > 0 ? chunks / 8 : 1;  // keep at least 8 chunks per split
+    if (s > 16) s = 16;
+    return s;
+}
+void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
+    if (a.M <= 0) return;
+    // 32-bit byte offsets inside the kernel: a packed matrix of PK_MAX_BYTES or more is walked in row slabs
+    const size_t row_bytes = (size_t)ceil_div(a.K, 16) * 32;  // packed bytes per weight row
+    bool big = false;
+    for (int i = 0; i < 3; ++i)
+        if (a.P[i] && (size_t)ceil_div(a.rows[i], 32) * 32 * row_bytes >= PK_MAX_BYTES) big = true;
+    if (big) {
+        const int rows_max = (int)((PK_MAX_BYTES / row_bytes) / 256 * 256);
+        const size_t out_elem = a.epilogue == EPI_SWIGLU ? sizeof(f16_t) : sizeof(float);
+        int col = 0;
+        for (int i = 0; i < (a.epilogue == EPI_SWIGLU ? 1 : 3); ++i) {
+            if (!a.P[i] || a.rows[i] <= 0) continue;
+            for (int n = 0; n < a.rows[i]; n += rows_max) {
+                PackedGemmArgs s = a;
+                const size_t skip = (size_t)(n / 32) * ceil_div(a.K, 16) * 512;  // halves
+                s.P[0] = a.P[i] + skip;
+                s.rows[0] = a.rows[i] - n < rows_max ? a.rows[i] - n : rows_max;
+                s.P[1] = s.P[2] = nullptr;
+                s.rows[1] = s.rows[2] = 0;
+                if (a.epilogue == EPI_SWIGLU) { s.P[1] = a.P[1] + skip; s.rows[1] = s.rows[0]; }
+                s.out = static_cast<char *>(a.out) + (size_t)(col + n) * out_elem;
+                launch_gemm_packed(s, st);
+            }
+            col += a.rows[i];
+        }
+        return;
+    }
+    PackedParams p;
+    p.A = a.A;
+    p.A_lo = a.A_lo;
+    p.lda_bytes = (int)(a.lda * 2);
+    p.a_bytes = (uint32_t)((((size_t)a.M - 1) * a.lda + a.K) * 2);
+    p.M = a.M;
+    p.K = a.K;
+    p.ksteps = ceil_div(a.K, 16);
+    p.chunks = ceil_div(a.K, PK_BK);
+    p.epilogue = a.epilogue;
+    p.splits = a.epilogue != EPI_F32 ? 1 : (a.splits < 1 ? 1 : a.splits);
+    if (p.splits > p.chunks) p.splits = p.chunks;
+    p.out = a.out;
+    p.ldc = a.ldc;
+    p.split_stride = a.split_stride;
+    const bool swiglu = a.epilogue == EPI_SWIGLU;
+    const int nb = swiglu ? 2 : (a.nb == 2 ? 2 : 1);
+    int tiles = 0, col = 0;
+    for (int i = 0; i < 3; ++i) {
+        p.P[i] = a.P[i] ? a.P[i] : a.P[0];
+        p.rows[i] = a.P[i] ? a.rows[i] : 0;
+        p.tile_begin[i] = tiles;
+        p.col_off[i] = col;
+        if (swiglu) continue;
+        tiles += ceil_div(p.rows[i], 128 * nb);
+        col += p.rows[i];
+    }
+    if (swiglu) tiles = ceil_div(a.rows[0], 128);
+    p.tile_begin[3] = tiles;
+    if (tiles <= 0) return;
+    const bool two = a.A_lo != nullptr;
+    if (nb == 2) {
+        if (two) launch_p<2, 2>(p, tiles, st);
+        else launch_p<2, 1>(p, tiles, st);
+    } else {
+        if (two) launch_p<1, 2>(p, tiles, st);
+        else launch_p<1, 1>(p, tiles, st);
+    }
+}

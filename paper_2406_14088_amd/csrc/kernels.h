@@ -54,6 +54,30 @@ void launch_gemm_skinny(const GemmArgs &a, hipStream_t st);
 void launch_gemm_tiled(const GemmArgs &a, hipStream_t st);
 int gemm_skinny_default_splits(int M, int N, int K);
 
+// ---- gemm_packed.hip -----------------------------------------------------------------------------
+// Weights re-laid-out once in matrix-core fragment order: P[ceil(N/32)][ceil(K/16)][64 lanes][8] halves, lane l of
+// fragment (nb, ks) = W[32 nb + (l & 31), 16 ks + 8 (l >> 5) + 0..7], zero outside W.
+size_t packed_weight_bytes(int N, int K);
+void launch_pack_weights(const bf16_t *W, f16_t *P, int N, int K, hipStream_t st);  // K % 8 == 0
+struct PackedGemmArgs {
+    const f16_t *A;       // [M, K] half, row stride lda (elements)
+    const f16_t *A_lo;    // optional second term of the activations (same shape and stride): out = (A + A_lo) W^T
+    int64_t lda;
+    const f16_t *P[3];    // packed matrices, side by side along the output columns as in GemmArgs
+    int rows[3];
+    int M, K;
+    void *out;
+    int64_t ldc;
+    size_t split_stride;
+    int splits;
+    int epilogue;         // GemmEpilogue; EPI_SWIGLU: P[0] = gate, P[1] = up
+    int nb;               // 32-column blocks per wavefront, 1 or 2 (fp32 epilogues; SwiGLU always uses 2)
+};
+// M of any size (row blocks of 128 re-stream the weights; meant for M <= 256).
+void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st);
+int gemm_packed_default_nb(int N);
+int gemm_packed_default_splits(int N, int K, int nb, int M);
+
 // ---- attention_decode.hip ------------------------------------------------------------------------
 // One new query per (sequence, query head) against cache rows 0 .. *d_len (inclusive).
 // q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's slabs (half); out half [B, Hq*hd].

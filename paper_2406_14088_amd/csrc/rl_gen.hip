@@ -103,6 +103,10 @@ struct rl_gen {
     std::vector<const bf16_t *> lw[9];
     const bf16_t *tok_emb, *final_norm, *lm_head;
     std::vector<void *> owned;
+    // fragment-order copies of the projection matrices (decode path); empty until rl_gen_pack_weights
+    std::vector<const f16_t *> pw[9];
+    const f16_t *p_lm_head;
+    bool packed;
     f16_t *kv;
     unsigned char *work;
     WorkPlan wp;
@@ -173,6 +177,24 @@ struct Scope {
     }
 };
 
+// Projection of M <= kSkinnyMaxM rows over fragment-order weights: fp32 split-K partials in h->part().
+// A_lo (optional): second term of the activations, folded into the same accumulators.
+int project_packed(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, int M, int K, const f16_t *P0, int r0,
+                   const f16_t *P1, int r1, const f16_t *P2, int r2, hipStream_t st) {
+    PackedGemmArgs a;
+    a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
+    a.P[0] = P0; a.P[1] = P1; a.P[2] = P2;
+    a.rows[0] = r0; a.rows[1] = r1; a.rows[2] = r2;
+    int N = r0 + r1 + r2;
+    a.nb = gemm_packed_default_nb(N);
+    int splits = gemm_packed_default_splits(N, K, a.nb, M);
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    a.out = h->part(); a.ldc = N; a.split_stride = (size_t)M * N; a.splits = splits; a.epilogue = EPI_F32;
+    Scope sc(h, cls, st);
+    launch_gemm_packed(a, st);
+    return splits;
+}
+
 // One projection.  Returns the number of fp32 partials written to h->part() (0 when the result was
 // accumulated straight into `acc_out`).
 int project(rl_gen *h, int cls, const f16_t *A, int64_t lda, int M, int K, const bf16_t *W0, int r0, const bf16_t *W1,
@@ -233,11 +255,17 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
                            L > 0 ? h_lo : nullptr, M, d, st);
     }
     for (int l = 0; l < L; ++l) {
-        int ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l],
-                         kvd, nullptr, 0, st);
+        const bool pk = h->packed && M <= kSkinnyMaxM;
+        int ns;
+        if (pk)  // both terms go through the same weight fragments into the same accumulators
+            ns = project_packed(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->pw[W_Q][l], qd, h->pw[W_K][l], kvd, h->pw[W_V][l],
+                                kvd, st);
+        else
+            ns = terms * project(h, RL_GEN_K_GEMM_QKV, h->h(), d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd,
+                                 h->lw[W_V][l], kvd, nullptr, 0, st);
         {
             Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
-            launch_rope_append(h->part(), ns * terms, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_len() : h->d_zero(),
+            launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_len() : h->d_zero(),
                                h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
                                decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st);
         }
@@ -250,14 +278,17 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             launch_prefill_attention(h->qbf(), h->kslab(l), h->vslab(l), h->attn(), nb, b0, T, s.n_heads, s.n_kv_heads,
                                      s.head_dim, s.max_seq, st);
         }
-        ns = project(h, RL_GEN_K_GEMM_O, h->attn(), qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
+        if (pk) ns = project_packed(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->pw[W_O][l], d, nullptr, 0, nullptr, 0, st);
+        else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), nullptr, M, d, st);
         }
         swiglu_project(h, h->h(), M, l, st);
-        ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d,
-                     st);
+        if (pk)
+            ns = project_packed(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->pw[W_DOWN][l], d, nullptr, 0, nullptr, 0, st);
+        else
+            ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, l + 1 < L ? h->lw[W_ATTN_NORM][l + 1] : h->final_norm,
@@ -275,7 +306,14 @@ void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st) {
     a.rows[0] = s.vocab; a.rows[1] = 0; a.rows[2] = 0;
     a.out = logits + (size_t)b0 * s.vocab; a.ldc = s.vocab; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
     Scope sc(h, RL_GEN_K_GEMM_LM_HEAD, st);
-    if (nb <= kSkinnyMaxM) launch_gemm_skinny(a, st);
+    if (h->packed && nb <= kSkinnyMaxM) {
+        PackedGemmArgs q;
+        q.A = a.A; q.A_lo = nullptr; q.lda = a.lda; q.M = nb; q.K = s.hidden;
+        q.P[0] = h->p_lm_head; q.P[1] = nullptr; q.P[2] = nullptr;
+        q.rows[0] = s.vocab; q.rows[1] = 0; q.rows[2] = 0;
+        q.out = a.out; q.ldc = s.vocab; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_F32; q.nb = 1;
+        launch_gemm_packed(q, st);
+    } else if (nb <= kSkinnyMaxM) launch_gemm_skinny(a, st);
     else launch_gemm_tiled(a, st);
 }
 
@@ -329,6 +367,60 @@ size_t rl_gen_work_bytes(const rl_gen_shape *s) {
     return plan_work(s).total;
 }
 
+// packed arena: per layer Wq, Wk, Wv, Wo, gate, up, down, then the LM head; every matrix 256-byte aligned
+static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs) {
+    const int d = s->hidden, qd = s->n_heads * s->head_dim, kvd = s->n_kv_heads * s->head_dim;
+    const int NK[7][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {s->ffn, d}, {s->ffn, d}, {d, s->ffn}};
+    size_t off = 0;
+    for (int l = 0; l < s->n_layers; ++l)
+        for (int m = 0; m < 7; ++m) {
+            if (offs) offs->push_back(off);
+            off += align_up(packed_weight_bytes(NK[m][0], NK[m][1]));
+        }
+    if (offs) offs->push_back(off);
+    off += align_up(packed_weight_bytes(s->vocab, d));
+    return off;
+}
+
+size_t rl_gen_packed_bytes(const rl_gen_shape *s) {
+    if (validate(s) != RL_GEN_OK) return 0;
+    return packed_plan(s, nullptr);
+}
+
+int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    drop_graphs(h);  // captured decode steps hold the old weight pointers
+    if (!packed_arena) {
+        h->packed = false;
+        return RL_GEN_OK;
+    }
+    std::vector<size_t> offs;
+    size_t need = packed_plan(&h->s, &offs);
+    if (packed_bytes < need) { set_err(h, "rl_gen_pack_weights: arena too small (%zu < %zu)", packed_bytes, need); return RL_GEN_E_CAPACITY; }
+    if ((uintptr_t)packed_arena % kAlign) { set_err(h, "rl_gen_pack_weights: arena not 256-byte aligned"); return RL_GEN_E_SHAPE; }
+    const rl_gen_shape &s = h->s;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
+    const int which[7] = {W_Q, W_K, W_V, W_O, W_GATE, W_UP, W_DOWN};
+    const int NK[7][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {s.ffn, d}, {s.ffn, d}, {d, s.ffn}};
+    unsigned char *base = reinterpret_cast<unsigned char *>(packed_arena);
+    for (int m = 0; m < 7; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
+    size_t i = 0;
+    for (int l = 0; l < s.n_layers; ++l)
+        for (int m = 0; m < 7; ++m, ++i) {
+            f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i]);
+            launch_pack_weights(h->lw[which[m]][l], dst, NK[m][0], NK[m][1], st);
+            h->pw[which[m]][l] = dst;
+        }
+    f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i]);
+    launch_pack_weights(h->lm_head, dst, s.vocab, d, st);
+    h->p_lm_head = dst;
+    int rc = check_hip(h, "rl_gen_pack_weights");
+    if (rc != RL_GEN_OK) return rc;
+    h->packed = true;
+    return RL_GEN_OK;
+}
+
 int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_arena, size_t kv_bytes, void *work_arena,
                   size_t work_bytes, rl_gen_t **out) {
     if (!shape || !w || !out) { set_err(nullptr, "rl_gen_create: NULL argument"); return RL_GEN_E_NULL; }
@@ -360,6 +452,7 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     h->nsplit_attn = attn_splits(shape);
     h->B = 0; h->len = 0;
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
+    h->packed = false; h->p_lm_head = nullptr;
     h->err[0] = 0;
     memset(h->prof_launches, 0, sizeof h->prof_launches);
     memset(h->prof_ms, 0, sizeof h->prof_ms);
@@ -604,6 +697,37 @@ int rl_op_gemm(const uint16_t *A, int64_t lda, const uint16_t *W0, const uint16_
     bool skinny = kernel == 1 || (kernel == 0 && M <= kSkinnyMaxM);
     if (skinny) launch_gemm_skinny(a, reinterpret_cast<hipStream_t>(st));
     else launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+size_t rl_op_packed_weight_bytes(int32_t N, int32_t K) {
+    if (N <= 0 || K <= 0) return 0;
+    return packed_weight_bytes(N, K);
+}
+
+int rl_op_pack_weights(const uint16_t *W, uint16_t *P, int32_t N, int32_t K, void *st) {
+    if (!W || !P) return RL_GEN_E_NULL;
+    if (N <= 0 || K <= 0 || K % 8) return RL_GEN_E_SHAPE;
+    launch_pack_weights(W, P, N, K, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P0, const uint16_t *P1,
+                      const uint16_t *P2, int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out,
+                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, void *st) {
+    if (!A || !P0 || !out) return RL_GEN_E_NULL;
+    if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
+    if (epilogue < 0 || epilogue > 2 || splits < 1 || nb < 0 || nb > 2) return RL_GEN_E_SHAPE;
+    if (epilogue == EPI_SWIGLU && (!P1 || rows1 != rows0 || P2)) return RL_GEN_E_SHAPE;
+    if (epilogue != EPI_F32 && splits != 1) return RL_GEN_E_SHAPE;
+    if (((uint64_t)M * (uint64_t)lda + (uint64_t)K) * 2 > 0xf0000000ull) return RL_GEN_E_SHAPE;
+    PackedGemmArgs a;
+    a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
+    a.P[0] = P0; a.P[1] = rows1 > 0 ? P1 : nullptr; a.P[2] = rows2 > 0 ? P2 : nullptr;
+    a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
+    a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue;
+    a.nb = nb == 0 ? gemm_packed_default_nb(rows0 + rows1 + rows2) : nb;
+    launch_gemm_packed(a, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

@@ -21,14 +21,14 @@ LOGIT_TOL = 3e-2
 TOTALS = {"agree": 0, "total": 0}
 
 
-def run_teacher_forced(shape, seed_index, B, P, G, graph=True, max_batch=None, max_seq=None, std=0.02):
+def run_teacher_forced(shape, seed_index, B, P, G, graph=True, max_batch=None, max_seq=None, std=0.02, packed=True):
     from paper_2406_14088_amd import Generator
     wl = Workload("t", seed_index, shape, B, P, G)
     W = make_weights(shape, seed_index, device="cpu", std=std)
     Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
     prompts = make_prompts(wl)
     om = orc.OracleModel(shape, orc.weights_to_numpy(W), B, P + G)
-    gen = Generator(shape, Wg, max_batch or B, max_seq or (P + G))
+    gen = Generator(shape, Wg, max_batch or B, max_seq or (P + G), packed=packed)
     gen.set_graph(graph)
     o_logits, o_next = om.prefill(prompts.numpy())
     g_logits, g_next = gen.prefill(prompts.to(DEV))
@@ -72,11 +72,12 @@ def check(shape, seed_index, B, P, G, **kw):
     return worst, agreement
 
 
+@pytest.mark.parametrize("packed", [True, False])
 @pytest.mark.parametrize("graph", [True, False])
-def test_tiny_config_full_workload(graph):
+def test_tiny_config_full_workload(graph, packed):
     wl = PRESETS["tiny"]
-    step(f"tiny preset: B={wl.batch} P={wl.prompt_len} G={wl.gen_len} graph={graph}")
-    check(wl.shape, wl.index, wl.batch, wl.prompt_len, wl.gen_len, graph=graph)
+    step(f"tiny preset: B={wl.batch} P={wl.prompt_len} G={wl.gen_len} graph={graph} packed={packed}")
+    check(wl.shape, wl.index, wl.batch, wl.prompt_len, wl.gen_len, graph=graph, packed=packed)
 
 
 def test_tiny_interleaved_rope_and_spare_capacity():
@@ -93,6 +94,7 @@ def test_gqa_small_model():
 def test_batch_256_and_above_uses_wide_tiles():
     s = ModelShape(1, 256, 4, 4, 64, 688, 1024)
     check(s, 13, 256, 3, 3)
+    check(s, 13, 256, 3, 3, packed=False)
     check(s, 14, 300, 2, 3)     # more than 256 rows per decode step: the tiled projection path
 
 
@@ -102,10 +104,11 @@ def test_long_sequences_split_attention():
     check(s, 15, 2, 333, 4, max_seq=2048)
 
 
-def test_width_of_7b_reduced_depth():
+@pytest.mark.parametrize("packed", [True, False])
+def test_width_of_7b_reduced_depth(packed):
     s = PRESETS["llama7b"].shape.with_layers(2)
-    step("7B width (hidden 4096, 32 heads, FFN 11008, vocab 32000), 2 layers")
-    check(s, 2, 4, 32, 4)
+    step(f"7B width (hidden 4096, 32 heads, FFN 11008, vocab 32000), 2 layers, packed={packed}")
+    check(s, 2, 4, 32, 4, packed=packed)
 
 
 def test_width_of_13b_reduced_depth():
@@ -162,6 +165,33 @@ def test_free_running_generation_is_deterministic_and_graph_invariant():
         gen.close()
     for t, l in runs[1:]:
         assert torch.equal(t, runs[0][0]) and torch.equal(l, runs[0][1])
+
+
+def test_repacking_follows_a_weight_update():
+    """The fragment-order copies are a snapshot: after the weight tensors change in place (a training step between two
+    generation phases) pack_weights() must be called, and then the step computes with the new weights."""
+    from paper_2406_14088_amd import Generator
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    W2 = make_weights(wl.shape, wl.index + 40, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    ref = Generator(wl.shape, W2, wl.batch, wl.max_seq, packed=False)
+    want, _ = ref.prefill(prompts)
+    gen = Generator(wl.shape, W, wl.batch, wl.max_seq)
+    before, _ = gen.prefill(prompts)
+    for k, v in W.items():                      # in-place update of every borrowed tensor
+        for dst, src in zip(v if isinstance(v, list) else [v], W2[k] if isinstance(v, list) else [W2[k]]):
+            dst.copy_(src)
+    gen.pack_weights()
+    after, _ = gen.prefill(prompts)
+    torch.cuda.synchronize()
+    assert (before - want).abs().max() > 1e-2          # the two weight sets really differ
+    assert (after - want).abs().max() <= 1e-3          # same weights, packed vs row-major: fp32 summation order only
+    with pytest.raises(Exception):
+        lib_small = torch.empty(256, dtype=torch.uint8, device=DEV)
+        gen._check(__import__("paper_2406_14088_amd").binding.lib().rl_gen_pack_weights(gen._h, lib_small.data_ptr(), 256, None), "pack")
+    ref.close()
+    gen.close()
 
 
 def test_error_paths_on_device():

@@ -111,6 +111,93 @@ def test_gemm_swiglu(ops, M, K, F, kernel):
     assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), err.max()
 
 
+def pack(ops, W):
+    N, K = W.shape
+    P = torch.full((ops.packed_weight_bytes(N, K) // 2,), -1, dtype=torch.int16, device=DEV)
+    ops.pack_weights(W, P)
+    return P
+
+
+def f16_toward_zero(x32):
+    """float32 -> float16, rounded toward zero (what the weight widening does; exact for normal halves)."""
+    h = x32.astype(np.float16)
+    over = np.abs(h.astype(np.float32)) > np.abs(x32)
+    return np.where(over, np.nextafter(h, np.float16(0)), h)
+
+
+@pytest.mark.parametrize("N,K", [(32, 16), (100, 72), (688, 256), (1000, 1000)])
+def test_pack_weights_layout(ops, N, K):
+    # index work: every element of the packed buffer is compared bit for bit with the stated layout
+    W = randn_bf16((N, K), 70 + N, std=0.05)
+    P = pack(ops, W)
+    torch.cuda.synchronize()
+    nbl, ks = -(-N // 32), -(-K // 16)
+    got = P.cpu().numpy().view(np.uint16).reshape(nbl, ks, 64, 8)
+    w32 = (W.cpu().view(torch.int16).numpy().astype(np.uint16).astype(np.uint32) << 16).view(np.float32)
+    full = np.zeros((nbl * 32, ks * 16), np.float16)
+    full[:N, :K] = f16_toward_zero(w32)
+    lane = np.arange(64)
+    rows = (np.arange(nbl)[:, None, None, None] * 32 + (lane & 31)[None, None, :, None])
+    cols = (np.arange(ks)[None, :, None, None] * 16 + ((lane >> 5) * 8)[None, None, :, None] + np.arange(8)[None, None, None, :])
+    ref = full[rows, cols].view(np.uint16)
+    assert (got == ref).all()
+
+
+PACKED_CASES = [
+    # M, K, rows of up to three matrices, splits, blocks per wavefront, activation terms
+    (1, 256, (256,), 1, 1, 1), (4, 688, (256,), 2, 2, 1), (4, 256, (256, 256, 256), 1, 1, 2), (33, 688, (1000, 72), 3, 2, 1),
+    (128, 4096, (512, 128, 128), 4, 1, 2), (200, 1024, (688,), 2, 2, 2), (256, 512, (300,), 1, 1, 1), (64, 264, (1024,), 1, 2, 1),
+    (128, 2048, (2048,), 16, 1, 1), (77, 72, (40,), 1, 0, 1),
+]
+
+
+@pytest.mark.parametrize("M,K,rows,splits,nb,terms", PACKED_CASES)
+def test_gemm_packed_f32(ops, M, K, rows, splits, nb, terms):
+    step(f"gemm_packed M={M} K={K} rows={rows} splits={splits} nb={nb} terms={terms}")
+    A = randn_f16((M, K), 20 + M)
+    A_lo = randn_f16((M, K), 21 + M) * 2.0 ** -11 if terms == 2 else None
+    Ws = [randn_bf16((r, K), 30 + i + r, std=0.05) for i, r in enumerate(rows)]
+    Ps = [pack(ops, w) for w in Ws]
+    N = sum(rows)
+    out = torch.full((splits, M, N), float("nan"), dtype=torch.float32, device=DEV)
+    ops.gemm_packed(A, Ps, rows, K, out, N, A_lo=A_lo, split_stride=M * N, splits=splits, epilogue=0, nb=nb)
+    torch.cuda.synchronize()
+    got = np64(out).sum(0)
+    a = np64(A) + (np64(A_lo) if terms == 2 else 0.0)
+    ref = np.concatenate([orc.linear(bits(w), a) for w in Ws], axis=1)
+    tol = 2e-6 * np.sqrt(K) * (np.abs(ref).max() + 1.0)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= tol, (np.abs(got - ref).max(), tol)
+
+
+@pytest.mark.parametrize("M,nb", [(4, 1), (128, 2), (200, 1)])
+def test_gemm_packed_row_stride_and_accumulate(ops, M, nb):
+    K, N, T = 256, 264, 3
+    buf = randn_f16((M * T, K), 40)
+    A = buf[T - 1::T]
+    W = randn_bf16((N, K), 41, std=0.05)
+    out = randn_f32((M, N), 42)
+    base = np64(out)
+    ops.gemm_packed(A, [pack(ops, W)], (N,), K, out, N, M=M, lda=T * K, epilogue=2, nb=nb)
+    torch.cuda.synchronize()
+    ref = base + orc.linear(bits(W), np64(A))
+    assert np.abs(np64(out) - ref).max() <= 1e-4
+
+
+@pytest.mark.parametrize("M,K,F", [(4, 256, 688), (128, 512, 1000), (256, 256, 72), (130, 1000, 4128)])
+def test_gemm_packed_swiglu(ops, M, K, F):
+    step(f"packed swiglu M={M} K={K} F={F}")
+    A = randn_f16((M, K), 50)
+    Wg, Wu = randn_bf16((F, K), 51, std=0.1), randn_bf16((F, K), 52, std=0.1)
+    out = torch.zeros((M, F), dtype=torch.float16, device=DEV)
+    ops.gemm_packed(A, [pack(ops, Wg), pack(ops, Wu)], (F, F), K, out, F, epilogue=1)
+    torch.cuda.synchronize()
+    g, u = orc.linear(bits(Wg), np64(A)), orc.linear(bits(Wu), np64(A))
+    ref = g / (1.0 + np.exp(-g)) * u
+    err = np.abs(np64(out) - ref)
+    assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), err.max()
+
+
 @pytest.mark.parametrize("style", [0, 1])
 @pytest.mark.parametrize("hd,Hq,Hkv", [(64, 4, 4), (128, 8, 2)])
 def test_rope_append(ops, style, hd, Hq, Hkv):
