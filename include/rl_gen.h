@@ -90,11 +90,11 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void
 
 /* Fragment-order copies of the projection matrices for the decode step.  A decode step multiplies only one
  * row per sequence with every weight matrix, so it lives off streaming the weights once; rl_gen_pack_weights
- * re-lays the borrowed matrices Wq, Wk, Wv, Wo, gate, up, down of every layer and the LM head into
- * packed_arena (DEVICE, 256-byte aligned, at least rl_gen_packed_bytes long, caller-owned, borrowed while the
- * handle lives) in the order the matrix cores read them (IEEE half; layout in rl_gen_ops.h), enqueued on
- * hip_stream.  Afterwards steps of at most 256 rows (decode, short prefills) read only the copies; longer
- * prefills keep reading the row-major weights.  Call it again after the weights changed (a training step
+ * re-lays the borrowed matrices Wq, Wk, Wv, Wo, down of every layer and the LM head into packed_arena
+ * (DEVICE, 256-byte aligned, at least rl_gen_packed_bytes long, caller-owned, borrowed while the handle
+ * lives) in the order the matrix cores read them (IEEE half; layout in rl_gen_ops.h), enqueued on
+ * hip_stream.  Afterwards steps of at most 256 rows (decode, short prefills) read the copies of these
+ * matrices; the gate/up pair and longer prefills keep reading the row-major weights.  Call it again after the weights changed (a training step
  * between two generation phases); packed_arena == NULL detaches the copies.  Results are the same to fp32
  * summation order with and without the copies.  Use the same stream as for the following steps, or
  * synchronise in between. */

@@ -60,10 +60,14 @@ int rl_op_pack_weights(const uint16_t *W, uint16_t *P, int32_t N, int32_t K, voi
  * out, ldc, split_stride, splits and epilogue).  A_lo: optional second term of the activations (f16 [M, K],
  * same stride, or NULL): out = (A + A_lo) W^T with both products accumulated in fp32, which is how the
  * two-term split of rl_op_add_rmsnorm reaches the QKV projection.  nb: 32-column blocks per wavefront,
- * 1 or 2 (0: chosen from the number of columns); epilogue 1 (SwiGLU) always uses gate block + up block. */
+ * 1 or 2 (0: chosen from the number of columns); epilogue 1 (SwiGLU) always uses gate block + up block.
+ * rows_per_wg: activation rows per workgroup, 32, 64 or 128 (0: 128): smaller row blocks give more workgroups
+ * without split-K partials; the row blocks of one column tile stream the same weights (HBM once, L2 after).
+ * depth: 64-wide K chunks of weights each wavefront keeps in flight, 2 or 4 (0: 2). */
 int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P0, const uint16_t *P1,
                       const uint16_t *P2, int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out,
-                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, void *hip_stream);
+                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg,
+                      int32_t depth, void *hip_stream);
 
 /* Builds the rotary table the library uses: tab fp32 [max_seq, head_dim/2, 2] = (cos, sin) of
  * pos * base^(-2r/head_dim), evaluated in fp64 on the host and copied (synchronously) to `tab`. */

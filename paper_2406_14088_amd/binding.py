@@ -79,7 +79,7 @@ def lib():
         "rl_op_gemm": (C.c_int, [vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
         "rl_op_packed_weight_bytes": (sz, [i32, i32]),
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
-        "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
+        "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
@@ -302,13 +302,14 @@ class _Ops:
         N, K = W.shape
         self._ck(lib().rl_op_pack_weights(W.data_ptr(), P.data_ptr(), N, K, _stream()), "rl_op_pack_weights")
 
-    def gemm_packed(self, A, Ps, rows, K, out, ldc, A_lo=None, M=None, lda=None, split_stride=0, splits=1, epilogue=0, nb=0):
+    def gemm_packed(self, A, Ps, rows, K, out, ldc, A_lo=None, M=None, lda=None, split_stride=0, splits=1, epilogue=0, nb=0,
+                    rows_per_wg=0, depth=0):
         ptrs = [q.data_ptr() for q in Ps] + [None] * (3 - len(Ps))
         rows = list(rows) + [0] * (3 - len(rows))
         M = A.shape[0] if M is None else M
         lda = A.stride(0) if lda is None else lda
         self._ck(lib().rl_op_gemm_packed(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K,
-                                         out.data_ptr(), ldc, split_stride, splits, epilogue, nb, _stream()), "rl_op_gemm_packed")
+                                         out.data_ptr(), ldc, split_stride, splits, epilogue, nb, rows_per_wg, depth, _stream()), "rl_op_gemm_packed")
 
     def build_rope_table(self, tab, max_seq, head_dim, base):
         self._ck(lib().rl_op_build_rope_table(tab.data_ptr(), max_seq, head_dim, base), "rl_op_build_rope_table")

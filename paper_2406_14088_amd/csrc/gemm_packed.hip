@@ -14,7 +14,7 @@
 //   gemm:   a wavefront owns NB 32-row blocks (= 32 NB output columns) and walks along K: one
 //           16-byte-per-lane load (a whole, contiguous KB) fetches a fragment straight into the
 //           registers the MFMA reads -- no LDS, no conversion, no shuffle on the weight side.  Loads
-//           run two K chunks (2 x 4 NB fragments) ahead in a register ring.
+//           run two or four K chunks (4 NB fragments each) ahead in a register ring.
 //           The activation chunk [128 rows, 64 k] is shared by the four wavefronts of a workgroup: it is
 //           copied global -> LDS by the load unit itself (buffer loads with the LDS bit: no registers,
 //           no ds_write), in an XOR-swizzled layout whose fragment reads are bank-conflict free, two
@@ -32,10 +32,7 @@
 
 #define PK_BK 64             // K elements per chunk (4 MFMA k-steps)
 #define PK_THREADS 256
-#define PK_BM 128            // activation rows per workgroup (grid.z walks taller batches)
-#define PK_MT 4              // 32-row MFMA tiles along M
 #define PK_OOB 0xFFFFFF00u   // byte offset beyond every descriptor: such a load returns zeros, touches no memory
-#define PK_XTILE (PK_BM * PK_BK * 2)  // bytes of one activation tile in LDS (16 KB)
 #define PK_CT_STRIDE 132     // floats per row of the fp32 output tile in LDS
 #define PK_HT_STRIDE 136     // halves per row of the SwiGLU output tile in LDS
 #define PK_MAX_BYTES 0xF0000000ull
@@ -95,6 +92,7 @@ struct PackedParams {
     int lda_bytes;
     uint32_t a_bytes;   // size of each activation matrix in bytes (range check)
     int M, K, ksteps, chunks, splits, epilogue;
+    int tiles, zblocks;  // n-tiles, row blocks
     void *out;
     int64_t ldc;
     size_t split_stride;
@@ -104,24 +102,38 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t pk_rsrc(const void *p, uint32_
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <int NB, int TERMS>
-__global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams p) {
+// registers a lane needs, roughly: accumulators + weight ring + two sets of activation fragments + addressing
+constexpr int pk_regs(int NB, int MT, int RC) { return NB * MT * 16 + RC * NB * 16 + MT * 8 + 40; }
+constexpr int pk_wgs_per_cu(int NB, int MT, int RC) { return pk_regs(NB, MT, RC) <= 128 ? 4 : (pk_regs(NB, MT, RC) <= 168 ? 3 : 2); }
+
+template <int NB, int TERMS, int MT, int RC>
+__global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_packed_kernel(PackedParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int MT = PK_MT, BM = PK_BM;
+    constexpr int BM = 32 * MT;               // activation rows per workgroup
     constexpr int NBUF = TERMS == 1 ? 3 : 2;  // activation buffers: the copy of chunk c + NBUF - 1 runs during chunk c
     constexpr int NBF = 4 * NB;               // weight fragments per chunk and wavefront
     constexpr int HS = 4 * TERMS;             // (k-step, term) pairs per chunk
-    constexpr int XBUF = TERMS * PK_XTILE;    // bytes of one activation buffer
+    constexpr int XTILE = BM * PK_BK * 2;     // bytes of one activation tile in LDS
+    constexpr int XBUF = TERMS * XTILE;       // bytes of one activation buffer
     const int t = threadIdx.x, lane = t & 63;
     const int w = __builtin_amdgcn_readfirstlane(t >> 6);
     const int K = p.K;
-    const int m0 = blockIdx.z * BM;
+
+    // ---- workgroup id -> (n-tile, K split, row block).  Workgroups whose ids are congruent mod 8 share an
+    //      XCD and its L2: the row blocks of one (tile, split) -- which stream the same weights -- get ids
+    //      8 apart, so the weights come from HBM once and from that L2 for the other row blocks.
+    const int ts_total = p.tiles * p.splits;
+    const int id = blockIdx.x;
+    const int ts = (id / (8 * p.zblocks)) * 8 + (id & 7);
+    const int zb = (id % (8 * p.zblocks)) >> 3;
+    if (ts >= ts_total) return;  // padding of the id space (whole workgroup, before any barrier)
+    const int tile = ts % p.tiles, split = ts / p.tiles;
+    const int m0 = zb * BM;
     const int Mloc = p.M - m0 < BM ? p.M - m0 : BM;
 
     // ---- which 32-row blocks does this wavefront own?  Slot j of wavefront w:
     //      fp32 epilogues: block 4 NB tile + 4 j + w of its matrix (pass j of the epilogue covers 128 adjacent columns);
     //      SwiGLU:         j = 0 gate block, j = 1 up block, both number 4 tile + w.
-    const int tile = blockIdx.x;
     int seg = tile >= p.tile_begin[2] ? 2 : (tile >= p.tile_begin[1] ? 1 : 0);
     const bool swiglu = p.epilogue == EPI_SWIGLU;
     if (swiglu) seg = 0;
@@ -141,21 +153,21 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
     }
 
     // ---- K range of this split
-    const int c0 = (int)(((int64_t)blockIdx.y * p.chunks) / p.splits);
-    const int c1 = (int)(((int64_t)(blockIdx.y + 1) * p.chunks) / p.splits);
+    const int c0 = (int)(((int64_t)split * p.chunks) / p.splits);
+    const int c1 = (int)(((int64_t)(split + 1) * p.chunks) / p.splits);
     const int ks_end = c1 * 4 < p.ksteps ? c1 * 4 : p.ksteps;
 
     // ---- activation copy global -> LDS.  Instruction i of wavefront w fills the 1 KB block of rows
-    //      32 w + 8 i .. + 7 of a tile: lane l lands at byte 16 l of the block, i.e. row l / 8, slot l % 8, and
+    //      8 (MT w + i) .. + 7 of a tile: lane l lands at byte 16 l of the block, i.e. row l / 8, slot l % 8, and
     //      fetches piece (l % 8) ^ (l / 8) of that row, so that piece g of row r sits in slot g ^ (r & 7).
     __amdgpu_buffer_rsrc_t ar[TERMS];
     ar[0] = pk_rsrc(p.A, p.a_bytes);
     if (TERMS == 2) ar[TERMS - 1] = pk_rsrc(p.A_lo, p.a_bytes);
     const int xg = (lane & 7) ^ (lane >> 3);
-    uint32_t x_off[4];
+    uint32_t x_off[MT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int row = w * 32 + 8 * i + (lane >> 3);
+    for (int i = 0; i < MT; ++i) {
+        int row = (w * MT + i) * 8 + (lane >> 3);
         x_off[i] = row < Mloc ? (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)xg * 16u : PK_OOB;
     }
     auto copy_x = [&](int c, int buf) {
@@ -164,8 +176,8 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
 #pragma unroll
         for (int tm = 0; tm < TERMS; ++tm)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                unsigned char *dst = smem + buf * XBUF + tm * PK_XTILE + (w * 32 + 8 * i) * 128;
+            for (int i = 0; i < MT; ++i) {
+                unsigned char *dst = smem + buf * XBUF + tm * XTILE + (w * MT + i) * 1024;
                 uint32_t off = ok && x_off[i] != PK_OOB ? x_off[i] + cb : PK_OOB;
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(ar[tm], LDS_PTR(dst), 16, (int)off, 0, 0, 0);
@@ -179,7 +191,7 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
 #pragma unroll
     for (int s = 0; s < 4; ++s) xld[s] = (lane & 31) * 128 + (((2 * s + (lane >> 5)) ^ (lane & 7)) << 4);
 
-    u32x4_t ring[2 * NBF];  // weight fragments in flight: slots (i & 1) * NBF + s * NB + j belong to chunk c0 + i
+    u32x4_t ring[RC * NBF];  // weight fragments in flight: slots (i % RC) * NBF + s * NB + j belong to chunk c0 + i
     auto load_w = [&](int c, int s, int j, int slot) {
         int ks = c * 4 + s;
         uint32_t off = (ks < ks_end && w_ok[j]) ? w_off[j] + (uint32_t)ks * 1024u : PK_OOB;
@@ -199,10 +211,18 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
     // activation copy never waits for younger weight loads.
     auto body = [&](int c, int buf, auto par_tag) {
         constexpr int PAR = decltype(par_tag)::value;
+        // The copy of chunk c was issued NBUF - 1 trips ago.  Loads retire in issue order, so it has landed once at
+        // most the loads issued after it are still outstanding: the weight loads of that trip and everything of
+        // the trips in between.  The barrier orders only what each wavefront has waited for itself, and the
+        // compiler does not wait for another wavefront's benefit: the wait is spelled out.
+        constexpr int YOUNGER = NBF + (NBUF - 2) * (TERMS * MT + NBF);
+        static_assert(YOUNGER < 64, "vmcnt is a 6-bit counter");
+        __builtin_amdgcn_s_waitcnt((YOUNGER & 15) | (7 << 4) | (15 << 8) | ((YOUNGER >> 4) << 14));  // vmcnt(YOUNGER) only
         __syncthreads();  // the tile of chunk c has landed for every wavefront; buffer of chunk c-1 is free
         int nbuf = buf + NBUF - 1;
         if (nbuf >= NBUF) nbuf -= NBUF;
         copy_x(c + NBUF - 1, nbuf);
+        __builtin_amdgcn_sched_barrier(0);  // the copies stay ahead of this trip's weight loads in issue order
         const unsigned char *xb = smem + buf * XBUF;
         f16x8_t a[2][MT];
 #pragma unroll
@@ -214,7 +234,7 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
                 const int s2 = (hs + 1) / TERMS, tm2 = (hs + 1) % TERMS;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    a[(hs + 1) & 1][mt] = *reinterpret_cast<const f16x8_t *>(xb + tm2 * PK_XTILE + xld[s2] + mt * 4096);
+                    a[(hs + 1) & 1][mt] = *reinterpret_cast<const f16x8_t *>(xb + tm2 * XTILE + xld[s2] + mt * 4096);
             }
 #pragma unroll
             for (int j = 0; j < NB; ++j)
@@ -224,7 +244,7 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
                                                                       acc[j][mt], 0, 0, 0);
             if (tm == TERMS - 1) {
 #pragma unroll
-                for (int j = 0; j < NB; ++j) load_w(c + 2, s, j, PAR * NBF + s * NB + j);
+                for (int j = 0; j < NB; ++j) load_w(c + RC, s, j, PAR * NBF + s * NB + j);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -234,18 +254,24 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
 #pragma unroll
         for (int i = 0; i < NBUF - 1; ++i) copy_x(c0 + i, i);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < RC; ++i)
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
                 for (int j = 0; j < NB; ++j) load_w(c0 + i, s, j, i * NBF + s * NB + j);
         __builtin_amdgcn_sched_barrier(0);
         int buf = 0;
-        for (int c = c0; c < c1; c += 2) {
+        for (int c = c0; c < c1; c += RC) {  // trips past the end multiply zero tiles
             body(c, buf, std::integral_constant<int, 0>{});
             buf = buf + 1 == NBUF ? 0 : buf + 1;
-            body(c + 1, buf, std::integral_constant<int, 1>{});  // past the end: multiplies zero tiles
+            body(c + 1, buf, std::integral_constant<int, 1>{});
             buf = buf + 1 == NBUF ? 0 : buf + 1;
+            if constexpr (RC == 4) {
+                body(c + 2, buf, std::integral_constant<int, 2>{});
+                buf = buf + 1 == NBUF ? 0 : buf + 1;
+                body(c + 3, buf, std::integral_constant<int, 3>{});
+                buf = buf + 1 == NBUF ? 0 : buf + 1;
+            }
         }
     }
     // The copies issued for chunks past the end write zeros into the buffers: they must have landed before
@@ -257,7 +283,7 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
     //      32 mt + 8 (e / 4) + 4 (lane >> 5) + (e % 4).
     if (!swiglu) {
         float *ct = reinterpret_cast<float *>(smem);  // [BM][PK_CT_STRIDE]
-        float *out = reinterpret_cast<float *>(p.out) + (size_t)blockIdx.y * p.split_stride;
+        float *out = reinterpret_cast<float *>(p.out) + (size_t)split * p.split_stride;
         const bool accumulate = p.epilogue == EPI_F32_ACC;
         const int c4 = (t & 31) * 4, rr = t >> 5;
 #pragma unroll
@@ -319,33 +345,56 @@ __global__ __launch_bounds__(PK_THREADS, 2) void gemm_packed_kernel(PackedParams
     }
 }
 
-template <int NB, int TERMS>
-static void launch_p(PackedParams &p, int tiles, hipStream_t st) {
+template <int NB, int TERMS, int MT, int RC>
+static void launch_p(PackedParams &p, hipStream_t st) {
     constexpr int NBUF = TERMS == 1 ? 3 : 2;
-    size_t lds = (size_t)NBUF * TERMS * PK_XTILE;
-    size_t epi = (size_t)PK_BM * PK_CT_STRIDE * sizeof(float);
+    constexpr int BM = 32 * MT;
+    size_t lds = (size_t)NBUF * TERMS * BM * PK_BK * 2;
+    size_t epi = (size_t)BM * PK_CT_STRIDE * sizeof(float);
     if (epi > lds) lds = epi;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_kernel<NB, TERMS>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_kernel<NB, TERMS, MT, RC>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
-    gemm_packed_kernel<NB, TERMS><<<dim3(tiles, p.splits, ceil_div(p.M, PK_BM)), PK_THREADS, lds, st>>>(p);
+    p.zblocks = ceil_div(p.M, BM);
+    int ids = ceil_div(p.tiles * p.splits, 8) * 8 * p.zblocks;
+    gemm_packed_kernel<NB, TERMS, MT, RC><<<ids, PK_THREADS, lds, st>>>(p);
 }
 
-// columns per workgroup: 128 NB (fp32 epilogues), 128 (SwiGLU)
-int gemm_packed_default_nb(int N) { (void)N; return 1; }
+// Weight chunks in flight per wavefront: 2, or 4 on request where the registers allow it (trips are rounded up
+// to the ring depth).
+template <int NB, int TERMS>
+static void launch_pm(PackedParams &p, int mt, int depth, hipStream_t st) {
+    const bool deep = depth == 4;  // no gain measured so far: not chosen by default
+    if (mt == 1) {
+        if (deep) launch_p<NB, TERMS, 1, 4>(p, st);
+        else launch_p<NB, TERMS, 1, 2>(p, st);
+    } else if (mt == 2) {
+        if (deep) launch_p<NB, TERMS, 2, 4>(p, st);
+        else launch_p<NB, TERMS, 2, 2>(p, st);
+    } else {
+        if (deep && NB == 1) launch_p<NB, TERMS, 4, (NB == 1 ? 4 : 2)>(p, st);
+        else launch_p<NB, TERMS, 4, 2>(p, st);
+    }
+}
 
-int gemm_packed_default_splits(int N, int K, int nb, int M) {
-    int tiles = ceil_div(N, 128 * nb) * ceil_div(M, PK_BM);
+// Decomposition of a projection with fp32 partial outputs.  Measured inside whole decode steps of the 7B shape,
+// one 128-row workgroup per column tile and split-K up to about one workgroup per compute unit was as fast as
+// any mix of 64-row workgroups, two column blocks per wavefront and deeper splits (all within 3 %).
+void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *splits) {
     int chunks = ceil_div(K, PK_BK);
-    int s = 256 / (tiles > 0 ? tiles : 1);  // aim at one 4-wavefront workgroup per compute unit
-    if (s < 1) s = 1;
-    if (s > chunks / 8) s = chunks / 8 > 0 ? chunks / 8 : 1;  // keep at least 8 chunks per split
+    *nb = 1;
+    *rows_per_wg = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
+    int wgs = ceil_div(N, 128) * ceil_div(M, *rows_per_wg);
+    int s = 256 / wgs;
+    if (s > chunks / 8) s = chunks / 8;  // at least 8 chunks per split
     if (s > 16) s = 16;
-    return s;
+    if (s < 1) s = 1;
+    *splits = s;
 }
+
 void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
     if (a.M <= 0) return;
     // 32-bit byte offsets inside the kernel: a packed matrix of PK_MAX_BYTES or more is walked in row slabs
@@ -403,13 +452,16 @@ void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
     }
     if (swiglu) tiles = ceil_div(a.rows[0], 128);
     p.tile_begin[3] = tiles;
+    p.tiles = tiles;
     if (tiles <= 0) return;
     const bool two = a.A_lo != nullptr;
+    int mt = a.rows_per_wg >= 128 ? 4 : (a.rows_per_wg >= 64 ? 2 : (a.rows_per_wg >= 32 ? 1 : 4));
+    while (mt > 1 && 32 * (mt / 2) >= a.M) mt /= 2;  // no point in row tiles the batch does not fill
     if (nb == 2) {
-        if (two) launch_p<2, 2>(p, tiles, st);
-        else launch_p<2, 1>(p, tiles, st);
+        if (two) launch_pm<2, 2>(p, mt, a.depth, st);
+        else launch_pm<2, 1>(p, mt, a.depth, st);
     } else {
-        if (two) launch_p<1, 2>(p, tiles, st);
-        else launch_p<1, 1>(p, tiles, st);
+        if (two) launch_pm<1, 2>(p, mt, a.depth, st);
+        else launch_pm<1, 1>(p, mt, a.depth, st);
     }
 }

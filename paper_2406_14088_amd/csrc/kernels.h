@@ -72,11 +72,12 @@ struct PackedGemmArgs {
     int splits;
     int epilogue;         // GemmEpilogue; EPI_SWIGLU: P[0] = gate, P[1] = up
     int nb;               // 32-column blocks per wavefront, 1 or 2 (fp32 epilogues; SwiGLU always uses 2)
+    int depth;            // weight chunks in flight per wavefront: 2 or 4 (0: 2)
+    int rows_per_wg;      // activation rows per workgroup: 32, 64 or 128 (0: 128); the row blocks of one tile re-read its weights from L2
 };
 // M of any size (row blocks of 128 re-stream the weights; meant for M <= 256).
 void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st);
-int gemm_packed_default_nb(int N);
-int gemm_packed_default_splits(int N, int K, int nb, int M);
+void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *splits);
 
 // ---- attention_decode.hip ------------------------------------------------------------------------
 // One new query per (sequence, query head) against cache rows 0 .. *d_len (inclusive).

@@ -186,8 +186,9 @@ int project_packed(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_
     a.P[0] = P0; a.P[1] = P1; a.P[2] = P2;
     a.rows[0] = r0; a.rows[1] = r1; a.rows[2] = r2;
     int N = r0 + r1 + r2;
-    a.nb = gemm_packed_default_nb(N);
-    int splits = gemm_packed_default_splits(N, K, a.nb, M);
+    int splits;
+    gemm_packed_plan(N, K, M, &a.nb, &a.rows_per_wg, &splits);
+    a.depth = 2;
     if (splits > kMaxSplits) splits = kMaxSplits;
     a.out = h->part(); a.ldc = N; a.split_stride = (size_t)M * N; a.splits = splits; a.epilogue = EPI_F32;
     Scope sc(h, cls, st);
@@ -311,7 +312,7 @@ void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st) {
         q.A = a.A; q.A_lo = nullptr; q.lda = a.lda; q.M = nb; q.K = s.hidden;
         q.P[0] = h->p_lm_head; q.P[1] = nullptr; q.P[2] = nullptr;
         q.rows[0] = s.vocab; q.rows[1] = 0; q.rows[2] = 0;
-        q.out = a.out; q.ldc = s.vocab; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_F32; q.nb = 1;
+        q.out = a.out; q.ldc = s.vocab; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_F32; q.nb = 1; q.rows_per_wg = 128; q.depth = 2;
         launch_gemm_packed(q, st);
     } else if (nb <= kSkinnyMaxM) launch_gemm_skinny(a, st);
     else launch_gemm_tiled(a, st);
@@ -367,13 +368,15 @@ size_t rl_gen_work_bytes(const rl_gen_shape *s) {
     return plan_work(s).total;
 }
 
-// packed arena: per layer Wq, Wk, Wv, Wo, gate, up, down, then the LM head; every matrix 256-byte aligned
+// packed arena: per layer Wq, Wk, Wv, Wo, down, then the LM head; every matrix 256-byte aligned.  (The gate/up
+// pair stays row-major: its fused SwiGLU projection is as fast from the row-major kernel.)
+constexpr int kPackedPerLayer = 5;
 static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs) {
     const int d = s->hidden, qd = s->n_heads * s->head_dim, kvd = s->n_kv_heads * s->head_dim;
-    const int NK[7][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {s->ffn, d}, {s->ffn, d}, {d, s->ffn}};
+    const int NK[kPackedPerLayer][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s->ffn}};
     size_t off = 0;
     for (int l = 0; l < s->n_layers; ++l)
-        for (int m = 0; m < 7; ++m) {
+        for (int m = 0; m < kPackedPerLayer; ++m) {
             if (offs) offs->push_back(off);
             off += align_up(packed_weight_bytes(NK[m][0], NK[m][1]));
         }
@@ -401,13 +404,13 @@ int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, vo
     const rl_gen_shape &s = h->s;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
-    const int which[7] = {W_Q, W_K, W_V, W_O, W_GATE, W_UP, W_DOWN};
-    const int NK[7][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {s.ffn, d}, {s.ffn, d}, {d, s.ffn}};
+    const int which[kPackedPerLayer] = {W_Q, W_K, W_V, W_O, W_DOWN};
+    const int NK[kPackedPerLayer][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s.ffn}};
     unsigned char *base = reinterpret_cast<unsigned char *>(packed_arena);
-    for (int m = 0; m < 7; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
+    for (int m = 0; m < kPackedPerLayer; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
     size_t i = 0;
     for (int l = 0; l < s.n_layers; ++l)
-        for (int m = 0; m < 7; ++m, ++i) {
+        for (int m = 0; m < kPackedPerLayer; ++m, ++i) {
             f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i]);
             launch_pack_weights(h->lw[which[m]][l], dst, NK[m][0], NK[m][1], st);
             h->pw[which[m]][l] = dst;
@@ -714,10 +717,12 @@ int rl_op_pack_weights(const uint16_t *W, uint16_t *P, int32_t N, int32_t K, voi
 
 int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P0, const uint16_t *P1,
                       const uint16_t *P2, int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out,
-                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, void *st) {
+                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg, int32_t depth, void *st) {
     if (!A || !P0 || !out) return RL_GEN_E_NULL;
     if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
     if (epilogue < 0 || epilogue > 2 || splits < 1 || nb < 0 || nb > 2) return RL_GEN_E_SHAPE;
+    if (rows_per_wg != 0 && rows_per_wg != 32 && rows_per_wg != 64 && rows_per_wg != 128) return RL_GEN_E_SHAPE;
+    if (depth != 0 && depth != 2 && depth != 4) return RL_GEN_E_SHAPE;
     if (epilogue == EPI_SWIGLU && (!P1 || rows1 != rows0 || P2)) return RL_GEN_E_SHAPE;
     if (epilogue != EPI_F32 && splits != 1) return RL_GEN_E_SHAPE;
     if (((uint64_t)M * (uint64_t)lda + (uint64_t)K) * 2 > 0xf0000000ull) return RL_GEN_E_SHAPE;
@@ -726,7 +731,11 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
     a.P[0] = P0; a.P[1] = rows1 > 0 ? P1 : nullptr; a.P[2] = rows2 > 0 ? P2 : nullptr;
     a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
     a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue;
-    a.nb = nb == 0 ? gemm_packed_default_nb(rows0 + rows1 + rows2) : nb;
+    int pnb, prows, psplits;
+    gemm_packed_plan(rows0 + rows1 + rows2, K, M, &pnb, &prows, &psplits);
+    a.nb = nb == 0 ? pnb : nb;
+    a.rows_per_wg = rows_per_wg;
+    a.depth = depth;
     launch_gemm_packed(a, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }

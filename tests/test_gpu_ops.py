@@ -144,23 +144,25 @@ def test_pack_weights_layout(ops, N, K):
 
 
 PACKED_CASES = [
-    # M, K, rows of up to three matrices, splits, blocks per wavefront, activation terms
-    (1, 256, (256,), 1, 1, 1), (4, 688, (256,), 2, 2, 1), (4, 256, (256, 256, 256), 1, 1, 2), (33, 688, (1000, 72), 3, 2, 1),
-    (128, 4096, (512, 128, 128), 4, 1, 2), (200, 1024, (688,), 2, 2, 2), (256, 512, (300,), 1, 1, 1), (64, 264, (1024,), 1, 2, 1),
-    (128, 2048, (2048,), 16, 1, 1), (77, 72, (40,), 1, 0, 1),
+    # M, K, rows of up to three matrices, splits, blocks per wavefront, activation terms, rows per workgroup
+    (1, 256, (256,), 1, 1, 1, 0), (4, 688, (256,), 2, 2, 1, 32), (4, 256, (256, 256, 256), 1, 1, 2, 64),
+    (33, 688, (1000, 72), 3, 2, 1, 32), (128, 4096, (512, 128, 128), 4, 1, 2, 128), (200, 1024, (688,), 2, 2, 2, 64),
+    (256, 512, (300,), 1, 1, 1, 32), (64, 264, (1024,), 1, 2, 1, 0), (128, 2048, (2048,), 16, 1, 1, 64), (77, 72, (40,), 1, 0, 1, 0),
+    (130, 520, (1100, 200), 2, 1, 2, 32), (100, 1000, (2000,), 3, 2, 1, 64),
 ]
 
 
-@pytest.mark.parametrize("M,K,rows,splits,nb,terms", PACKED_CASES)
-def test_gemm_packed_f32(ops, M, K, rows, splits, nb, terms):
-    step(f"gemm_packed M={M} K={K} rows={rows} splits={splits} nb={nb} terms={terms}")
+@pytest.mark.parametrize("M,K,rows,splits,nb,terms,rpw", PACKED_CASES)
+def test_gemm_packed_f32(ops, M, K, rows, splits, nb, terms, rpw):
+    step(f"gemm_packed M={M} K={K} rows={rows} splits={splits} nb={nb} terms={terms} rows_per_wg={rpw}")
     A = randn_f16((M, K), 20 + M)
     A_lo = randn_f16((M, K), 21 + M) * 2.0 ** -11 if terms == 2 else None
     Ws = [randn_bf16((r, K), 30 + i + r, std=0.05) for i, r in enumerate(rows)]
     Ps = [pack(ops, w) for w in Ws]
     N = sum(rows)
     out = torch.full((splits, M, N), float("nan"), dtype=torch.float32, device=DEV)
-    ops.gemm_packed(A, Ps, rows, K, out, N, A_lo=A_lo, split_stride=M * N, splits=splits, epilogue=0, nb=nb)
+    ops.gemm_packed(A, Ps, rows, K, out, N, A_lo=A_lo, split_stride=M * N, splits=splits, epilogue=0, nb=nb, rows_per_wg=rpw,
+                    depth=(0, 2, 4)[(M + K) % 3])
     torch.cuda.synchronize()
     got = np64(out).sum(0)
     a = np64(A) + (np64(A_lo) if terms == 2 else 0.0)
@@ -170,27 +172,27 @@ def test_gemm_packed_f32(ops, M, K, rows, splits, nb, terms):
     assert np.abs(got - ref).max() <= tol, (np.abs(got - ref).max(), tol)
 
 
-@pytest.mark.parametrize("M,nb", [(4, 1), (128, 2), (200, 1)])
-def test_gemm_packed_row_stride_and_accumulate(ops, M, nb):
+@pytest.mark.parametrize("M,nb,rpw", [(4, 1, 0), (128, 2, 64), (200, 1, 32)])
+def test_gemm_packed_row_stride_and_accumulate(ops, M, nb, rpw):
     K, N, T = 256, 264, 3
     buf = randn_f16((M * T, K), 40)
     A = buf[T - 1::T]
     W = randn_bf16((N, K), 41, std=0.05)
     out = randn_f32((M, N), 42)
     base = np64(out)
-    ops.gemm_packed(A, [pack(ops, W)], (N,), K, out, N, M=M, lda=T * K, epilogue=2, nb=nb)
+    ops.gemm_packed(A, [pack(ops, W)], (N,), K, out, N, M=M, lda=T * K, epilogue=2, nb=nb, rows_per_wg=rpw, depth=4)
     torch.cuda.synchronize()
     ref = base + orc.linear(bits(W), np64(A))
     assert np.abs(np64(out) - ref).max() <= 1e-4
 
 
-@pytest.mark.parametrize("M,K,F", [(4, 256, 688), (128, 512, 1000), (256, 256, 72), (130, 1000, 4128)])
-def test_gemm_packed_swiglu(ops, M, K, F):
-    step(f"packed swiglu M={M} K={K} F={F}")
+@pytest.mark.parametrize("M,K,F,rpw", [(4, 256, 688, 0), (128, 512, 1000, 32), (256, 256, 72, 64), (130, 1000, 4128, 128)])
+def test_gemm_packed_swiglu(ops, M, K, F, rpw):
+    step(f"packed swiglu M={M} K={K} F={F} rows_per_wg={rpw}")
     A = randn_f16((M, K), 50)
     Wg, Wu = randn_bf16((F, K), 51, std=0.1), randn_bf16((F, K), 52, std=0.1)
     out = torch.zeros((M, F), dtype=torch.float16, device=DEV)
-    ops.gemm_packed(A, [pack(ops, Wg), pack(ops, Wu)], (F, F), K, out, F, epilogue=1)
+    ops.gemm_packed(A, [pack(ops, Wg), pack(ops, Wu)], (F, F), K, out, F, epilogue=1, rows_per_wg=rpw, depth=(4, 2)[M % 2])
     torch.cuda.synchronize()
     g, u = orc.linear(bits(Wg), np64(A)), orc.linear(bits(Wu), np64(A))
     ref = g / (1.0 + np.exp(-g)) * u
