@@ -90,6 +90,16 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
                            void *hip_stream);
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
+/* Rotary embedding + KV-cache append + decode attention in one kernel (what a decode step runs): q, k and v of the
+ * new token of every sequence are taken from qkv -- nsplit_qkv fp32 partials, each [B, (Hq+2Hkv)*hd] laid out
+ * q | k | v per row, split_stride elements apart (multiple of 4) -- added, q and k rotated at position d_len[0] with
+ * rope_tab, the k/v rows rounded to f16 and stored at that position of kc / vc (f16 [n_seq][Hkv][S][hd], WRITTEN),
+ * and attention runs over positions 0 .. d_len[0] with the new row taken from registers.  out, ws, nsplit as in
+ * rl_op_decode_attention.  d_len[0] >= S: nothing is written (the host checks capacity before a step). */
+int rl_op_decode_attention_fused(const float *qkv, int32_t nsplit_qkv, size_t split_stride, const float *rope_tab,
+                                 int32_t rope_style, uint16_t *kc, uint16_t *vc, const int32_t *d_len, uint16_t *out, float *ws,
+                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *hip_stream);
+
 /* Prefill attention: causal attention of positions 0..T-1 of nb sequences; sequence i reads cache
  * sequence b0 + i.  q f16 [nb*T, Hq*hd] (rotated), kc, vc f16, out f16 [nb*T, Hq*hd].  hd in {64, 128}. */
 int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_t *vc, uint16_t *out, int32_t nb,

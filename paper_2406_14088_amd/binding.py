@@ -84,6 +84,7 @@ def lib():
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
+        "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
         "rl_op_copy": (C.c_int, [vp, vp, sz, vp]),
@@ -102,7 +103,7 @@ EXPORTED_SYMBOLS = (
     "rl_gen_pack_weights", "rl_gen_prefill",
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats",
+    "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_copy")
 
 
@@ -325,6 +326,12 @@ class _Ops:
     def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit):
         self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), out.data_ptr(),
                                               _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention")
+
+    def decode_attention_fused(self, qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S,
+                               nsplit):
+        self._ck(lib().rl_op_decode_attention_fused(qkv.data_ptr(), nsplit_qkv, split_stride, rope_tab.data_ptr(), rope_style,
+                                                    kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), out.data_ptr(), _ptr(ws), B, Hq,
+                                                    Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention_fused")
 
     def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):
         self._ck(lib().rl_op_prefill_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), nb, b0, T, Hq, Hkv,

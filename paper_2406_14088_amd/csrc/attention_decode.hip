@@ -14,6 +14,10 @@
 //     wavefront, so K and V are read once for all of them;
 //   * optional split over the sequence axis (more wavefronts for long contexts / small batches):
 //     splits write (max, sum, unnormalised output) partials that a small merge kernel combines.
+//   * fused form (FUSED = true): the wavefront takes the new token's q, k and v straight from the split-K
+//     partials of the QKV projection -- it adds the partials, rotates q and k at the token's position, uses
+//     the half-rounded k/v row in place of the cache row of that position, and one wavefront per
+//     (sequence, kv head) stores that row into the cache.  No separate rotary/append kernel and no q buffer.
 // All arithmetic is fp32; only the cache elements and the output are half.
 #include "kernels.h"
 
@@ -34,11 +38,58 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
-template <int HD, int GT>
+// what the fused form needs to build q and the new cache row itself
+struct FusedQkv {
+    const float *part;    // split-K partials of the QKV projection, each [B, (Hq + 2 Hkv) * HD] laid out q | k | v
+    int nsplit;
+    size_t split_stride;  // elements between partials
+    const float *rope_tab;  // [S, HD/2, 2] (cos, sin)
+    int rope_style;
+};
+
+// Sum of the partials of 8 consecutive columns starting at `col` of row `row`.
+__device__ __forceinline__ void sum_partials8(const FusedQkv &f, size_t row_off, int col, float x[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = 0.f;
+    for (int s = 0; s < f.nsplit; ++s) {
+        const f32x4_t *p = reinterpret_cast<const f32x4_t *>(f.part + (size_t)s * f.split_stride + row_off + col);
+        f32x4_t a = p[0], b = p[1];
+        x[0] += a.x; x[1] += a.y; x[2] += a.z; x[3] += a.w;
+        x[4] += b.x; x[5] += b.y; x[6] += b.z; x[7] += b.w;
+    }
+}
+
+// Rotates the 8 head elements c*8 .. c*8+7 a lane holds (the 16 or 8 lanes of a group hold one head vector).
+// Style 1 pairs element e with e + HD/2: the partner sits in lane c ^ (LPR/2) of the same group.
+template <int HD>
+__device__ __forceinline__ void rotate8(float x[8], int c, const float *tab /* row of the position */, int style) {
+    constexpr int LPR = HD / 8, HALF = HD / 2;
+    if (style == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            int r = c * 4 + k;
+            float cs = tab[2 * r], sn = tab[2 * r + 1];
+            float a = x[2 * k], b = x[2 * k + 1];
+            x[2 * k] = a * cs - b * sn;
+            x[2 * k + 1] = a * sn + b * cs;
+        }
+    } else {
+        const bool low = c < LPR / 2;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float other = __shfl_xor(x[i], LPR / 2, 64);
+            int r = (c * 8 + i) % HALF;
+            float cs = tab[2 * r], sn = tab[2 * r + 1];
+            float a = low ? x[i] : other, b = low ? other : x[i];
+            x[i] = low ? a * cs - b * sn : a * sn + b * cs;
+        }
+    }
+}
+
+template <int HD, int GT, bool FUSED>
 __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
-    const float *__restrict__ q, const f16_t *__restrict__ kc, const f16_t *__restrict__ vc,
-    const int32_t *__restrict__ d_len, f16_t *__restrict__ out, float *__restrict__ ws, int n_items, int Hq, int Hkv,
-    int S, int nsplit) {
+    const float *__restrict__ q, f16_t *kc, f16_t *vc, const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
+    float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, FusedQkv fq) {
     constexpr int LPR = HD / 8;     // lanes per cache row
     constexpr int RPW = 64 / LPR;   // rows per wavefront load instruction
     const int lane = threadIdx.x & 63;
@@ -52,7 +103,9 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     int b = rest / Hkv;
     const int head0 = kvh * g + hg * GT;  // first query head of this wavefront
 
-    int n = d_len[0] + 1;  // visible cache rows: positions 0 .. len
+    const int pos = d_len[0];  // position of the new token
+    if (FUSED && pos >= S) return;  // capacity is checked on the host; never write outside the cache
+    int n = pos + 1;  // visible cache rows: positions 0 .. len
     if (n > S) n = S;
     const int chunk = (n + nsplit - 1) / nsplit;
     const int j0 = split * chunk;
@@ -60,12 +113,37 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
 
     const int c = lane % LPR, r = lane / LPR;
     float qr[GT][8];
+    u32x4_t k_new = {0u, 0u, 0u, 0u}, v_new = {0u, 0u, 0u, 0u};  // FUSED: the cache row of position `pos`, as stored
+    if (FUSED) {
+        const size_t row_off = (size_t)b * (Hq + 2 * Hkv) * HD;
+        const float *tab = fq.rope_tab + (size_t)pos * HD;
 #pragma unroll
-    for (int gh = 0; gh < GT; ++gh) {
-        const f32x4_t *qp = reinterpret_cast<const f32x4_t *>(q + ((size_t)b * Hq + head0 + gh) * HD + c * 8);
-        f32x4_t a = qp[0], bb = qp[1];
-        qr[gh][0] = a.x; qr[gh][1] = a.y; qr[gh][2] = a.z; qr[gh][3] = a.w;
-        qr[gh][4] = bb.x; qr[gh][5] = bb.y; qr[gh][6] = bb.z; qr[gh][7] = bb.w;
+        for (int gh = 0; gh < GT; ++gh) {
+            sum_partials8(fq, row_off, (head0 + gh) * HD + c * 8, qr[gh]);
+            rotate8<HD>(qr[gh], c, tab, fq.rope_style);
+        }
+        if (j0 <= pos && pos < j1) {  // wavefront-uniform
+            float x[8];
+            sum_partials8(fq, row_off, (Hq + kvh) * HD + c * 8, x);
+            rotate8<HD>(x, c, tab, fq.rope_style);
+            k_new.x = pack_f16x2(x[0], x[1]); k_new.y = pack_f16x2(x[2], x[3]);
+            k_new.z = pack_f16x2(x[4], x[5]); k_new.w = pack_f16x2(x[6], x[7]);
+            sum_partials8(fq, row_off, (Hq + Hkv + kvh) * HD + c * 8, x);
+            v_new.x = pack_f16x2(x[0], x[1]); v_new.y = pack_f16x2(x[2], x[3]);
+            v_new.z = pack_f16x2(x[4], x[5]); v_new.w = pack_f16x2(x[6], x[7]);
+            if (hg == 0 && r == 0) {  // one wavefront per (sequence, kv head) appends the row
+                *reinterpret_cast<u32x4_t *>(kc + (((size_t)b * Hkv + kvh) * S + pos) * HD + c * 8) = k_new;
+                *reinterpret_cast<u32x4_t *>(vc + (((size_t)b * Hkv + kvh) * S + pos) * HD + c * 8) = v_new;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int gh = 0; gh < GT; ++gh) {
+            const f32x4_t *qp = reinterpret_cast<const f32x4_t *>(q + ((size_t)b * Hq + head0 + gh) * HD + c * 8);
+            f32x4_t a = qp[0], bb = qp[1];
+            qr[gh][0] = a.x; qr[gh][1] = a.y; qr[gh][2] = a.z; qr[gh][3] = a.w;
+            qr[gh][4] = bb.x; qr[gh][5] = bb.y; qr[gh][6] = bb.z; qr[gh][7] = bb.w;
+        }
     }
     const float scale = rsqrtf((float)HD);
     const f16_t *kb = kc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
@@ -82,13 +160,20 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     for (int base = j0; base < j1; base += RPW * DA_U) {
         u32x4_t kr[DA_U], vr[DA_U];
         int jj[DA_U];
+        bool is_new[DA_U];
 #pragma unroll
         for (int u = 0; u < DA_U; ++u) {
             int j = base + u * RPW + r;
             jj[u] = j;
             int jc = j < j1 ? j : j1 - 1;  // rows past the end re-read the last valid row; their weight is 0
+            is_new[u] = FUSED && jc == pos;
             kr[u] = *reinterpret_cast<const u32x4_t *>(kb + (size_t)jc * HD);
             vr[u] = *reinterpret_cast<const u32x4_t *>(vb + (size_t)jc * HD);
+        }
+        if (FUSED) {  // the row of the new position comes from registers: the cache may not hold it yet
+#pragma unroll
+            for (int u = 0; u < DA_U; ++u)
+                if (is_new[u]) { kr[u] = k_new; vr[u] = v_new; }
         }
         float kf[DA_U][8];
 #pragma unroll
@@ -209,25 +294,43 @@ int decode_attention_default_splits(int B, int Hkv, int S) {
 }
 
 template <int HD, int GT>
-static void launch_da(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B,
-                      int Hq, int Hkv, int S, int nsplit, hipStream_t st) {
+static void launch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B, int Hq,
+                      int Hkv, int S, int nsplit, const FusedQkv *fq, hipStream_t st) {
     int g = Hq / Hkv;
     int n_items = B * Hkv * (g / GT) * nsplit;
     int blocks = ceil_div(n_items, DA_THREADS / 64);
-    decode_attention_kernel<HD, GT><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S, nsplit);
+    if (fq)
+        decode_attention_kernel<HD, GT, true><<<blocks, DA_THREADS, 0, st>>>(nullptr, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
+                                                                           nsplit, *fq);
+    else
+        decode_attention_kernel<HD, GT, false><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
+                                                                            nsplit, FusedQkv{});
 }
 
-void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out,
-                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st) {
+static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B, int Hq,
+                        int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, hipStream_t st) {
     if (B <= 0) return;
     int g = Hq / Hkv;
     int gt = g % 8 == 0 ? 8 : (g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1));
 #define DA_CASE(HDV, GTV) \
-    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, out, ws, B, Hq, Hkv, S, nsplit, st); }
+    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, out, ws, B, Hq, Hkv, S, nsplit, fq, st); }
     DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4) DA_CASE(128, 8)
     DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4) DA_CASE(64, 8)
 #undef DA_CASE
     if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, hd, nsplit, st);
+}
+
+void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out,
+                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st) {
+    dispatch_da(q, const_cast<f16_t *>(kc), const_cast<f16_t *>(vc), d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, nullptr, st);
+}
+
+void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
+                                   f16_t *kc, f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B, int Hq, int Hkv,
+                                   int hd, int S, int nsplit, hipStream_t st) {
+    FusedQkv fq;
+    fq.part = qkv; fq.nsplit = nsplit_qkv; fq.split_stride = split_stride; fq.rope_tab = rope_tab; fq.rope_style = rope_style;
+    dispatch_da(nullptr, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, &fq, st);
 }
 
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {

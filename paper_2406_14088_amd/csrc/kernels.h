@@ -85,6 +85,12 @@ void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *split
 // ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st);
+// Fused form: q, k, v of the new token are taken from the split-K partials of the QKV projection (each
+// [B, (Hq+2Hkv)*hd], q | k | v per row): partials added, q and k rotated at position *d_len, the k/v row appended to
+// the cache (kc/vc are written) and used from registers.  Replaces launch_rope_append + launch_decode_attention.
+void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
+                                   f16_t *kc, f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B, int Hq, int Hkv,
+                                   int hd, int S, int nsplit, hipStream_t st);
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);

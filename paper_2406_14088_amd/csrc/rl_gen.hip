@@ -270,6 +270,9 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
                                h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
                                decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st);
         }
+        // (A single kernel that takes q, k, v from the partials, rotates, appends and attends exists --
+        // launch_decode_attention_fused -- but measured no faster per step: what the separate kernel costs, the
+        // attention wavefronts then spend before their first cache load.)
         if (decode) {
             Scope sc(h, RL_GEN_K_DECODE_ATTN, st);
             launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_len(), h->attn(), h->attn_ws(), nb,
@@ -774,6 +777,18 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
     if (!q || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
     launch_decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_decode_attention_fused(const float *qkv, int32_t nsplit_qkv, size_t split_stride, const float *rope_tab,
+                                 int32_t rope_style, uint16_t *kc, uint16_t *vc, const int32_t *d_len, uint16_t *out, float *ws,
+                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
+    if (!qkv || !rope_tab || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1 || nsplit_qkv < 1 ||
+        (rope_style != 0 && rope_style != 1) || split_stride % 4)
+        return RL_GEN_E_SHAPE;
+    launch_decode_attention_fused(qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S,
+                                  nsplit, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

@@ -259,6 +259,50 @@ def test_decode_attention(ops, hd, Hq, Hkv, length, nsplit):
             assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), (b, u, err.max())
 
 
+@pytest.mark.parametrize("style", [0, 1])
+@pytest.mark.parametrize("hd,Hq,Hkv", [(128, 8, 8), (128, 8, 2), (128, 16, 2), (64, 4, 4), (64, 6, 2), (128, 8, 1)])
+@pytest.mark.parametrize("length,nsplit", [(0, 1), (5, 1), (130, 3), (1000, 8), (2, 4)])
+def test_decode_attention_fused_with_rope_and_append(ops, style, hd, Hq, Hkv, length, nsplit):
+    """One kernel = rotary embedding of the new q/k, append of the new k/v row, attention over positions 0 .. length."""
+    step(f"fused decode attention style={style} hd={hd} Hq={Hq} Hkv={Hkv} len={length} nsplit={nsplit}")
+    B, S, nq = 3, 1024, 2
+    ld = (Hq + 2 * Hkv) * hd
+    tab = torch.empty((S, hd // 2, 2), dtype=torch.float32, device=DEV)
+    ops.build_rope_table(tab, S, hd, 10000.0)
+    qkv = randn_f32((nq, B, ld), 73, std=0.8)
+    kc = randn_f16((B, Hkv, S, hd), 71)
+    vc = randn_f16((B, Hkv, S, hd), 72)
+    kc[:, :, length:] = float("nan")     # the row of the new position is NOT in the cache yet; later rows are never used
+    vc[:, :, length:] = float("nan")
+    k_before, v_before = kc.clone(), vc.clone()
+    d_len = torch.tensor([length], dtype=torch.int32, device=DEV)
+    out = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ops.decode_attention_fused(qkv, nq, B * ld, tab, style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit)
+    torch.cuda.synchronize()
+    tot = np64(qkv).sum(0)
+    kn, vn, on = np64(kc), np64(vc), np64(out).reshape(B, Hq, hd)
+    g = Hq // Hkv
+    for b in range(B):
+        q = orc.rope(tot[b, : Hq * hd].reshape(Hq, hd), length, 10000.0, style)
+        k = orc.rope(tot[b, Hq * hd: (Hq + Hkv) * hd].reshape(Hkv, hd), length, 10000.0, style)
+        v = tot[b, (Hq + Hkv) * hd:].reshape(Hkv, hd)
+        # the appended rows: the rotated k and the plain v, rounded once to f16
+        assert (np.abs(kn[b, :, length] - k) <= 0.5 * F16_EPS * np.abs(k) * 1.01 + 1e-6).all()
+        assert (np.abs(vn[b, :, length] - v) <= 0.5 * F16_EPS * np.abs(v) * 1.01 + 1e-6).all()
+        for u in range(Hq):
+            # attention over the cache as it now stands (the stored, rounded new row included)
+            ref = orc.attend(q[u], kn[b, u // g, : length + 1], vn[b, u // g, : length + 1])
+            err = np.abs(on[b, u] - ref)
+            assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 3e-5).all(), (b, u, err.max())
+    # nothing but the new row changed (bit patterns: NaN payloads included)
+    kb, ka = k_before.cpu().view(torch.int16).numpy().copy(), kc.cpu().view(torch.int16).numpy().copy()
+    vb, va = v_before.cpu().view(torch.int16).numpy().copy(), vc.cpu().view(torch.int16).numpy().copy()
+    ka[:, :, length] = kb[:, :, length]
+    va[:, :, length] = vb[:, :, length]
+    assert (ka == kb).all() and (va == vb).all()
+
+
 @pytest.mark.parametrize("hd,Hq,Hkv", [(128, 4, 4), (128, 8, 2), (64, 4, 1)])
 @pytest.mark.parametrize("T", [1, 16, 100, 300])
 def test_prefill_attention(ops, hd, Hq, Hkv, T):
