@@ -283,9 +283,14 @@ size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit) {
     return nsplit > 1 ? (size_t)B * Hq * nsplit * (hd + 2) : 0;
 }
 
+// Query heads of one kv head that a wavefront processes together (they share every cache row it loads).  At most 4:
+// with 8 the per-head state fills the register file and one wavefront per SIMD cannot hide the cache latency;
+// the second wavefront of a kv head finds the rows in L2.
+int decode_attention_group(int g) { return g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1); }
+
 int decode_attention_default_splits(int B, int Hkv, int S) {
     long items = (long)B * Hkv;
-    int s = (int)((4096 + items - 1) / items);  // aim at >= 4 wavefronts per SIMD over 256 compute units
+    int s = (int)((2048 + items - 1) / items);  // aim at >= 2 wavefronts per SIMD over 256 compute units
     int cap = S / 128;                          // but keep >= 128 positions per split at full length
     if (s > cap) s = cap;
     if (s > 16) s = 16;
@@ -311,11 +316,11 @@ static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_l
                         int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, hipStream_t st) {
     if (B <= 0) return;
     int g = Hq / Hkv;
-    int gt = g % 8 == 0 ? 8 : (g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1));
+    int gt = decode_attention_group(g);
 #define DA_CASE(HDV, GTV) \
     if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, out, ws, B, Hq, Hkv, S, nsplit, fq, st); }
-    DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4) DA_CASE(128, 8)
-    DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4) DA_CASE(64, 8)
+    DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4)
+    DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4)
 #undef DA_CASE
     if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, hd, nsplit, st);
 }

@@ -94,6 +94,7 @@ void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t spli
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);
+int decode_attention_group(int g);  // query heads per wavefront for Hq/Hkv = g
 
 // ---- attention_prefill.hip -----------------------------------------------------------------------
 // Causal attention over the T prompt positions of nb sequences whose K/V already sit in the cache.

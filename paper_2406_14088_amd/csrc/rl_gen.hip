@@ -48,7 +48,7 @@ int validate(const rl_gen_shape *s) {
 
 int attn_splits(const rl_gen_shape *s) {
     int g = s->n_heads / s->n_kv_heads;
-    int gt = g % 8 == 0 ? 8 : (g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1));
+    int gt = decode_attention_group(g);
     return decode_attention_default_splits(s->max_batch, s->n_kv_heads * (g / gt), s->max_seq);
 }
 

@@ -123,6 +123,15 @@ def test_width_of_70b_gqa_reduced_depth():
     check(s, 5, 2, 16, 3)
 
 
+def test_width_of_the_papers_llama3_7b_row_reduced_depth():
+    """The paper's own model-configuration table, 7B row: grouped-query attention 32/8, FFN 14336, vocabulary 128256
+    (LM head of 1.05 GB, argmax over 128256 logits; 128256 = 2^8 * 3 * 167 exercises the tile tails)."""
+    from workload.configs import LLAMA3_TABLE_SHAPES
+    s = LLAMA3_TABLE_SHAPES["7B"].with_layers(1)
+    step("LLaMA-3 7B row width (hidden 4096, 32/8 heads, FFN 14336, vocab 128256), 1 layer")
+    check(s, 6, 3, 20, 3)
+
+
 def test_prefill_equals_incremental_decode_on_device():
     """Causality/caching invariant on the GPU itself: prefill(P) and prefill(P-k) + k decode steps give the
     same last-position logits up to the bf16 path's own rounding differences."""

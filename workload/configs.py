@@ -48,20 +48,23 @@ _L7B = ModelShape(32, 4096, 32, 32, 128, 11008, 32000)
 _L13B = ModelShape(40, 5120, 40, 40, 128, 13824, 32000)
 _L70B = ModelShape(80, 8192, 64, 8, 128, 28672, 32000)
 
-PRESETS = {
-    "tiny": Workload("tiny", 1, _TINY, 4, 16, 16, weights_fp32_master=True),
-    "llama7b": Workload("llama7b", 2, _L7B, 128, 128, 256),
-    "llama13b": Workload("llama13b", 3, _L13B, 256, 256, 256),
-    "llama7b_long": Workload("llama7b_long", 4, _L7B, 32, 2048, 2048),
-    "llama70b": Workload("llama70b", 5, _L70B, 64, 128, 256),
-}
-
 # The paper's model-configuration table (LLaMA-3 shapes, vocabulary 128256).
 LLAMA3_TABLE_SHAPES = {
     "7B": ModelShape(32, 4096, 32, 8, 128, 14336, 128256),
     "13B": ModelShape(40, 5120, 40, 40, 128, 13824, 128256),
     "34B": ModelShape(48, 8192, 64, 8, 128, 22016, 128256),
     "70B": ModelShape(80, 8192, 64, 8, 128, 28672, 128256),
+}
+
+PRESETS = {
+    "tiny": Workload("tiny", 1, _TINY, 4, 16, 16, weights_fp32_master=True),
+    "llama7b": Workload("llama7b", 2, _L7B, 128, 128, 256),
+    "llama13b": Workload("llama13b", 3, _L13B, 256, 256, 256),
+    "llama7b_long": Workload("llama7b_long", 4, _L7B, 32, 2048, 2048),
+    "llama70b": Workload("llama70b", 5, _L70B, 64, 128, 256),
+    # the paper's own 7B row (grouped-query attention 32/8, vocabulary 128256) at its base context: prompt 1024,
+    # 1024 generated tokens (Appendix A); one GPU's share of the batch
+    "llama3_7b": Workload("llama3_7b", 6, LLAMA3_TABLE_SHAPES["7B"], 128, 1024, 1024),
 }
 
 
