@@ -160,6 +160,19 @@ int32_t orc_argmax(const double *x, int n) {
     return best;
 }
 
+/* Log-probability of one token under the softmax of a logit row (the quantity the inference function call of
+ * Section 2.1 returns for every generated token): log p_t = x_t - log sum_v exp(x_v), with the maximum taken out
+ * of the exponentials.  NaN if target is outside [0, n). */
+double orc_token_logprob(const double *x, int n, int target) {
+    if (n <= 0 || target < 0 || target >= n) return NAN;
+    double mx = x[0];
+    for (int i = 1; i < n; ++i)
+        if (x[i] > mx) mx = x[i];
+    double sum = 0.0;
+    for (int i = 0; i < n; ++i) sum += exp(x[i] - mx);
+    return x[target] - (mx + log(sum));
+}
+
 /* ------------------------------------------------------------------ closed forms */
 
 static int shape_ok(const orc_shape *s) {

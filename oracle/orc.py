@@ -52,6 +52,8 @@ def lib():
         L.orc_silu.restype = C.c_double
         L.orc_argmax.argtypes = [dp, C.c_int]
         L.orc_argmax.restype = C.c_int32
+        L.orc_token_logprob.argtypes = [dp, C.c_int, C.c_int]
+        L.orc_token_logprob.restype = C.c_double
         L.orc_param_count.argtypes = [C.POINTER(OrcShape)]
         L.orc_param_count.restype = C.c_int64
         L.orc_kv_bytes_per_token.argtypes = [C.POINTER(OrcShape), C.c_int]
@@ -147,6 +149,22 @@ def silu(z: float) -> float:
 def argmax(x: np.ndarray) -> int:
     x = np.ascontiguousarray(x, dtype=np.float64)
     return int(lib().orc_argmax(_dp(x), x.shape[0]))
+
+
+def token_logprob(x: np.ndarray, target: int) -> float:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    return float(lib().orc_token_logprob(_dp(x), x.shape[0], int(target)))
+
+
+def sequence_logprobs(logits: np.ndarray, tokens: np.ndarray) -> np.ndarray:
+    """logits [B, T, V] of every position, tokens [B, T] -> [B, T-1]: log-probability that position i assigns to the
+    token that follows it (Section 2.1: what the inference call over prompt + response returns per token)."""
+    B, T, _ = logits.shape
+    out = np.empty((B, T - 1), dtype=np.float64)
+    for b in range(B):
+        for i in range(T - 1):
+            out[b, i] = token_logprob(logits[b, i], int(tokens[b, i + 1]))
+    return out
 
 
 def param_count(shape) -> int:

@@ -10,7 +10,7 @@ import pytest
 
 from oracle import orc
 from tests import ref_numpy
-from workload import LLAMA3_TABLE_SHAPES, PRESETS, ModelShape
+from workload import LLAMA3_TABLE_SHAPES, PRESETS, ModelShape, make_prompts, make_weights
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -359,3 +359,45 @@ def test_error_paths():
         m.decode_step(np.zeros(2, np.int32))                 # sequence capacity reached
     with pytest.raises(orc.OracleError):
         orc.OracleModel(small_shape(n_kv_heads=3), W, 1, 1)  # heads not divisible by kv heads
+
+
+# ---------------------------------------------------------------------------------------------- token log-probability
+def test_token_logprob_pins():
+    """log-softmax gather: a library routine (scipy), closed forms and invariants."""
+    from scipy.special import log_softmax, logsumexp
+    rng = np.random.default_rng(77)
+    x = rng.normal(0, 3.0, size=1000)
+    ref = log_softmax(x)
+    for t in (0, 1, 499, 999):
+        assert abs(orc.token_logprob(x, t) - ref[t]) <= 1e-12
+    # probabilities sum to one
+    assert abs(logsumexp([orc.token_logprob(x, t) for t in range(1000)])) <= 1e-10
+    # uniform logits: -log n, whatever the common value
+    for c in (0.0, -7.5, 1e4):
+        assert abs(orc.token_logprob(np.full(64, c), 5) + np.log(64)) <= 1e-12
+    # shift invariance, and no overflow for large logits
+    assert abs(orc.token_logprob(x + 900.0, 3) - orc.token_logprob(x, 3)) <= 1e-9
+    assert np.isfinite(orc.token_logprob(np.array([800.0, -800.0, 0.0]), 1))
+    # two logits: log sigmoid of the difference
+    assert abs(orc.token_logprob(np.array([1.25, -0.5]), 0) + np.log1p(np.exp(-1.75))) <= 1e-14
+    # a planted mistake would show: gathering the wrong index or dropping the max term
+    assert abs(orc.token_logprob(np.array([0.0, np.log(3.0)]), 1) - np.log(0.75)) <= 1e-14
+    assert np.isnan(orc.token_logprob(x, 1000)) and np.isnan(orc.token_logprob(x, -1))
+
+
+def test_sequence_logprobs_follow_the_next_token():
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device="cpu")
+    om = orc.OracleModel(wl.shape, orc.weights_to_numpy(W), 2, 8)
+    toks = make_prompts(wl, batch=2, prompt_len=8).numpy()
+    logits = om.forward_all(toks)
+    lp = orc.sequence_logprobs(logits, toks)
+    assert lp.shape == (2, 7) and (lp < 0).all()
+    from scipy.special import log_softmax
+    assert abs(lp[1, 3] - log_softmax(logits[1, 3])[toks[1, 4]]) <= 1e-12     # position i scores token i+1
+    # causality carries over: the first k log-probs depend only on the first k+1 tokens
+    toks2 = toks.copy()
+    toks2[:, 6:] = (toks2[:, 6:] + 1) % wl.shape.vocab
+    lp2 = orc.sequence_logprobs(om.forward_all(toks2), toks2)
+    assert np.array_equal(lp[:, :5], lp2[:, :5]) and not np.array_equal(lp[:, 5:], lp2[:, 5:])
+    om.close()
