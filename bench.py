@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--call", default="generation", choices=["generation", "logprobs"],
+                    help="generation (the benchmark) or the inference call that scores every token of [B, P+G] sequences")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (copy_kernel: a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -84,6 +86,11 @@ def main():
     gen.set_graph(not args.no_graph)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
+
+    if args.call == "logprobs":
+        print(json.dumps(bench_logprobs(args, gen, wl, shape, dev, setup_s)))
+        gen.close()
+        return
 
     buf = [torch.empty((B,), dtype=torch.int32, device=dev) for _ in range(2)]
     if args.copy_calibration:
@@ -185,6 +192,51 @@ def main():
     out["checksum_last_tokens"] = int(last_tokens.to(torch.int64).sum().item())
     gen.close()
     print(json.dumps(out))
+
+
+def bench_logprobs(args, gen, wl, shape, dev, setup_s):
+    """The inference call (log-probability of every following token) over B sequences of P+G tokens: a step is one
+    call; value = scored tokens per second.  Bound by the matrix cores: the roofline entry is the tiled projection
+    kernel, flops of the calls it served / their summed event-timed duration."""
+    import torch
+    from workload import Workload, make_prompts
+    B, T = wl.batch, wl.prompt_len + wl.gen_len
+    toks = make_prompts(Workload(wl.name, wl.index, shape, B, T, 0), device=dev)
+    logp = torch.empty((B, T), dtype=torch.float32, device=dev)
+    for _ in range(args.warmup):
+        gen.logprobs(toks, logp)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        gen.logprobs(toks, logp)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    d, hd, Hq, Hkv, F, V, L = shape.hidden, shape.head_dim, shape.n_heads, shape.n_kv_heads, shape.ffn, shape.vocab, shape.n_layers
+    proj_flops = 2 * B * T * (L * ((Hq + 2 * Hkv) * hd * d + Hq * hd * d + 3 * d * F) + V * d)
+    flops = proj_flops + 4 * L * B * Hq * hd * T * (T + 1) // 2
+    out = {"metric": f"inference call (token log-probabilities), scored tokens/sec on 1 GPU, {wl.name}", "value": B * T * args.steps / elapsed,
+           "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
+           "config": {"workload": f"{wl.name}: L{L} d{d} H{Hq}/{Hkv} F{F} V{V}, batch {B}, sequence {T}", "global_batch": B, "seq_len": T},
+           "phases": {"tflops": flops / (elapsed / args.steps) / 1e12, "frac_of_mfma_peak": flops / (elapsed / args.steps) / 1e12 / MFMA_PEAK_TFLOPS},
+           "setup_s": setup_s, "checksum_logp": float(logp.double().sum().item())}
+    if not args.no_roofline:
+        gen.profile(True)
+        gen.profile_read()
+        gen.logprobs(toks, logp)
+        prof = gen.profile_read()
+        gen.profile(False)
+        ms = sum(prof[k]["ms"] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head"))
+        n = sum(prof[k]["launches"] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head"))
+        # executed flops of the projections: the QKV projection runs on both terms of its activations
+        executed = proj_flops + 2 * B * T * L * (Hq + 2 * Hkv) * hd * d
+        if ms > 0:
+            out["roofline"] = {"kernel": "gemm_tiled (all projections)", "bound": "mfma", "achieved": executed / (ms * 1e-3) / 1e12,
+                               "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": executed / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                               "traffic": None, "launches": n, "avg_launch_us": ms * 1e3 / max(n, 1)}
+        out["kernels"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 3)} for k, v in prof.items() if v["launches"]}
+    return out
 
 
 def cpu_baseline(shape, wl, W):

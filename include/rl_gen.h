@@ -117,6 +117,15 @@ int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, flo
  * would exceed max_seq, RL_GEN_E_STATE before a prefill. */
 int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_t *next, void *hip_stream);
 
+/* Inference call (Section 2.1: one forward pass over prompt + response that scores every generated token; the
+ * next call after generation in the RLHF dataflow).  tokens: DEVICE int32 [B, T] row-major.  logp: DEVICE fp32
+ * [B, T]: logp[b, i] = log softmax(logits of position i)[tokens[b, i+1]] for i < T-1 -- the log-probability the
+ * model assigns to the token that follows position i -- and logp[b, T-1] = 0.  The [B, T, vocab] logits are never
+ * handed out: the LM head runs over blocks of rows into the workspace and a gather kernel reduces each block.
+ * Same limits and errors as rl_gen_prefill, and like a prefill it replaces the sequence state (afterwards every
+ * sequence has length T and decode steps may follow). */
+int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logp, void *hip_stream);
+
 /* Whether decode steps are replayed as one captured HIP graph (1, default) or launched kernel by
  * kernel (0).  Both produce identical results. */
 int rl_gen_set_graph(rl_gen_t *h, int32_t enabled);

@@ -108,6 +108,13 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
 /* Greedy token: next[b] = lowest index of the largest of logits[b, 0..V-1]; -1 if the row has a NaN. */
 int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *hip_stream);
 
+/* Log-probability of the following token (Section 2.1, inference call): for the M rows g = m_first .. m_first+M-1 of
+ * a flattened [n_seq, T] token grid, out[g] = logits[g - m_first, tokens[g+1]] - log sum_v exp(logits[g - m_first, v]);
+ * rows with g % T == T-1 (no following token) get 0.  logits fp32 [M, V] with row stride ld; tokens int32, indexed
+ * up to m_first + M (ids outside [0, V) are clamped); out fp32, indexed by g. */
+int rl_op_logprob_gather(const float *logits, int64_t ld, int32_t M, int32_t V, const int32_t *tokens, int32_t T,
+                         int64_t m_first, float *out, void *hip_stream);
+
 /* Plain device-to-device copy of `bytes` bytes (multiple of 16; 16-byte aligned pointers), 16 bytes per
  * lane.  Not a step of the method: a kernel of exactly known traffic that the benchmark profiles next
  * to the real kernels to scale hardware byte counters. */

@@ -65,6 +65,7 @@ def lib():
         "rl_gen_pack_weights": (C.c_int, [vp, vp, sz, vp]),
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
+        "rl_gen_logprobs": (C.c_int, [vp, vp, i32, i32, vp, vp]),
         "rl_gen_set_graph": (C.c_int, [vp, i32]),
         "rl_gen_set_qkv_terms": (C.c_int, [vp, i32]),
         "rl_gen_reset": (C.c_int, [vp]),
@@ -87,6 +88,7 @@ def lib():
         "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
+        "rl_op_logprob_gather": (C.c_int, [vp, i64, i32, i32, vp, i32, i64, vp, vp]),
         "rl_op_copy": (C.c_int, [vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
@@ -100,11 +102,11 @@ def lib():
 
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_packed_bytes",
-    "rl_gen_pack_weights", "rl_gen_prefill",
+    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_logprobs",
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_fused",
-    "rl_op_prefill_attention", "rl_op_argmax", "rl_op_copy")
+    "rl_op_prefill_attention", "rl_op_argmax", "rl_op_logprob_gather", "rl_op_copy")
 
 
 def _shape_of(shape, max_batch=1, max_seq=1, weight_dtype=1) -> RlGenShape:
@@ -235,6 +237,16 @@ class Generator:
                     "rl_gen_decode_step")
         return logits, next_tokens
 
+    def logprobs(self, tokens, logp=None):
+        """tokens: int32 GPU tensor [B, T].  Returns fp32 [B, T]: log-probability of token i+1 at position i (last column 0)."""
+        import torch
+        B, T = tokens.shape
+        assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        if logp is None:
+            logp = torch.empty((B, T), dtype=torch.float32, device=tokens.device)
+        self._check(lib().rl_gen_logprobs(self._h, tokens.data_ptr(), B, T, logp.data_ptr(), _stream()), "rl_gen_logprobs")
+        return logp
+
     def set_graph(self, enabled: bool):
         self._check(lib().rl_gen_set_graph(self._h, int(enabled)), "rl_gen_set_graph")
 
@@ -336,6 +348,11 @@ class _Ops:
     def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):
         self._ck(lib().rl_op_prefill_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), nb, b0, T, Hq, Hkv,
                                                hd, S, _stream()), "rl_op_prefill_attention")
+
+    def logprob_gather(self, logits, tokens, T, m_first, out):
+        M, V = logits.shape
+        self._ck(lib().rl_op_logprob_gather(logits.data_ptr(), logits.stride(0), M, V, tokens.data_ptr(), T, m_first, out.data_ptr(),
+                                            _stream()), "rl_op_logprob_gather")
 
     def copy(self, src, dst):
         self._ck(lib().rl_op_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream()), "rl_op_copy")

@@ -204,6 +204,53 @@ void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *in
     argmax_kernel<<<B, AM_THREADS, 0, st>>>(logits, V, next, inc_len);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Log-probability of the following token: out[g] = x[target] - log sum_v exp(x[v]) for the logit row of global row
+// g = m_first + blockIdx.x, target = tokens[g + 1]; rows that end a sequence (g % T == T - 1) have no following
+// token and get 0.  One pass: every thread keeps a running (max, sum of exp(x - max)) over its strided share, the
+// pairs are merged across the wavefront and the workgroup.
+#define LP_THREADS 512
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2) {
+    float mn = fmaxf(m, m2);
+    if (mn == -INFINITY) { m = mn; s = 0.f; return; }
+    s = s * expf(m - mn) + s2 * expf(m2 - mn);
+    m = mn;
+}
+__global__ __launch_bounds__(LP_THREADS) void logprob_gather_kernel(const float *__restrict__ logits, int64_t ld, int V,
+                                                                    const int32_t *__restrict__ tokens, int T, int64_t m_first,
+                                                                    float *__restrict__ out) {
+    __shared__ float sm[LP_THREADS / RL_WAVE], ss[LP_THREADS / RL_WAVE];
+    const int t = threadIdx.x;
+    const int64_t g = m_first + blockIdx.x;
+    if (g % T == T - 1) {
+        if (t == 0) out[g] = 0.f;
+        return;
+    }
+    const float *row = logits + (size_t)blockIdx.x * ld;
+    float m = -INFINITY, s = 0.f;
+    for (int i = t; i < V; i += LP_THREADS) {
+        float x = row[i];
+        if (x > m) { s = s * expf(m - x) + 1.f; m = x; }  // exp(-inf) = 0 on the first element
+        else s += expf(x - m);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lse_merge(m, s, __shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
+    if ((t & 63) == 0) { sm[t >> 6] = m; ss[t >> 6] = s; }
+    __syncthreads();
+    if (t == 0) {
+        for (int w = 1; w < LP_THREADS / RL_WAVE; ++w) lse_merge(m, s, sm[w], ss[w]);
+        int target = tokens[g + 1];
+        target = target < 0 ? 0 : (target >= V ? V - 1 : target);  // ids outside the vocabulary are clamped, as in the embedding
+        out[g] = row[target] - (m + logf(s));
+    }
+}
+
+void launch_logprob_gather(const float *logits, int64_t ld, int M, int V, const int32_t *tokens, int T, int64_t m_first,
+                           float *out, hipStream_t st) {
+    if (M <= 0) return;
+    logprob_gather_kernel<<<M, LP_THREADS, 0, st>>>(logits, ld, V, tokens, T, m_first, out);
+}
+
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st) { set_i32_kernel<<<1, 1, 0, st>>>(p, v); }
 

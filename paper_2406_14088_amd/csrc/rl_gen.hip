@@ -25,6 +25,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct WorkPlan {
     size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, rope, state, total;
+    size_t part_elems;  // floats in the split-K partial area
     int rows;  // activation rows the workspace can hold
 };
 
@@ -70,6 +71,7 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.x = take((size_t)rows * d * 4);
     p.h = take((size_t)2 * rows * d * 2);
     p.part = take(part_elems * 4);
+    p.part_elems = part_elems;
     p.qf32 = take((size_t)s->max_batch * qd * 4);
     p.qbf = take((size_t)rows * qd * 2);
     p.attn = take((size_t)rows * qd * 2);
@@ -540,6 +542,52 @@ int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, flo
     return RL_GEN_OK;
 }
 
+int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logp, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!tokens || !logp) { set_err(h, "rl_gen_logprobs: NULL argument"); return RL_GEN_E_NULL; }
+    if (B <= 0 || T <= 0) { set_err(h, "rl_gen_logprobs: B and T must be positive"); return RL_GEN_E_SHAPE; }
+    if (B > h->s.max_batch || T > h->s.max_seq) {
+        set_err(h, "rl_gen_logprobs: B=%d T=%d exceed capacity %d x %d", B, T, h->s.max_batch, h->s.max_seq);
+        return RL_GEN_E_CAPACITY;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const rl_gen_shape &s = h->s;
+    int per_chunk = h->wp.rows / T;
+    if (per_chunk < 1) per_chunk = 1;
+    // logits of a block of rows live in the split-K partial area, which is idle once the layers are done
+    int64_t rows_fit = (int64_t)(h->wp.part_elems / (size_t)s.vocab);
+    if (rows_fit >= 256) rows_fit = rows_fit / 256 * 256;
+    if (rows_fit < 1) { set_err(h, "rl_gen_logprobs: workspace holds no logit row"); return RL_GEN_E_CAPACITY; }
+    for (int b0 = 0; b0 < B; b0 += per_chunk) {
+        int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
+        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
+        const int M = nb * T;
+        for (int m0 = 0; m0 < M; m0 += (int)rows_fit) {
+            int mm = M - m0 < rows_fit ? M - m0 : (int)rows_fit;
+            GemmArgs a;
+            a.A = h->h() + (size_t)m0 * s.hidden; a.lda = s.hidden; a.M = mm; a.K = s.hidden;
+            a.W[0] = h->lm_head; a.W[1] = nullptr; a.W[2] = nullptr;
+            a.rows[0] = s.vocab; a.rows[1] = 0; a.rows[2] = 0;
+            a.out = h->part(); a.ldc = s.vocab; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
+            {
+                Scope sc(h, RL_GEN_K_GEMM_LM_HEAD, st);
+                if (mm <= kSkinnyMaxM) launch_gemm_skinny(a, st);
+                else launch_gemm_tiled(a, st);
+            }
+            Scope sc(h, RL_GEN_K_MISC, st);
+            launch_logprob_gather(h->part(), s.vocab, mm, s.vocab, tokens, T, (int64_t)b0 * T + m0, logp, st);
+        }
+    }
+    {
+        Scope sc(h, RL_GEN_K_MISC, st);
+        launch_set_i32(h->d_len(), T, st);
+    }
+    int rc = check_hip(h, "rl_gen_logprobs");
+    if (rc != RL_GEN_OK) return rc;
+    h->B = B; h->len = T;
+    return RL_GEN_OK;
+}
+
 int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_t *next, void *hip_stream) {
     if (!h) return RL_GEN_E_NULL;
     if (!tokens) { set_err(h, "rl_gen_decode_step: NULL tokens"); return RL_GEN_E_NULL; }
@@ -798,6 +846,14 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
     if (nb < 0 || b0 < 0 || T <= 0 || T > S || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || nb > 65535)
         return RL_GEN_E_SHAPE;
     launch_prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_logprob_gather(const float *logits, int64_t ld, int32_t M, int32_t V, const int32_t *tokens, int32_t T, int64_t m_first,
+                         float *out, void *st) {
+    if (!logits || !tokens || !out) return RL_GEN_E_NULL;
+    if (M < 0 || V <= 0 || ld < V || T <= 0 || m_first < 0) return RL_GEN_E_SHAPE;
+    launch_logprob_gather(logits, ld, M, V, tokens, T, m_first, out, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

@@ -132,6 +132,46 @@ def test_width_of_the_papers_llama3_7b_row_reduced_depth():
     check(s, 6, 3, 20, 3)
 
 
+@pytest.mark.parametrize("case", ["tiny", "7b_width", "chunked_head"])
+def test_inference_call_logprobs(case):
+    """rl_gen_logprobs: one forward pass over whole sequences, log-probability of every following token.
+    |d logp| <= |d logit_target| + |d logsumexp| <= 2 * LOGIT_TOL (the logits themselves are within LOGIT_TOL)."""
+    from paper_2406_14088_amd import Generator
+    if case == "tiny":
+        shape, idx, B, T = PRESETS["tiny"].shape, 1, 5, 90       # 450 rows: the large-M projection kernel serves the LM head
+    elif case == "7b_width":
+        shape, idx, B, T = PRESETS["llama7b"].shape.with_layers(2), 2, 3, 24
+    else:   # more rows than one block of the LM head holds (vocabulary large against the workspace)
+        shape, idx, B, T = ModelShape(1, 256, 4, 4, 64, 688, 50000), 21, 6, 100
+    step(f"inference call {case}: B={B} T={T} vocab={shape.vocab}")
+    wl = Workload("t", idx, shape, B, T, 0)
+    W = make_weights(shape, idx, device="cpu")
+    Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
+    toks = make_prompts(wl)
+    om = orc.OracleModel(shape, orc.weights_to_numpy(W), B, T)
+    want = orc.sequence_logprobs(om.forward_all(toks.numpy()), toks.numpy())
+    om.close()
+    gen = Generator(shape, Wg, B, T + 1)
+    got = gen.logprobs(toks.to(DEV))
+    torch.cuda.synchronize()
+    gn = np64(got)
+    assert gn.shape == (B, T) and (gn[:, T - 1] == 0).all()
+    err = np.abs(gn[:, : T - 1] - want).max()
+    step(f"  max-abs log-prob error {err:.3e}")
+    assert err <= 2 * LOGIT_TOL
+    # the call leaves the cache as a prefill of the same tokens would: a decode step may follow
+    assert gen.state() == (B, T)
+    ref = Generator(shape, Wg, B, T + 1)
+    ref.prefill(toks.to(DEV))
+    nxt = torch.zeros((B,), dtype=torch.int32, device=DEV)
+    a, _ = gen.decode_step(nxt)
+    b, _ = ref.decode_step(nxt)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    gen.close()
+    ref.close()
+
+
 def test_prefill_equals_incremental_decode_on_device():
     """Causality/caching invariant on the GPU itself: prefill(P) and prefill(P-k) + k decode steps give the
     same last-position logits up to the bf16 path's own rounding differences."""

@@ -349,3 +349,26 @@ def test_argmax(ops, V):
     for b in range(B):
         assert int(nxt[b]) == orc.argmax(ln[b]), b
     assert int(nxt[1]) == min(17, 4000 % V) and int(nxt[2]) == 0 and int(nxt[3]) == V - 1 and int(nxt[4]) == -1
+
+
+@pytest.mark.parametrize("M,V,T,m_first", [(7, 97, 4, 0), (64, 1000, 16, 32), (33, 32000, 11, 22), (5, 128256, 5, 0)])
+def test_logprob_gather(ops, M, V, T, m_first):
+    """out[g] = log softmax(row)[next token]; rows that end a sequence get 0."""
+    step(f"logprob gather M={M} V={V} T={T} m_first={m_first}")
+    logits = randn_f32((M, V), 90 + M, std=2.5)
+    total = m_first + M + 1
+    g = torch.Generator(device="cpu").manual_seed(91)
+    tokens = torch.randint(0, V, (total,), generator=g, dtype=torch.int32).to(DEV)
+    out = torch.full((total,), float("nan"), dtype=torch.float32, device=DEV)
+    ops.logprob_gather(logits, tokens, T, m_first, out)
+    torch.cuda.synchronize()
+    ln, tn, on = np64(logits), tokens.cpu().numpy(), np64(out)
+    assert np.isnan(on[:m_first]).all() and np.isnan(on[m_first + M:]).all()       # rows outside the block are untouched
+    for r in range(M):
+        gidx = m_first + r
+        if gidx % T == T - 1:
+            assert on[gidx] == 0.0
+        else:
+            ref = orc.token_logprob(ln[r], int(tn[gidx + 1]))
+            # fp32 exp/log and a 512-way merge of (max, sum) pairs: a few ulp of the log-sum (|lse| <= ~20)
+            assert abs(on[gidx] - ref) <= 2e-5 * (1.0 + abs(ref)), (r, on[gidx], ref)
