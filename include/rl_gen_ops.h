@@ -43,9 +43,11 @@ int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_s
  * epilogue 1: SwiGLU, W_0 = gate, W_1 = up (equal shapes): out f16 [m*ldc + n] = silu(gate)*up;
  * epilogue 2: fp32 out[m*ldc + col] += result (residual add).
  * splits applies to the skinny kernel with epilogue 0 only.  kernel: 0 = choose by M, 1 = skinny
- * (weights streamed once through registers; M <= 256), 2 = tiled (both operands through LDS). */
-int rl_op_gemm(const uint16_t *A, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2, int32_t rows0,
-               int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
+ * (weights streamed once through registers; M <= 256), 2 = tiled (both operands through LDS).
+ * A_lo (kernel 2, epilogues 0 and 2; else NULL): second term of the activations, f16 [M, K] with the same stride,
+ * located above A in the same allocation: out = (A + A_lo) W^T as one contraction over [A | A_lo] x [W | W]. */
+int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2,
+               int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
                int32_t splits, int32_t epilogue, int32_t kernel, void *hip_stream);
 
 /* Weights in matrix-core fragment order.  rl_op_pack_weights converts W bf16 [N, K] row-major (K % 8 == 0)

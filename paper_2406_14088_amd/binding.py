@@ -77,7 +77,7 @@ def lib():
         "rl_gen_kernel_class_name": (C.c_char_p, [i32]),
         "rl_op_embed": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
         "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, vp, i32, i32, vp]),
-        "rl_op_gemm": (C.c_int, [vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
+        "rl_op_gemm": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
         "rl_op_packed_weight_bytes": (sz, [i32, i32]),
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
         "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp]),
@@ -299,13 +299,13 @@ class _Ops:
         self._ck(lib().rl_op_add_rmsnorm(x.data_ptr(), _ptr(part), nsplit, part_stride, gain.data_ptr(), eps, h.data_ptr(), _ptr(h_lo), M, d,
                                          _stream()), "rl_op_add_rmsnorm")
 
-    def gemm(self, A, Ws, out, ldc, M=None, lda=None, split_stride=0, splits=1, epilogue=0, kernel=0):
+    def gemm(self, A, Ws, out, ldc, M=None, lda=None, split_stride=0, splits=1, epilogue=0, kernel=0, A_lo=None):
         K = Ws[0].shape[1]
         ptrs = [w.data_ptr() for w in Ws] + [None] * (3 - len(Ws))
         rows = [w.shape[0] for w in Ws] + [0] * (3 - len(Ws))
         M = A.shape[0] if M is None else M
         lda = A.stride(0) if lda is None else lda
-        self._ck(lib().rl_op_gemm(A.data_ptr(), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K, out.data_ptr(),
+        self._ck(lib().rl_op_gemm(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K, out.data_ptr(),
                                   ldc, split_stride, splits, epilogue, kernel, _stream()), "rl_op_gemm")
 
     def packed_weight_bytes(self, N, K):

@@ -28,8 +28,9 @@ struct TiledParams {
     int tile_begin[4];
     int col_off[3];
     int64_t lda;
-    uint32_t a_bytes;  // size of A in bytes (range check)
-    int M, K, chunks, epilogue;
+    uint32_t a_bytes;  // size of A (both terms) in bytes (range check)
+    uint32_t lo_delta;  // byte distance from the first to the second activation term (0: one term)
+    int M, K, chunks, terms, epilogue;
     int tiles_m, tiles_n;
     void *out;
     int64_t ldc;
@@ -109,14 +110,19 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // Trip c covers K chunk c % chunks of activation term c / chunks: with two terms the contraction runs over
+    // [A | A_lo] against [W | W], so both products land in the same accumulators.
+    const int trips = p.chunks * p.terms;
     auto load_a1 = [&](int c, int i) {
-        uint32_t kb = (uint32_t)c * (TG_BK * 2);
-        bool kok = c * TG_BK + lc * 8 < K;
+        int term = c >= p.chunks ? 1 : 0, ck = c - term * p.chunks;
+        uint32_t kb = (uint32_t)ck * (TG_BK * 2) + (term ? p.lo_delta : 0u);
+        bool kok = c < trips && ck * TG_BK + lc * 8 < K;
         ar[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)(kok && a_off[i] != OOB ? a_off[i] + kb : OOB), 0, 0);
     };
     auto load_b1 = [&](int c, int i) {
-        uint32_t kb = (uint32_t)c * (TG_BK * 2);
-        bool kok = c * TG_BK + lc * 8 < K;
+        int ck = c >= p.chunks ? c - p.chunks : c;
+        uint32_t kb = (uint32_t)ck * (TG_BK * 2);
+        bool kok = c < trips && ck * TG_BK + lc * 8 < K;
         // piece i belongs to half (32 i) / HALF_N: a compile-time choice of descriptor
         br[i] = __builtin_amdgcn_raw_buffer_load_b128((32 * i) / HALF_N == 0 ? b_rs[0] : b_rs[1], (int)(kok ? b_off[i] + kb : OOB), 0, 0);
     };
@@ -174,7 +180,7 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) { store_b1(0, i); load_b1(1, i); }
     __builtin_amdgcn_sched_barrier(0);
-    for (int c = 0; c < p.chunks; c += 2) {
+    for (int c = 0; c < trips; c += 2) {
         body(c, std::integral_constant<int, 0>{});
         body(c + 1, std::integral_constant<int, 1>{});  // past the end: multiplies zero tiles
     }
@@ -264,6 +270,13 @@ static void launch_one(const GemmArgs &a, hipStream_t st) {
     p.A = a.A;
     p.lda = a.lda;
     p.a_bytes = (uint32_t)((((size_t)a.M - 1) * a.lda + a.K) * 2);
+    p.lo_delta = 0;
+    p.terms = 1;
+    if (a.A_lo) {  // the caller has checked that A_lo lies above A and both fit one descriptor
+        p.lo_delta = (uint32_t)((a.A_lo - a.A) * sizeof(f16_t));
+        p.a_bytes += p.lo_delta;
+        p.terms = 2;
+    }
     p.M = a.M;
     p.K = a.K;
     p.chunks = ceil_div(a.K, TG_BK);
@@ -290,11 +303,23 @@ void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
     if (a.M <= 0) return;
     const size_t out_elem = a.epilogue == EPI_SWIGLU ? sizeof(f16_t) : sizeof(float);
     size_t a_bytes = (((size_t)a.M - 1) * a.lda + a.K) * 2;
+    if (a.A_lo) a_bytes += (size_t)(a.A_lo - a.A) * 2;
+    if (a_bytes >= TG_MAX_BYTES && a.A_lo && (size_t)(a.A_lo - a.A) * 2 >= TG_MAX_BYTES / 2) {
+        // the two terms are too far apart for one descriptor: two passes, the second accumulating (fp32 outputs only)
+        GemmArgs s = a;
+        s.A_lo = nullptr;
+        launch_gemm_tiled(s, st);
+        s.A = a.A_lo;
+        s.epilogue = EPI_F32_ACC;
+        launch_gemm_tiled(s, st);
+        return;
+    }
     if (a_bytes >= TG_MAX_BYTES) {
         int rows_max = (int)((TG_MAX_BYTES / ((size_t)a.lda * 2)) / 256 * 256);
         for (int m = 0; m < a.M; m += rows_max) {
             GemmArgs s = a;
             s.A = a.A + (size_t)m * a.lda;
+            if (a.A_lo) s.A_lo = a.A_lo + (size_t)m * a.lda;
             s.M = a.M - m < rows_max ? a.M - m : rows_max;
             s.out = static_cast<char *>(a.out) + (size_t)m * a.ldc * out_elem;
             launch_gemm_tiled(s, st);

@@ -42,6 +42,8 @@ enum GemmEpilogue {
 };
 struct GemmArgs {
     const f16_t *A;       // [M, K] half, row stride lda (elements)
+    const f16_t *A_lo = nullptr;  // tiled kernel only: second term of the activations (same shape and stride, above A within
+                                  // 3.75 GB): out = (A + A_lo) W^T, computed as one contraction over [A | A_lo] x [W | W]
     int64_t lda;
     const bf16_t *W[3];
     int rows[3];          // rows of each W_i (0 for unused)

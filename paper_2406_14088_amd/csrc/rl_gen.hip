@@ -200,10 +200,11 @@ int project_packed(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_
 
 // One projection.  Returns the number of fp32 partials written to h->part() (0 when the result was
 // accumulated straight into `acc_out`).
-int project(rl_gen *h, int cls, const f16_t *A, int64_t lda, int M, int K, const bf16_t *W0, int r0, const bf16_t *W1,
-            int r1, const bf16_t *W2, int r2, float *acc_out, int64_t ld_acc, hipStream_t st) {
+int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, int M, int K, const bf16_t *W0, int r0,
+            const bf16_t *W1, int r1, const bf16_t *W2, int r2, float *acc_out, int64_t ld_acc, hipStream_t st) {
     GemmArgs a;
     a.A = A; a.lda = lda; a.M = M; a.K = K;
+    a.A_lo = M > kSkinnyMaxM ? A_lo : nullptr;  // second activation term: large-M kernel only
     a.W[0] = W0; a.W[1] = W1; a.W[2] = W2;
     a.rows[0] = r0; a.rows[1] = r1; a.rows[2] = r2;
     int N = r0 + r1 + r2;
@@ -263,8 +264,11 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         if (pk)  // both terms go through the same weight fragments into the same accumulators
             ns = project_packed(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->pw[W_Q][l], qd, h->pw[W_K][l], kvd, h->pw[W_V][l],
                                 kvd, st);
-        else
-            ns = terms * project(h, RL_GEN_K_GEMM_QKV, h->h(), d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd,
+        else if (M > kSkinnyMaxM)  // large-M kernel: one contraction over [h | h_lo] x [W | W]
+            ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
+                         nullptr, 0, st);
+        else  // row-major skinny kernel: stacked rows [h; h_lo], the consumer adds the two row blocks
+            ns = terms * project(h, RL_GEN_K_GEMM_QKV, h->h(), nullptr, d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd,
                                  h->lw[W_V][l], kvd, nullptr, 0, st);
         {
             Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
@@ -285,7 +289,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
                                      s.head_dim, s.max_seq, st);
         }
         if (pk) ns = project_packed(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->pw[W_O][l], d, nullptr, 0, nullptr, 0, st);
-        else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
+        else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), nullptr, M, d, st);
@@ -294,7 +298,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         if (pk)
             ns = project_packed(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->pw[W_DOWN][l], d, nullptr, 0, nullptr, 0, st);
         else
-            ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
+            ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, l + 1 < L ? h->lw[W_ATTN_NORM][l + 1] : h->final_norm,
@@ -731,10 +735,11 @@ int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_s
     RL_OP_RETURN();
 }
 
-int rl_op_gemm(const uint16_t *A, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2, int32_t rows0,
-               int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
+int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2,
+               int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
                int32_t splits, int32_t epilogue, int32_t kernel, void *st) {
     if (!A || !W0 || !out) return RL_GEN_E_NULL;
+    if (A_lo && (kernel != 2 || epilogue == EPI_SWIGLU || A_lo <= A)) return RL_GEN_E_SHAPE;
     if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
     if (epilogue < 0 || epilogue > 2 || kernel < 0 || kernel > 2 || splits < 1) return RL_GEN_E_SHAPE;
     if (epilogue == EPI_SWIGLU && (!W1 || rows1 != rows0 || W2)) return RL_GEN_E_SHAPE;
@@ -744,7 +749,7 @@ int rl_op_gemm(const uint16_t *A, int64_t lda, const uint16_t *W0, const uint16_
     if ((uint64_t)rows0 * K * 2 > 0xffffffffull || (uint64_t)rows1 * K * 2 > 0xffffffffull || (uint64_t)rows2 * K * 2 > 0xffffffffull)
         return RL_GEN_E_SHAPE;
     GemmArgs a;
-    a.A = A; a.lda = lda; a.M = M; a.K = K;
+    a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
     a.W[0] = W0; a.W[1] = rows1 > 0 ? W1 : nullptr; a.W[2] = rows2 > 0 ? W2 : nullptr;
     a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
     a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue;

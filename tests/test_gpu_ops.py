@@ -96,6 +96,22 @@ def test_gemm_row_stride_and_accumulate(ops, M, kernel):
     assert np.abs(np64(out) - ref).max() <= 1e-4
 
 
+@pytest.mark.parametrize("M,K,N,epilogue", [(300, 256, 688, 0), (1100, 136, 300, 0), (600, 1000, 264, 2)])
+def test_gemm_tiled_two_term_activations(ops, M, K, N, epilogue):
+    """(A + A_lo) W^T in one pass of the large-M kernel: the K loop walks [A | A_lo] against [W | W]."""
+    both = randn_f16((2 * M, K), 43)
+    both[M:] *= 2.0 ** -11
+    A, A_lo = both[:M], both[M:]
+    W = randn_bf16((N, K), 44, std=0.05)
+    out = randn_f32((M, N), 45)
+    base = np64(out) if epilogue == 2 else 0.0
+    ops.gemm(A, [W], out, N, epilogue=epilogue, kernel=2, A_lo=A_lo)
+    torch.cuda.synchronize()
+    ref = base + orc.linear(bits(W), np64(A) + np64(A_lo))
+    tol = 2e-6 * np.sqrt(K) * (np.abs(ref).max() + 1.0)
+    assert np.abs(np64(out) - ref).max() <= tol
+
+
 @pytest.mark.parametrize("M,K,F,kernel", [(4, 256, 688, 1), (128, 512, 1000, 1), (256, 256, 72, 1), (100, 256, 688, 2),
                                           (1024, 128, 8200, 2)])
 def test_gemm_swiglu(ops, M, K, F, kernel):

@@ -78,6 +78,6 @@ def test_null_arguments_are_rejected_without_a_gpu(binding):
     assert L.rl_gen_reset(None) == -1
     L.rl_gen_destroy(None)
     assert L.rl_op_argmax(None, 1, 1, None, None) == -1
-    assert L.rl_op_gemm(None, 8, None, None, None, 1, 0, 0, 1, 8, None, 1, 0, 1, 0, 0, None) == -1
+    assert L.rl_op_gemm(None, None, 8, None, None, None, 1, 0, 0, 1, 8, None, 1, 0, 1, 0, 0, None) == -1
     assert L.rl_gen_kernel_class_name(4) == b"decode_attention"
     assert len(binding.KERNEL_CLASSES) == 13
