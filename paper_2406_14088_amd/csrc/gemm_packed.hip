@@ -388,6 +388,7 @@ void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *split
     *nb = 1;
     *rows_per_wg = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
     int wgs = ceil_div(N, 128) * ceil_div(M, *rows_per_wg);
+    if (wgs < 1) wgs = 1;  // empty input
     int s = 256 / wgs;
     if (s > chunks / 8) s = chunks / 8;  // at least 8 chunks per split
     if (s > 16) s = 16;

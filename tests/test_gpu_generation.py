@@ -243,6 +243,27 @@ def test_repacking_follows_a_weight_update():
     gen.close()
 
 
+def test_degenerate_models_and_inputs():
+    """No layers (logits = LM head of the normalised embedding), a one-token prompt, a batch of one, capacity filled to the
+    last position, and token ids outside the vocabulary (clamped on the device: no fault)."""
+    from paper_2406_14088_amd import Generator
+    from dataclasses import replace
+    wl = PRESETS["tiny"]
+    check(wl.shape.with_layers(0), 31, 2, 3, 3)        # L = 0
+    check(wl.shape, 32, 1, 1, 4)                       # B = 1, P = 1
+    check(replace(wl.shape, vocab=97, ffn=72), 33, 3, 5, 3)   # sizes that are no multiple of any tile
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    gen = Generator(wl.shape, W, 2, 5)
+    bad = torch.tensor([[5, -3, 2000000, 7], [1, 2, 3, 4]], dtype=torch.int32, device=DEV)
+    clamped = torch.tensor([[5, 0, wl.shape.vocab - 1, 7], [1, 2, 3, 4]], dtype=torch.int32, device=DEV)
+    a, _ = gen.prefill(bad)
+    b, _ = gen.prefill(clamped)
+    lg, _ = gen.decode_step(torch.tensor([-1, 3], dtype=torch.int32, device=DEV))      # fills the cache to max_seq
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.isfinite(lg).all() and gen.state() == (2, 5)
+    gen.close()
+
+
 def test_error_paths_on_device():
     from paper_2406_14088_amd import Generator, RlGenError
     wl = PRESETS["tiny"]

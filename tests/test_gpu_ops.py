@@ -388,3 +388,35 @@ def test_logprob_gather(ops, M, V, T, m_first):
             ref = orc.token_logprob(ln[r], int(tn[gidx + 1]))
             # fp32 exp/log and a 512-way merge of (max, sum) pairs: a few ulp of the log-sum (|lse| <= ~20)
             assert abs(on[gidx] - ref) <= 2e-5 * (1.0 + abs(ref)), (r, on[gidx], ref)
+
+
+def test_empty_inputs_enqueue_nothing(ops):
+    """M = 0 / B = 0: every entry point returns success and leaves its outputs alone.  (Called through the C ABI directly:
+    an empty torch tensor has a NULL pointer, which the entry points reject.)"""
+    from paper_2406_14088_amd.binding import lib
+    L = lib()
+    d, V = 64, 97
+    sentinel = lambda *shape, dtype=torch.float32: torch.full(shape, 7.0, dtype=dtype, device=DEV)
+    emb, gain, W = randn_bf16((V, d), 1), randn_bf16((d,), 2), randn_bf16((96, d), 3)
+    x, h, out, lg = sentinel(2, d), sentinel(2, d, dtype=torch.float16), sentinel(2, 96), sentinel(2, V)
+    A = randn_f16((2, d), 4)
+    toks = torch.zeros((2,), dtype=torch.int32, device=DEV)
+    nxt = torch.full((2,), 5, dtype=torch.int32, device=DEV)
+    kc = torch.zeros((1, 1, 8, 64), dtype=torch.float16, device=DEV)
+    P = torch.zeros(ops.packed_weight_bytes(96, d) // 2, dtype=torch.int16, device=DEV)
+    ops.pack_weights(W, P)
+    p = lambda t: t.data_ptr()
+    rcs = [
+        L.rl_op_embed(p(toks), p(emb), p(x), 0, d, V, None),
+        L.rl_op_add_rmsnorm(p(x), None, 0, 0, p(gain), 1e-5, p(h), None, 0, d, None),
+        L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 1, None),
+        L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 2, None),
+        L.rl_op_gemm_packed(p(A), None, d, p(P), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 0, 0, 0, None),
+        L.rl_op_argmax(p(lg), 0, V, p(nxt), None),
+        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), p(h), None, 0, 1, 1, 64, 8, 1, None),
+        L.rl_op_prefill_attention(p(h), p(kc), p(kc), p(h), 0, 0, 1, 1, 1, 64, 8, None),
+        L.rl_op_logprob_gather(p(lg), V, 0, V, p(toks), 4, 0, p(x), None),
+    ]
+    torch.cuda.synchronize()
+    assert rcs == [0] * len(rcs), rcs
+    assert (x == 7).all() and (h == 7).all() and (out == 7).all() and (nxt == 5).all() and (lg == 7).all()
