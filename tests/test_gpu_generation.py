@@ -313,52 +313,56 @@ def test_zz_overall_agreement():
 
 
 def test_benchmark_workload_full_size_sampled():
-    """The benchmark configuration itself (LLaMA-7B shape, all 32 layers, batch 128, prompt 128, HIP-graph decode):
-    the GPU runs the whole batch exactly as bench.py does; the oracle recomputes sampled sequences one by one (sequences
-    are independent) and is fed the GPU's own greedy tokens, so both sides see identical inputs at every step."""
+    """The benchmark configuration itself (LLaMA-7B shape, all 32 layers, batch 128, prompt 128, 256 generated tokens,
+    packed weights, HIP-graph decode): the GPU runs the whole batch exactly as bench.py does; the oracle recomputes sampled
+    sequences one by one (sequences are independent) and is fed the GPU's own greedy tokens, so both sides see identical
+    inputs at every one of the 256 steps."""
     from paper_2406_14088_amd import Generator
     wl = PRESETS["llama7b"]
-    shape, B, P = wl.shape, wl.batch, wl.prompt_len
-    sample, steps = [5, 77], 3
+    shape, B, P, G = wl.shape, wl.batch, wl.prompt_len, wl.gen_len
+    sample = [5, 77]
     step("7B full depth: drawing weights on the GPU")
     W = make_weights(shape, wl.index, device=DEV)
     prompts = make_prompts(wl, device=DEV)
     gen = Generator(shape, W, B, wl.max_seq)
     bufs = [torch.empty((B,), dtype=torch.int32, device=DEV) for _ in range(2)]
-    g_logits = [gen.prefill(prompts, next_tokens=bufs[0])[0].clone()]
-    g_tokens = [bufs[0].clone()]
+    lowest_argmax = lambda lg: (lg == lg.max(-1, keepdim=True).values).int().argmax(-1)   # first index of the maximum
+    lg = gen.prefill(prompts, next_tokens=bufs[0])[0]
+    g_logits, g_tokens = [lg[sample].clone()], [bufs[0][sample].clone()]
+    assert torch.isfinite(lg).all() and torch.equal(bufs[0].long(), lowest_argmax(lg))
     cur = 0
-    for _ in range(steps):
+    for i in range(G - 1):
         lg, _ = gen.decode_step(bufs[cur], next_tokens=bufs[1 - cur])
         cur = 1 - cur
-        g_logits.append(lg.clone())
-        g_tokens.append(bufs[cur].clone())
+        g_logits.append(lg[sample].clone())
+        g_tokens.append(bufs[cur][sample].clone())
+        if i % 32 == 0 or i == G - 2:        # whole-batch properties that hold at any size
+            assert torch.isfinite(lg).all() and torch.equal(bufs[cur].long(), lowest_argmax(lg))
     torch.cuda.synchronize()
-    assert gen.state() == (B, P + steps)
+    assert gen.state() == (B, P + G - 1)
     gen.close()
     step("copying weights to the host for the oracle")
     Wn = orc.weights_to_numpy(W)
     del W
-    om = orc.OracleModel(shape, Wn, len(sample), P + steps + 1)
+    om = orc.OracleModel(shape, Wn, len(sample), P + G)
     step("oracle prefill of the sampled sequences")
     o_logits, o_next = om.prefill(prompts[sample].cpu().numpy())
     worst, agree, total = 0.0, 0, 0
-    for i in range(steps + 1):
-        gl = np64(g_logits[i][sample])
-        gn = g_tokens[i][sample].cpu().numpy()
+    for i in range(G):
+        gl = np64(g_logits[i])
+        gn = g_tokens[i].cpu().numpy()
         err = np.abs(gl - o_logits).max()
         worst = max(worst, err)
-        step(f"  step {i}: max-abs logit error {err:.3e}, rms {np.sqrt(((gl - o_logits) ** 2).mean()):.3e}")
+        if i < 4 or i % 32 == 0 or i == G - 1:
+            step(f"  step {i}: max-abs logit error {err:.3e}, rms {np.sqrt(((gl - o_logits) ** 2).mean()):.3e}")
+        assert err <= LOGIT_TOL, (i, err)
         assert np.array_equal(gn, np.array([orc.argmax(r) for r in gl]))
         for b in np.nonzero(gn != o_next)[0]:
             assert o_logits[b, o_next[b]] - o_logits[b, gn[b]] <= 2.0 * err
         agree += int((gn == o_next).sum())
         total += len(gn)
-        if i < steps:
+        if i < G - 1:
             o_logits, o_next = om.decode_step(gn)      # the oracle is fed the GPU's tokens
+    om.close()
     step(f"  worst {worst:.3e}, greedy agreement {agree}/{total}")
-    # whole-batch properties that hold at any size: finite logits, tokens = argmax of the GPU's logits
-    for i in range(steps + 1):
-        assert torch.isfinite(g_logits[i]).all()
-        assert torch.equal(g_tokens[i].long(), g_logits[i].argmax(-1)) or True
-    assert worst <= LOGIT_TOL
+    assert agree >= 0.99 * total
