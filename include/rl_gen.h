@@ -19,9 +19,10 @@
  *     that point.  One handle must not be used from two streams or two host threads at once.
  *   - Return value: RL_GEN_OK (0) or a negative rl_gen_status.  A failed call leaves the sequence
  *     state (batch, length) unchanged.  No exception crosses this boundary.
- *   - Number formats: weights are bf16 (as given) and are widened to IEEE half inside the kernels;
- *     activations that feed a projection and the KV cache are IEEE half (same size as bf16, 11
- *     instead of 8 significant bits); the residual stream, normalisation statistics, softmax,
+ *   - Number formats: weights are bf16 (as given) and are widened to IEEE half inside the kernels, or
+ *     once per generation phase into the fragment-order copies of rl_gen_pack_weights (exact for
+ *     |w| >= 2^-14); activations that feed a projection and the KV cache are IEEE half (same size as
+ *     bf16, 11 instead of 8 significant bits); the residual stream, normalisation statistics, softmax,
  *     accumulators and logits are fp32.
  *   - Matrices are row-major [out_features, in_features]; token ids are int32 in [0, vocab) --
  *     ids outside that range are clamped on the device (no fault), the result is then unspecified.
