@@ -127,6 +127,13 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
  * sequence has length T and decode steps may follow). */
 int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logp, void *hip_stream);
 
+/* Inference call with a scalar head (Section 2.1: the Critic and Reward models score every token of prompt +
+ * response with one number).  head: DEVICE [hidden], of the handle's weight dtype (bf16 bits, or fp32 when
+ * weight_dtype is 0), borrowed for the call.  values: DEVICE fp32 [B, T]: values[b, i] = head . (final RMSNorm of
+ * the residual stream at position i), the normalised row rounded to half as for the LM head.  The decoder
+ * weights are the handle's; limits, errors and the effect on the sequence state are those of rl_gen_logprobs. */
+int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, const void *head, float *values, void *hip_stream);
+
 /* Whether decode steps are replayed as one captured HIP graph (1, default) or launched kernel by
  * kernel (0).  Both produce identical results. */
 int rl_gen_set_graph(rl_gen_t *h, int32_t enabled);

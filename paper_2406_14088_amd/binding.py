@@ -66,6 +66,7 @@ def lib():
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "rl_gen_logprobs": (C.c_int, [vp, vp, i32, i32, vp, vp]),
+        "rl_gen_values": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_set_graph": (C.c_int, [vp, i32]),
         "rl_gen_set_qkv_terms": (C.c_int, [vp, i32]),
         "rl_gen_reset": (C.c_int, [vp]),
@@ -102,7 +103,7 @@ def lib():
 
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_packed_bytes",
-    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_logprobs",
+    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_fused",
@@ -246,6 +247,17 @@ class Generator:
             logp = torch.empty((B, T), dtype=torch.float32, device=tokens.device)
         self._check(lib().rl_gen_logprobs(self._h, tokens.data_ptr(), B, T, logp.data_ptr(), _stream()), "rl_gen_logprobs")
         return logp
+
+    def values(self, tokens, head, out=None):
+        """tokens: int32 GPU tensor [B, T]; head: GPU tensor [hidden] of the weights' dtype.  Returns fp32 [B, T]."""
+        import torch
+        B, T = tokens.shape
+        assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        assert head.is_cuda and head.is_contiguous() and head.numel() == self.shape.hidden and head.dtype == self._keep[0].dtype
+        if out is None:
+            out = torch.empty((B, T), dtype=torch.float32, device=tokens.device)
+        self._check(lib().rl_gen_values(self._h, tokens.data_ptr(), B, T, head.data_ptr(), out.data_ptr(), _stream()), "rl_gen_values")
+        return out
 
     def set_graph(self, enabled: bool):
         self._check(lib().rl_gen_set_graph(self._h, int(enabled)), "rl_gen_set_graph")

@@ -251,6 +251,27 @@ void launch_logprob_gather(const float *logits, int64_t ld, int M, int V, const 
     logprob_gather_kernel<<<M, LP_THREADS, 0, st>>>(logits, ld, V, tokens, T, m_first, out);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Scalar head: out[m] = sum_k h[m, k] * w[k] (h half, w bf16 or fp32, fp32 accumulation), one wavefront per row.
+__global__ __launch_bounds__(256) void rowdot_kernel(const f16_t *__restrict__ h, const void *__restrict__ w, int w_is_f32, int M,
+                                                     int d, float *__restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const f16_t *row = h + (size_t)m * d;
+    float acc = 0.f;
+    for (int k = lane; k < d; k += 64) {
+        float wk = w_is_f32 ? reinterpret_cast<const float *>(w)[k] : bf16_to_f32(reinterpret_cast<const bf16_t *>(w)[k]);
+        acc = fmaf(f16_to_f32(row[k]), wk, acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) out[m] = acc;
+}
+void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st) {
+    if (M <= 0) return;
+    rowdot_kernel<<<ceil_div(M, 4), 256, 0, st>>>(h, w, w_is_f32, M, d, out);
+}
+
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st) { set_i32_kernel<<<1, 1, 0, st>>>(p, v); }
 

@@ -20,6 +20,8 @@ void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M
 // next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN); optionally *inc_len += 1.
 void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *inc_len, hipStream_t st);
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
+// out[m] = sum_k h[m, k] * w[k]   (h half [M, d]; w bf16 or fp32 [d]; fp32 accumulation)
+void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st);
 // Rows m_first .. m_first + M - 1 of a [n_seq * T] token grid: out[g] = log softmax(logits[g - m_first, :])[tokens[g + 1]],
 // 0 for the last position of a sequence.  logits fp32 [M, V] with row stride ld.
 void launch_logprob_gather(const float *logits, int64_t ld, int M, int V, const int32_t *tokens, int T, int64_t m_first,

@@ -592,6 +592,33 @@ int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, fl
     return RL_GEN_OK;
 }
 
+int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, const void *head, float *values, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!tokens || !head || !values) { set_err(h, "rl_gen_values: NULL argument"); return RL_GEN_E_NULL; }
+    if (B <= 0 || T <= 0) { set_err(h, "rl_gen_values: B and T must be positive"); return RL_GEN_E_SHAPE; }
+    if (B > h->s.max_batch || T > h->s.max_seq) {
+        set_err(h, "rl_gen_values: B=%d T=%d exceed capacity %d x %d", B, T, h->s.max_batch, h->s.max_seq);
+        return RL_GEN_E_CAPACITY;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    int per_chunk = h->wp.rows / T;
+    if (per_chunk < 1) per_chunk = 1;
+    for (int b0 = 0; b0 < B; b0 += per_chunk) {
+        int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
+        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
+        Scope sc(h, RL_GEN_K_MISC, st);
+        launch_rowdot(h->h(), head, h->s.weight_dtype == 0, nb * T, h->s.hidden, values + (size_t)b0 * T, st);
+    }
+    {
+        Scope sc(h, RL_GEN_K_MISC, st);
+        launch_set_i32(h->d_len(), T, st);
+    }
+    int rc = check_hip(h, "rl_gen_values");
+    if (rc != RL_GEN_OK) return rc;
+    h->B = B; h->len = T;
+    return RL_GEN_OK;
+}
+
 int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_t *next, void *hip_stream) {
     if (!h) return RL_GEN_E_NULL;
     if (!tokens) { set_err(h, "rl_gen_decode_step: NULL tokens"); return RL_GEN_E_NULL; }

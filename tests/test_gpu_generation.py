@@ -172,6 +172,29 @@ def test_inference_call_logprobs(case):
     ref.close()
 
 
+@pytest.mark.parametrize("fp32_weights", [False, True])
+def test_inference_call_scalar_head(fp32_weights):
+    """rl_gen_values: the Critic/Reward form of the inference call.  A scalar head w gives, at every position, what the LM
+    head would give for a vocabulary row equal to w: the oracle runs the same decoder with w as row 0 of its LM head."""
+    from paper_2406_14088_amd import Generator
+    shape, idx, B, T = ModelShape(2, 256, 4, 2, 64, 688, 300), 23, 5, 70
+    wl = Workload("t", idx, shape, B, T, 0)
+    W = make_weights(shape, idx, device="cpu", dtype=torch.float32 if fp32_weights else torch.bfloat16)
+    head = W["lm_head"][0].clone()
+    Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
+    toks = make_prompts(wl)
+    om = orc.OracleModel(shape, orc.weights_to_numpy(W, as_bf16_bits=not fp32_weights), B, T)
+    want = om.forward_all(toks.numpy())[:, :, 0]
+    om.close()
+    gen = Generator(shape, Wg, B, T)
+    got = np64(gen.values(toks.to(DEV), head.to(DEV)))
+    torch.cuda.synchronize()
+    err = np.abs(got - want).max()
+    step(f"  scalar head: max-abs error {err:.3e}")
+    assert got.shape == (B, T) and err <= LOGIT_TOL and gen.state() == (B, T)
+    gen.close()
+
+
 def test_prefill_equals_incremental_decode_on_device():
     """Causality/caching invariant on the GPU itself: prefill(P) and prefill(P-k) + k decode steps give the
     same last-position logits up to the bf16 path's own rounding differences."""
