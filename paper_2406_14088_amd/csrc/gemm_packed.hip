@@ -17,7 +17,7 @@
 //           run two or four K chunks (4 NB fragments each) ahead in a register ring.
 //           The activation chunk [128 rows, 64 k] is shared by the four wavefronts of a workgroup: it is
 //           copied global -> LDS by the load unit itself (buffer loads with the LDS bit: no registers,
-//           no ds_write), in an XOR-swizzled layout whose fragment reads are bank-conflict free, two
+//           no ds_write), in an XOR-swizzled layout whose fragment reads are free of bank conflicts, two
 //           chunks ahead in a three-deep buffer ring.
 //           TERMS = 2 multiplies the same weight fragment with two activation tiles (the two-term split
 //           of the normalised activations) into the same accumulators.
@@ -158,26 +158,29 @@ __global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_pa
     const int ks_end = c1 * 4 < p.ksteps ? c1 * 4 : p.ksteps;
 
     // ---- activation copy global -> LDS.  Instruction i of wavefront w fills the 1 KB block of rows
-    //      8 (MT w + i) .. + 7 of a tile: lane l lands at byte 16 l of the block, i.e. row l / 8, slot l % 8, and
-    //      fetches piece (l % 8) ^ (l / 8) of that row, so that piece g of row r sits in slot g ^ (r & 7).
+    //      8 (MT w + i) .. + 7 of a tile: lane l lands at byte 16 l of the block, i.e. row l / 8, slot l % 8.
+    //      Piece g (16 bytes) of row r is kept in slot g ^ ((r >> 1) & 7): the LDS has 64 banks (256 bytes per
+    //      clock), a 16-byte-per-lane read is served 16 lanes at a time, and a fragment read has 16 consecutive
+    //      rows of one piece in those lanes -- two rows per 256 bytes, so the slot must change every second row.
     __amdgpu_buffer_rsrc_t ar[TERMS];
     ar[0] = pk_rsrc(p.A, p.a_bytes);
     if (TERMS == 2) ar[TERMS - 1] = pk_rsrc(p.A_lo, p.a_bytes);
-    const int xg = (lane & 7) ^ (lane >> 3);
     uint32_t x_off[MT];
+    int x_piece[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
         int row = (w * MT + i) * 8 + (lane >> 3);
-        x_off[i] = row < Mloc ? (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)xg * 16u : PK_OOB;
+        x_piece[i] = (lane & 7) ^ ((row >> 1) & 7);
+        x_off[i] = row < Mloc ? (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)x_piece[i] * 16u : PK_OOB;
     }
     auto copy_x = [&](int c, int buf) {
-        bool ok = c < c1 && (c * PK_BK + xg * 8 < K);
         uint32_t cb = (uint32_t)c * (PK_BK * 2);
 #pragma unroll
         for (int tm = 0; tm < TERMS; ++tm)
 #pragma unroll
             for (int i = 0; i < MT; ++i) {
                 unsigned char *dst = smem + buf * XBUF + tm * XTILE + (w * MT + i) * 1024;
+                bool ok = c < c1 && (c * PK_BK + x_piece[i] * 8 < K);
                 uint32_t off = ok && x_off[i] != PK_OOB ? x_off[i] + cb : PK_OOB;
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(ar[tm], LDS_PTR(dst), 16, (int)off, 0, 0, 0);
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_pa
     // fragment of k-step s, tile mt: row 32 mt + (lane & 31), pieces 2 s + (lane >> 5)
     int xld[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) xld[s] = (lane & 31) * 128 + (((2 * s + (lane >> 5)) ^ (lane & 7)) << 4);
+    for (int s = 0; s < 4; ++s) xld[s] = (lane & 31) * 128 + (((2 * s + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
     u32x4_t ring[RC * NBF];  // weight fragments in flight: slots (i % RC) * NBF + s * NB + j belong to chunk c0 + i
     auto load_w = [&](int c, int s, int j, int slot) {

@@ -90,12 +90,16 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
         // rows past the matrix read row 0 instead (always in bounds); their columns are never stored
         w_off[i] = (uint32_t)(r < rows ? r : 0) * (uint32_t)K * 2u + (uint32_t)kg * 128u + (uint32_t)(lane & 7) * 16u;
     }
-    // wavefront-private LDS strip, [2][32 rows][8 pieces of 16 B]; piece j of row r sits in slot j ^ (r & 7)
+    // wavefront-private LDS strip, [2][32 rows][8 pieces of 16 B]; piece j of row r sits in slot j ^ ((r >> 1) & 7):
+    // 64 banks = 256 bytes = two rows per clock, and a fragment read has 16 consecutive rows in the 16 lanes served
+    // together, so the slot changes every second row
     unsigned char *wl = smem + SK_X_BYTES + w * 8192;
-    const int wst = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) << 4);  // store address (row = lane/8 + 8i)
+    int wst[4];  // store address of instruction i (row = lane/8 + 8i)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wst[i] = (lane >> 3) * 128 + (((lane & 7) ^ (((8 * i + (lane >> 3)) >> 1) & 7)) << 4);
     int wld[4];                                                             // fragment address of k-step s
 #pragma unroll
-    for (int s = 0; s < 4; ++s) wld[s] = (lane & 31) * 128 + (((2 * s + (lane >> 5)) ^ (lane & 7)) << 4);
+    for (int s = 0; s < 4; ++s) wld[s] = (lane & 31) * 128 + (((2 * s + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
 
     // ---- K range of this split
     const int c0 = (int)(((int64_t)blockIdx.y * p.chunks) / p.splits);
@@ -137,7 +141,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
         wq[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(c < c1 ? w_off[i] + cb : SK_OOB), 0, 0);
     };
     auto stage_w1 = [&](int slot, int buf, int i) {  // ring slot -> half -> LDS strip `buf`
-        *reinterpret_cast<u32x4_t *>(wl + buf * 4096 + i * 1024 + wst) = bf16x8_to_f16x8(wq[slot]);
+        *reinterpret_cast<u32x4_t *>(wl + buf * 4096 + i * 1024 + wst[i]) = bf16x8_to_f16x8(wq[slot]);
     };
 
     // One chunk (index i relative to c0, PAR = i & 1): MFMAs on the strip/tile staged one chunk ago.
