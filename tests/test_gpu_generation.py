@@ -287,6 +287,35 @@ def test_degenerate_models_and_inputs():
     gen.close()
 
 
+def test_graph_cache_eviction_and_internal_logit_buffer():
+    """More distinct (token, next) buffer pairs than the library keeps captured graphs for, and decode steps that keep the
+    logits in the library's own workspace: tokens must equal those of a plain eager run."""
+    from paper_2406_14088_amd import Generator
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    ref = Generator(wl.shape, W, wl.batch, wl.max_seq)
+    ref.set_graph(False)
+    _, t = ref.prefill(prompts)
+    want = [t.clone()]
+    for _ in range(wl.gen_len - 1):
+        _, t = ref.decode_step(want[-1])
+        want.append(t.clone())
+    ref.close()
+    gen = Generator(wl.shape, W, wl.batch, wl.max_seq)
+    bufs = [torch.empty((wl.batch,), dtype=torch.int32, device=DEV) for _ in range(11)]   # 11 buffers: 11 distinct pairs in a ring
+    gen.prefill(prompts, next_tokens=bufs[0])
+    got = [bufs[0].clone()]
+    for i in range(wl.gen_len - 1):
+        a, b = bufs[i % 11], bufs[(i + 1) % 11]
+        gen.decode_step(a, next_tokens=b, want_logits=False)
+        got.append(b.clone())
+    torch.cuda.synchronize()
+    for g, w_ in zip(got, want):
+        assert torch.equal(g, w_)
+    gen.close()
+
+
 def test_error_paths_on_device():
     from paper_2406_14088_amd import Generator, RlGenError
     wl = PRESETS["tiny"]
