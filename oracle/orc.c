@@ -173,6 +173,29 @@ double orc_token_logprob(const double *x, int n, int target) {
     return x[target] - (mx + log(sum));
 }
 
+/* Temperature sampling by inversion (Section 2.1 samples the next token; the uniform draw u in [0, 1) is an input):
+ * p_v = softmax(x / temperature)_v, result = the smallest v with p_0 + ... + p_v > u (the last index with p > 0 if
+ * rounding leaves the total at or below u).  -1 for n <= 0, temperature <= 0 or a NaN logit. */
+int32_t orc_sample(const double *x, int n, double temperature, double u) {
+    if (n <= 0 || !(temperature > 0.0)) return -1;
+    double mx = x[0];
+    for (int i = 0; i < n; ++i) {
+        if (x[i] != x[i]) return -1;
+        if (x[i] > mx) mx = x[i];
+    }
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) total += exp((x[i] - mx) / temperature);
+    double run = 0.0;
+    int32_t last = 0;
+    for (int i = 0; i < n; ++i) {
+        double p = exp((x[i] - mx) / temperature) / total;
+        if (p > 0.0) last = i;
+        run += p;
+        if (run > u) return i;
+    }
+    return last;
+}
+
 /* ------------------------------------------------------------------ closed forms */
 
 static int shape_ok(const orc_shape *s) {

@@ -52,6 +52,8 @@ def lib():
         L.orc_silu.restype = C.c_double
         L.orc_argmax.argtypes = [dp, C.c_int]
         L.orc_argmax.restype = C.c_int32
+        L.orc_sample.argtypes = [dp, C.c_int, C.c_double, C.c_double]
+        L.orc_sample.restype = C.c_int32
         L.orc_token_logprob.argtypes = [dp, C.c_int, C.c_int]
         L.orc_token_logprob.restype = C.c_double
         L.orc_param_count.argtypes = [C.POINTER(OrcShape)]
@@ -149,6 +151,11 @@ def silu(z: float) -> float:
 def argmax(x: np.ndarray) -> int:
     x = np.ascontiguousarray(x, dtype=np.float64)
     return int(lib().orc_argmax(_dp(x), x.shape[0]))
+
+
+def sample(x: np.ndarray, temperature: float, u: float) -> int:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    return int(lib().orc_sample(_dp(x), x.shape[0], float(temperature), float(u)))
 
 
 def token_logprob(x: np.ndarray, target: int) -> float:

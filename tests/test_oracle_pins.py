@@ -401,3 +401,33 @@ def test_sequence_logprobs_follow_the_next_token():
     lp2 = orc.sequence_logprobs(om.forward_all(toks2), toks2)
     assert np.array_equal(lp[:, :5], lp2[:, :5]) and not np.array_equal(lp[:, 5:], lp2[:, 5:])
     om.close()
+
+
+# ---------------------------------------------------------------------------------------------- temperature sampling
+def test_sampling_by_inversion_pins():
+    from scipy.special import softmax
+    rng = np.random.default_rng(5)
+    x = rng.normal(0, 2.0, size=50)
+    # against the library: index where the cumulative softmax first exceeds u
+    for temp in (0.5, 1.0, 2.0):
+        cdf = np.cumsum(softmax(x / temp))
+        for u in (0.0, 0.1234, 0.5, 0.87, 0.999):
+            assert orc.sample(x, temp, u) == int(np.searchsorted(cdf, u, side="right"))
+    # uniform logits: the u-th equal slice
+    for u, want in ((0.0, 0), (0.249, 0), (0.251, 1), (0.99, 3)):
+        assert orc.sample(np.zeros(4), 1.0, u) == want
+    # two logits with probabilities 1/4 and 3/4
+    two = np.array([0.0, np.log(3.0)])
+    assert orc.sample(two, 1.0, 0.2499) == 0 and orc.sample(two, 1.0, 0.2501) == 1
+    # temperature scales the logits: at T = 2 the same logits give 1/(1+sqrt 3) and the rest
+    b = 1.0 / (1.0 + np.sqrt(3.0))
+    assert orc.sample(two, 2.0, b - 1e-6) == 0 and orc.sample(two, 2.0, b + 1e-6) == 1
+    # cold temperature concentrates on the argmax; a probability-zero tail is never drawn
+    assert all(orc.sample(x, 1e-3, u) == int(np.argmax(x)) for u in (0.0, 0.5, 0.999999))
+    assert orc.sample(np.array([0.0, -5000.0]), 1.0, 0.9999999999) == 0
+    # empirical frequencies follow the probabilities (20000 evenly spaced draws: exact up to 1/20000 per cell)
+    p = softmax(x)
+    counts = np.bincount([orc.sample(x, 1.0, (i + 0.5) / 20000) for i in range(20000)], minlength=50)
+    assert np.abs(counts / 20000 - p).max() <= 1.5 / 20000
+    # invalid input
+    assert orc.sample(x, 0.0, 0.5) == -1 and orc.sample(np.array([0.0, np.nan]), 1.0, 0.5) == -1
