@@ -138,6 +138,13 @@ int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, cons
  * kernel (0).  Both produce identical results. */
 int rl_gen_set_graph(rl_gen_t *h, int32_t enabled);
 
+/* Sampling instead of the greedy choice (Section 2.1: the generation call samples the next token).  temperature > 0:
+ * prefill and decode steps return next[b] = the smallest v whose cumulative softmax(logits[b] / temperature) exceeds
+ * u[b], with u: DEVICE fp32 [max_batch] of uniform draws in [0, 1), borrowed until the next call of this function;
+ * the caller refreshes its contents between steps (in stream order) -- the library draws no random numbers.
+ * temperature <= 0 (u may be NULL): back to greedy.  Takes effect from the next step. */
+int rl_gen_set_sampling(rl_gen_t *h, float temperature, const float *u);
+
 /* Number of half-precision terms in which the normalised activations reach the QKV projection: 2 (default;
  * the projection runs on the stacked rows [h; h - half(h)] and k, v, q carry ~22-bit activations) or 1 (faster,
  * less accurate: the projection that feeds the KV cache is the rounding the logits are most sensitive to).

@@ -110,6 +110,11 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
 /* Greedy token: next[b] = lowest index of the largest of logits[b, 0..V-1]; -1 if the row has a NaN. */
 int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *hip_stream);
 
+/* Temperature sampling by inversion: next[b] = smallest v with sum_{i<=v} e_i > u[b] * sum_i e_i, e_i = exp((logits[b,i] -
+ * max_i logits[b,i]) / temperature); u fp32 [B] in [0, 1); temperature > 0; -1 if the row has a NaN.  fp32 sums in a fixed
+ * order (deterministic); a draw within rounding distance of a step of the cumulative distribution may land on either side. */
+int rl_op_sample(const float *logits, int32_t B, int32_t V, float temperature, const float *u, int32_t *next, void *hip_stream);
+
 /* Log-probability of the following token (Section 2.1, inference call): for the M rows g = m_first .. m_first+M-1 of
  * a flattened [n_seq, T] token grid, out[g] = logits[g - m_first, tokens[g+1]] - log sum_v exp(logits[g - m_first, v]);
  * rows with g % T == T-1 (no following token) get 0.  logits fp32 [M, V] with row stride ld; tokens int32, indexed

@@ -69,6 +69,7 @@ def lib():
         "rl_gen_values": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_set_graph": (C.c_int, [vp, i32]),
         "rl_gen_set_qkv_terms": (C.c_int, [vp, i32]),
+        "rl_gen_set_sampling": (C.c_int, [vp, f32, vp]),
         "rl_gen_reset": (C.c_int, [vp]),
         "rl_gen_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32)]),
         "rl_gen_destroy": (None, [vp]),
@@ -89,6 +90,7 @@ def lib():
         "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
+        "rl_op_sample": (C.c_int, [vp, i32, i32, f32, vp, vp, vp]),
         "rl_op_logprob_gather": (C.c_int, [vp, i64, i32, i32, vp, i32, i64, vp, vp]),
         "rl_op_copy": (C.c_int, [vp, vp, sz, vp]),
     }
@@ -104,10 +106,10 @@ def lib():
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_packed_bytes",
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_logprobs", "rl_gen_values",
-    "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
+    "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_fused",
-    "rl_op_prefill_attention", "rl_op_argmax", "rl_op_logprob_gather", "rl_op_copy")
+    "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
 def _shape_of(shape, max_batch=1, max_seq=1, weight_dtype=1) -> RlGenShape:
@@ -262,6 +264,12 @@ class Generator:
     def set_graph(self, enabled: bool):
         self._check(lib().rl_gen_set_graph(self._h, int(enabled)), "rl_gen_set_graph")
 
+    def set_sampling(self, temperature: float, u=None):
+        """temperature > 0: sample with the uniform draws in `u` (fp32 GPU tensor [max_batch], refreshed by the caller between
+        steps); temperature <= 0: greedy."""
+        self._sample_u = u           # keep the borrowed tensor alive
+        self._check(lib().rl_gen_set_sampling(self._h, float(temperature), _ptr(u)), "rl_gen_set_sampling")
+
     def set_qkv_terms(self, terms: int):
         self._check(lib().rl_gen_set_qkv_terms(self._h, int(terms)), "rl_gen_set_qkv_terms")
 
@@ -360,6 +368,10 @@ class _Ops:
     def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):
         self._ck(lib().rl_op_prefill_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), nb, b0, T, Hq, Hkv,
                                                hd, S, _stream()), "rl_op_prefill_attention")
+
+    def sample(self, logits, temperature, u, nxt):
+        B, V = logits.shape
+        self._ck(lib().rl_op_sample(logits.data_ptr(), B, V, float(temperature), u.data_ptr(), nxt.data_ptr(), _stream()), "rl_op_sample")
 
     def logprob_gather(self, logits, tokens, T, m_first, out):
         M, V = logits.shape

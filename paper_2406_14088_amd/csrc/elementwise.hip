@@ -272,6 +272,87 @@ void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, fl
     rowdot_kernel<<<ceil_div(M, 4), 256, 0, st>>>(h, w, w_is_f32, M, d, out);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Temperature sampling by inversion: e_v = exp((x_v - max) / temperature), next = smallest v with
+// e_0 + ... + e_v > u * sum(e); -1 if the row holds a NaN.  One workgroup per row.  Every thread owns a contiguous
+// segment of the row, the segment sums are scanned in thread order (fixed summation order: deterministic), and the
+// one thread whose prefix range contains the target walks its segment.
+#define SP_THREADS 1024
+__global__ __launch_bounds__(SP_THREADS) void sample_kernel(const float *__restrict__ logits, int V, float inv_temp,
+                                                            const float *__restrict__ u, int32_t *__restrict__ next,
+                                                            int32_t *inc_len) {
+    __shared__ float red[SP_THREADS / RL_WAVE];
+    __shared__ float bcast;
+    __shared__ int snan, stoken;
+    const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const float *row = logits + (size_t)b * V;
+    const int seg = (V + SP_THREADS - 1) / SP_THREADS;
+    const int i0 = t * seg < V ? t * seg : V, i1 = i0 + seg < V ? i0 + seg : V;
+    if (t == 0) { snan = 0; stoken = -1; }
+    __syncthreads();
+    // ---- row maximum
+    float m = -INFINITY;
+    bool nan = false;
+    for (int i = i0; i < i1; ++i) { float x = row[i]; nan |= (x != x); m = fmaxf(m, x); }
+    m = wave_max(m);
+    if (nan) snan = 1;
+    if (lane == 0) red[wv] = m;
+    __syncthreads();
+    if (t == 0) {
+        float mm = red[0];
+        for (int w = 1; w < SP_THREADS / RL_WAVE; ++w) mm = fmaxf(mm, red[w]);
+        bcast = mm;
+    }
+    __syncthreads();
+    const float mx = bcast;
+    const bool bad = snan != 0;
+    __syncthreads();
+    // ---- segment sums and their inclusive scan in thread order
+    float s = 0.f;
+    for (int i = i0; i < i1; ++i) s += expf((row[i] - mx) * inv_temp);
+    float incl = s;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        float up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) red[wv] = incl;
+    __syncthreads();
+    float base = 0.f;
+    for (int w = 0; w < wv; ++w) base += red[w];
+    float total = 0.f;
+    for (int w = 0; w < SP_THREADS / RL_WAVE; ++w) total += red[w];
+    incl += base;
+    const float excl = incl - s;
+    const float target = u[b] * total;
+    // ---- the thread whose range [excl, incl) holds the target walks its segment
+    if (!bad && s > 0.f && excl <= target && target < incl) {
+        float run = excl;
+        int tok = i1 - 1;
+        for (int i = i0; i < i1; ++i) {
+            run += expf((row[i] - mx) * inv_temp);
+            if (run > target) { tok = i; break; }
+        }
+        stoken = tok;
+    }
+    __syncthreads();
+    if (t == 0) {
+        int tok = stoken;
+        if (!bad && tok < 0) {  // u * total rounded up to the total: the last index that carries weight
+            for (int i = V - 1; i >= 0; --i)
+                if (expf((row[i] - mx) * inv_temp) > 0.f) { tok = i; break; }
+        }
+        next[b] = bad ? -1 : tok;
+        if (inc_len && b == 0) inc_len[0] += 1;
+    }
+}
+
+void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *inc_len,
+                   hipStream_t st) {
+    if (B <= 0) return;
+    sample_kernel<<<B, SP_THREADS, 0, st>>>(logits, V, 1.0f / temperature, u, next, inc_len);
+}
+
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st) { set_i32_kernel<<<1, 1, 0, st>>>(p, v); }
 

@@ -19,6 +19,9 @@ void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M
                         f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st);
 // next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN); optionally *inc_len += 1.
 void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *inc_len, hipStream_t st);
+// next[b] = smallest v with cumulative softmax(logits[b] / temperature) above u[b] (-1 on NaN); optionally *inc_len += 1.
+void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *inc_len,
+                   hipStream_t st);
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
 // out[m] = sum_k h[m, k] * w[k]   (h half [M, d]; w bf16 or fp32 [d]; fp32 accumulation)
 void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st);

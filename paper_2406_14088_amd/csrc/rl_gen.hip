@@ -115,6 +115,8 @@ struct rl_gen {
     int nsplit_attn;
     int B, len;
     bool graph_on, prof_on, qkv_two_term;
+    float temperature;       // > 0: the next token is sampled (rl_gen_set_sampling); else greedy
+    const float *sample_u;   // DEVICE [max_batch] uniform draws, borrowed, refreshed by the caller between steps
     std::vector<GraphEntry> graphs;
     std::vector<ProfEvent> prof_events;
     std::vector<ProfEvent> prof_pool;
@@ -331,7 +333,8 @@ void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, int32_t *ne
     run_layers(h, tokens, h->B, 1, 0, true, st);
     lm_head(h, h->B, 1, 0, logits, st);
     Scope sc(h, RL_GEN_K_ARGMAX, st);
-    launch_argmax(logits, h->B, h->s.vocab, next, h->d_len(), st);
+    if (h->temperature > 0.f) launch_sample(logits, h->B, h->s.vocab, h->temperature, h->sample_u, next, h->d_len(), st);
+    else launch_argmax(logits, h->B, h->s.vocab, next, h->d_len(), st);
 }
 
 int check_hip(rl_gen *h, const char *where) {
@@ -465,6 +468,7 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     h->B = 0; h->len = 0;
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
     h->packed = false; h->p_lm_head = nullptr;
+    h->temperature = 0.f; h->sample_u = nullptr;
     h->err[0] = 0;
     memset(h->prof_launches, 0, sizeof h->prof_launches);
     memset(h->prof_ms, 0, sizeof h->prof_ms);
@@ -534,7 +538,8 @@ int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, flo
     }
     {
         Scope sc(h, RL_GEN_K_ARGMAX, st);
-        launch_argmax(lg, B, h->s.vocab, nx, nullptr, st);
+        if (h->temperature > 0.f) launch_sample(lg, B, h->s.vocab, h->temperature, h->sample_u, nx, nullptr, st);
+        else launch_argmax(lg, B, h->s.vocab, nx, nullptr, st);
     }
     {
         Scope sc(h, RL_GEN_K_MISC, st);
@@ -669,6 +674,16 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
 int rl_gen_set_graph(rl_gen_t *h, int32_t enabled) {
     if (!h) return RL_GEN_E_NULL;
     h->graph_on = enabled != 0;
+    return RL_GEN_OK;
+}
+
+int rl_gen_set_sampling(rl_gen_t *h, float temperature, const float *u) {
+    if (!h) return RL_GEN_E_NULL;
+    if (temperature > 0.f && !u) { set_err(h, "rl_gen_set_sampling: NULL draws"); return RL_GEN_E_NULL; }
+    if (temperature != temperature) { set_err(h, "rl_gen_set_sampling: temperature is NaN"); return RL_GEN_E_SHAPE; }
+    drop_graphs(h);  // captured steps end in the other kernel
+    h->temperature = temperature > 0.f ? temperature : 0.f;
+    h->sample_u = temperature > 0.f ? u : nullptr;
     return RL_GEN_OK;
 }
 
@@ -878,6 +893,13 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
     if (nb < 0 || b0 < 0 || T <= 0 || T > S || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || nb > 65535)
         return RL_GEN_E_SHAPE;
     launch_prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_sample(const float *logits, int32_t B, int32_t V, float temperature, const float *u, int32_t *next, void *st) {
+    if (!logits || !u || !next) return RL_GEN_E_NULL;
+    if (B < 0 || V <= 0 || !(temperature > 0.f)) return RL_GEN_E_SHAPE;
+    launch_sample(logits, B, V, temperature, u, next, nullptr, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

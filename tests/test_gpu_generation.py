@@ -316,6 +316,53 @@ def test_graph_cache_eviction_and_internal_logit_buffer():
     gen.close()
 
 
+@pytest.mark.parametrize("graph", [False, True])
+def test_sampled_generation(graph):
+    """Generation with temperature sampling: the library draws nothing, the caller refreshes the uniform draws between steps.
+    Every returned token must be a valid inversion of the step's own logits (which the other tests tie to the oracle), both for
+    prefill and for (graph-replayed) decode steps; switching back gives the greedy tokens again."""
+    from paper_2406_14088_amd import Generator
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    B, temperature, delta = wl.batch, 0.9, 3e-5
+    gen = Generator(wl.shape, W, B, wl.max_seq)
+    gen.set_graph(graph)
+    u = torch.zeros((B,), dtype=torch.float32, device=DEV)
+    gen.set_sampling(temperature, u)
+    rng = torch.Generator(device="cpu").manual_seed(7)
+
+    def valid(logits, tokens, draws):
+        for b in range(B):
+            x = np64(logits[b])
+            e = np.exp((x - x.max()) / temperature)
+            c = np.concatenate([[0.0], np.cumsum(e) / e.sum()])
+            v = int(tokens[b])
+            assert c[v] - delta <= float(draws[b]) <= c[v + 1] + delta
+
+    draws = torch.rand((B,), generator=rng)
+    u.copy_(draws)
+    lg, tok = gen.prefill(prompts)
+    torch.cuda.synchronize()
+    valid(lg, tok.cpu(), draws)
+    seen_non_greedy = not torch.equal(tok.cpu(), lg.argmax(-1).int().cpu())
+    nxt = torch.empty_like(tok)
+    for i in range(8):
+        draws = torch.rand((B,), generator=rng)
+        u.copy_(draws)
+        lg, _ = gen.decode_step(tok, next_tokens=nxt)
+        torch.cuda.synchronize()
+        valid(lg, nxt.cpu(), draws)
+        seen_non_greedy |= not torch.equal(nxt.cpu(), lg.argmax(-1).int().cpu())
+        tok, nxt = nxt, tok
+    assert seen_non_greedy                       # the draws really steer the tokens
+    gen.set_sampling(0.0)
+    lg, t2 = gen.decode_step(tok)
+    torch.cuda.synchronize()
+    assert torch.equal(t2.cpu().long(), (lg == lg.max(-1, keepdim=True).values).int().argmax(-1).cpu())
+    gen.close()
+
+
 def test_error_paths_on_device():
     from paper_2406_14088_amd import Generator, RlGenError
     wl = PRESETS["tiny"]

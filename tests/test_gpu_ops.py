@@ -420,3 +420,56 @@ def test_empty_inputs_enqueue_nothing(ops):
     torch.cuda.synchronize()
     assert rcs == [0] * len(rcs), rcs
     assert (x == 7).all() and (h == 7).all() and (out == 7).all() and (nxt == 5).all() and (lg == 7).all()
+
+
+def cdf_interval(x64, temperature):
+    z = (x64 - x64.max()) / temperature
+    e = np.exp(z)
+    c = np.cumsum(e) / e.sum()
+    return np.concatenate([[0.0], c])
+
+
+@pytest.mark.parametrize("B,V,temperature", [(5, 97, 1.0), (16, 1000, 0.7), (8, 32000, 1.0), (3, 128256, 1.3), (4, 1500, 0.05)])
+def test_sampling_kernel(ops, B, V, temperature):
+    """Index decided by floating point: the returned token must be a valid inversion of the row's own cumulative softmax
+    (the draw lies in the token's probability interval up to fp32 summation error), and equal to the oracle's token whenever
+    the draw is not within that error of an interval end."""
+    step(f"sample B={B} V={V} T={temperature}")
+    logits = randn_f32((B, V), 95 + B, std=2.0)
+    g = torch.Generator(device="cpu").manual_seed(96)
+    rounds, delta, exact, total = (6 if V <= 2000 else 2), 3e-5, 0, 0
+    for r in range(rounds):
+        u = torch.rand((B,), generator=g, dtype=torch.float32)
+        if r == 0:
+            u[0] = 0.0
+        if r == 1:
+            u[0] = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
+        nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+        ops.sample(logits, temperature, u.to(DEV), nxt)
+        torch.cuda.synchronize()
+        got = nxt.cpu().numpy()
+        for b in range(B):
+            x = np64(logits[b])
+            c = cdf_interval(x, temperature)
+            ub, v = float(u[b]), int(got[b])
+            assert 0 <= v < V
+            assert c[v] - delta <= ub <= c[v + 1] + delta, (b, v, ub, c[v], c[v + 1])
+            want = orc.sample(x, temperature, ub)
+            total += 1
+            if min(abs(ub - c[want]), abs(ub - c[want + 1])) > delta:
+                assert v == want
+                exact += 1
+    if V <= 2000:       # with a large vocabulary most probability intervals are no wider than the summation error
+        assert exact >= 0.9 * total
+    # determinism, and NaN rows
+    a = torch.empty((B,), dtype=torch.int32, device=DEV)
+    b2 = torch.empty((B,), dtype=torch.int32, device=DEV)
+    ud = torch.full((B,), 0.3712, dtype=torch.float32, device=DEV)
+    ops.sample(logits, temperature, ud, a)
+    ops.sample(logits, temperature, ud, b2)
+    bad = logits.clone()
+    bad[1, V // 2] = float("nan")
+    c2 = torch.empty((B,), dtype=torch.int32, device=DEV)
+    ops.sample(bad, temperature, ud, c2)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b2) and int(c2[1]) == -1 and torch.equal(c2[2:], a[2:]) and int(c2[0]) == int(a[0])
