@@ -3,7 +3,10 @@
 
 One "step" is one pass of the whole hot path over one batch of synthetic input: prefill of B prompts
 of P tokens plus G-1 decode steps (B*G generated tokens), free-running greedy generation with on-device
-token feedback.  Prints ONE JSON line; see the design doc for the definition of every field.
+token feedback.  Prints ONE JSON line: `value` = generated tokens/s of the whole step (weight re-layout + prefill + decode),
+`phases` = prefill TFLOP/s and decode algorithmic GB/s with their fractions of the published peaks, `roofline` = the dominant
+kernel (decode attention) timed with HIP events on the launch stream against its algorithmic bytes, `cpu_baseline` = the CPU
+oracle timed on a bounded sample of the same model.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--no-cpu-baseline] [--no-roofline]
 """
