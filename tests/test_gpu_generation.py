@@ -363,6 +363,36 @@ def test_sampled_generation(graph):
     gen.close()
 
 
+def test_per_kernel_timing_counts_every_launch():
+    """rl_gen_profile: while on, every kernel launch of prefill and decode is bracketed by events on the caller's stream; the
+    counts per kernel class follow from the model depth, and results are the same as without timing."""
+    from paper_2406_14088_amd import Generator
+    wl = PRESETS["tiny"]
+    L = wl.shape.n_layers
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    gen = Generator(wl.shape, W, wl.batch, wl.max_seq)
+    lg0, t0 = gen.prefill(prompts)
+    lg1, _ = gen.decode_step(t0)
+    ref = (lg0.clone(), lg1.clone())
+    gen.profile(True)
+    gen.profile_read()
+    lg0, t0 = gen.prefill(prompts)
+    lg1, _ = gen.decode_step(t0)
+    prof = gen.profile_read()
+    gen.profile(False)
+    torch.cuda.synchronize()
+    assert torch.equal(lg0, ref[0]) and torch.equal(lg1, ref[1])
+    n = {k: v["launches"] for k, v in prof.items()}
+    assert n["embed"] == 2 and n["add_rmsnorm"] == 2 * (2 * L + 1) and n["gemm_qkv"] == 2 * L and n["rope_append"] == 2 * L
+    assert n["decode_attention"] == L and n["prefill_attention"] == L and n["gemm_o"] == 2 * L and n["gemm_gate_up"] == 2 * L
+    assert n["gemm_down"] == 2 * L and n["gemm_lm_head"] == 2 and n["argmax"] == 2
+    assert all(v["ms"] > 0 for k, v in prof.items() if v["launches"])
+    again = gen.profile_read()                      # reading clears the sums
+    assert all(v["launches"] == 0 for v in again.values())
+    gen.close()
+
+
 def test_error_paths_on_device():
     from paper_2406_14088_amd import Generator, RlGenError
     wl = PRESETS["tiny"]
