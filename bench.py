@@ -121,12 +121,19 @@ def main():
             torch.cuda.synchronize()
             tb = time.perf_counter()
         cur = 0
-        for _ in range(G - 1):
+        marks = {}
+        for i in range(G - 1):
+            if timing is not None and i in (1, (G - 1) // 2, G - 2):     # single steps early, in the middle and at the end
+                marks[i] = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                marks[i][0].record()
             gen.decode_step(buf[cur], next_tokens=buf[1 - cur], want_logits=False)
+            if i in marks:
+                marks[i][1].record()
             cur = 1 - cur
         if timing is not None:
             torch.cuda.synchronize()
             tc = time.perf_counter()
+            timing["step_ms"] = {i: m[0].elapsed_time(m[1]) for i, m in marks.items()}
             timing["prefill_s"] = timing.get("prefill_s", 0.0) + tb - ta
             timing["decode_s"] = timing.get("decode_s", 0.0) + tc - tb
         return buf[cur]
@@ -157,6 +164,9 @@ def main():
         "decode_algorithmic_GBs": dec_bytes / split["decode_s"] / 1e9,
         "decode_frac_of_hbm_peak": dec_bytes / split["decode_s"] / 1e9 / HBM_PEAK_GBS,
         "decode_tokens_per_s": B * (G - 1) / split["decode_s"],
+        # single decode steps (events on the launch stream): position, ms, algorithmic GB/s
+        "decode_steps": [{"position": P + i, "ms": ms, "algorithmic_GBs": decode_bytes(shape, B, P + i) / (ms * 1e-3) / 1e9}
+                         for i, ms in sorted(split["step_ms"].items())],
     }
 
     out = {
