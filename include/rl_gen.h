@@ -110,6 +110,24 @@ int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, vo
 int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logits, int32_t *next,
                    void *hip_stream);
 
+/* Prefill of prompts of different lengths (Appendix A notes that prompt and generation lengths vary in practice; the
+ * benchmark pads to the maximum).  tokens: DEVICE int32 [B, T], sequence b holds lens[b] prompt tokens followed by
+ * padding (any valid ids).  lens: DEVICE int32 [B], values clamped to [1, T] on the device.  logits / next are those of
+ * each sequence's own last prompt position.  Afterwards sequence b has length lens[b] and decode steps append at each
+ * sequence's own position; rl_gen_state reports T, the upper bound the capacity check uses.  All B*T rows are
+ * computed; padded positions never reach a later result (causal attention, and decode overwrites them first). */
+int rl_gen_prefill_ragged(rl_gen_t *h, const int32_t *tokens, const int32_t *lens, int32_t B, int32_t T, float *logits,
+                          int32_t *next, void *hip_stream);
+
+/* End token (Section 2.1: generation runs until termination).  eos >= 0: a sequence whose returned token is eos has ended:
+ * from the next step on it returns eos, its length stays, and what is fed for it is ignored (its logits are not
+ * meaningful).  eos < 0 (default): sequences never end, as in the fixed-length benchmark.  Applies from the next step. */
+int rl_gen_set_eos(rl_gen_t *h, int32_t eos);
+
+/* Copies the per-sequence lengths and end flags (HOST int32 [batch] each, either may be NULL) after waiting for the
+ * stream. */
+int rl_gen_read_state(rl_gen_t *h, int32_t *lens, int32_t *done, void *hip_stream);
+
 /* One decode step (Section 2.1: input the single latest token of each sequence, produce the next).
  * tokens: DEVICE int32 [B] with B as given to the last prefill -- the caller chooses what to feed
  * (the previous `next` buffer for free-running greedy generation, or reference tokens for teacher

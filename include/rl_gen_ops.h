@@ -77,29 +77,30 @@ int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float 
 
 /* Rotary embedding + KV-cache append.  qkv fp32: nsplit partials, each [M, (Hq+2Hkv)*hd] laid out
  * q | k | v per row, split_stride elements apart.  Row m is sequence b0 + m / T at position
- * d_pos0[0] + m % T (d_pos0: DEVICE int32).  Writes q_f32 and/or q_f16 ([M, Hq*hd], either may
+ * d_pos0[(m / T) * pos_stride] + m % T (d_pos0: DEVICE int32; pos_stride 0: one start position, 1: one per sequence).  Writes q_f32 and/or q_f16 ([M, Hq*hd], either may
  * be NULL) and the cache rows of kc / vc (f16 [n_seq][Hkv][S][hd]).  Positions >= S are skipped. */
 int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
-                      const int32_t *d_pos0, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv,
+                      const int32_t *d_pos0, int32_t pos_stride, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv,
                       int32_t hd, int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *hip_stream);
 
 /* Decode attention: for each sequence b < B and query head u, softmax(q_u . k_j / sqrt(hd)) v_j over
- * cache rows j = 0 .. d_len[0] of kv head u / (Hq/Hkv).  q fp32 [B, Hq*hd]; kc, vc f16; out f16 [B, Hq*hd].
+ * cache rows j = 0 .. d_len[b * len_stride] of kv head u / (Hq/Hkv) (len_stride 0: one length for all, 1: per sequence).  q fp32 [B, Hq*hd]; kc, vc f16; out f16 [B, Hq*hd].
  * nsplit >= 1 splits the rows over wavefronts; ws must then hold rl_op_decode_attention_ws_floats
  * floats (may be NULL for nsplit == 1).  hd in {64, 128}. */
-int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, uint16_t *out,
-                           float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
+int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
+                           uint16_t *out, float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
                            void *hip_stream);
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
 /* Rotary embedding + KV-cache append + decode attention in one kernel (what a decode step runs): q, k and v of the
  * new token of every sequence are taken from qkv -- nsplit_qkv fp32 partials, each [B, (Hq+2Hkv)*hd] laid out
- * q | k | v per row, split_stride elements apart (multiple of 4) -- added, q and k rotated at position d_len[0] with
+ * q | k | v per row, split_stride elements apart (multiple of 4) -- added, q and k rotated at position d_len[b * len_stride] with
  * rope_tab, the k/v rows rounded to f16 and stored at that position of kc / vc (f16 [n_seq][Hkv][S][hd], WRITTEN),
  * and attention runs over positions 0 .. d_len[0] with the new row taken from registers.  out, ws, nsplit as in
  * rl_op_decode_attention.  d_len[0] >= S: nothing is written (the host checks capacity before a step). */
 int rl_op_decode_attention_fused(const float *qkv, int32_t nsplit_qkv, size_t split_stride, const float *rope_tab,
-                                 int32_t rope_style, uint16_t *kc, uint16_t *vc, const int32_t *d_len, uint16_t *out, float *ws,
+                                 int32_t rope_style, uint16_t *kc, uint16_t *vc, const int32_t *d_len, int32_t len_stride,
+                                 uint16_t *out, float *ws,
                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *hip_stream);
 
 /* Prefill attention: causal attention of positions 0..T-1 of nb sequences; sequence i reads cache

@@ -64,6 +64,9 @@ def lib():
         "rl_gen_packed_bytes": (sz, [sp]),
         "rl_gen_pack_weights": (C.c_int, [vp, vp, sz, vp]),
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
+        "rl_gen_prefill_ragged": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp]),
+        "rl_gen_set_eos": (C.c_int, [vp, i32]),
+        "rl_gen_read_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "rl_gen_logprobs": (C.c_int, [vp, vp, i32, i32, vp, vp]),
         "rl_gen_values": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
@@ -84,10 +87,10 @@ def lib():
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
         "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
-        "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
-        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
+        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
-        "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
         "rl_op_sample": (C.c_int, [vp, i32, i32, f32, vp, vp, vp]),
@@ -105,7 +108,7 @@ def lib():
 
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_packed_bytes",
-    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_logprobs", "rl_gen_values",
+    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_fused",
@@ -227,6 +230,31 @@ class Generator:
                     "rl_gen_prefill")
         return logits, next_tokens
 
+    def prefill_ragged(self, tokens, lens, logits=None, next_tokens=None):
+        """tokens: int32 GPU tensor [B, T] (padded), lens: int32 GPU tensor [B].  Returns (logits of each sequence's last
+        prompt position, next)."""
+        import torch
+        B, T = tokens.shape
+        assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.is_contiguous()
+        assert lens.dtype == torch.int32 and lens.is_cuda and lens.is_contiguous() and lens.numel() == B
+        if logits is None:
+            logits = torch.empty((B, self.shape.vocab), dtype=torch.float32, device=tokens.device)
+        if next_tokens is None:
+            next_tokens = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+        self._check(lib().rl_gen_prefill_ragged(self._h, tokens.data_ptr(), lens.data_ptr(), B, T, _ptr(logits), _ptr(next_tokens),
+                                                _stream()), "rl_gen_prefill_ragged")
+        return logits, next_tokens
+
+    def set_eos(self, eos: int):
+        self._check(lib().rl_gen_set_eos(self._h, int(eos)), "rl_gen_set_eos")
+
+    def read_state(self):
+        """(lengths, end flags) of the current sequences as Python lists."""
+        b, _ = self.state()
+        lens, done = (C.c_int32 * max(b, 1))(), (C.c_int32 * max(b, 1))()
+        self._check(lib().rl_gen_read_state(self._h, lens, done, _stream()), "rl_gen_read_state")
+        return list(lens)[:b], list(done)[:b]
+
     def decode_step(self, tokens, logits=None, next_tokens=None, want_logits=True):
         """tokens: int32 GPU tensor [B].  Returns (logits or None, next)."""
         import torch
@@ -347,22 +375,23 @@ class _Ops:
     def build_rope_table(self, tab, max_seq, head_dim, base):
         self._ck(lib().rl_op_build_rope_table(tab.data_ptr(), max_seq, head_dim, base), "rl_op_build_rope_table")
 
-    def rope_append(self, qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_bf16, kc, vc):
-        self._ck(lib().rl_op_rope_append(qkv.data_ptr(), nsplit, split_stride, M, T, b0, d_pos0.data_ptr(), rope_tab.data_ptr(),
+    def rope_append(self, qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_bf16, kc, vc,
+                    pos_stride=0):
+        self._ck(lib().rl_op_rope_append(qkv.data_ptr(), nsplit, split_stride, M, T, b0, d_pos0.data_ptr(), pos_stride, rope_tab.data_ptr(),
                                          rope_style, Hq, Hkv, hd, S, _ptr(q_f32), _ptr(q_bf16), kc.data_ptr(), vc.data_ptr(),
                                          _stream()), "rl_op_rope_append")
 
     def decode_attention_ws_floats(self, B, Hq, hd, nsplit):
         return int(lib().rl_op_decode_attention_ws_floats(B, Hq, hd, nsplit))
 
-    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit):
-        self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), out.data_ptr(),
+    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0):
+        self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(),
                                               _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention")
 
     def decode_attention_fused(self, qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S,
-                               nsplit):
+                               nsplit, len_stride=0):
         self._ck(lib().rl_op_decode_attention_fused(qkv.data_ptr(), nsplit_qkv, split_stride, rope_tab.data_ptr(), rope_style,
-                                                    kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), out.data_ptr(), _ptr(ws), B, Hq,
+                                                    kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(), _ptr(ws), B, Hq,
                                                     Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention_fused")
 
     def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):

@@ -108,14 +108,14 @@ void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_str
 // Pair r of a head turns by the angle pos * base^(-2r/hd); cos/sin come from a table built in fp64.
 // One thread per (token row, head, pair) item.
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ qkv, int nsplit, size_t split_stride,
-                                                          int T, int b0, const int32_t *__restrict__ d_pos0,
+                                                          int T, int b0, const int32_t *__restrict__ d_pos0, int pos_stride,
                                                           const float *__restrict__ rope_tab, int rope_style, int Hq,
                                                           int Hkv, int hd, int S, float *__restrict__ q_f32,
                                                           f16_t *__restrict__ q_f16, f16_t *__restrict__ kc,
                                                           f16_t *__restrict__ vc) {
     int m = blockIdx.x;
     int b = b0 + m / T;
-    int pos = d_pos0[0] + m % T;
+    int pos = d_pos0[(size_t)(m / T) * pos_stride] + m % T;  // pos_stride 0: one start for all rows; 1: one per sequence
     if (pos >= S) return;  // capacity is checked on the host; never write outside the cache
     int half = hd >> 1;
     int nq = Hq * half, nk = Hkv * half;
@@ -153,20 +153,30 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
 }
 
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
-                        const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
+                        int pos_stride, const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
                         f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st) {
     if (M <= 0) return;
     int items = (Hq + 2 * Hkv) * (hd / 2);
     dim3 grid(M, ceil_div(items, 256));
-    rope_append_kernel<<<grid, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S,
+    rope_append_kernel<<<grid, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, pos_stride, rope_tab, rope_style, Hq, Hkv, hd, S,
                                           q_f32, q_f16, kc, vc);
 }
 
 // ------------------------------------------------------------------------------------------------
+// What follows the choice of a token (one thread per sequence): a sequence that had already ended keeps returning the
+// end token and does not grow; otherwise the sequence grows by the token it was just fed, and ends if the new token is
+// the end token.  lens / done may be NULL (no bookkeeping), eos < 0 means no end token.
+__device__ __forceinline__ int finish_token(int tok, int b, int32_t *lens, int32_t *done, int eos) {
+    if (done && done[b]) return eos;
+    if (lens) lens[b] += 1;
+    if (done && eos >= 0 && tok == eos) done[b] = 1;
+    return tok;
+}
+
 // Greedy token: index of the largest logit, lowest index on ties; -1 if the row holds a NaN.
 #define AM_THREADS 1024
 __global__ __launch_bounds__(AM_THREADS) void argmax_kernel(const float *__restrict__ logits, int V,
-                                                            int32_t *__restrict__ next, int32_t *inc_len) {
+                                                            int32_t *__restrict__ next, int32_t *lens, int32_t *done, int eos) {
     __shared__ float sv[AM_THREADS / RL_WAVE];
     __shared__ int si[AM_THREADS / RL_WAVE];
     __shared__ int snan;
@@ -194,14 +204,41 @@ __global__ __launch_bounds__(AM_THREADS) void argmax_kernel(const float *__restr
     if (t == 0) {
         for (int w = 1; w < AM_THREADS / RL_WAVE; ++w)
             if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
-        next[b] = (snan || bi == 0x7fffffff) ? -1 : bi;
-        if (inc_len && b == 0) inc_len[0] += 1;
+        next[b] = finish_token((snan || bi == 0x7fffffff) ? -1 : bi, b, lens, done, eos);
     }
 }
 
-void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *inc_len, hipStream_t st) {
+void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *lens, int32_t *done, int eos, hipStream_t st) {
     if (B <= 0) return;
-    argmax_kernel<<<B, AM_THREADS, 0, st>>>(logits, V, next, inc_len);
+    argmax_kernel<<<B, AM_THREADS, 0, st>>>(logits, V, next, lens, done, eos);
+}
+
+// lens[b] = clamp(lens_in[b], 1, T) (T when lens_in is NULL), done[b] = 0: the sequence state a prefill leaves behind.
+__global__ void init_state_kernel(int32_t *lens, int32_t *done, int B, const int32_t *lens_in, int T) {
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int n = lens_in ? lens_in[b] : T;
+    lens[b] = n < 1 ? 1 : (n > T ? T : n);
+    done[b] = 0;
+}
+void launch_init_state(int32_t *lens, int32_t *done, int B, const int32_t *lens_in, int T, hipStream_t st) {
+    if (B <= 0) return;
+    init_state_kernel<<<ceil_div(B, 256), 256, 0, st>>>(lens, done, B, lens_in, T);
+}
+
+// out[i, :] = h[i * T + clamp(lens[b0 + i], 1, T) - 1, :]: the last valid position of every sequence (half rows of d elements)
+__global__ __launch_bounds__(256) void gather_last_rows_kernel(const f16_t *__restrict__ h, const int32_t *__restrict__ lens, int b0,
+                                                               int T, int d, f16_t *__restrict__ out) {
+    int i = blockIdx.x;
+    int n = lens[b0 + i];
+    n = n < 1 ? 1 : (n > T ? T : n);
+    const u32x4_t *src = reinterpret_cast<const u32x4_t *>(h + ((size_t)i * T + n - 1) * d);
+    u32x4_t *dst = reinterpret_cast<u32x4_t *>(out + (size_t)i * d);
+    for (int k = threadIdx.x; k < d / 8; k += 256) dst[k] = src[k];
+}
+void launch_gather_last_rows(const f16_t *h, const int32_t *lens, int b0, int nb, int T, int d, f16_t *out, hipStream_t st) {
+    if (nb <= 0) return;
+    gather_last_rows_kernel<<<nb, 256, 0, st>>>(h, lens, b0, T, d, out);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -280,7 +317,7 @@ void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, fl
 #define SP_THREADS 1024
 __global__ __launch_bounds__(SP_THREADS) void sample_kernel(const float *__restrict__ logits, int V, float inv_temp,
                                                             const float *__restrict__ u, int32_t *__restrict__ next,
-                                                            int32_t *inc_len) {
+                                                            int32_t *lens, int32_t *done, int eos) {
     __shared__ float red[SP_THREADS / RL_WAVE];
     __shared__ float bcast;
     __shared__ int snan, stoken;
@@ -342,15 +379,14 @@ __global__ __launch_bounds__(SP_THREADS) void sample_kernel(const float *__restr
             for (int i = V - 1; i >= 0; --i)
                 if (expf((row[i] - mx) * inv_temp) > 0.f) { tok = i; break; }
         }
-        next[b] = bad ? -1 : tok;
-        if (inc_len && b == 0) inc_len[0] += 1;
+        next[b] = finish_token(bad ? -1 : tok, b, lens, done, eos);
     }
 }
 
-void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *inc_len,
-                   hipStream_t st) {
+void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *lens,
+                   int32_t *done, int eos, hipStream_t st) {
     if (B <= 0) return;
-    sample_kernel<<<B, SP_THREADS, 0, st>>>(logits, V, 1.0f / temperature, u, next, inc_len);
+    sample_kernel<<<B, SP_THREADS, 0, st>>>(logits, V, 1.0f / temperature, u, next, lens, done, eos);
 }
 
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }

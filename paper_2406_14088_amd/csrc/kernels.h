@@ -12,16 +12,22 @@ void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_str
                         f16_t *h, f16_t *h_lo, int M, int d, hipStream_t st);
 // Sums the split partials of the fused QKV projection, rotates q and k heads at their positions and
 // writes q (fp32 and/or half, [M, Hq*hd]) and the cache rows.  Row m is sequence b0 + m / T at
-// position *d_pos0 + m % T.  rope_tab: fp32 [max_seq, hd/2, 2] (cos, sin).
+// position d_pos0[(m / T) * pos_stride] + m % T (pos_stride 0: one start position for all; 1: one per sequence).  rope_tab: fp32 [max_seq, hd/2, 2] (cos, sin).
 // kc / vc: this layer's K and V slabs, half [max_batch][Hkv][S][hd].
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
-                        const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
+                        int pos_stride, const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
                         f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st);
-// next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN); optionally *inc_len += 1.
-void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *inc_len, hipStream_t st);
-// next[b] = smallest v with cumulative softmax(logits[b] / temperature) above u[b] (-1 on NaN); optionally *inc_len += 1.
-void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *inc_len,
-                   hipStream_t st);
+// next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN).  Optional bookkeeping per sequence
+// (lens, done may be NULL; eos < 0: no end token): a sequence with done[b] returns eos and does not grow; otherwise
+// lens[b] += 1 and done[b] = (next[b] == eos).
+void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *lens, int32_t *done, int eos, hipStream_t st);
+// lens[b] = clamp(lens_in[b], 1, T) (T if lens_in is NULL), done[b] = 0
+void launch_init_state(int32_t *lens, int32_t *done, int B, const int32_t *lens_in, int T, hipStream_t st);
+// out[i, :] = h[i * T + clamp(lens[b0 + i], 1, T) - 1, :]  (half rows of d elements, d % 8 == 0)
+void launch_gather_last_rows(const f16_t *h, const int32_t *lens, int b0, int nb, int T, int d, f16_t *out, hipStream_t st);
+// next[b] = smallest v with cumulative softmax(logits[b] / temperature) above u[b] (-1 on NaN); bookkeeping as launch_argmax.
+void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *lens,
+                   int32_t *done, int eos, hipStream_t st);
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
 // out[m] = sum_k h[m, k] * w[k]   (h half [M, d]; w bf16 or fp32 [d]; fp32 accumulation)
 void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st);
@@ -91,17 +97,17 @@ void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st);
 void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *splits);
 
 // ---- attention_decode.hip ------------------------------------------------------------------------
-// One new query per (sequence, query head) against cache rows 0 .. *d_len (inclusive).
+// One new query per (sequence, query head) against cache rows 0 .. d_len[b * len_stride] (inclusive).
 // q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's slabs (half); out half [B, Hq*hd].
 // ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
-void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, f16_t *out,
+void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st);
 // Fused form: q, k, v of the new token are taken from the split-K partials of the QKV projection (each
 // [B, (Hq+2Hkv)*hd], q | k | v per row): partials added, q and k rotated at position *d_len, the k/v row appended to
 // the cache (kc/vc are written) and used from registers.  Replaces launch_rope_append + launch_decode_attention.
 void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
-                                   f16_t *kc, f16_t *vc, const int32_t *d_len, f16_t *out, float *ws, int B, int Hq, int Hkv,
-                                   int hd, int S, int nsplit, hipStream_t st);
+                                   f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B, int Hq,
+                                   int Hkv, int hd, int S, int nsplit, hipStream_t st);
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);

@@ -80,7 +80,7 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.logits = take((size_t)s->max_batch * s->vocab * 4);
     p.next = take((size_t)s->max_batch * 4);
     p.rope = take((size_t)s->max_seq * s->head_dim * 4);
-    p.state = take(64);
+    p.state = take(((size_t)2 * s->max_batch + 16) * 4);  // per-sequence lengths, per-sequence end flags, a constant 0
     p.total = off;
     return p;
 }
@@ -115,6 +115,7 @@ struct rl_gen {
     int nsplit_attn;
     int B, len;
     bool graph_on, prof_on, qkv_two_term;
+    int eos;                 // end token (rl_gen_set_eos), -1: none
     float temperature;       // > 0: the next token is sampled (rl_gen_set_sampling); else greedy
     const float *sample_u;   // DEVICE [max_batch] uniform draws, borrowed, refreshed by the caller between steps
     std::vector<GraphEntry> graphs;
@@ -135,8 +136,10 @@ struct rl_gen {
     float *logits_ws() const { return reinterpret_cast<float *>(work + wp.logits); }
     int32_t *next_ws() const { return reinterpret_cast<int32_t *>(work + wp.next); }
     float *rope() const { return reinterpret_cast<float *>(work + wp.rope); }
-    int32_t *d_len() const { return reinterpret_cast<int32_t *>(work + wp.state); }
-    int32_t *d_zero() const { return reinterpret_cast<int32_t *>(work + wp.state) + 1; }
+    // device-side sequence state: tokens held per sequence, whether it has produced the end token, and a constant 0
+    int32_t *d_lens() const { return reinterpret_cast<int32_t *>(work + wp.state); }
+    int32_t *d_done() const { return d_lens() + s.max_batch; }
+    int32_t *d_zero() const { return d_lens() + 2 * s.max_batch; }
     f16_t *kslab(int l) const {
         return kv + (size_t)(2 * l) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
     }
@@ -274,8 +277,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
                                  h->lw[W_V][l], kvd, nullptr, 0, st);
         {
             Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
-            launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_len() : h->d_zero(),
-                               h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
+            launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_lens() : h->d_zero(),
+                               decode ? 1 : 0, h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
                                decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st);
         }
         // (A single kernel that takes q, k, v from the partials, rotates, appends and attends exists --
@@ -283,7 +286,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         // attention wavefronts then spend before their first cache load.)
         if (decode) {
             Scope sc(h, RL_GEN_K_DECODE_ATTN, st);
-            launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_len(), h->attn(), h->attn_ws(), nb,
+            launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_lens(), 1, h->attn(), h->attn_ws(), nb,
                                     s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st);
         } else {
             Scope sc(h, RL_GEN_K_PREFILL_ATTN, st);
@@ -310,10 +313,12 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
 }
 
 // logits[b0 + i, :] = lm_head * h[row i*T + T-1]  for i < nb
-void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st) {
+// (rows: optional compact [nb, hidden] rows to use instead -- the last valid position of ragged sequences)
+void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, const f16_t *rows = nullptr) {
     const rl_gen_shape &s = h->s;
     GemmArgs a;
     a.A = h->h() + (size_t)(T - 1) * s.hidden; a.lda = (int64_t)T * s.hidden; a.M = nb; a.K = s.hidden;
+    if (rows) { a.A = rows; a.lda = s.hidden; }
     a.W[0] = h->lm_head; a.W[1] = nullptr; a.W[2] = nullptr;
     a.rows[0] = s.vocab; a.rows[1] = 0; a.rows[2] = 0;
     a.out = logits + (size_t)b0 * s.vocab; a.ldc = s.vocab; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
@@ -333,8 +338,10 @@ void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, int32_t *ne
     run_layers(h, tokens, h->B, 1, 0, true, st);
     lm_head(h, h->B, 1, 0, logits, st);
     Scope sc(h, RL_GEN_K_ARGMAX, st);
-    if (h->temperature > 0.f) launch_sample(logits, h->B, h->s.vocab, h->temperature, h->sample_u, next, h->d_len(), st);
-    else launch_argmax(logits, h->B, h->s.vocab, next, h->d_len(), st);
+    if (h->temperature > 0.f)
+        launch_sample(logits, h->B, h->s.vocab, h->temperature, h->sample_u, next, h->d_lens(), h->d_done(), h->eos, st);
+    else
+        launch_argmax(logits, h->B, h->s.vocab, next, h->d_lens(), h->d_done(), h->eos, st);
 }
 
 int check_hip(rl_gen *h, const char *where) {
@@ -468,7 +475,7 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     h->B = 0; h->len = 0;
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
     h->packed = false; h->p_lm_head = nullptr;
-    h->temperature = 0.f; h->sample_u = nullptr;
+    h->temperature = 0.f; h->sample_u = nullptr; h->eos = -1;
     h->err[0] = 0;
     memset(h->prof_launches, 0, sizeof h->prof_launches);
     memset(h->prof_ms, 0, sizeof h->prof_ms);
@@ -502,9 +509,8 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
                 tab[((size_t)pos * half + r) * 2] = (float)cos(ang);
                 tab[((size_t)pos * half + r) * 2 + 1] = (float)sin(ang);
             }
-        int32_t zeros[16] = {0};
         if (hipMemcpy(h->rope(), tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
-            hipMemcpy(h->d_len(), zeros, sizeof zeros, hipMemcpyHostToDevice) != hipSuccess)
+            hipMemset(h->d_lens(), 0, ((size_t)2 * shape->max_batch + 16) * 4) != hipSuccess)
             fail = true;
     }
     if (!fail && hipDeviceSynchronize() != hipSuccess) fail = true;
@@ -518,36 +524,76 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     return RL_GEN_OK;
 }
 
-int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logits, int32_t *next, void *hip_stream) {
+static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, const int32_t *lens, int32_t B, int32_t T,
+                        float *logits, int32_t *next, void *hip_stream) {
     if (!h) return RL_GEN_E_NULL;
-    if (!tokens) { set_err(h, "rl_gen_prefill: NULL tokens"); return RL_GEN_E_NULL; }
-    if (B <= 0 || T <= 0) { set_err(h, "rl_gen_prefill: B and T must be positive"); return RL_GEN_E_SHAPE; }
+    if (!tokens) { set_err(h, "%s: NULL tokens", who); return RL_GEN_E_NULL; }
+    if (B <= 0 || T <= 0) { set_err(h, "%s: B and T must be positive", who); return RL_GEN_E_SHAPE; }
     if (B > h->s.max_batch || T > h->s.max_seq) {
-        set_err(h, "rl_gen_prefill: B=%d T=%d exceed capacity %d x %d", B, T, h->s.max_batch, h->s.max_seq);
+        set_err(h, "%s: B=%d T=%d exceed capacity %d x %d", who, B, T, h->s.max_batch, h->s.max_seq);
         return RL_GEN_E_CAPACITY;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     float *lg = logits ? logits : h->logits_ws();
     int32_t *nx = next ? next : h->next_ws();
+    {
+        Scope sc(h, RL_GEN_K_MISC, st);
+        launch_init_state(h->d_lens(), h->d_done(), B, lens, T, st);
+    }
     int per_chunk = h->wp.rows / T;  // whole sequences per pass through the layers
     if (per_chunk < 1) per_chunk = 1;
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
         int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
         run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
-        lm_head(h, nb, T, b0, lg, st);
+        if (lens) {
+            // ragged prompts: the row that feeds the LM head is each sequence's own last position; the attention
+            // output area is idle by now and takes the gathered rows
+            {
+                Scope sc(h, RL_GEN_K_MISC, st);
+                launch_gather_last_rows(h->h(), h->d_lens(), b0, nb, T, h->s.hidden, h->attn(), st);
+            }
+            lm_head(h, nb, T, b0, lg, st, h->attn());
+        } else {
+            lm_head(h, nb, T, b0, lg, st);
+        }
     }
     {
         Scope sc(h, RL_GEN_K_ARGMAX, st);
-        if (h->temperature > 0.f) launch_sample(lg, B, h->s.vocab, h->temperature, h->sample_u, nx, nullptr, st);
-        else launch_argmax(lg, B, h->s.vocab, nx, nullptr, st);
+        // lengths were set by launch_init_state; here only the end flags follow from the first generated token
+        if (h->temperature > 0.f) launch_sample(lg, B, h->s.vocab, h->temperature, h->sample_u, nx, nullptr, h->d_done(), h->eos, st);
+        else launch_argmax(lg, B, h->s.vocab, nx, nullptr, h->d_done(), h->eos, st);
     }
-    {
-        Scope sc(h, RL_GEN_K_MISC, st);
-        launch_set_i32(h->d_len(), T, st);
-    }
-    int rc = check_hip(h, "rl_gen_prefill");
+    int rc = check_hip(h, who);
     if (rc != RL_GEN_OK) return rc;
     h->B = B; h->len = T;
+    return RL_GEN_OK;
+}
+
+int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, float *logits, int32_t *next, void *hip_stream) {
+    return prefill_impl(h, "rl_gen_prefill", tokens, nullptr, B, T, logits, next, hip_stream);
+}
+
+int rl_gen_prefill_ragged(rl_gen_t *h, const int32_t *tokens, const int32_t *lens, int32_t B, int32_t T, float *logits,
+                          int32_t *next, void *hip_stream) {
+    if (h && !lens) { set_err(h, "rl_gen_prefill_ragged: NULL lens"); return RL_GEN_E_NULL; }
+    return prefill_impl(h, "rl_gen_prefill_ragged", tokens, lens, B, T, logits, next, hip_stream);
+}
+
+int rl_gen_set_eos(rl_gen_t *h, int32_t eos) {
+    if (!h) return RL_GEN_E_NULL;
+    if (eos >= h->s.vocab) { set_err(h, "rl_gen_set_eos: token %d outside the vocabulary", eos); return RL_GEN_E_SHAPE; }
+    drop_graphs(h);  // the end token is a kernel argument of captured steps
+    h->eos = eos < 0 ? -1 : eos;
+    return RL_GEN_OK;
+}
+
+int rl_gen_read_state(rl_gen_t *h, int32_t *lens, int32_t *done, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    if (h->B <= 0) return RL_GEN_OK;
+    if (lens && hipMemcpyAsync(lens, h->d_lens(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return RL_GEN_E_HIP;
+    if (done && hipMemcpyAsync(done, h->d_done(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return RL_GEN_E_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) { set_err(h, "rl_gen_read_state: stream error"); return RL_GEN_E_HIP; }
     return RL_GEN_OK;
 }
 
@@ -589,7 +635,7 @@ int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, fl
     }
     {
         Scope sc(h, RL_GEN_K_MISC, st);
-        launch_set_i32(h->d_len(), T, st);
+        launch_init_state(h->d_lens(), h->d_done(), B, nullptr, T, st);
     }
     int rc = check_hip(h, "rl_gen_logprobs");
     if (rc != RL_GEN_OK) return rc;
@@ -616,7 +662,7 @@ int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, cons
     }
     {
         Scope sc(h, RL_GEN_K_MISC, st);
-        launch_set_i32(h->d_len(), T, st);
+        launch_init_state(h->d_lens(), h->d_done(), B, nullptr, T, st);
     }
     int rc = check_hip(h, "rl_gen_values");
     if (rc != RL_GEN_OK) return rc;
@@ -853,12 +899,13 @@ int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float 
 }
 
 int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
-                      const int32_t *d_pos0, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv, int32_t hd,
+                      const int32_t *d_pos0, int32_t pos_stride, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv, int32_t hd,
                       int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *st) {
     if (!qkv || !d_pos0 || !rope_tab || !kc || !vc) return RL_GEN_E_NULL;
     if (nsplit < 1 || M < 0 || T <= 0 || b0 < 0 || Hq <= 0 || Hkv <= 0 || hd <= 0 || hd % 2 || S <= 0 || (rope_style != 0 && rope_style != 1))
         return RL_GEN_E_SHAPE;
-    launch_rope_append(qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_f16, kc, vc,
+    if (pos_stride != 0 && pos_stride != 1) return RL_GEN_E_SHAPE;
+    launch_rope_append(qkv, nsplit, split_stride, M, T, b0, d_pos0, pos_stride, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_f16, kc, vc,
                        reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
@@ -867,22 +914,26 @@ size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32
     return decode_attention_ws_floats(B, Hq, hd, nsplit);
 }
 
-int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, uint16_t *out, float *ws,
+int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
+                           uint16_t *out, float *ws,
                            int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
     if (!q || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
-    launch_decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st));
+    if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
+    launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 
 int rl_op_decode_attention_fused(const float *qkv, int32_t nsplit_qkv, size_t split_stride, const float *rope_tab,
-                                 int32_t rope_style, uint16_t *kc, uint16_t *vc, const int32_t *d_len, uint16_t *out, float *ws,
+                                 int32_t rope_style, uint16_t *kc, uint16_t *vc, const int32_t *d_len, int32_t len_stride,
+                                 uint16_t *out, float *ws,
                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
     if (!qkv || !rope_tab || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1 || nsplit_qkv < 1 ||
         (rope_style != 0 && rope_style != 1) || split_stride % 4)
         return RL_GEN_E_SHAPE;
-    launch_decode_attention_fused(qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S,
+    if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
+    launch_decode_attention_fused(qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S,
                                   nsplit, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
@@ -899,7 +950,7 @@ int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_
 int rl_op_sample(const float *logits, int32_t B, int32_t V, float temperature, const float *u, int32_t *next, void *st) {
     if (!logits || !u || !next) return RL_GEN_E_NULL;
     if (B < 0 || V <= 0 || !(temperature > 0.f)) return RL_GEN_E_SHAPE;
-    launch_sample(logits, B, V, temperature, u, next, nullptr, reinterpret_cast<hipStream_t>(st));
+    launch_sample(logits, B, V, temperature, u, next, nullptr, nullptr, -1, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 
@@ -921,7 +972,7 @@ int rl_op_copy(const void *src, void *dst, size_t bytes, void *st) {
 int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *st) {
     if (!logits || !next) return RL_GEN_E_NULL;
     if (B < 0 || V <= 0) return RL_GEN_E_SHAPE;
-    launch_argmax(logits, B, V, next, nullptr, reinterpret_cast<hipStream_t>(st));
+    launch_argmax(logits, B, V, next, nullptr, nullptr, -1, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

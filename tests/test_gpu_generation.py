@@ -393,6 +393,84 @@ def test_per_kernel_timing_counts_every_launch():
     gen.close()
 
 
+def test_ragged_prompts_against_the_oracle():
+    """Prompts of different lengths in one batch: every sequence must behave exactly as if it were alone (the oracle runs
+    them one by one at their own lengths), through prefill and teacher-forced decode steps at per-sequence positions."""
+    from paper_2406_14088_amd import Generator
+    shape = ModelShape(2, 256, 4, 2, 64, 688, 1000)
+    B, T, steps = 5, 40, 4
+    lens = [40, 1, 17, 33, 8]
+    W = make_weights(shape, 41, device="cpu")
+    Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
+    toks = make_prompts(Workload("t", 41, shape, B, T, 0))
+    gen = Generator(shape, Wg, B, T + steps)
+    g_logits, g_next = gen.prefill_ragged(toks.to(DEV), torch.tensor(lens, dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    assert gen.read_state() == (lens, [0] * B)
+    Wn = orc.weights_to_numpy(W)
+    oms = []
+    worst = 0.0
+    feed = np.zeros((B,), np.int32)
+    for b in range(B):
+        om = orc.OracleModel(shape, Wn, 1, T + steps)
+        ol, on = om.prefill(toks[b: b + 1, : lens[b]].numpy())
+        worst = max(worst, np.abs(np64(g_logits[b]) - ol[0]).max())
+        feed[b] = on[0]
+        oms.append(om)
+    for i in range(steps):
+        g_logits, g_next = gen.decode_step(torch.from_numpy(feed).to(DEV))
+        torch.cuda.synchronize()
+        for b in range(B):
+            ol, on = oms[b].decode_step(feed[b: b + 1])
+            worst = max(worst, np.abs(np64(g_logits[b]) - ol[0]).max())
+            feed[b] = on[0]
+        assert gen.read_state()[0] == [n + i + 1 for n in lens]
+    for om in oms:
+        om.close()
+    step(f"  ragged batch: max-abs logit error {worst:.3e}")
+    assert worst <= LOGIT_TOL
+    gen.close()
+
+
+@pytest.mark.parametrize("graph", [False, True])
+def test_end_token_stops_a_sequence(graph):
+    """With an end token set, a sequence that produces it keeps returning it, stops growing and leaves the others alone."""
+    from paper_2406_14088_amd import Generator
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    B, G = wl.batch, wl.gen_len
+
+    def run(eos):
+        gen = Generator(wl.shape, W, B, wl.max_seq)
+        gen.set_graph(graph)
+        gen.set_eos(eos)
+        _, t = gen.prefill(prompts)
+        out = [t.clone()]
+        for _ in range(G - 1):
+            _, t2 = gen.decode_step(out[-1])
+            out.append(t2.clone())
+        torch.cuda.synchronize()
+        state = gen.read_state()
+        gen.close()
+        return torch.stack(out).cpu().numpy(), state          # [G, B]
+
+    free, (lens_free, done_free) = run(-1)
+    assert done_free == [0] * B and lens_free == [wl.prompt_len + G - 1] * B
+    b_stop, k_stop = 1, 5
+    eos = int(free[k_stop, b_stop])                           # the token sequence 1 produces at step 5 becomes the end token
+    got, (lens, done) = run(eos)
+    for b in range(B):
+        hits = np.nonzero(free[:, b] == eos)[0]
+        if len(hits) == 0:
+            assert (got[:, b] == free[:, b]).all() and done[b] == 0 and lens[b] == wl.prompt_len + G - 1
+        else:
+            k = int(hits[0])                                   # first time the free run of this sequence emits the end token
+            assert (got[: k + 1, b] == free[: k + 1, b]).all() and (got[k:, b] == eos).all() and done[b] == 1
+            assert lens[b] == wl.prompt_len + k                # the prompt plus the k tokens fed back before it ended
+    assert done[b_stop] == 1
+
+
 def test_error_paths_on_device():
     from paper_2406_14088_amd import Generator, RlGenError
     wl = PRESETS["tiny"]

@@ -413,7 +413,7 @@ def test_empty_inputs_enqueue_nothing(ops):
         L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 2, None),
         L.rl_op_gemm_packed(p(A), None, d, p(P), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 0, 0, 0, None),
         L.rl_op_argmax(p(lg), 0, V, p(nxt), None),
-        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), p(h), None, 0, 1, 1, 64, 8, 1, None),
+        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), 0, p(h), None, 0, 1, 1, 64, 8, 1, None),
         L.rl_op_prefill_attention(p(h), p(kc), p(kc), p(h), 0, 0, 1, 1, 1, 64, 8, None),
         L.rl_op_logprob_gather(p(lg), V, 0, V, p(toks), 4, 0, p(x), None),
     ]
@@ -473,3 +473,35 @@ def test_sampling_kernel(ops, B, V, temperature):
     ops.sample(bad, temperature, ud, c2)
     torch.cuda.synchronize()
     assert torch.equal(a, b2) and int(c2[1]) == -1 and torch.equal(c2[2:], a[2:]) and int(c2[0]) == int(a[0])
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv,nsplit", [(128, 4, 4, 1), (128, 8, 2, 3), (64, 4, 2, 1)])
+def test_per_sequence_lengths_in_rope_append_and_attention(ops, hd, Hq, Hkv, nsplit):
+    """Ragged batches: every sequence appends and attends at its own length (pos_stride / len_stride = 1)."""
+    B, S, style = 4, 256, 1
+    lens = [0, 7, 130, 255]
+    ld = (Hq + 2 * Hkv) * hd
+    tab = torch.empty((S, hd // 2, 2), dtype=torch.float32, device=DEV)
+    ops.build_rope_table(tab, S, hd, 10000.0)
+    qkv = randn_f32((1, B, ld), 97, std=0.8)
+    kc, vc = randn_f16((B, Hkv, S, hd), 98), randn_f16((B, Hkv, S, hd), 99)
+    for b, n in enumerate(lens):                      # nothing at or beyond a sequence's own length may be used
+        kc[b, :, n:] = float("nan")
+        vc[b, :, n:] = float("nan")
+    d_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    qf = torch.empty((B, Hq * hd), dtype=torch.float32, device=DEV)
+    ops.rope_append(qkv, 1, B * ld, B, 1, 0, d_len, tab, style, Hq, Hkv, hd, S, qf, None, kc, vc, pos_stride=1)
+    out = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ops.decode_attention(qf, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=1)
+    torch.cuda.synchronize()
+    tot, kn, vn, on = np64(qkv)[0], np64(kc), np64(vc), np64(out).reshape(B, Hq, hd)
+    g = Hq // Hkv
+    for b, n in enumerate(lens):
+        q = orc.rope(tot[b, : Hq * hd].reshape(Hq, hd), n, 10000.0, style)
+        k = orc.rope(tot[b, Hq * hd: (Hq + Hkv) * hd].reshape(Hkv, hd), n, 10000.0, style)
+        assert (np.abs(kn[b, :, n] - k) <= 0.5 * F16_EPS * np.abs(k) * 1.01 + 1e-6).all()
+        assert np.isnan(kn[b, :, n + 1:]).all()                       # rows past the new one stay untouched
+        for u in range(Hq):
+            ref = orc.attend(q[u], kn[b, u // g, : n + 1], vn[b, u // g, : n + 1])
+            assert (np.abs(on[b, u] - ref) <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 3e-5).all(), (b, u)
