@@ -115,9 +115,45 @@ int rl_gen_prefill(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, flo
  * padding (any valid ids).  lens: DEVICE int32 [B], values clamped to [1, T] on the device.  logits / next are those of
  * each sequence's own last prompt position.  Afterwards sequence b has length lens[b] and decode steps append at each
  * sequence's own position; rl_gen_state reports T, the upper bound the capacity check uses.  All B*T rows are
- * computed; padded positions never reach a later result (causal attention, and decode overwrites them first). */
+ * computed; padded positions reach neither the cache nor a later result.  On a paged generator the call first reads
+ * lens back (one stream synchronisation). */
 int rl_gen_prefill_ragged(rl_gen_t *h, const int32_t *tokens, const int32_t *lens, int32_t B, int32_t T, float *logits,
                           int32_t *next, void *hip_stream);
+
+/* ---- Paged KV cache -----------------------------------------------------------------------------------------------
+ * Section 5.1 counts the KV cache as memory that a call holds only while it runs, and Section 7 names paged attention
+ * as a technique the generation backend can take in: the cache becomes a pool of fixed-size pages, and a per-sequence
+ * page list says where each run of positions lives, so a batch of sequences of different lengths occupies pool memory
+ * in proportion to what each one needs rather than max_batch * max_seq.
+ *
+ * rl_gen_page_bytes: bytes one page takes across all layers, K and V (0 for an invalid shape or page size; page_size is
+ * a power of two in [16, 4096] positions).
+ * rl_gen_create_paged: as rl_gen_create, but the kv arena is a pool of floor(kv_bytes / page bytes) >= 1 pages
+ * (rl_gen_pool_pages returns the count).  Before the first prefill / inference call the caller hands over the page
+ * lists with rl_gen_set_block_table. */
+size_t rl_gen_page_bytes(const rl_gen_shape *shape, int32_t page_size);
+int rl_gen_create_paged(const rl_gen_shape *shape, const rl_gen_weights *weights, void *kv_arena, size_t kv_bytes,
+                        void *work_arena, size_t work_bytes, int32_t page_size, rl_gen_t **out);
+int rl_gen_pool_pages(const rl_gen_t *h);
+
+/* Page lists.  table: HOST int32 [B, pages_per_seq], entry (b, i) = pool page holding positions i*page .. (i+1)*page-1
+ * of sequence b; capacity: HOST int32 [B], positions reserved for sequence b (0 .. max_seq): only the first
+ * ceil(capacity[b] / page) entries of row b are read.  Every entry read must lie in [0, pool pages) and no page may be
+ * named twice, else RL_GEN_E_CAPACITY / RL_GEN_E_SHAPE and the previous lists stay.  The lists are copied to the device
+ * on `hip_stream`, which is synchronised; no other call on this handle may be in flight.  Cache contents are not
+ * touched, so a caller may extend a sequence (append pages, raise its capacity) or hand the pages of an ended sequence
+ * to another between steps.  The calls that store cache rows check capacity on the host: prefill and the inference
+ * calls need capacity[b] >= the sequence's length, a decode step needs room for one more row in every sequence the host
+ * does not know to have ended (it learns about ended sequences and exact lengths in rl_gen_read_state; until then it
+ * counts every sequence as growing).  A violated check returns RL_GEN_E_CAPACITY before anything is launched. */
+int rl_gen_set_block_table(rl_gen_t *h, const int32_t *table, const int32_t *capacity, int32_t B, int32_t pages_per_seq,
+                           void *hip_stream);
+
+/* Host-only helper (no device work): fills table (HOST int32 [B, pages_per_seq]) with consecutive pool pages, sequence
+ * after sequence, ceil(capacity[b] / page_size) each, -1 in unused entries.  Returns the number of pages used, or
+ * RL_GEN_E_CAPACITY if they exceed n_pages or a sequence needs more than pages_per_seq, RL_GEN_E_SHAPE for a bad argument. */
+int32_t rl_gen_plan_pages(const int32_t *capacity, int32_t B, int32_t page_size, int32_t n_pages, int32_t pages_per_seq,
+                          int32_t *table);
 
 /* End token (Section 2.1: generation runs until termination).  eos >= 0: a sequence whose returned token is eos has ended:
  * from the next step on it returns eos, its length stays, and what is fed for it is ignored (its logits are not

@@ -92,6 +92,16 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
                            void *hip_stream);
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
+/* The same attention over a paged cache (Section 7 names paged attention as a technique the generation backend can
+ * take in).  k_pool / v_pool: DEVICE f16 [n_pages][Hkv][page_size][hd]; table: DEVICE int32 [B, table_stride], entry
+ * (b, i) = pool page that holds positions i*page_size .. of sequence b; page_size a power of two in [16, 4096],
+ * table_stride * page_size >= S.  Entries for positions 0 .. d_len[b] are read and must name pages inside the pool:
+ * they are not checked.  The result equals rl_op_decode_attention on the same rows bit for bit. */
+int rl_op_decode_attention_paged(const float *q, const uint16_t *k_pool, const uint16_t *v_pool, const int32_t *table,
+                                 int32_t table_stride, int32_t page_size, const int32_t *d_len, int32_t len_stride, uint16_t *out,
+                                 float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
+                                 void *hip_stream);
+
 /* Rotary embedding + KV-cache append + decode attention in one kernel (what a decode step runs): q, k and v of the
  * new token of every sequence are taken from qkv -- nsplit_qkv fp32 partials, each [B, (Hq+2Hkv)*hd] laid out
  * q | k | v per row, split_stride elements apart (multiple of 4) -- added, q and k rotated at position d_len[b * len_stride] with

@@ -61,6 +61,11 @@ def lib():
         "rl_gen_kv_bytes": (sz, [sp]),
         "rl_gen_work_bytes": (sz, [sp]),
         "rl_gen_create": (C.c_int, [sp, C.POINTER(RlGenWeights), vp, sz, vp, sz, C.POINTER(vp)]),
+        "rl_gen_page_bytes": (sz, [sp, i32]),
+        "rl_gen_create_paged": (C.c_int, [sp, C.POINTER(RlGenWeights), vp, sz, vp, sz, i32, C.POINTER(vp)]),
+        "rl_gen_pool_pages": (C.c_int, [vp]),
+        "rl_gen_set_block_table": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), i32, i32, vp]),
+        "rl_gen_plan_pages": (i32, [C.POINTER(i32), i32, i32, i32, i32, C.POINTER(i32)]),
         "rl_gen_packed_bytes": (sz, [sp]),
         "rl_gen_pack_weights": (C.c_int, [vp, vp, sz, vp]),
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
@@ -90,6 +95,7 @@ def lib():
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
+        "rl_op_decode_attention_paged": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
@@ -107,11 +113,11 @@ def lib():
 
 
 EXPORTED_SYMBOLS = (
-    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_packed_bytes",
+    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes",
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_fused",
+    "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
@@ -135,6 +141,22 @@ def work_bytes(shape, max_batch=1, max_seq=1) -> int:
     return int(lib().rl_gen_work_bytes(C.byref(_shape_of(shape, max_batch, max_seq))))
 
 
+def page_bytes(shape, page_size: int) -> int:
+    return int(lib().rl_gen_page_bytes(C.byref(_shape_of(shape)), int(page_size)))
+
+
+def plan_pages(capacity, page_size: int, n_pages: int, pages_per_seq: int):
+    """Consecutive pool pages for sequences of the given capacities: (pages used, table as a list of rows)."""
+    B = len(capacity)
+    cap = (C.c_int32 * max(B, 1))(*[int(c) for c in capacity])
+    tab = (C.c_int32 * max(B * pages_per_seq, 1))()
+    used = int(lib().rl_gen_plan_pages(cap, B, int(page_size), int(n_pages), int(pages_per_seq), tab))
+    if used < 0:
+        raise RlGenError(used, "rl_gen_plan_pages")
+    flat = list(tab)[: B * pages_per_seq]
+    return used, [flat[b * pages_per_seq:(b + 1) * pages_per_seq] for b in range(B)]
+
+
 def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
 
@@ -152,7 +174,8 @@ class Generator:
     call pack_weights() again after the weight tensors were updated in place.
     """
 
-    def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int, packed: bool = True):
+    def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int, packed: bool = True,
+                 page_size: int = 0, n_pages: int = 0):
         import torch
         self._h = None
         any_w = weights["tok_emb"]
@@ -185,13 +208,25 @@ class Generator:
         rc = L.rl_gen_validate_shape(C.byref(self.cshape))
         if rc != 0:
             raise RlGenError(rc, "rl_gen_validate_shape")
-        nkv, nwork = L.rl_gen_kv_bytes(C.byref(self.cshape)), L.rl_gen_work_bytes(C.byref(self.cshape))
+        nwork = L.rl_gen_work_bytes(C.byref(self.cshape))
+        self.page_size = int(page_size)
+        if page_size:   # paged cache: the arena is a pool of n_pages pages
+            pb = L.rl_gen_page_bytes(C.byref(self.cshape), int(page_size))
+            if pb == 0 and shape.n_layers > 0:
+                raise RlGenError(-2, "rl_gen_page_bytes", f"page size {page_size}")
+            nkv = pb * int(n_pages)
+        else:
+            nkv = L.rl_gen_kv_bytes(C.byref(self.cshape))
         dev = any_w.device
         self.kv_arena = torch.empty(max(nkv, 256), dtype=torch.uint8, device=dev)
         self.work_arena = torch.empty(nwork, dtype=torch.uint8, device=dev)
         h = C.c_void_p()
-        rc = L.rl_gen_create(C.byref(self.cshape), C.byref(w), self.kv_arena.data_ptr(), nkv, self.work_arena.data_ptr(),
-                             nwork, C.byref(h))
+        if page_size:
+            rc = L.rl_gen_create_paged(C.byref(self.cshape), C.byref(w), self.kv_arena.data_ptr(), nkv,
+                                       self.work_arena.data_ptr(), nwork, int(page_size), C.byref(h))
+        else:
+            rc = L.rl_gen_create(C.byref(self.cshape), C.byref(w), self.kv_arena.data_ptr(), nkv, self.work_arena.data_ptr(),
+                                 nwork, C.byref(h))
         if rc != 0:
             raise RlGenError(rc, "rl_gen_create", L.rl_gen_last_error(None).decode())
         self._h = h
@@ -244,6 +279,20 @@ class Generator:
         self._check(lib().rl_gen_prefill_ragged(self._h, tokens.data_ptr(), lens.data_ptr(), B, T, _ptr(logits), _ptr(next_tokens),
                                                 _stream()), "rl_gen_prefill_ragged")
         return logits, next_tokens
+
+    def pool_pages(self) -> int:
+        return int(lib().rl_gen_pool_pages(self._h))
+
+    def set_block_table(self, table, capacity):
+        """table: rows of pool page numbers (one row per sequence), capacity: positions reserved per sequence."""
+        B = len(capacity)
+        pps = max(len(r) for r in table) if B else 1
+        flat = (C.c_int32 * max(B * pps, 1))()
+        for b, row in enumerate(table):
+            for i, v in enumerate(row):
+                flat[b * pps + i] = int(v)
+        cap = (C.c_int32 * max(B, 1))(*[int(c) for c in capacity])
+        self._check(lib().rl_gen_set_block_table(self._h, flat, cap, B, pps, _stream()), "rl_gen_set_block_table")
 
     def set_eos(self, eos: int):
         self._check(lib().rl_gen_set_eos(self._h, int(eos)), "rl_gen_set_eos")
@@ -387,6 +436,11 @@ class _Ops:
     def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0):
         self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(),
                                               _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention")
+
+    def decode_attention_paged(self, q, k_pool, v_pool, table, page_size, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0):
+        self._ck(lib().rl_op_decode_attention_paged(q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(), table.data_ptr(),
+                                                    table.shape[1], page_size, d_len.data_ptr(), len_stride, out.data_ptr(), _ptr(ws),
+                                                    B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention_paged")
 
     def decode_attention_fused(self, qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S,
                                nsplit, len_stride=0):

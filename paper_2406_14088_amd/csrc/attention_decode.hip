@@ -12,6 +12,9 @@
 //     the rows it sees; groups are merged once at the end by wavefront shuffles;
 //   * grouped-query attention: the GT query heads that share a kv head are processed by the same
 //     wavefront, so K and V are read once for all of them;
+//   * paged cache (PAGED = true): the cache is a pool of pages of 2^k positions and a per-sequence page list says
+//     where each run of positions lives; a page of one kv head is still a contiguous run of rows, and the page
+//     numbers of the next iteration are fetched while the current rows are in flight;
 //   * optional split over the sequence axis (more wavefronts for long contexts / small batches):
 //     splits write (max, sum, unnormalised output) partials that a small merge kernel combines.
 //   * fused form (FUSED = true): the wavefront takes the new token's q, k and v straight from the split-K
@@ -86,10 +89,11 @@ __device__ __forceinline__ void rotate8(float x[8], int c, const float *tab /* r
     }
 }
 
-template <int HD, int GT, bool FUSED>
+template <int HD, int GT, bool FUSED, bool PAGED>
 __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     const float *__restrict__ q, f16_t *kc, f16_t *vc, const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
-    float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, int len_stride, FusedQkv fq) {
+    float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, int len_stride, FusedQkv fq, KvMap map) {
+    static_assert(!(FUSED && PAGED), "the fused form addresses contiguous slabs only");
     constexpr int LPR = HD / 8;     // lanes per cache row
     constexpr int RPW = 64 / LPR;   // rows per wavefront load instruction
     const int lane = threadIdx.x & 63;
@@ -146,8 +150,21 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
         }
     }
     const float scale = rsqrtf((float)HD);
-    const f16_t *kb = kc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
-    const f16_t *vb = vc + ((size_t)b * Hkv + kvh) * S * HD + c * 8;
+    // contiguous: the slab of this (sequence, kv head); paged: the pool, rows found through the sequence's page list
+    const f16_t *kb = kc + (PAGED ? (size_t)0 : ((size_t)b * Hkv + kvh) * S * HD) + c * 8;
+    const f16_t *vb = vc + (PAGED ? (size_t)0 : ((size_t)b * Hkv + kvh) * S * HD) + c * 8;
+    const int32_t *pages = PAGED ? map.table + (size_t)b * map.table_stride : nullptr;
+    const int pmask = (1 << map.page_shift) - 1;
+    // page numbers are fetched one iteration ahead, so the cache loads never wait for the page list
+    int pg[DA_U];
+    if (PAGED) {
+#pragma unroll
+        for (int u = 0; u < DA_U; ++u) {
+            int j = j0 + u * RPW + r;
+            int jc = j < j1 ? j : j1 - 1;
+            pg[u] = pages[jc >> map.page_shift];
+        }
+    }
 
     float mx[GT], den[GT], acc[GT][8];
 #pragma unroll
@@ -167,8 +184,17 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
             jj[u] = j;
             int jc = j < j1 ? j : j1 - 1;  // rows past the end re-read the last valid row; their weight is 0
             is_new[u] = FUSED && jc == pos;
-            kr[u] = *reinterpret_cast<const u32x4_t *>(kb + (size_t)jc * HD);
-            vr[u] = *reinterpret_cast<const u32x4_t *>(vb + (size_t)jc * HD);
+            const size_t row = PAGED ? (((size_t)pg[u] * Hkv + kvh) << map.page_shift) + (jc & pmask) : (size_t)jc;
+            kr[u] = *reinterpret_cast<const u32x4_t *>(kb + row * HD);
+            vr[u] = *reinterpret_cast<const u32x4_t *>(vb + row * HD);
+        }
+        if (PAGED) {
+#pragma unroll
+            for (int u = 0; u < DA_U; ++u) {
+                int j = base + RPW * DA_U + u * RPW + r;
+                int jc = j < j1 ? j : j1 - 1;
+                pg[u] = pages[jc >> map.page_shift];
+            }
         }
         if (FUSED) {  // the row of the new position comes from registers: the cache may not hold it yet
 #pragma unroll
@@ -300,25 +326,28 @@ int decode_attention_default_splits(int B, int Hkv, int S) {
 
 template <int HD, int GT>
 static void launch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B,
-                      int Hq, int Hkv, int S, int nsplit, const FusedQkv *fq, hipStream_t st) {
+                      int Hq, int Hkv, int S, int nsplit, const FusedQkv *fq, const KvMap &map, hipStream_t st) {
     int g = Hq / Hkv;
     int n_items = B * Hkv * (g / GT) * nsplit;
     int blocks = ceil_div(n_items, DA_THREADS / 64);
     if (fq)
-        decode_attention_kernel<HD, GT, true><<<blocks, DA_THREADS, 0, st>>>(nullptr, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
-                                                                           nsplit, len_stride, *fq);
+        decode_attention_kernel<HD, GT, true, false><<<blocks, DA_THREADS, 0, st>>>(nullptr, kc, vc, d_len, out, ws, n_items, Hq,
+                                                                                  Hkv, S, nsplit, len_stride, *fq, KvMap());
+    else if (map.table)
+        decode_attention_kernel<HD, GT, false, true><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
+                                                                                  nsplit, len_stride, FusedQkv{}, map);
     else
-        decode_attention_kernel<HD, GT, false><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
-                                                                            nsplit, len_stride, FusedQkv{});
+        decode_attention_kernel<HD, GT, false, false><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv,
+                                                                                   S, nsplit, len_stride, FusedQkv{}, KvMap());
 }
 
 static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B,
-                        int Hq, int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, hipStream_t st) {
+                        int Hq, int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, const KvMap &map, hipStream_t st) {
     if (B <= 0) return;
     int g = Hq / Hkv;
     int gt = decode_attention_group(g);
 #define DA_CASE(HDV, GTV) \
-    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, fq, st); }
+    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, fq, map, st); }
     DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4)
     DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4)
 #undef DA_CASE
@@ -326,9 +355,9 @@ static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_l
 }
 
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
-                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st) {
+                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map) {
     dispatch_da(q, const_cast<f16_t *>(kc), const_cast<f16_t *>(vc), d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, nullptr,
-                st);
+                map, st);
 }
 
 void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
@@ -336,7 +365,7 @@ void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t spli
                                    int Hkv, int hd, int S, int nsplit, hipStream_t st) {
     FusedQkv fq;
     fq.part = qkv; fq.nsplit = nsplit_qkv; fq.split_stride = split_stride; fq.rope_tab = rope_tab; fq.rope_style = rope_style;
-    dispatch_da(nullptr, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, &fq, st);
+    dispatch_da(nullptr, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, &fq, KvMap(), st);
 }
 
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {

@@ -22,7 +22,8 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const f16
                                                                       const f16_t *__restrict__ kc,
                                                                       const f16_t *__restrict__ vc,
                                                                       f16_t *__restrict__ out, int b0, int T, int Hq,
-                                                                      int Hkv, int S) {
+                                                                      int Hkv, int S, KvMap map,
+                                                                      const int32_t *__restrict__ d_valid) {
     constexpr int KS = HD / 16;   // k16 steps of the QK product
     constexpr int ET = HD / 32;   // 32-row tiles of O^T
     constexpr int STR = PA_STRIDE(HD);
@@ -45,8 +46,11 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const f16
 #pragma unroll
         for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const f16x8_t *>(qp + s * 16);
     }
-    const f16_t *kbase = kc + ((size_t)(b0 + bl) * Hkv + kvh) * S * HD;
-    const f16_t *vbase = vc + ((size_t)(b0 + bl) * Hkv + kvh) * S * HD;
+    int n_keys = T;  // keys this sequence really has in the cache
+    if (d_valid) {
+        int nv = d_valid[b0 + bl];
+        n_keys = nv < 1 ? 1 : (nv > T ? T : nv);
+    }
 
     f32x16_t oacc[ET];
 #pragma unroll
@@ -66,9 +70,10 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const f16
             int row = idx / (HD / 8), piece = idx % (HD / 8);
             int key = kt * PA_KT + row;
             u32x4_t kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-            if (key < T) {  // rows past the prompt may hold arbitrary bits: keep them out (0 * NaN)
-                kv = *reinterpret_cast<const u32x4_t *>(kbase + (size_t)key * HD + piece * 8);
-                vv = *reinterpret_cast<const u32x4_t *>(vbase + (size_t)key * HD + piece * 8);
+            if (key < n_keys) {  // rows past the prompt may hold arbitrary bits: keep them out (0 * NaN)
+                const size_t at = kv_row_index(map, b0 + bl, kvh, Hkv, S, key) * HD + piece * 8;
+                kv = *reinterpret_cast<const u32x4_t *>(kc + at);
+                vv = *reinterpret_cast<const u32x4_t *>(vc + at);
             }
             *reinterpret_cast<u32x4_t *>(ks + row * STR + piece * 8) = kv;
             *reinterpret_cast<u32x4_t *>(vs + row * STR + piece * 8) = vv;
@@ -145,9 +150,9 @@ __global__ __launch_bounds__(PA_THREADS) void prefill_attention_kernel(const f16
 }
 
 void launch_prefill_attention(const f16_t *q, const f16_t *kc, const f16_t *vc, f16_t *out, int nb, int b0, int T,
-                              int Hq, int Hkv, int hd, int S, hipStream_t st) {
+                              int Hq, int Hkv, int hd, int S, hipStream_t st, KvMap map, const int32_t *d_valid) {
     if (nb <= 0 || T <= 0) return;
     dim3 grid(ceil_div(T, 128), Hq, nb);
-    if (hd == 128) prefill_attention_kernel<128><<<grid, PA_THREADS, 0, st>>>(q, kc, vc, out, b0, T, Hq, Hkv, S);
-    else prefill_attention_kernel<64><<<grid, PA_THREADS, 0, st>>>(q, kc, vc, out, b0, T, Hq, Hkv, S);
+    if (hd == 128) prefill_attention_kernel<128><<<grid, PA_THREADS, 0, st>>>(q, kc, vc, out, b0, T, Hq, Hkv, S, map, d_valid);
+    else prefill_attention_kernel<64><<<grid, PA_THREADS, 0, st>>>(q, kc, vc, out, b0, T, Hq, Hkv, S, map, d_valid);
 }

@@ -65,5 +65,20 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// Where the KV cache keeps row j of (sequence b, kv head kvh), in rows of head_dim elements from the start of a layer's
+// K (or V) area.  table == NULL: contiguous slabs [max_batch][Hkv][S][hd].  Otherwise the area is a pool of pages
+// [n_pages][Hkv][page][hd] with page = 1 << page_shift positions, and table[b * table_stride + (j >> page_shift)]
+// names the page that holds position j of sequence b.
+struct KvMap {
+    const int32_t *table = nullptr;
+    int table_stride = 0;
+    int page_shift = 0;
+};
+__device__ __forceinline__ size_t kv_row_index(const KvMap &m, int b, int kvh, int Hkv, int S, int j) {
+    if (!m.table) return ((size_t)b * Hkv + kvh) * S + j;
+    const int page = m.table[(size_t)b * m.table_stride + (j >> m.page_shift)];
+    return (((size_t)page * Hkv + kvh) << m.page_shift) + (j & ((1 << m.page_shift) - 1));
+}
+
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }

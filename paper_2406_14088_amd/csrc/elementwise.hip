@@ -112,9 +112,18 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
                                                           const float *__restrict__ rope_tab, int rope_style, int Hq,
                                                           int Hkv, int hd, int S, float *__restrict__ q_f32,
                                                           f16_t *__restrict__ q_f16, f16_t *__restrict__ kc,
-                                                          f16_t *__restrict__ vc) {
+                                                          f16_t *__restrict__ vc, KvMap map,
+                                                          const int32_t *__restrict__ d_valid,
+                                                          const int32_t *__restrict__ d_done) {
     int m = blockIdx.x;
     int b = b0 + m / T;
+    bool store_kv = true;  // rows past a sequence's own length never reach the cache
+    if (d_valid) {
+        int nv = d_valid[b];
+        nv = nv < 1 ? 1 : (nv > T ? T : nv);
+        store_kv = m % T < nv;
+    }
+    if (d_done && d_done[b]) store_kv = false;  // an ended sequence is fed its end token again: nothing new to keep
     int pos = d_pos0[(size_t)(m / T) * pos_stride] + m % T;  // pos_stride 0: one start for all rows; 1: one per sequence
     if (pos >= S) return;  // capacity is checked on the host; never write outside the cache
     int half = hd >> 1;
@@ -144,8 +153,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
             size_t o = (size_t)m * Hq * hd + (size_t)head * hd;
             if (q_f32) { q_f32[o + ia] = a; q_f32[o + ib] = c; }
             if (q_f16) { q_f16[o + ia] = f32_to_f16(a); q_f16[o + ib] = f32_to_f16(c); }
-        } else {
-            f16_t *dst = (kind == 1 ? kc : vc) + (((size_t)b * Hkv + head) * S + pos) * hd;
+        } else if (store_kv) {
+            f16_t *dst = (kind == 1 ? kc : vc) + kv_row_index(map, b, head, Hkv, S, pos) * hd;
             dst[ia] = f32_to_f16(a);
             dst[ib] = f32_to_f16(c);
         }
@@ -154,12 +163,13 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
 
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
                         int pos_stride, const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
-                        f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st) {
+                        f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st, KvMap map, const int32_t *d_valid,
+                        const int32_t *d_done) {
     if (M <= 0) return;
     int items = (Hq + 2 * Hkv) * (hd / 2);
     dim3 grid(M, ceil_div(items, 256));
     rope_append_kernel<<<grid, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, pos_stride, rope_tab, rope_style, Hq, Hkv, hd, S,
-                                          q_f32, q_f16, kc, vc);
+                                          q_f32, q_f16, kc, vc, map, d_valid, d_done);
 }
 
 // ------------------------------------------------------------------------------------------------

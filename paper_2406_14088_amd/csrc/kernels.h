@@ -13,10 +13,13 @@ void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_str
 // Sums the split partials of the fused QKV projection, rotates q and k heads at their positions and
 // writes q (fp32 and/or half, [M, Hq*hd]) and the cache rows.  Row m is sequence b0 + m / T at
 // position d_pos0[(m / T) * pos_stride] + m % T (pos_stride 0: one start position for all; 1: one per sequence).  rope_tab: fp32 [max_seq, hd/2, 2] (cos, sin).
-// kc / vc: this layer's K and V slabs, half [max_batch][Hkv][S][hd].
+// kc / vc: this layer's K and V areas (half), laid out as `map` says (default: slabs [max_batch][Hkv][S][hd]).
+// d_valid (optional, indexed by sequence): only the first clamp(d_valid[b], 1, T) rows of a sequence reach the cache.
+// d_done (optional, indexed by sequence): sequences with a non-zero flag store no cache row (q is still written).
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
                         int pos_stride, const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
-                        f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st);
+                        f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st, KvMap map = KvMap(),
+                        const int32_t *d_valid = nullptr, const int32_t *d_done = nullptr);
 // next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN).  Optional bookkeeping per sequence
 // (lens, done may be NULL; eos < 0: no end token): a sequence with done[b] returns eos and does not grow; otherwise
 // lens[b] += 1 and done[b] = (next[b] == eos).
@@ -98,10 +101,10 @@ void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *split
 
 // ---- attention_decode.hip ------------------------------------------------------------------------
 // One new query per (sequence, query head) against cache rows 0 .. d_len[b * len_stride] (inclusive).
-// q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's slabs (half); out half [B, Hq*hd].
-// ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
+// q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's K and V areas (half) laid out as `map` says; out half
+// [B, Hq*hd].  ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
-                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st);
+                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map = KvMap());
 // Fused form: q, k, v of the new token are taken from the split-K partials of the QKV projection (each
 // [B, (Hq+2Hkv)*hd], q | k | v per row): partials added, q and k rotated at position *d_len, the k/v row appended to
 // the cache (kc/vc are written) and used from registers.  Replaces launch_rope_append + launch_decode_attention.
@@ -116,5 +119,8 @@ int decode_attention_group(int g);  // query heads per wavefront for Hq/Hkv = g
 // ---- attention_prefill.hip -----------------------------------------------------------------------
 // Causal attention over the T prompt positions of nb sequences whose K/V already sit in the cache.
 // q half [nb*T, Hq*hd] (rotated); sequence i of the chunk is cache sequence b0 + i; out half [nb*T, Hq*hd].
+// d_valid (optional, indexed by cache sequence): only keys below clamp(d_valid[b], 1, T) exist; later keys count as
+// zero rows with zero weight, and the output rows of later queries are unspecified (finite).
 void launch_prefill_attention(const f16_t *q, const f16_t *kc, const f16_t *vc, f16_t *out, int nb, int b0, int T,
-                              int Hq, int Hkv, int hd, int S, hipStream_t st);
+                              int Hq, int Hkv, int hd, int S, hipStream_t st, KvMap map = KvMap(),
+                              const int32_t *d_valid = nullptr);

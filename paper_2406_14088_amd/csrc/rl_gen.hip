@@ -20,11 +20,12 @@ constexpr int kPrefillChunkTokens = 16384;  // prompt tokens pushed through the 
 constexpr int kSkinnyMaxM = 256;
 constexpr int kMaxSplits = 16;
 constexpr size_t kAlign = 256;
+constexpr int kMinPage = 16, kMaxPage = 4096;  // positions per page of a paged cache (powers of two)
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct WorkPlan {
-    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, rope, state, total;
+    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, rope, state, table, total;
     size_t part_elems;  // floats in the split-K partial area
     int rows;  // activation rows the workspace can hold
 };
@@ -45,6 +46,12 @@ int validate(const rl_gen_shape *s) {
     const uint64_t lim = 0xffffffffull;
     if ((uint64_t)s->vocab * s->hidden * 2 > lim || (uint64_t)s->ffn * s->hidden * 2 > lim) return RL_GEN_E_SHAPE;
     return RL_GEN_OK;
+}
+
+int page_shift_of(int page_size) {
+    for (int sh = 4; (1 << sh) <= kMaxPage; ++sh)
+        if ((1 << sh) == page_size) return sh;
+    return 0;
 }
 
 int attn_splits(const rl_gen_shape *s) {
@@ -81,6 +88,7 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.next = take((size_t)s->max_batch * 4);
     p.rope = take((size_t)s->max_seq * s->head_dim * 4);
     p.state = take(((size_t)2 * s->max_batch + 16) * 4);  // per-sequence lengths, per-sequence end flags, a constant 0
+    p.table = take((size_t)s->max_batch * ceil_div(s->max_seq, kMinPage) * 4);  // page lists of a paged cache
     p.total = off;
     return p;
 }
@@ -115,6 +123,14 @@ struct rl_gen {
     int nsplit_attn;
     int B, len;
     bool graph_on, prof_on, qkv_two_term;
+    // paged cache (rl_gen_create_paged): the kv arena is a pool of n_pages pages of 1 << page_shift positions
+    int page_shift;          // 0: contiguous slabs
+    int n_pages, table_stride;
+    bool table_set;
+    std::vector<int32_t> cap;        // HOST: positions reserved per sequence (rl_gen_set_block_table)
+    std::vector<int32_t> host_len;   // HOST: upper bound of each sequence's length
+    std::vector<int32_t> host_done;  // HOST: end flags as last read back
+    std::vector<int32_t> table_img;  // HOST: image of the device page lists
     int eos;                 // end token (rl_gen_set_eos), -1: none
     float temperature;       // > 0: the next token is sampled (rl_gen_set_sampling); else greedy
     const float *sample_u;   // DEVICE [max_batch] uniform draws, borrowed, refreshed by the caller between steps
@@ -140,11 +156,17 @@ struct rl_gen {
     int32_t *d_lens() const { return reinterpret_cast<int32_t *>(work + wp.state); }
     int32_t *d_done() const { return d_lens() + s.max_batch; }
     int32_t *d_zero() const { return d_lens() + 2 * s.max_batch; }
-    f16_t *kslab(int l) const {
-        return kv + (size_t)(2 * l) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
+    int32_t *d_table() const { return reinterpret_cast<int32_t *>(work + wp.table); }
+    size_t area_elems() const {  // one layer's K (or V) area
+        return page_shift ? ((size_t)n_pages * s.n_kv_heads << page_shift) * s.head_dim
+                          : (size_t)s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
     }
-    f16_t *vslab(int l) const {
-        return kv + (size_t)(2 * l + 1) * s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
+    f16_t *kslab(int l) const { return kv + (size_t)(2 * l) * area_elems(); }
+    f16_t *vslab(int l) const { return kv + (size_t)(2 * l + 1) * area_elems(); }
+    KvMap kvmap() const {
+        KvMap m;
+        if (page_shift) { m.table = d_table(); m.table_stride = table_stride; m.page_shift = page_shift; }
+        return m;
     }
 };
 
@@ -244,7 +266,10 @@ void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
 
 // All layers for M = nb*T rows (sequences b0 .. b0+nb-1, T new positions each starting at *d_pos0),
 // then final norm; leaves the normalised rows in h->h().  decode == (T == 1 and attention over the cache).
-void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool decode, hipStream_t st) {
+// d_valid (prefill of ragged prompts): per-sequence count of rows that exist; later rows never reach the cache.
+void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool decode, hipStream_t st,
+                const int32_t *d_valid = nullptr) {
+    const KvMap map = h->kvmap();
     const rl_gen_shape &s = h->s;
     const int M = nb * T, d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
     const int L = s.n_layers;
@@ -279,7 +304,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
             launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_lens() : h->d_zero(),
                                decode ? 1 : 0, h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
-                               decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st);
+                               decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st, map,
+                               d_valid, decode ? h->d_done() : nullptr);
         }
         // (A single kernel that takes q, k, v from the partials, rotates, appends and attends exists --
         // launch_decode_attention_fused -- but measured no faster per step: what the separate kernel costs, the
@@ -287,11 +313,11 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         if (decode) {
             Scope sc(h, RL_GEN_K_DECODE_ATTN, st);
             launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_lens(), 1, h->attn(), h->attn_ws(), nb,
-                                    s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st);
+                                    s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st, map);
         } else {
             Scope sc(h, RL_GEN_K_PREFILL_ATTN, st);
             launch_prefill_attention(h->qbf(), h->kslab(l), h->vslab(l), h->attn(), nb, b0, T, s.n_heads, s.n_kv_heads,
-                                     s.head_dim, s.max_seq, st);
+                                     s.head_dim, s.max_seq, st, map, d_valid);
         }
         if (pk) ns = project_packed(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->pw[W_O][l], d, nullptr, 0, nullptr, 0, st);
         else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
@@ -443,8 +469,28 @@ int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, vo
     return RL_GEN_OK;
 }
 
-int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_arena, size_t kv_bytes, void *work_arena,
-                  size_t work_bytes, rl_gen_t **out) {
+size_t rl_gen_page_bytes(const rl_gen_shape *s, int32_t page_size) {
+    if (validate(s) != RL_GEN_OK || !page_shift_of(page_size)) return 0;
+    return (size_t)2 * s->n_layers * s->n_kv_heads * page_size * s->head_dim * sizeof(f16_t);
+}
+
+int32_t rl_gen_plan_pages(const int32_t *capacity, int32_t B, int32_t page_size, int32_t n_pages, int32_t pages_per_seq,
+                          int32_t *table) {
+    if (!capacity || !table) return RL_GEN_E_NULL;
+    if (B < 0 || !page_shift_of(page_size) || n_pages < 0 || pages_per_seq < 0) return RL_GEN_E_SHAPE;
+    int64_t used = 0;
+    for (int b = 0; b < B; ++b) {
+        if (capacity[b] < 0) return RL_GEN_E_SHAPE;
+        int64_t need = ((int64_t)capacity[b] + page_size - 1) / page_size;
+        if (need > pages_per_seq || used + need > n_pages) return RL_GEN_E_CAPACITY;
+        for (int i = 0; i < pages_per_seq; ++i) table[(size_t)b * pages_per_seq + i] = i < need ? (int32_t)(used + i) : -1;
+        used += need;
+    }
+    return (int32_t)used;
+}
+
+static int create_impl(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_arena, size_t kv_bytes, void *work_arena,
+                       size_t work_bytes, int page_size, rl_gen_t **out) {
     if (!shape || !w || !out) { set_err(nullptr, "rl_gen_create: NULL argument"); return RL_GEN_E_NULL; }
     *out = nullptr;
     int rc = validate(shape);
@@ -457,7 +503,13 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
         for (int l = 0; l < L; ++l)
             if (!arrs[a][l]) { set_err(nullptr, "rl_gen_create: NULL layer weight"); return RL_GEN_E_NULL; }
     }
-    size_t need_kv = rl_gen_kv_bytes(shape);
+    const int page_shift = page_size ? page_shift_of(page_size) : 0;
+    if (page_size && !page_shift) {
+        set_err(nullptr, "rl_gen_create_paged: page size must be a power of two in [%d, %d]", kMinPage, kMaxPage);
+        return RL_GEN_E_SHAPE;
+    }
+    // paged: any whole number of pages (at least one) makes a pool
+    size_t need_kv = page_shift ? rl_gen_page_bytes(shape, page_size) : rl_gen_kv_bytes(shape);
     WorkPlan wp = plan_work(shape);
     if ((need_kv > 0 && !kv_arena) || !work_arena) { set_err(nullptr, "rl_gen_create: NULL arena"); return RL_GEN_E_NULL; }
     if (kv_bytes < need_kv || work_bytes < wp.total) {
@@ -476,6 +528,13 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
     h->packed = false; h->p_lm_head = nullptr;
     h->temperature = 0.f; h->sample_u = nullptr; h->eos = -1;
+    h->page_shift = page_shift; h->n_pages = 0; h->table_stride = 0; h->table_set = false;
+    if (page_shift) {
+        h->table_stride = ceil_div(shape->max_seq, page_size);
+        // a model without layers has no cache: any page number up to what the lists can name is accepted
+        int64_t n = need_kv ? (int64_t)(kv_bytes / need_kv) : (int64_t)shape->max_batch * h->table_stride;
+        h->n_pages = (int)(n < 0x7fffffff ? n : 0x7fffffff);
+    }
     h->err[0] = 0;
     memset(h->prof_launches, 0, sizeof h->prof_launches);
     memset(h->prof_ms, 0, sizeof h->prof_ms);
@@ -510,7 +569,8 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
                 tab[((size_t)pos * half + r) * 2 + 1] = (float)sin(ang);
             }
         if (hipMemcpy(h->rope(), tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
-            hipMemset(h->d_lens(), 0, ((size_t)2 * shape->max_batch + 16) * 4) != hipSuccess)
+            hipMemset(h->d_lens(), 0, ((size_t)2 * shape->max_batch + 16) * 4) != hipSuccess ||
+            hipMemset(h->d_table(), 0, (size_t)shape->max_batch * ceil_div(shape->max_seq, kMinPage) * 4) != hipSuccess)
             fail = true;
     }
     if (!fail && hipDeviceSynchronize() != hipSuccess) fail = true;
@@ -524,6 +584,84 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_a
     return RL_GEN_OK;
 }
 
+int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_arena, size_t kv_bytes, void *work_arena,
+                  size_t work_bytes, rl_gen_t **out) {
+    return create_impl(shape, w, kv_arena, kv_bytes, work_arena, work_bytes, 0, out);
+}
+
+int rl_gen_create_paged(const rl_gen_shape *shape, const rl_gen_weights *w, void *kv_arena, size_t kv_bytes, void *work_arena,
+                        size_t work_bytes, int32_t page_size, rl_gen_t **out) {
+    if (page_size == 0) { set_err(nullptr, "rl_gen_create_paged: page size 0"); return RL_GEN_E_SHAPE; }
+    return create_impl(shape, w, kv_arena, kv_bytes, work_arena, work_bytes, page_size, out);
+}
+
+int rl_gen_pool_pages(const rl_gen_t *h) { return h ? h->n_pages : RL_GEN_E_NULL; }
+
+int rl_gen_set_block_table(rl_gen_t *h, const int32_t *table, const int32_t *capacity, int32_t B, int32_t pages_per_seq,
+                           void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!h->page_shift) { set_err(h, "rl_gen_set_block_table: the cache of this generator is not paged"); return RL_GEN_E_STATE; }
+    if (!table || !capacity) { set_err(h, "rl_gen_set_block_table: NULL argument"); return RL_GEN_E_NULL; }
+    if (B <= 0 || B > h->s.max_batch || pages_per_seq <= 0) {
+        set_err(h, "rl_gen_set_block_table: B=%d (max %d), pages_per_seq=%d", B, h->s.max_batch, pages_per_seq);
+        return RL_GEN_E_SHAPE;
+    }
+    const int page = 1 << h->page_shift;
+    std::vector<int32_t> img((size_t)h->s.max_batch * h->table_stride, 0);
+    std::vector<unsigned char> taken((size_t)h->n_pages, 0);
+    for (int b = 0; b < B; ++b) {
+        if (capacity[b] < 0 || capacity[b] > h->s.max_seq) {
+            set_err(h, "rl_gen_set_block_table: capacity[%d]=%d outside [0, %d]", b, capacity[b], h->s.max_seq);
+            return RL_GEN_E_CAPACITY;
+        }
+        const int need = ceil_div(capacity[b], page);
+        if (need > pages_per_seq) {
+            set_err(h, "rl_gen_set_block_table: sequence %d needs %d pages, the table has %d per sequence", b, need, pages_per_seq);
+            return RL_GEN_E_SHAPE;
+        }
+        for (int i = 0; i < need; ++i) {
+            const int32_t pg = table[(size_t)b * pages_per_seq + i];
+            if (pg < 0 || pg >= h->n_pages) {
+                set_err(h, "rl_gen_set_block_table: page %d of sequence %d is %d, the pool has %d pages", i, b, pg, h->n_pages);
+                return RL_GEN_E_CAPACITY;
+            }
+            if (taken[pg]) {
+                set_err(h, "rl_gen_set_block_table: pool page %d is named twice", pg);
+                return RL_GEN_E_SHAPE;
+            }
+            taken[pg] = 1;
+            img[(size_t)b * h->table_stride + i] = pg;
+        }
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    h->table_img.swap(img);  // the copy source must outlive the copy
+    if (hipMemcpyAsync(h->d_table(), h->table_img.data(), h->table_img.size() * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        set_err(h, "rl_gen_set_block_table: copy failed");
+        h->table_set = false;
+        return RL_GEN_E_HIP;
+    }
+    h->cap.assign(capacity, capacity + B);
+    h->table_set = true;
+    return RL_GEN_OK;
+}
+
+// Paged cache: every one of the B sequences must have `need` positions reserved.
+static int check_reserved(rl_gen_t *h, const char *who, int B, int need) {
+    if (!h->page_shift) return RL_GEN_OK;
+    if (!h->table_set || (int)h->cap.size() < B) {
+        set_err(h, "%s: the page lists cover %d sequences, %d needed (rl_gen_set_block_table)", who,
+                h->table_set ? (int)h->cap.size() : 0, B);
+        return RL_GEN_E_STATE;
+    }
+    for (int b = 0; b < B; ++b)
+        if (h->cap[b] < need) {
+            set_err(h, "%s: sequence %d has %d positions reserved, %d needed", who, b, h->cap[b], need);
+            return RL_GEN_E_CAPACITY;
+        }
+    return RL_GEN_OK;
+}
+
 static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, const int32_t *lens, int32_t B, int32_t T,
                         float *logits, int32_t *next, void *hip_stream) {
     if (!h) return RL_GEN_E_NULL;
@@ -534,6 +672,24 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
         return RL_GEN_E_CAPACITY;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    if (h->page_shift) {
+        // the host has to know how long each sequence is: it checks every later step against the reserved pages
+        std::vector<int32_t> hl((size_t)B, T);
+        if (lens) {
+            if (hipMemcpyAsync(hl.data(), lens, (size_t)B * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+                hipStreamSynchronize(st) != hipSuccess) { set_err(h, "%s: reading lens failed", who); return RL_GEN_E_HIP; }
+            for (auto &n : hl) n = n < 1 ? 1 : (n > T ? T : n);
+        }
+        int rc = check_reserved(h, who, B, 0);
+        if (rc != RL_GEN_OK) return rc;
+        for (int b = 0; b < B; ++b)
+            if (hl[b] > h->cap[b]) {
+                set_err(h, "%s: sequence %d holds %d tokens, %d positions reserved", who, b, hl[b], h->cap[b]);
+                return RL_GEN_E_CAPACITY;
+            }
+        h->host_len.swap(hl);
+        h->host_done.assign((size_t)B, 0);
+    }
     float *lg = logits ? logits : h->logits_ws();
     int32_t *nx = next ? next : h->next_ws();
     {
@@ -544,7 +700,7 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
     if (per_chunk < 1) per_chunk = 1;
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
         int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
-        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
+        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st, lens ? h->d_lens() : nullptr);
         if (lens) {
             // ragged prompts: the row that feeds the LM head is each sequence's own last position; the attention
             // output area is idle by now and takes the gathered rows
@@ -591,6 +747,16 @@ int rl_gen_read_state(rl_gen_t *h, int32_t *lens, int32_t *done, void *hip_strea
     if (!h) return RL_GEN_E_NULL;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     if (h->B <= 0) return RL_GEN_OK;
+    if (h->page_shift) {  // the host-side bounds become exact: ended sequences stop counting against their pages
+        h->host_len.resize((size_t)h->B);
+        h->host_done.resize((size_t)h->B);
+        if (hipMemcpyAsync(h->host_len.data(), h->d_lens(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipMemcpyAsync(h->host_done.data(), h->d_done(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) { set_err(h, "rl_gen_read_state: stream error"); return RL_GEN_E_HIP; }
+        if (lens) memcpy(lens, h->host_len.data(), (size_t)h->B * 4);
+        if (done) memcpy(done, h->host_done.data(), (size_t)h->B * 4);
+        return RL_GEN_OK;
+    }
     if (lens && hipMemcpyAsync(lens, h->d_lens(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return RL_GEN_E_HIP;
     if (done && hipMemcpyAsync(done, h->d_done(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return RL_GEN_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) { set_err(h, "rl_gen_read_state: stream error"); return RL_GEN_E_HIP; }
@@ -607,6 +773,7 @@ int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, fl
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const rl_gen_shape &s = h->s;
+    if (int rcp = check_reserved(h, "rl_gen_logprobs", B, T)) return rcp;
     int per_chunk = h->wp.rows / T;
     if (per_chunk < 1) per_chunk = 1;
     // logits of a block of rows live in the split-K partial area, which is idle once the layers are done
@@ -640,6 +807,7 @@ int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, fl
     int rc = check_hip(h, "rl_gen_logprobs");
     if (rc != RL_GEN_OK) return rc;
     h->B = B; h->len = T;
+    if (h->page_shift) { h->host_len.assign((size_t)B, T); h->host_done.assign((size_t)B, 0); }
     return RL_GEN_OK;
 }
 
@@ -652,6 +820,7 @@ int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, cons
         return RL_GEN_E_CAPACITY;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    if (int rcp = check_reserved(h, "rl_gen_values", B, T)) return rcp;
     int per_chunk = h->wp.rows / T;
     if (per_chunk < 1) per_chunk = 1;
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
@@ -667,6 +836,7 @@ int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, cons
     int rc = check_hip(h, "rl_gen_values");
     if (rc != RL_GEN_OK) return rc;
     h->B = B; h->len = T;
+    if (h->page_shift) { h->host_len.assign((size_t)B, T); h->host_done.assign((size_t)B, 0); }
     return RL_GEN_OK;
 }
 
@@ -675,6 +845,15 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
     if (!tokens) { set_err(h, "rl_gen_decode_step: NULL tokens"); return RL_GEN_E_NULL; }
     if (h->B <= 0) { set_err(h, "rl_gen_decode_step: no prefill yet"); return RL_GEN_E_STATE; }
     if (h->len + 1 > h->s.max_seq) { set_err(h, "rl_gen_decode_step: sequence capacity %d reached", h->s.max_seq); return RL_GEN_E_CAPACITY; }
+    if (h->page_shift) {
+        // a sequence that has not (to the host's knowledge) ended stores one more row: its pages must hold it
+        for (int b = 0; b < h->B; ++b)
+            if (!h->host_done[b] && h->host_len[b] + 1 > h->cap[b]) {
+                set_err(h, "rl_gen_decode_step: sequence %d may hold %d tokens, %d positions reserved", b, h->host_len[b],
+                        h->cap[b]);
+                return RL_GEN_E_CAPACITY;
+            }
+    }
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     float *lg = logits ? logits : h->logits_ws();
     int32_t *nx = next ? next : h->next_ws();
@@ -714,6 +893,9 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
     int rc = check_hip(h, "rl_gen_decode_step");
     if (rc != RL_GEN_OK) return rc;
     h->len += 1;
+    if (h->page_shift)
+        for (int b = 0; b < h->B; ++b)
+            if (!h->host_done[b]) h->host_len[b] += 1;
     return RL_GEN_OK;
 }
 
@@ -921,6 +1103,21 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
     if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
     launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_decode_attention_paged(const float *q, const uint16_t *k_pool, const uint16_t *v_pool, const int32_t *table,
+                                 int32_t table_stride, int32_t page_size, const int32_t *d_len, int32_t len_stride, uint16_t *out,
+                                 float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
+    if (!q || !k_pool || !v_pool || !table || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
+    if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
+    const int shift = page_shift_of(page_size);
+    if (!shift || (int64_t)table_stride * page_size < S) return RL_GEN_E_SHAPE;
+    KvMap map;
+    map.table = table; map.table_stride = table_stride; map.page_shift = shift;
+    launch_decode_attention(q, k_pool, v_pool, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st),
+                            map);
     RL_OP_RETURN();
 }
 

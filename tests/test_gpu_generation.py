@@ -432,6 +432,167 @@ def test_ragged_prompts_against_the_oracle():
     gen.close()
 
 
+def _shuffled_pages(capacity, page, n_pages, seed):
+    """Page lists that scatter every sequence over the pool (no two runs of positions adjacent on purpose)."""
+    need = [(c + page - 1) // page for c in capacity]
+    perm = [int(v) for v in np.random.default_rng(seed).permutation(n_pages)]
+    rows, at = [], 0
+    for n in need:
+        rows.append(perm[at: at + n])
+        at += n
+    width = max(max(need), 1)
+    return [r + [-1] * (width - len(r)) for r in rows]
+
+
+@pytest.mark.parametrize("graph", [False, True])
+@pytest.mark.parametrize("page", [16, 64])
+def test_paged_cache_equals_contiguous_cache(graph, page):
+    """Ragged prompts over a paged cache whose pool holds just what the sequences need, pages scattered: logits and
+    tokens equal those of the contiguous cache bit for bit (which the ragged test ties to the oracle), and one
+    sequence is also checked against the oracle directly."""
+    from paper_2406_14088_amd import Generator
+    shape = ModelShape(2, 256, 4, 2, 64, 688, 1000)
+    B, T, steps = 5, 40, 6
+    lens = [40, 1, 17, 33, 8]
+    capacity = [n + steps for n in lens]
+    W = make_weights(shape, 43, device="cpu")
+    Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
+    toks = make_prompts(Workload("t", 43, shape, B, T, 0)).to(DEV)
+    d_lens = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    n_pages = sum((c + page - 1) // page for c in capacity)
+
+    def run(gen):
+        gen.set_graph(graph)
+        out = []
+        lg, nx = gen.prefill_ragged(toks, d_lens)
+        out.append((lg.clone(), nx.clone()))
+        for _ in range(steps):
+            lg, nx = gen.decode_step(out[-1][1])
+            out.append((lg.clone(), nx.clone()))
+        torch.cuda.synchronize()
+        return out
+
+    flat = Generator(shape, Wg, B, T + steps)
+    want = run(flat)
+    flat_bytes = flat.kv_arena.numel()
+    flat.close()
+    paged = Generator(shape, Wg, B, T + steps, page_size=page, n_pages=n_pages)
+    assert paged.pool_pages() == n_pages
+    if page == 16:
+        assert paged.kv_arena.numel() < flat_bytes                 # the point of paging: memory follows the real lengths
+    paged.set_block_table(_shuffled_pages(capacity, page, n_pages, 44), capacity)
+    got = run(paged)
+    assert paged.read_state() == ([n + steps for n in lens], [0] * B)
+    for i, ((lw, nw), (lg, ng)) in enumerate(zip(want, got)):
+        assert torch.equal(lg.view(torch.int32), lw.view(torch.int32)), i
+        assert torch.equal(ng, nw), i
+    # sequence 2 alone on the oracle, fed the tokens the batch produced
+    b = 2
+    om = orc.OracleModel(shape, orc.weights_to_numpy(W), 1, T + steps)
+    ol, _ = om.prefill(toks[b: b + 1, : lens[b]].cpu().numpy())
+    worst = np.abs(np64(got[0][0][b]) - ol[0]).max()
+    for i in range(steps):
+        ol, _ = om.decode_step(got[i][1][b: b + 1].cpu().numpy())
+        worst = max(worst, np.abs(np64(got[i + 1][0][b]) - ol[0]).max())
+    om.close()
+    assert worst <= LOGIT_TOL
+    paged.close()
+    # the inference call over a paged cache: every sequence needs T positions for it
+    cap_T = [T] * B
+    pages_T = sum((c + page - 1) // page for c in cap_T)
+    paged = Generator(shape, Wg, B, T + steps, page_size=page, n_pages=pages_T + 2)
+    paged.set_block_table(_shuffled_pages(cap_T, page, pages_T + 2, 45), cap_T)
+    lp = paged.logprobs(toks)
+    flat = Generator(shape, Wg, B, T + steps)
+    lp_want = flat.logprobs(toks)
+    torch.cuda.synchronize()
+    assert torch.equal(lp.view(torch.int32), lp_want.view(torch.int32))
+    flat.close()
+    paged.close()
+
+
+def test_paged_cache_capacity_is_checked_on_the_host():
+    """Nothing is launched that would store a row outside a sequence's pages: the calls fail with E_CAPACITY / E_STATE."""
+    from paper_2406_14088_amd import Generator, RlGenError
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    B, P, page = wl.batch, wl.prompt_len, 16
+    gen = Generator(wl.shape, W, B, wl.max_seq, page_size=page, n_pages=2 * B)
+    with pytest.raises(RlGenError) as e:               # no page lists yet
+        gen.prefill(prompts)
+    assert e.value.code == -4
+    rows = [[2 * b, 2 * b + 1] for b in range(B)]
+    for bad, code in (([[0, 1]] + [[0, 3]] + rows[2:], -2),          # page 0 named twice
+                      ([[0, 2 * B]] + rows[1:], -3),                # outside the pool
+                      ([[0, -1]] + rows[1:], -3)):
+        with pytest.raises(RlGenError) as e:
+            gen.set_block_table(bad, [2 * page] * B)
+        assert e.value.code == code
+    with pytest.raises(RlGenError) as e:               # more positions than the rows of the table can name
+        gen.set_block_table(rows, [2 * page + 1] * B)
+    assert e.value.code in (-2, -3)
+    gen.set_block_table(rows, [P - 1] + [2 * page] * (B - 1))
+    with pytest.raises(RlGenError) as e:               # sequence 0 cannot hold its prompt
+        gen.prefill(prompts)
+    assert e.value.code == -3
+    cap = [P + 2] + [2 * page] * (B - 1)
+    gen.set_block_table(rows, cap)
+    _, t = gen.prefill(prompts)
+    _, t = gen.decode_step(t)
+    _, t = gen.decode_step(t)
+    with pytest.raises(RlGenError) as e:               # a third appended row would not fit sequence 0
+        gen.decode_step(t)
+    assert e.value.code == -3
+    assert gen.read_state()[0] == [P + 2] * B
+    gen.set_block_table(rows, [2 * page] * B)           # more room for sequence 0 in the page it already has: goes on
+    gen.decode_step(t)
+    torch.cuda.synchronize()
+    assert gen.read_state()[0] == [P + 3] * B
+    gen.close()
+
+
+def test_paged_cache_ended_sequence_stops_counting():
+    """Once the host has read the end flags, an ended sequence no longer needs room, and it stores nothing more: the
+    other sequences produce what they produce without an end token."""
+    from paper_2406_14088_amd import Generator, RlGenError
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    B, P, G, page = wl.batch, wl.prompt_len, wl.gen_len, 16
+    flat = Generator(wl.shape, W, B, wl.max_seq)
+    _, t = flat.prefill(prompts)
+    free = [t.clone()]
+    for _ in range(G - 1):
+        free.append(flat.decode_step(free[-1])[1].clone())
+    torch.cuda.synchronize()
+    flat.close()
+    eos = int(free[1][0])                               # sequence 0 ends with the token of its first decode step
+    rows = [[2 * b + 1, 2 * b] for b in range(B)]
+    gen = Generator(wl.shape, W, B, wl.max_seq, page_size=page, n_pages=2 * B)
+    cap = [P + 1] + [2 * page] * (B - 1)               # sequence 0 has room for exactly the one row it stores before ending
+    gen.set_block_table(rows, cap)
+    gen.set_eos(eos)
+    _, t = gen.prefill(prompts)
+    if int(t[0]) == eos:
+        pytest.skip("the first token already is the end token")
+    _, t = gen.decode_step(t)                           # stores row P of sequence 0 and returns eos for it
+    with pytest.raises(RlGenError):                     # the host does not know yet that sequence 0 has ended
+        gen.decode_step(t)
+    lens, done = gen.read_state()
+    assert done[0] == 1 and lens[0] == P + 1
+    out = [None, t.clone()]
+    for _ in range(G - 2):
+        out.append(gen.decode_step(out[-1])[1].clone())
+    torch.cuda.synchronize()
+    for k in range(1, G):
+        assert int(out[k][0]) == eos
+        for b in range(1, B):
+            if not any(int(free[j][b]) == eos for j in range(k + 1)):
+                assert int(out[k][b]) == int(free[k][b]), (k, b)
+    gen.close()
+
+
 @pytest.mark.parametrize("graph", [False, True])
 def test_end_token_stops_a_sequence(graph):
     """With an end token set, a sequence that produces it keeps returning it, stops growing and leaves the others alone."""

@@ -505,3 +505,58 @@ def test_per_sequence_lengths_in_rope_append_and_attention(ops, hd, Hq, Hkv, nsp
         for u in range(Hq):
             ref = orc.attend(q[u], kn[b, u // g, : n + 1], vn[b, u // g, : n + 1])
             assert (np.abs(on[b, u] - ref) <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 3e-5).all(), (b, u)
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv,nsplit,page", [(128, 4, 4, 1, 16), (128, 8, 2, 3, 64), (64, 4, 2, 2, 32), (128, 16, 2, 1, 128)])
+def test_paged_decode_attention_equals_contiguous(ops, hd, Hq, Hkv, nsplit, page):
+    """A paged cache is a layout, not another computation: the same rows reached through shuffled page lists give
+    the same output bit for bit (and, by the contiguous kernel's own test, the oracle's attention)."""
+    B, S = 5, 320
+    lens = [0, 15, 16, 200, 319]                      # positions of the newest row: page borders, one row, the whole cache
+    kc, vc = randn_f16((B, Hkv, S, hd), 201), randn_f16((B, Hkv, S, hd), 202)
+    q = randn_f32((B, Hq * hd), 203, std=0.7)
+    d_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    pps = (S + page - 1) // page
+    n_pages = B * pps + 3
+    rng = np.random.default_rng(204)
+    perm = rng.permutation(n_pages)[: B * pps].reshape(B, pps)
+    k_pool = torch.full((n_pages, Hkv, page, hd), float("nan"), dtype=torch.float16, device=DEV)
+    v_pool = torch.full((n_pages, Hkv, page, hd), float("nan"), dtype=torch.float16, device=DEV)
+    for b in range(B):
+        for i in range(pps):
+            lo, hi = i * page, min((i + 1) * page, S)
+            if lo > lens[b]:
+                continue                              # pages a sequence has not reached stay NaN: they must not be read
+            k_pool[perm[b, i], :, : hi - lo] = kc[b, :, lo:hi]
+            v_pool[perm[b, i], :, : hi - lo] = vc[b, :, lo:hi]
+    for b, n in enumerate(lens):                      # and inside the last page nothing beyond the newest row
+        i, r = n // page, n % page
+        k_pool[perm[b, i], :, r + 1:] = float("nan")
+        v_pool[perm[b, i], :, r + 1:] = float("nan")
+    table = torch.tensor(perm, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ref = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, ref, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=1)
+    got = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ops.decode_attention_paged(q, k_pool, v_pool, table, page, d_len, got, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=1)
+    torch.cuda.synchronize()
+    assert not torch.isnan(got).any()
+    assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+    # one sequence against the oracle directly
+    b, g = 3, Hq // Hkv
+    kn, vn, on = np64(kc), np64(vc), np64(got).reshape(B, Hq, hd)
+    for u in range(Hq):
+        want = orc.attend(np64(q).reshape(B, Hq, hd)[b, u], kn[b, u // g, : lens[b] + 1], vn[b, u // g, : lens[b] + 1])
+        assert (np.abs(on[b, u] - want) <= 0.5 * F16_EPS * np.abs(want) * 1.02 + 3e-5).all()
+
+
+def test_paged_decode_attention_rejects_bad_page_sizes(ops):
+    t = torch.zeros((1, 64), dtype=torch.int32, device=DEV)
+    x = torch.zeros((4096,), dtype=torch.float16, device=DEV)
+    qf = torch.zeros((128,), dtype=torch.float32, device=DEV)
+    from paper_2406_14088_amd import RlGenError
+    for page in (0, 8, 24, 8192):
+        with pytest.raises(RlGenError):
+            ops.decode_attention_paged(qf, x, x, t, page, t, x, None, 1, 1, 1, 128, 16, 1)
+    with pytest.raises(RlGenError):                   # the page lists must cover S positions
+        ops.decode_attention_paged(qf, x, x, t, 16, t, x, None, 1, 1, 1, 128, 16 * 64 + 1, 1)

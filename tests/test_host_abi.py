@@ -81,3 +81,30 @@ def test_null_arguments_are_rejected_without_a_gpu(binding):
     assert L.rl_op_gemm(None, None, 8, None, None, None, 1, 0, 0, 1, 8, None, 1, 0, 1, 0, 0, None) == -1
     assert L.rl_gen_kernel_class_name(4) == b"decode_attention"
     assert len(binding.KERNEL_CLASSES) == 13
+
+
+def test_page_bytes_and_page_planning_on_the_host(binding):
+    s = PRESETS["llama7b"].shape
+    assert binding.page_bytes(s, 16) == 16 * 524288                 # a page of 16 positions: 16 x the per-token bytes
+    assert binding.page_bytes(s, 64) * 6 == binding.kv_bytes(s, 1, 384)
+    for bad in (0, 8, 24, 100, 8192, -16):
+        assert binding.page_bytes(s, bad) == 0
+    # consecutive pages, ceil(capacity / page) per sequence, -1 in the unused entries
+    used, table = binding.plan_pages([33, 0, 16, 1], 16, 10, 4)
+    assert used == 5
+    assert table == [[0, 1, 2, -1], [-1, -1, -1, -1], [3, -1, -1, -1], [4, -1, -1, -1]]
+    assert binding.plan_pages([], 16, 0, 4) == (0, [])
+    from paper_2406_14088_amd import RlGenError
+    for cap, n_pages, pps, code in (([33, 16], 3, 4, -3),           # the pool is one page short
+                                    ([65], 10, 4, -3),              # more pages than a row of the table holds
+                                    ([-1], 10, 4, -2)):
+        with pytest.raises(RlGenError) as e:
+            binding.plan_pages(cap, 16, n_pages, pps)
+        assert e.value.code == code
+    L = binding.lib()
+    assert L.rl_gen_plan_pages(None, 1, 16, 1, 1, None) == -1
+    assert L.rl_gen_set_block_table(None, None, None, 1, 1, None) == -1
+    assert L.rl_gen_pool_pages(None) == -1
+    cs = binding.RlGenShape.from_model(PRESETS["tiny"].shape, 4, 32)
+    out = C.c_void_p()
+    assert L.rl_gen_create_paged(C.byref(cs), None, None, 0, None, 0, 16, C.byref(out)) == -1
