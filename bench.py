@@ -8,7 +8,7 @@ token feedback.  Prints ONE JSON line: `value` = generated tokens/s of the whole
 kernel (decode attention) timed with HIP events on the launch stream against its algorithmic bytes, `cpu_baseline` = the CPU
 oracle timed on a bounded sample of the same model.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--no-cpu-baseline] [--no-roofline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--no-cpu-baseline] [--no-roofline] [--mbs N]
 """
 from __future__ import annotations
 
@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--call", default="generation", choices=["generation", "logprobs"],
                     help="generation (the benchmark) or the inference call that scores every token of [B, P+G] sequences")
+    ap.add_argument("--mbs", type=int, default=1,
+                    help="generation only: run the batch as this many sequential portions through rl_gen_generate on a "
+                         "generator (and KV cache) of batch/mbs sequences; not the headline configuration")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (copy_kernel: a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -85,10 +88,18 @@ def main():
     t0 = time.perf_counter()
     W = make_weights(shape, wl.index, device=dev)
     prompts = make_prompts(wl, device=dev)
-    gen = Generator(shape, W, B, P + G)
+    if args.mbs < 1 or B % args.mbs:
+        print(f"bench.py: --mbs must divide the batch ({B})", file=sys.stderr)
+        sys.exit(2)
+    gen = Generator(shape, W, B // args.mbs, P + G)
     gen.set_graph(not args.no_graph)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
+
+    if args.mbs > 1 and args.call == "generation":
+        print(json.dumps(bench_portions(args, gen, wl, shape, prompts, setup_s)))
+        gen.close()
+        return
 
     if args.call == "logprobs":
         print(json.dumps(bench_logprobs(args, gen, wl, shape, dev, setup_s)))
@@ -205,6 +216,37 @@ def main():
     out["checksum_last_tokens"] = int(last_tokens.to(torch.int64).sum().item())
     gen.close()
     print(json.dumps(out))
+
+
+def bench_portions(args, gen, wl, shape, prompts, setup_s):
+    """The same generation through the single call rl_gen_generate, the batch cut into --mbs sequential portions (the
+    KV cache holds one portion): what the smaller cache costs in throughput, since every portion streams all weights
+    again at every decode step."""
+    import torch
+    B, P, G = wl.batch, wl.prompt_len, wl.gen_len
+    out_tokens = torch.empty((B, G), dtype=torch.int32, device=prompts.device)
+
+    def generate():
+        gen.pack_weights()
+        gen.generate(prompts, G, out=out_tokens)
+
+    for _ in range(args.warmup):
+        generate()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        generate()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    return {"metric": f"generated tokens/sec on 1 GPU, {wl.name}, batch in {args.mbs} sequential portions",
+            "value": B * G * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
+            "config": {"workload": f"{wl.name}: L{shape.n_layers} d{shape.hidden} H{shape.n_heads}/{shape.n_kv_heads} F{shape.ffn} "
+                                   f"V{shape.vocab}, batch {B} as {args.mbs} portions of {B // args.mbs}, prompt {P}, generate {G}",
+                       "global_batch": B, "prompt_len": P, "gen_len": G, "mbs": args.mbs, "hip_graph": not args.no_graph},
+            "kv_cache_bytes": gen.kv_arena.numel(), "setup_s": setup_s,
+            "checksum_last_tokens": int(out_tokens[:, G - 1].to(torch.int64).sum().item())}
 
 
 def bench_logprobs(args, gen, wl, shape, dev, setup_s):

@@ -172,6 +172,19 @@ int rl_gen_read_state(rl_gen_t *h, int32_t *lens, int32_t *done, void *hip_strea
  * would exceed max_seq, RL_GEN_E_STATE before a prefill. */
 int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_t *next, void *hip_stream);
 
+/* The whole generation call (Section 2.1: prefill, then decode steps that feed each sequence its own latest token),
+ * with the batch cut into sequential portions when it is larger than the generator (Section 4: a call may process its
+ * data in several sequential micro-batches so that its active memory -- here the KV cache -- fits the device).
+ * prompts: DEVICE int32 [B, P].  out: DEVICE int32 [B, G], row b = the G tokens generated for sequence b (the first by
+ * the prefill, the others by G-1 decode steps; after an end token the row repeats it).  Sequences b0 .. b0+max_batch-1
+ * form a portion; each portion runs prefill and all its decode steps before the next one starts, in the same cache.
+ * u: DEVICE fp32 [G, B] uniform draws in [0, 1), entry (g, b) chooses token g of sequence b -- required while sampling
+ * is on (rl_gen_set_sampling with a positive temperature; that call's own draw buffer is not used here), ignored
+ * otherwise.  Needs P + G - 1 <= max_seq (on a paged generator: that many positions reserved for each of the first
+ * min(B, max_batch) sequences).  Everything is enqueued on hip_stream; afterwards the state is that of the last portion. */
+int rl_gen_generate(rl_gen_t *h, const int32_t *prompts, int32_t B, int32_t P, int32_t G, const float *u, int32_t *out,
+                    void *hip_stream);
+
 /* Inference call (Section 2.1: one forward pass over prompt + response that scores every generated token; the
  * next call after generation in the RLHF dataflow).  tokens: DEVICE int32 [B, T] row-major.  logp: DEVICE fp32
  * [B, T]: logp[b, i] = log softmax(logits of position i)[tokens[b, i+1]] for i < T-1 -- the log-probability the

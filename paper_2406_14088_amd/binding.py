@@ -73,6 +73,7 @@ def lib():
         "rl_gen_set_eos": (C.c_int, [vp, i32]),
         "rl_gen_read_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
+        "rl_gen_generate": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
         "rl_gen_logprobs": (C.c_int, [vp, vp, i32, i32, vp, vp]),
         "rl_gen_values": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_set_graph": (C.c_int, [vp, i32]),
@@ -115,7 +116,7 @@ def lib():
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes",
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
-    "rl_gen_decode_step", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
+    "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
@@ -316,6 +317,19 @@ class Generator:
         self._check(lib().rl_gen_decode_step(self._h, tokens.data_ptr(), _ptr(logits), _ptr(next_tokens), _stream()),
                     "rl_gen_decode_step")
         return logits, next_tokens
+
+    def generate(self, prompts, G: int, u=None, out=None):
+        """prompts: int32 GPU tensor [B, P] (B may exceed max_batch: sequential portions).  Returns int32 [B, G]."""
+        import torch
+        B, P = prompts.shape
+        assert prompts.dtype == torch.int32 and prompts.is_cuda and prompts.is_contiguous()
+        if u is not None:
+            assert u.dtype == torch.float32 and u.is_cuda and u.is_contiguous() and tuple(u.shape) == (G, B)
+        if out is None:
+            out = torch.empty((B, G), dtype=torch.int32, device=prompts.device)
+        self._check(lib().rl_gen_generate(self._h, prompts.data_ptr(), B, P, int(G), _ptr(u), out.data_ptr(), _stream()),
+                    "rl_gen_generate")
+        return out
 
     def logprobs(self, tokens, logp=None):
         """tokens: int32 GPU tensor [B, T].  Returns fp32 [B, T]: log-probability of token i+1 at position i (last column 0)."""

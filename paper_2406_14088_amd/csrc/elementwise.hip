@@ -399,6 +399,18 @@ void launch_sample(const float *logits, int B, int V, float temperature, const f
     sample_kernel<<<B, SP_THREADS, 0, st>>>(logits, V, 1.0f / temperature, u, next, lens, done, eos);
 }
 
+// dst[i * dst_stride] = src[i * src_stride] for i < n (32-bit words of any type)
+__global__ void copy_strided_kernel(const uint32_t *__restrict__ src, int64_t src_stride, uint32_t *__restrict__ dst,
+                                    int64_t dst_stride, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[(size_t)i * dst_stride] = src[(size_t)i * src_stride];
+}
+void launch_copy_strided(const void *src, int64_t src_stride, void *dst, int64_t dst_stride, int n, hipStream_t st) {
+    if (n <= 0) return;
+    copy_strided_kernel<<<ceil_div(n, 256), 256, 0, st>>>(reinterpret_cast<const uint32_t *>(src), src_stride,
+                                                          reinterpret_cast<uint32_t *>(dst), dst_stride, n);
+}
+
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st) { set_i32_kernel<<<1, 1, 0, st>>>(p, v); }
 

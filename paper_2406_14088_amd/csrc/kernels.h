@@ -32,6 +32,8 @@ void launch_gather_last_rows(const f16_t *h, const int32_t *lens, int b0, int nb
 void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *lens,
                    int32_t *done, int eos, hipStream_t st);
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
+// dst[i * dst_stride] = src[i * src_stride] for i < n; 32-bit elements of any type, strides in elements
+void launch_copy_strided(const void *src, int64_t src_stride, void *dst, int64_t dst_stride, int n, hipStream_t st);
 // out[m] = sum_k h[m, k] * w[k]   (h half [M, d]; w bf16 or fp32 [d]; fp32 accumulation)
 void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st);
 // Rows m_first .. m_first + M - 1 of a [n_seq * T] token grid: out[g] = log softmax(logits[g - m_first, :])[tokens[g + 1]],

@@ -25,7 +25,7 @@ constexpr int kMinPage = 16, kMaxPage = 4096;  // positions per page of a paged 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct WorkPlan {
-    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, rope, state, table, total;
+    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, draws, rope, state, table, total;
     size_t part_elems;  // floats in the split-K partial area
     int rows;  // activation rows the workspace can hold
 };
@@ -86,6 +86,7 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.attn_ws = take(decode_attention_ws_floats(s->max_batch, s->n_heads, s->head_dim, attn_splits(s)) * 4 + 16);
     p.logits = take((size_t)s->max_batch * s->vocab * 4);
     p.next = take((size_t)s->max_batch * 4);
+    p.draws = take((size_t)s->max_batch * 4);  // uniform draws of the current step of rl_gen_generate
     p.rope = take((size_t)s->max_seq * s->head_dim * 4);
     p.state = take(((size_t)2 * s->max_batch + 16) * 4);  // per-sequence lengths, per-sequence end flags, a constant 0
     p.table = take((size_t)s->max_batch * ceil_div(s->max_seq, kMinPage) * 4);  // page lists of a paged cache
@@ -151,6 +152,7 @@ struct rl_gen {
     float *attn_ws() const { return reinterpret_cast<float *>(work + wp.attn_ws); }
     float *logits_ws() const { return reinterpret_cast<float *>(work + wp.logits); }
     int32_t *next_ws() const { return reinterpret_cast<int32_t *>(work + wp.next); }
+    float *draws_ws() const { return reinterpret_cast<float *>(work + wp.draws); }
     float *rope() const { return reinterpret_cast<float *>(work + wp.rope); }
     // device-side sequence state: tokens held per sequence, whether it has produced the end token, and a constant 0
     int32_t *d_lens() const { return reinterpret_cast<int32_t *>(work + wp.state); }
@@ -897,6 +899,38 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
         for (int b = 0; b < h->B; ++b)
             if (!h->host_done[b]) h->host_len[b] += 1;
     return RL_GEN_OK;
+}
+
+int rl_gen_generate(rl_gen_t *h, const int32_t *prompts, int32_t B, int32_t P, int32_t G, const float *u, int32_t *out,
+                    void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!prompts || !out) { set_err(h, "rl_gen_generate: NULL argument"); return RL_GEN_E_NULL; }
+    if (B <= 0 || P <= 0 || G <= 0) { set_err(h, "rl_gen_generate: B, P and G must be positive"); return RL_GEN_E_SHAPE; }
+    if ((int64_t)P + G - 1 > h->s.max_seq) {
+        set_err(h, "rl_gen_generate: P + G - 1 = %lld positions exceed capacity %d", (long long)P + G - 1, h->s.max_seq);
+        return RL_GEN_E_CAPACITY;
+    }
+    const bool sampling = h->temperature > 0.f;
+    if (sampling && !u) { set_err(h, "rl_gen_generate: sampling is on and no draws were given"); return RL_GEN_E_NULL; }
+    const int portion = h->s.max_batch;
+    if (int rcp = check_reserved(h, "rl_gen_generate", B < portion ? B : portion, P + G - 1)) return rcp;
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    // the token-choice kernel of every step reads its draws from one fixed place, so captured steps stay valid
+    const float *caller_u = h->sample_u;
+    if (sampling && caller_u != h->draws_ws()) { drop_graphs(h); h->sample_u = h->draws_ws(); }
+    int rc = RL_GEN_OK;
+    for (int b0 = 0; b0 < B && rc == RL_GEN_OK; b0 += portion) {
+        const int nb = B - b0 < portion ? B - b0 : portion;
+        for (int g = 0; g < G && rc == RL_GEN_OK; ++g) {
+            if (sampling) launch_copy_strided(u + (size_t)g * B + b0, 1, h->draws_ws(), 1, nb, st);
+            if (g == 0) rc = prefill_impl(h, "rl_gen_generate", prompts + (size_t)b0 * P, nullptr, nb, P, nullptr, h->next_ws(), hip_stream);
+            else rc = rl_gen_decode_step(h, h->next_ws(), nullptr, h->next_ws(), hip_stream);
+            if (rc == RL_GEN_OK) launch_copy_strided(h->next_ws(), 1, out + (size_t)b0 * G + g, G, nb, st);
+        }
+    }
+    if (sampling && caller_u != h->draws_ws()) { drop_graphs(h); h->sample_u = caller_u; }
+    if (rc != RL_GEN_OK) return rc;
+    return check_hip(h, "rl_gen_generate");
 }
 
 int rl_gen_set_graph(rl_gen_t *h, int32_t enabled) {

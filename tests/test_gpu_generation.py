@@ -593,6 +593,72 @@ def test_paged_cache_ended_sequence_stops_counting():
     gen.close()
 
 
+@pytest.mark.parametrize("sampling", [False, True])
+def test_generate_call_runs_the_batch_in_portions(sampling):
+    """rl_gen_generate on a generator smaller than the batch: portions of max_batch sequences, each prefilled and decoded
+    to the end before the next.  Equal, token for token, to the step calls run portion by portion; and every greedy token
+    is a best token of the oracle's own logits (teacher-forced on what the GPU generated) within the logit tolerance."""
+    from paper_2406_14088_amd import Generator
+    shape = ModelShape(2, 256, 4, 2, 64, 688, 1000)
+    B, P, G, portion = 10, 12, 8, 4
+    W = make_weights(shape, 47, device="cpu")
+    Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
+    prompts = make_prompts(Workload("t", 47, shape, B, P, 0)).to(DEV)
+    gen = Generator(shape, Wg, portion, P + G - 1)
+    u = None
+    if sampling:
+        u = torch.rand((G, B), generator=torch.Generator().manual_seed(48)).to(DEV)
+        ubuf = torch.zeros((portion,), dtype=torch.float32, device=DEV)
+        gen.set_sampling(0.9, ubuf)
+    out = gen.generate(prompts, G, u)
+    again = gen.generate(prompts, G, u)                     # second call: the decode steps are replayed from the captured graph
+    torch.cuda.synchronize()
+    assert out.shape == (B, G) and torch.equal(out, again)
+    for b0 in range(0, B, portion):
+        nb = min(portion, B - b0)
+        if sampling:
+            ubuf[:nb] = u[0, b0: b0 + nb]
+        _, t = gen.prefill(prompts[b0: b0 + nb].contiguous())
+        assert torch.equal(t, out[b0: b0 + nb, 0])
+        for g in range(1, G):
+            if sampling:
+                ubuf[:nb] = u[g, b0: b0 + nb]
+            _, t = gen.decode_step(t)
+            assert torch.equal(t, out[b0: b0 + nb, g]), (b0, g)
+    gen.close()
+    if sampling:
+        return                                              # the sampled choice itself is tied to the oracle by the step-call tests
+    om = orc.OracleModel(shape, orc.weights_to_numpy(W), B, P + G)
+    toks = out.cpu().numpy()
+    ol, _ = om.prefill(prompts.cpu().numpy())
+    for g in range(G):
+        for b in range(B):
+            assert ol[b, toks[b, g]] >= ol[b].max() - 2 * LOGIT_TOL, (b, g)
+        if g + 1 < G:
+            ol, _ = om.decode_step(toks[:, g].copy())
+    om.close()
+
+
+def test_generate_call_argument_errors():
+    from paper_2406_14088_amd import Generator, RlGenError
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)
+    gen = Generator(wl.shape, W, 2, wl.prompt_len + 3)
+    with pytest.raises(RlGenError) as e:                    # prompt + 5 generated tokens store 4 rows too many... one too many
+        gen.generate(prompts, 5)
+    assert e.value.code == -3
+    gen.set_sampling(1.0, torch.zeros((2,), dtype=torch.float32, device=DEV))
+    with pytest.raises(RlGenError) as e:                    # sampling without draws
+        gen.generate(prompts, 2)
+    assert e.value.code == -1
+    gen.set_sampling(0.0)
+    out = gen.generate(prompts, 4)                          # exactly fills the cache
+    torch.cuda.synchronize()
+    assert out.shape == (wl.batch, 4) and int(out.min()) >= 0
+    gen.close()
+
+
 @pytest.mark.parametrize("graph", [False, True])
 def test_end_token_stops_a_sequence(graph):
     """With an end token set, a sequence that produces it keeps returning it, stops growing and leaves the others alone."""
