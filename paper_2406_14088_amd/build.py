@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librl_gen.so")
-SOURCES = ("elementwise.hip", "gemm_skinny.hip", "gemm_tiled.hip", "gemm_packed.hip", "attention_decode.hip", "attention_prefill.hip",
+SOURCES = ("elementwise.hip", "gemm_skinny.hip", "gemm_tiled.hip", "gemm_packed.hip", "attention_decode.hip", "attention_decode_gqa.hip", "attention_prefill.hip",
            "rl_gen.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -356,6 +356,10 @@ static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_l
 
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map) {
+    if (decode_attention_gqa_supported(Hq, Hkv, hd)) {  // many query heads per cache row: the matrix-core kernel
+        launch_decode_attention_gqa(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, st, map);
+        return;
+    }
     dispatch_da(q, const_cast<f16_t *>(kc), const_cast<f16_t *>(vc), d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, nullptr,
                 map, st);
 }

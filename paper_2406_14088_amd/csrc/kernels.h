@@ -113,6 +113,13 @@ void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, c
 void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
                                    f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B, int Hq,
                                    int Hkv, int hd, int S, int nsplit, hipStream_t st);
+// ---- attention_decode_gqa.hip: the same operation on the matrix cores for grouped-query shapes (head_dim 128 and 4, 8, 16,
+// ... query heads per kv head); launch_decode_attention forwards to it when decode_attention_gqa_supported().
+bool decode_attention_gqa_supported(int Hq, int Hkv, int hd);
+int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S);
+void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride,
+                                 f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st,
+                                 KvMap map = KvMap());
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);

@@ -132,6 +132,14 @@ def test_width_of_the_papers_llama3_7b_row_reduced_depth():
     check(s, 6, 3, 20, 3)
 
 
+def test_width_of_the_papers_llama3_34b_row_reduced_depth():
+    """34B row of the same table: hidden 8192, 64/8 heads, FFN 22016 (= 2^9 * 43), vocabulary 128256."""
+    from workload.configs import LLAMA3_TABLE_SHAPES
+    s = LLAMA3_TABLE_SHAPES["34B"].with_layers(1)
+    step("LLaMA-3 34B row width (hidden 8192, 64/8 heads, FFN 22016, vocab 128256), 1 layer")
+    check(s, 7, 2, 12, 3)
+
+
 @pytest.mark.parametrize("case", ["tiny", "7b_width", "chunked_head"])
 def test_inference_call_logprobs(case):
     """rl_gen_logprobs: one forward pass over whole sequences, log-probability of every following token.

@@ -560,3 +560,29 @@ def test_paged_decode_attention_rejects_bad_page_sizes(ops):
             ops.decode_attention_paged(qf, x, x, t, page, t, x, None, 1, 1, 1, 128, 16, 1)
     with pytest.raises(RlGenError):                   # the page lists must cover S positions
         ops.decode_attention_paged(qf, x, x, t, 16, t, x, None, 1, 1, 1, 128, 16 * 64 + 1, 1)
+
+
+@pytest.mark.parametrize("Hq,Hkv,nsplit", [(8, 2, 1), (8, 1, 1), (16, 1, 2), (32, 4, 5)])
+def test_grouped_query_decode_attention_tile_tails(ops, Hq, Hkv, nsplit):
+    """The matrix-core kernel for grouped-query shapes works on tiles of 16 cache rows in a ring of LDS stages: every
+    residue of the visible length modulo the tile, fewer tiles than stages, and splits that receive nothing."""
+    hd, S = 128, 256
+    lens = [0, 1, 14, 15, 16, 17, 30, 31, 32, 33, 46, 47, 48, 49, 63, 64, 65, 100, 127, 128, 129, 200, 254, 255]
+    B = len(lens)
+    q = randn_f32((B, Hq * hd), 301, std=1.2)
+    kc, vc = randn_f16((B, Hkv, S, hd), 302), randn_f16((B, Hkv, S, hd), 303)
+    for b, n in enumerate(lens):
+        kc[b, :, n + 1:] = float("nan")
+        vc[b, :, n + 1:] = float("nan")
+    d_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=1)
+    torch.cuda.synchronize()
+    qn, kn, vn, on = np64(q).reshape(B, Hq, hd), np64(kc), np64(vc), np64(out).reshape(B, Hq, hd)
+    g = Hq // Hkv
+    for b, n in enumerate(lens):
+        for u in range(Hq):
+            ref = orc.attend(qn[b, u], kn[b, u // g, : n + 1], vn[b, u // g, : n + 1])
+            err = np.abs(on[b, u] - ref)
+            assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), (b, n, u, err.max())

@@ -65,6 +65,8 @@ PRESETS = {
     # the paper's own 7B row (grouped-query attention 32/8, vocabulary 128256) at its base context: prompt 1024,
     # 1024 generated tokens (Appendix A); one GPU's share of the batch
     "llama3_7b": Workload("llama3_7b", 6, LLAMA3_TABLE_SHAPES["7B"], 128, 1024, 1024),
+    # the 34B row of the same table at the same context (70.6 GB of weights, 25.8 GB of cache)
+    "llama3_34b": Workload("llama3_34b", 7, LLAMA3_TABLE_SHAPES["34B"], 64, 1024, 1024),
 }
 
 
