@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--call", default="generation", choices=["generation", "logprobs"],
                     help="generation (the benchmark) or the inference call that scores every token of [B, P+G] sequences")
+    ap.add_argument("--pack-gate-up", default="auto", choices=["auto", "on", "off"],
+                    help="fragment-order copies of the gate/up pair too (auto: where the library prefers them and memory allows)")
     ap.add_argument("--mbs", type=int, default=1,
                     help="generation only: run the batch as this many sequential portions through rl_gen_generate on a "
                          "generator (and KV cache) of batch/mbs sequences; not the headline configuration")
@@ -91,7 +93,7 @@ def main():
     if args.mbs < 1 or B % args.mbs:
         print(f"bench.py: --mbs must divide the batch ({B})", file=sys.stderr)
         sys.exit(2)
-    gen = Generator(shape, W, B // args.mbs, P + G)
+    gen = Generator(shape, W, B // args.mbs, P + G, pack_gate_up={"auto": None, "on": True, "off": False}[args.pack_gate_up])
     gen.set_graph(not args.no_graph)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
@@ -188,7 +190,8 @@ def main():
         "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
         "config": {"workload": f"{wl.name}: L{shape.n_layers} d{shape.hidden} H{shape.n_heads}/{shape.n_kv_heads} F{shape.ffn} "
                                f"V{shape.vocab}, batch {B}, prompt {P}, generate {G}",
-                   "global_batch": B, "prompt_len": P, "gen_len": G, "hip_graph": not args.no_graph},
+                   "global_batch": B, "prompt_len": P, "gen_len": G, "hip_graph": not args.no_graph,
+                   "packed_gate_up": gen.pack_gate_up},
         "phases": phases, "setup_s": setup_s,
     }
 

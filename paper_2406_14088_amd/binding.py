@@ -67,6 +67,8 @@ def lib():
         "rl_gen_set_block_table": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), i32, i32, vp]),
         "rl_gen_plan_pages": (i32, [C.POINTER(i32), i32, i32, i32, i32, C.POINTER(i32)]),
         "rl_gen_packed_bytes": (sz, [sp]),
+        "rl_gen_packed_bytes_full": (sz, [sp]),
+        "rl_gen_prefers_packed_gate_up": (C.c_int, [sp]),
         "rl_gen_pack_weights": (C.c_int, [vp, vp, sz, vp]),
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_prefill_ragged": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp]),
@@ -114,7 +116,7 @@ def lib():
 
 
 EXPORTED_SYMBOLS = (
-    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes",
+    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes", "rl_gen_packed_bytes_full", "rl_gen_prefers_packed_gate_up",
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
@@ -176,7 +178,7 @@ class Generator:
     """
 
     def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int, packed: bool = True,
-                 page_size: int = 0, n_pages: int = 0):
+                 page_size: int = 0, n_pages: int = 0, pack_gate_up: Optional[bool] = None):
         import torch
         self._h = None
         any_w = weights["tok_emb"]
@@ -233,6 +235,8 @@ class Generator:
         self._h = h
         self.max_batch, self.max_seq = max_batch, max_seq
         self.packed_arena = None
+        # copies of the gate/up pair too?  None: where the library says its fragment-order kernel is the faster one
+        self.pack_gate_up = bool(L.rl_gen_prefers_packed_gate_up(C.byref(self.cshape)) == 1) if pack_gate_up is None else bool(pack_gate_up)
         if packed:
             self.pack_weights()
 
@@ -241,6 +245,13 @@ class Generator:
         import torch
         if self.packed_arena is None:
             n = lib().rl_gen_packed_bytes(C.byref(self.cshape))
+            if self.pack_gate_up:
+                full = lib().rl_gen_packed_bytes_full(C.byref(self.cshape))
+                free, _ = torch.cuda.mem_get_info(self.kv_arena.device)
+                if full + (8 << 30) <= free:       # the copies are optional: they must leave room for everything else
+                    n = full
+                else:
+                    self.pack_gate_up = False
             self.packed_arena = torch.empty(max(n, 256), dtype=torch.uint8, device=self.kv_arena.device)
         self._check(lib().rl_gen_pack_weights(self._h, self.packed_arena.data_ptr(), self.packed_arena.numel(), _stream()),
                     "rl_gen_pack_weights")

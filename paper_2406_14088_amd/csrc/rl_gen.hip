@@ -120,6 +120,7 @@ struct rl_gen {
     std::vector<const f16_t *> pw[9];
     const f16_t *p_lm_head;
     bool packed;
+    bool packed_gu;  // the gate/up pair has fragment-order copies too (pw[W_GATE], pw[W_UP])
     f16_t *kv;
     unsigned char *work;
     WorkPlan wp;
@@ -257,7 +258,22 @@ int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, 
     return 1;
 }
 
+// Is the fragment-order kernel the faster one for the fused gate/up projection of M rows?  Measured: for M <= 64 by
+// 1.4x (5.3 against 3.5 TB/s at the 34B shape); for 65 .. 128 rows about level at FFN 11008 and ahead at FFN 14336.
+bool packed_swiglu_wins(int M, int ffn) { return M <= 64 || (M <= 128 && ffn >= 14336); }
+
 void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
+    if (h->packed && h->packed_gu && packed_swiglu_wins(M, h->s.ffn)) {
+        PackedGemmArgs q;
+        q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
+        q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
+        q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
+        q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
+        q.nb = 2; q.rows_per_wg = 64; q.depth = 2;
+        Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
+        launch_gemm_packed(q, st);
+        return;
+    }
     GemmArgs a;
     a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
     a.W[0] = h->lw[W_GATE][l]; a.W[1] = h->lw[W_UP][l]; a.W[2] = nullptr;
@@ -419,13 +435,14 @@ size_t rl_gen_work_bytes(const rl_gen_shape *s) {
 
 // packed arena: per layer Wq, Wk, Wv, Wo, down, then the LM head; every matrix 256-byte aligned.  (The gate/up
 // pair stays row-major: its fused SwiGLU projection is as fast from the row-major kernel.)
-constexpr int kPackedPerLayer = 5;
-static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs) {
+constexpr int kPackedPerLayer = 5, kPackedPerLayerFull = 7;
+static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs, bool with_gate_up) {
     const int d = s->hidden, qd = s->n_heads * s->head_dim, kvd = s->n_kv_heads * s->head_dim;
-    const int NK[kPackedPerLayer][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s->ffn}};
+    const int NK[kPackedPerLayerFull][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s->ffn}, {s->ffn, d}, {s->ffn, d}};
+    const int per_layer = with_gate_up ? kPackedPerLayerFull : kPackedPerLayer;
     size_t off = 0;
     for (int l = 0; l < s->n_layers; ++l)
-        for (int m = 0; m < kPackedPerLayer; ++m) {
+        for (int m = 0; m < per_layer; ++m) {
             if (offs) offs->push_back(off);
             off += align_up(packed_weight_bytes(NK[m][0], NK[m][1]));
         }
@@ -436,7 +453,17 @@ static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs) {
 
 size_t rl_gen_packed_bytes(const rl_gen_shape *s) {
     if (validate(s) != RL_GEN_OK) return 0;
-    return packed_plan(s, nullptr);
+    return packed_plan(s, nullptr, false);
+}
+
+size_t rl_gen_packed_bytes_full(const rl_gen_shape *s) {
+    if (validate(s) != RL_GEN_OK) return 0;
+    return packed_plan(s, nullptr, true);
+}
+
+int rl_gen_prefers_packed_gate_up(const rl_gen_shape *s) {
+    if (validate(s) != RL_GEN_OK) return RL_GEN_E_SHAPE;
+    return packed_swiglu_wins(s->max_batch, s->ffn) ? 1 : 0;
 }
 
 int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, void *hip_stream) {
@@ -444,22 +471,26 @@ int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, vo
     drop_graphs(h);  // captured decode steps hold the old weight pointers
     if (!packed_arena) {
         h->packed = false;
+        h->packed_gu = false;
         return RL_GEN_OK;
     }
+    // an arena that also holds the gate/up pair gets it; a smaller one holds the five other matrices per layer
+    const bool with_gu = packed_bytes >= packed_plan(&h->s, nullptr, true);
     std::vector<size_t> offs;
-    size_t need = packed_plan(&h->s, &offs);
+    size_t need = packed_plan(&h->s, &offs, with_gu);
     if (packed_bytes < need) { set_err(h, "rl_gen_pack_weights: arena too small (%zu < %zu)", packed_bytes, need); return RL_GEN_E_CAPACITY; }
     if ((uintptr_t)packed_arena % kAlign) { set_err(h, "rl_gen_pack_weights: arena not 256-byte aligned"); return RL_GEN_E_SHAPE; }
     const rl_gen_shape &s = h->s;
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
-    const int which[kPackedPerLayer] = {W_Q, W_K, W_V, W_O, W_DOWN};
-    const int NK[kPackedPerLayer][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s.ffn}};
+    const int which[kPackedPerLayerFull] = {W_Q, W_K, W_V, W_O, W_DOWN, W_GATE, W_UP};
+    const int NK[kPackedPerLayerFull][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s.ffn}, {s.ffn, d}, {s.ffn, d}};
+    const int per_layer = with_gu ? kPackedPerLayerFull : kPackedPerLayer;
     unsigned char *base = reinterpret_cast<unsigned char *>(packed_arena);
-    for (int m = 0; m < kPackedPerLayer; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
+    for (int m = 0; m < per_layer; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
     size_t i = 0;
     for (int l = 0; l < s.n_layers; ++l)
-        for (int m = 0; m < kPackedPerLayer; ++m, ++i) {
+        for (int m = 0; m < per_layer; ++m, ++i) {
             f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i]);
             launch_pack_weights(h->lw[which[m]][l], dst, NK[m][0], NK[m][1], st);
             h->pw[which[m]][l] = dst;
@@ -470,6 +501,7 @@ int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, vo
     int rc = check_hip(h, "rl_gen_pack_weights");
     if (rc != RL_GEN_OK) return rc;
     h->packed = true;
+    h->packed_gu = with_gu;
     return RL_GEN_OK;
 }
 
@@ -530,7 +562,7 @@ static int create_impl(const rl_gen_shape *shape, const rl_gen_weights *w, void 
     h->nsplit_attn = attn_splits(shape);
     h->B = 0; h->len = 0;
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
-    h->packed = false; h->p_lm_head = nullptr;
+    h->packed = false; h->packed_gu = false; h->p_lm_head = nullptr;
     h->temperature = 0.f; h->sample_u = nullptr; h->eos = -1;
     h->page_shift = page_shift; h->n_pages = 0; h->table_stride = 0; h->table_set = false;
     if (page_shift) {
