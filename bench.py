@@ -191,7 +191,7 @@ def main():
         "config": {"workload": f"{wl.name}: L{shape.n_layers} d{shape.hidden} H{shape.n_heads}/{shape.n_kv_heads} F{shape.ffn} "
                                f"V{shape.vocab}, batch {B}, prompt {P}, generate {G}",
                    "global_batch": B, "prompt_len": P, "gen_len": G, "hip_graph": not args.no_graph,
-                   "packed_gate_up": gen.pack_gate_up},
+                   "packed_gate_up_layers": gen.packed_gate_up_layers()},
         "phases": phases, "setup_s": setup_s,
     }
 

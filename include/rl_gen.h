@@ -100,12 +100,14 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void
  * summation order with and without the copies.  Use the same stream as for the following steps, or
  * synchronise in between. */
 size_t rl_gen_packed_bytes(const rl_gen_shape *shape);
-/* The same plus copies of the gate/up pair of every layer: an arena of at least this size makes rl_gen_pack_weights
- * re-lay those too, and steps of few rows then run the fused gate/up projection from the copies where that is the
- * faster kernel (at most 64 rows, or at most 128 rows with an FFN width from 14336 -- rl_gen_prefers_packed_gate_up
- * returns 1 when that holds for max_batch rows, 0 otherwise).  A smaller arena is used as before. */
+/* The same plus copies of the gate/up pair of every layer.  Whatever an arena holds beyond rl_gen_packed_bytes goes
+ * to gate/up pairs, layer by layer from layer 0 ((full - base) / n_layers bytes each; rl_gen_packed_gate_up_layers tells
+ * how many the last rl_gen_pack_weights re-laid), and steps of few rows then run the fused gate/up projection of those
+ * layers from the copies where that is the faster kernel (at most 64 rows, or at most 128 rows with an FFN width from
+ * 14336 -- rl_gen_prefers_packed_gate_up returns 1 when that holds for max_batch rows, 0 otherwise). */
 size_t rl_gen_packed_bytes_full(const rl_gen_shape *shape);
 int rl_gen_prefers_packed_gate_up(const rl_gen_shape *shape);
+int rl_gen_packed_gate_up_layers(const rl_gen_t *h);
 int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, void *hip_stream);
 
 /* Prefill (Section 2.1: one forward pass that consumes all prompt tokens and yields the first

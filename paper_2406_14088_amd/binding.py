@@ -69,6 +69,7 @@ def lib():
         "rl_gen_packed_bytes": (sz, [sp]),
         "rl_gen_packed_bytes_full": (sz, [sp]),
         "rl_gen_prefers_packed_gate_up": (C.c_int, [sp]),
+        "rl_gen_packed_gate_up_layers": (C.c_int, [vp]),
         "rl_gen_pack_weights": (C.c_int, [vp, vp, sz, vp]),
         "rl_gen_prefill": (C.c_int, [vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_prefill_ragged": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp]),
@@ -116,7 +117,7 @@ def lib():
 
 
 EXPORTED_SYMBOLS = (
-    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes", "rl_gen_packed_bytes_full", "rl_gen_prefers_packed_gate_up",
+    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes", "rl_gen_packed_bytes_full", "rl_gen_prefers_packed_gate_up", "rl_gen_packed_gate_up_layers",
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
@@ -236,6 +237,8 @@ class Generator:
         self.max_batch, self.max_seq = max_batch, max_seq
         self.packed_arena = None
         # copies of the gate/up pair too?  None: where the library says its fragment-order kernel is the faster one
+        # (an int: at most that many layers)
+        self._gate_up_layer_limit = pack_gate_up if isinstance(pack_gate_up, int) and not isinstance(pack_gate_up, bool) else None
         self.pack_gate_up = bool(L.rl_gen_prefers_packed_gate_up(C.byref(self.cshape)) == 1) if pack_gate_up is None else bool(pack_gate_up)
         if packed:
             self.pack_weights()
@@ -245,16 +248,22 @@ class Generator:
         import torch
         if self.packed_arena is None:
             n = lib().rl_gen_packed_bytes(C.byref(self.cshape))
-            if self.pack_gate_up:
+            if self.pack_gate_up and self.shape.n_layers > 0:
+                # the copies are optional: as many layers as fit while leaving room for everything else
                 full = lib().rl_gen_packed_bytes_full(C.byref(self.cshape))
+                pair = (full - n) // self.shape.n_layers
                 free, _ = torch.cuda.mem_get_info(self.kv_arena.device)
-                if full + (8 << 30) <= free:       # the copies are optional: they must leave room for everything else
-                    n = full
-                else:
-                    self.pack_gate_up = False
+                layers = min(self.shape.n_layers, max(0, (free - (8 << 30) - n) // pair))
+                if self._gate_up_layer_limit is not None:
+                    layers = min(layers, self._gate_up_layer_limit)
+                n += layers * pair
+                self.pack_gate_up = layers > 0
             self.packed_arena = torch.empty(max(n, 256), dtype=torch.uint8, device=self.kv_arena.device)
         self._check(lib().rl_gen_pack_weights(self._h, self.packed_arena.data_ptr(), self.packed_arena.numel(), _stream()),
                     "rl_gen_pack_weights")
+
+    def packed_gate_up_layers(self) -> int:
+        return int(lib().rl_gen_packed_gate_up_layers(self._h))
 
     def unpack_weights(self):
         """Back to the row-major weights for every projection."""

@@ -120,7 +120,7 @@ struct rl_gen {
     std::vector<const f16_t *> pw[9];
     const f16_t *p_lm_head;
     bool packed;
-    bool packed_gu;  // the gate/up pair has fragment-order copies too (pw[W_GATE], pw[W_UP])
+    int packed_gu_layers;  // layers 0 .. n-1 have fragment-order copies of the gate/up pair too (pw[W_GATE], pw[W_UP])
     f16_t *kv;
     unsigned char *work;
     WorkPlan wp;
@@ -263,7 +263,7 @@ int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, 
 bool packed_swiglu_wins(int M, int ffn) { return M <= 64 || (M <= 128 && ffn >= 14336); }
 
 void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
-    if (h->packed && h->packed_gu && packed_swiglu_wins(M, h->s.ffn)) {
+    if (h->packed && l < h->packed_gu_layers && packed_swiglu_wins(M, h->s.ffn)) {
         PackedGemmArgs q;
         q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
         q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
@@ -433,32 +433,37 @@ size_t rl_gen_work_bytes(const rl_gen_shape *s) {
     return plan_work(s).total;
 }
 
-// packed arena: per layer Wq, Wk, Wv, Wo, down, then the LM head; every matrix 256-byte aligned.  (The gate/up
-// pair stays row-major: its fused SwiGLU projection is as fast from the row-major kernel.)
-constexpr int kPackedPerLayer = 5, kPackedPerLayerFull = 7;
-static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs, bool with_gate_up) {
+// packed arena: per layer Wq, Wk, Wv, Wo, down; then the LM head; then the gate/up pairs of the first gu_layers layers.
+// Every matrix is 256-byte aligned.
+constexpr int kPackedPerLayer = 5;
+static size_t packed_pair_bytes(const rl_gen_shape *s) { return 2 * align_up(packed_weight_bytes(s->ffn, s->hidden)); }
+static size_t packed_plan(const rl_gen_shape *s, std::vector<size_t> *offs, int gu_layers) {
     const int d = s->hidden, qd = s->n_heads * s->head_dim, kvd = s->n_kv_heads * s->head_dim;
-    const int NK[kPackedPerLayerFull][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s->ffn}, {s->ffn, d}, {s->ffn, d}};
-    const int per_layer = with_gate_up ? kPackedPerLayerFull : kPackedPerLayer;
+    const int NK[kPackedPerLayer][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s->ffn}};
     size_t off = 0;
     for (int l = 0; l < s->n_layers; ++l)
-        for (int m = 0; m < per_layer; ++m) {
+        for (int m = 0; m < kPackedPerLayer; ++m) {
             if (offs) offs->push_back(off);
             off += align_up(packed_weight_bytes(NK[m][0], NK[m][1]));
         }
     if (offs) offs->push_back(off);
     off += align_up(packed_weight_bytes(s->vocab, d));
+    for (int l = 0; l < gu_layers; ++l)
+        for (int m = 0; m < 2; ++m) {
+            if (offs) offs->push_back(off);
+            off += align_up(packed_weight_bytes(s->ffn, d));
+        }
     return off;
 }
 
 size_t rl_gen_packed_bytes(const rl_gen_shape *s) {
     if (validate(s) != RL_GEN_OK) return 0;
-    return packed_plan(s, nullptr, false);
+    return packed_plan(s, nullptr, 0);
 }
 
 size_t rl_gen_packed_bytes_full(const rl_gen_shape *s) {
     if (validate(s) != RL_GEN_OK) return 0;
-    return packed_plan(s, nullptr, true);
+    return packed_plan(s, nullptr, s->n_layers);
 }
 
 int rl_gen_prefers_packed_gate_up(const rl_gen_shape *s) {
@@ -471,39 +476,51 @@ int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, vo
     drop_graphs(h);  // captured decode steps hold the old weight pointers
     if (!packed_arena) {
         h->packed = false;
-        h->packed_gu = false;
+        h->packed_gu_layers = 0;
         return RL_GEN_OK;
     }
-    // an arena that also holds the gate/up pair gets it; a smaller one holds the five other matrices per layer
-    const bool with_gu = packed_bytes >= packed_plan(&h->s, nullptr, true);
-    std::vector<size_t> offs;
-    size_t need = packed_plan(&h->s, &offs, with_gu);
-    if (packed_bytes < need) { set_err(h, "rl_gen_pack_weights: arena too small (%zu < %zu)", packed_bytes, need); return RL_GEN_E_CAPACITY; }
-    if ((uintptr_t)packed_arena % kAlign) { set_err(h, "rl_gen_pack_weights: arena not 256-byte aligned"); return RL_GEN_E_SHAPE; }
     const rl_gen_shape &s = h->s;
+    const size_t base_bytes = packed_plan(&s, nullptr, 0);
+    if (packed_bytes < base_bytes) { set_err(h, "rl_gen_pack_weights: arena too small (%zu < %zu)", packed_bytes, base_bytes); return RL_GEN_E_CAPACITY; }
+    if ((uintptr_t)packed_arena % kAlign) { set_err(h, "rl_gen_pack_weights: arena not 256-byte aligned"); return RL_GEN_E_SHAPE; }
+    // what the arena holds beyond the five matrices per layer and the LM head goes to gate/up pairs, layer by layer
+    const size_t pair = packed_pair_bytes(&s);
+    int gu_layers = pair ? (int)((packed_bytes - base_bytes) / pair < (size_t)s.n_layers ? (packed_bytes - base_bytes) / pair : (size_t)s.n_layers) : 0;
+    std::vector<size_t> offs;
+    packed_plan(&s, &offs, gu_layers);
     hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
     const int d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
-    const int which[kPackedPerLayerFull] = {W_Q, W_K, W_V, W_O, W_DOWN, W_GATE, W_UP};
-    const int NK[kPackedPerLayerFull][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s.ffn}, {s.ffn, d}, {s.ffn, d}};
-    const int per_layer = with_gu ? kPackedPerLayerFull : kPackedPerLayer;
+    const int which[kPackedPerLayer] = {W_Q, W_K, W_V, W_O, W_DOWN};
+    const int NK[kPackedPerLayer][2] = {{qd, d}, {kvd, d}, {kvd, d}, {d, qd}, {d, s.ffn}};
     unsigned char *base = reinterpret_cast<unsigned char *>(packed_arena);
-    for (int m = 0; m < per_layer; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
+    for (int m = 0; m < kPackedPerLayer; ++m) h->pw[which[m]].assign(s.n_layers, nullptr);
+    h->pw[W_GATE].assign(s.n_layers, nullptr);
+    h->pw[W_UP].assign(s.n_layers, nullptr);
     size_t i = 0;
     for (int l = 0; l < s.n_layers; ++l)
-        for (int m = 0; m < per_layer; ++m, ++i) {
+        for (int m = 0; m < kPackedPerLayer; ++m, ++i) {
             f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i]);
             launch_pack_weights(h->lw[which[m]][l], dst, NK[m][0], NK[m][1], st);
             h->pw[which[m]][l] = dst;
         }
-    f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i]);
+    f16_t *dst = reinterpret_cast<f16_t *>(base + offs[i++]);
     launch_pack_weights(h->lm_head, dst, s.vocab, d, st);
     h->p_lm_head = dst;
+    for (int l = 0; l < gu_layers; ++l)
+        for (int m = 0; m < 2; ++m, ++i) {
+            const int w = m == 0 ? W_GATE : W_UP;
+            f16_t *dst2 = reinterpret_cast<f16_t *>(base + offs[i]);
+            launch_pack_weights(h->lw[w][l], dst2, s.ffn, d, st);
+            h->pw[w][l] = dst2;
+        }
     int rc = check_hip(h, "rl_gen_pack_weights");
     if (rc != RL_GEN_OK) return rc;
     h->packed = true;
-    h->packed_gu = with_gu;
+    h->packed_gu_layers = gu_layers;
     return RL_GEN_OK;
 }
+
+int rl_gen_packed_gate_up_layers(const rl_gen_t *h) { return h ? h->packed_gu_layers : RL_GEN_E_NULL; }
 
 size_t rl_gen_page_bytes(const rl_gen_shape *s, int32_t page_size) {
     if (validate(s) != RL_GEN_OK || !page_shift_of(page_size)) return 0;
@@ -562,7 +579,7 @@ static int create_impl(const rl_gen_shape *shape, const rl_gen_weights *w, void 
     h->nsplit_attn = attn_splits(shape);
     h->B = 0; h->len = 0;
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
-    h->packed = false; h->packed_gu = false; h->p_lm_head = nullptr;
+    h->packed = false; h->packed_gu_layers = 0; h->p_lm_head = nullptr;
     h->temperature = 0.f; h->sample_u = nullptr; h->eos = -1;
     h->page_shift = page_shift; h->n_pages = 0; h->table_stride = 0; h->table_set = false;
     if (page_shift) {

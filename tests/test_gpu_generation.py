@@ -91,6 +91,29 @@ def test_gqa_small_model():
     check(s, 12, 5, 21, 6)
 
 
+def test_gate_up_copies_for_some_layers_only():
+    """An arena with room for the gate/up copies of two of three layers: those layers run the fused projection from
+    the copies, the third from the row-major weights; the model as a whole stays within the oracle's tolerance."""
+    from paper_2406_14088_amd import Generator
+    s = ModelShape(3, 512, 8, 2, 64, 1000, 2048)
+    W = make_weights(s, 12, device=DEV)
+    for want, arg in ((2, 2), (3, True), (0, False)):
+        gen = Generator(s, W, 5, 32, pack_gate_up=arg)
+        assert gen.packed_gate_up_layers() == want
+        gen.close()
+    import paper_2406_14088_amd.binding as binding
+    orig = binding.Generator.__init__
+
+    def two_layers(self, *a, **kw):
+        kw["pack_gate_up"] = 2
+        orig(self, *a, **kw)
+    binding.Generator.__init__ = two_layers
+    try:
+        check(s, 12, 5, 21, 6)
+    finally:
+        binding.Generator.__init__ = orig
+
+
 def test_batch_256_and_above_uses_wide_tiles():
     s = ModelShape(1, 256, 4, 4, 64, 688, 1024)
     check(s, 13, 256, 3, 3)
