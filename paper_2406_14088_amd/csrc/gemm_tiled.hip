@@ -11,8 +11,9 @@
 //   * LDS rows padded to 72 elements: ds_read_b128 of MFMA fragments is bank-conflict free;
 //   * workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8)
 //     work on neighbouring tiles and share their operand panels in that XCD's L2;
-//   * fused epilogues: fp32 store, fp32 accumulate (residual add), SwiGLU (wavefront column 0 holds
-//     the gate tile, column 1 the up tile of the same outputs; exchanged through LDS).
+//   * fused epilogues: fp32 store, fp32 accumulate (residual add: read-modify-write of whole rows, 16 bytes per
+//     lane, staged through LDS, all reads of a band requested before its first write), SwiGLU (wavefront column 0
+//     holds the gate tile, column 1 the up tile of the same outputs; exchanged through LDS).
 #include <type_traits>
 
 #include "kernels.h"
@@ -36,7 +37,9 @@ struct TiledParams {
     int64_t ldc;
 };
 
-template <int WM, int WN>
+// EPI (GemmEpilogue) is a template parameter: each epilogue gets a kernel of its own, so that the registers one of them
+// needs after the loop do not change the allocation inside the loop of the others.
+template <int WM, int WN, int EPI>
 __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, HALF_N = WN * 32;
@@ -62,7 +65,7 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 
     // ---- weight rows of each half of the B tile (half h belongs to wavefront column h)
     int seg_h[2], nbase_h[2], ocol_h[2];
-    if (p.epilogue == EPI_SWIGLU) {
+    if (EPI == EPI_SWIGLU) {
         for (int h = 0; h < 2; ++h) { seg_h[h] = h; nbase_h[h] = tile_n * HALF_N; ocol_h[h] = tile_n * HALF_N; }
     } else {
         int seg = tile_n >= p.tile_begin[2] ? 2 : (tile_n >= p.tile_begin[1] ? 1 : 0);
@@ -189,9 +192,12 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     //      (e/4)*8 + (lane>>5)*4 + (e%4).
     const int rows_w = p.rows[seg_h[wn]];
     const int nb = nbase_h[wn], oc = ocol_h[wn];
-    if (p.epilogue != EPI_SWIGLU) {
+    constexpr int CT = WN * 32 + 8;  // floats per row of a 32-row band in LDS (4 rows apart = 32 banks apart: no conflicts)
+    if (EPI == EPI_F32_ACC) __syncthreads();  // every wavefront is done with the operand tiles
+    if (EPI == EPI_F32) {
+        // plain stores: a wavefront store instruction writes two runs of 128 bytes, which the memory system takes as
+        // well as whole rows; no detour through LDS
         float *out = reinterpret_cast<float *>(p.out);
-        const bool accumulate = p.epilogue == EPI_F32_ACC;
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             int n = j * 32 + (lane & 31);
@@ -201,11 +207,49 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     int m = m0 + (wm * WM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                    if (m < p.M) {
-                        float *dst = out + (size_t)m * p.ldc + oc + n;
-                        *dst = accumulate ? *dst + acc[i][j][e] : acc[i][j][e];
-                    }
+                    if (m < p.M) out[(size_t)m * p.ldc + oc + n] = acc[i][j][e];
                 }
+        }
+    } else if (EPI == EPI_F32_ACC) {
+        // read-modify-write of the residual: whole rows, 16 bytes per lane, and all reads of a band are requested
+        // before its first write (the compiler may not move a load of `out` above a store to it)
+        float *out = reinterpret_cast<float *>(p.out);
+        float *ct = reinterpret_cast<float *>(smem) + w * 32 * CT;  // private to the wavefront: no barriers below
+        constexpr int LPR = WN * 8;        // lanes per row (4 floats each)
+        constexpr int RPI = 64 / LPR;      // rows per store instruction
+        constexpr int NK = 32 / RPI;
+        const int c4 = (lane % LPR) * 4, r_in = lane / LPR;
+        const int ncols = rows_w - nb < WN * 32 ? rows_w - nb : WN * 32;
+        const bool vec = c4 + 4 <= ncols && ((p.ldc | oc) & 3) == 0;  // 16-byte aligned whole group
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int mb = m0 + (wm * WM + i) * 32;
+            f32x4_t old[NK];
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                const int m = mb + k * RPI + r_in;
+                old[k] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                if (vec && m < p.M) old[k] = *reinterpret_cast<const f32x4_t *>(out + (size_t)m * p.ldc + oc + c4);
+            }
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    ct[((e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * CT + j * 32 + (lane & 31)] = acc[i][j][e];
+#pragma unroll
+            for (int k = 0; k < NK; ++k) {
+                const int r = k * RPI + r_in, m = mb + r;
+                if (m >= p.M || c4 >= ncols) continue;
+                f32x4_t v = *reinterpret_cast<const f32x4_t *>(ct + r * CT + c4);
+                float *dst = out + (size_t)m * p.ldc + oc + c4;
+                if (vec) {
+                    v.x += old[k].x; v.y += old[k].y; v.z += old[k].z; v.w += old[k].w;
+                    *reinterpret_cast<f32x4_t *>(dst) = v;
+                } else {
+                    float vv[4] = {v.x, v.y, v.z, v.w};
+                    for (int q = 0; q < 4 && c4 + q < ncols; ++q) dst[q] += vv[q];
+                }
+            }
         }
     } else {
         // wavefront column 1 (up) -> LDS -> wavefront column 0 (gate), one 32-column strip at a time
@@ -237,7 +281,7 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     }
 }
 
-template <int WM, int WN>
+template <int WM, int WN, int EPI>
 static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
     constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
     int tiles = 0, col = 0;
@@ -256,13 +300,15 @@ static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
     size_t lds = (size_t)2 * (BM + BN) * TG_LDS_STRIDE * sizeof(f16_t);
     size_t ex = (size_t)2 * WM * 16 * 64 * sizeof(float);
     if (ex > lds) lds = ex;
+    size_t bands = (size_t)4 * 32 * (WN * 32 + 8) * sizeof(float);  // accumulate epilogue: one 32-row band per wavefront
+    if (bands > lds) lds = bands;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tiled_kernel<WM, WN>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tiled_kernel<WM, WN, EPI>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
-    gemm_tiled_kernel<WM, WN><<<p.tiles_m * p.tiles_n, TG_THREADS, lds, st>>>(p);
+    gemm_tiled_kernel<WM, WN, EPI><<<p.tiles_m * p.tiles_n, TG_THREADS, lds, st>>>(p);
 }
 
 static void launch_one(const GemmArgs &a, hipStream_t st) {
@@ -291,8 +337,10 @@ static void launch_one(const GemmArgs &a, hipStream_t st) {
     }
     // big tiles only when they still give every compute unit work
     long big_tiles = (long)ceil_div(a.M, 256) * ceil_div(n_total, 256);
-    if (a.M >= 1024 && big_tiles >= 256) launch_t<4, 4>(p, a, st);
-    else launch_t<2, 2>(p, a, st);
+    const bool big = a.M >= 1024 && big_tiles >= 256;
+    if (a.epilogue == EPI_SWIGLU) { if (big) launch_t<4, 4, EPI_SWIGLU>(p, a, st); else launch_t<2, 2, EPI_SWIGLU>(p, a, st); }
+    else if (a.epilogue == EPI_F32_ACC) { if (big) launch_t<4, 4, EPI_F32_ACC>(p, a, st); else launch_t<2, 2, EPI_F32_ACC>(p, a, st); }
+    else { if (big) launch_t<4, 4, EPI_F32>(p, a, st); else launch_t<2, 2, EPI_F32>(p, a, st); }
 }
 
 // The kernel addresses each operand through a buffer descriptor with 32-bit byte offsets: operands of

@@ -325,7 +325,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_lens() : h->d_zero(),
                                decode ? 1 : 0, h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
                                decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st, map,
-                               d_valid, decode ? h->d_done() : nullptr);
+                               d_valid, decode && h->eos >= 0 ? h->d_done() : nullptr);  // without an end token no sequence ever ends
         }
         // (A single kernel that takes q, k, v from the partials, rotates, appends and attends exists --
         // launch_decode_attention_fused -- but measured no faster per step: what the separate kernel costs, the
