@@ -252,30 +252,47 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
             }
         }
     } else {
-        // wavefront column 1 (up) -> LDS -> wavefront column 0 (gate), one 32-column strip at a time
-        float *ex = reinterpret_cast<float *>(smem);  // [2 (wm)][WM*16][64] floats per strip
+        // wavefront column 1 (up) hands its band to wavefront column 0 (gate) of the same rows through LDS
+        float *ex = reinterpret_cast<float *>(smem) + wm * (WN * 16 * 64);                // [WN][16][64] floats per wavefront row
+        f16_t *ht = reinterpret_cast<f16_t *>(smem + 2 * WN * 16 * 64 * 4) + wm * 32 * (2 * CT);  // [32][2 CT] halves
         f16_t *out = reinterpret_cast<f16_t *>(p.out);
+        constexpr int LPR = WN * 4;        // lanes per row (8 halves each)
+        constexpr int RPI = 64 / LPR;
+        const int c8 = (lane % LPR) * 8, r_in = lane / LPR;
+        const int ncols = rows_w - nb < WN * 32 ? rows_w - nb : WN * 32;
 #pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            __syncthreads();
+        for (int i = 0; i < WM; ++i) {
+            __syncthreads();  // the previous band has been read
             if (wn == 1) {
 #pragma unroll
-                for (int i = 0; i < WM; ++i)
+                for (int j = 0; j < WN; ++j)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) ex[((wm * WM + i) * 16 + e) * 64 + lane] = acc[i][j][e];
+                    for (int e = 0; e < 16; ++e) ex[(j * 16 + e) * 64 + lane] = acc[i][j][e];
             }
             __syncthreads();
-            int n = j * 32 + (lane & 31);
-            if (wn == 0 && nb + n < rows_w) {
+            if (wn == 0) {
 #pragma unroll
-                for (int i = 0; i < WM; ++i)
+                for (int j = 0; j < WN; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        int m = m0 + (wm * WM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                        float g = acc[i][j][e], u = ex[((wm * WM + i) * 16 + e) * 64 + lane];
+                        float g = acc[i][j][e], u = ex[(j * 16 + e) * 64 + lane];
                         float a = g / (1.0f + expf(-g)) * u;
-                        if (m < p.M) out[(size_t)m * p.ldc + oc + n] = f32_to_f16(a);
+                        ht[((e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * (2 * CT) + j * 32 + (lane & 31)] = f32_to_f16(a);
                     }
+                const int mb = m0 + (wm * WM + i) * 32;
+#pragma unroll
+                for (int k = 0; k < 32 / RPI; ++k) {
+                    const int r = k * RPI + r_in, m = mb + r;
+                    if (m >= p.M || c8 >= ncols) continue;
+                    u32x4_t v = *reinterpret_cast<const u32x4_t *>(ht + r * (2 * CT) + c8);
+                    f16_t *dst = out + (size_t)m * p.ldc + oc + c8;
+                    if (c8 + 8 <= ncols && (((size_t)m * p.ldc + oc) & 7) == 0) {
+                        *reinterpret_cast<u32x4_t *>(dst) = v;
+                    } else {
+                        const f16_t *src = ht + r * (2 * CT) + c8;
+                        for (int q = 0; q < 8 && c8 + q < ncols; ++q) dst[q] = src[q];
+                    }
+                }
             }
         }
     }
@@ -302,6 +319,9 @@ static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
     if (ex > lds) lds = ex;
     size_t bands = (size_t)4 * 32 * (WN * 32 + 8) * sizeof(float);  // accumulate epilogue: one 32-row band per wavefront
     if (bands > lds) lds = bands;
+    // SwiGLU epilogue: two exchange areas plus two half bands
+    size_t sw = (size_t)2 * WN * 16 * 64 * sizeof(float) + (size_t)2 * 32 * 2 * (WN * 32 + 8) * sizeof(f16_t);
+    if (sw > lds) lds = sw;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tiled_kernel<WM, WN, EPI>),
