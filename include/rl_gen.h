@@ -103,8 +103,9 @@ size_t rl_gen_packed_bytes(const rl_gen_shape *shape);
 /* The same plus copies of the gate/up pair of every layer.  Whatever an arena holds beyond rl_gen_packed_bytes goes
  * to gate/up pairs, layer by layer from layer 0 ((full - base) / n_layers bytes each; rl_gen_packed_gate_up_layers tells
  * how many the last rl_gen_pack_weights re-laid), and steps of few rows then run the fused gate/up projection of those
- * layers from the copies where that is the faster kernel (at most 64 rows, or at most 128 rows with an FFN width from
- * 14336 -- rl_gen_prefers_packed_gate_up returns 1 when that holds for max_batch rows, 0 otherwise). */
+ * layers from the copies where that is the faster kernel (more than 128 rows, an FFN width above 16384, or an FFN width
+ * from 14336 with more than 64 rows -- rl_gen_prefers_packed_gate_up returns 1 when that holds for max_batch rows, 0
+ * otherwise). */
 size_t rl_gen_packed_bytes_full(const rl_gen_shape *shape);
 int rl_gen_prefers_packed_gate_up(const rl_gen_shape *shape);
 int rl_gen_packed_gate_up_layers(const rl_gen_t *h);

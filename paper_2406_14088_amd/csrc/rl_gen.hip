@@ -258,9 +258,13 @@ int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, 
     return 1;
 }
 
-// Is the fragment-order kernel the faster one for the fused gate/up projection of M rows?  Measured: for M <= 64 by
-// 1.4x (5.3 against 3.5 TB/s at the 34B shape); for 65 .. 128 rows about level at FFN 11008 and ahead at FFN 14336.
-bool packed_swiglu_wins(int M, int ffn) { return M <= 64 || (M <= 128 && ffn >= 14336); }
+// Is the fragment-order kernel the faster one for the fused gate/up projection of M rows?  The row-major kernel runs
+// F / 64 workgroups that each own a compute unit, 128 rows at a time.  Measured crossovers: beyond 256 workgroups it needs
+// a second, partly empty round (34B shape at 64 rows: 192 against 137 us; 70B shape at 32 rows: 219 against 163 us);
+// above 128 rows it streams the weights once per 128-row block (13B shape at 256 rows: 164 against 110 us; 7B shape at
+// 192 rows: 102 against 68 us); at FFN 14336 and 128 rows it is 10 % behind (63 against 57.5 us); otherwise -- the 7B
+// shape at up to 128 rows -- it is level or slightly ahead (48 against 52 us at 32 rows, 54 against 55 us at 128).
+bool packed_swiglu_wins(int M, int ffn) { return M > 128 || ffn > 256 * 64 || (ffn >= 14336 && M > 64); }
 
 void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
     if (h->packed && l < h->packed_gu_layers && packed_swiglu_wins(M, h->s.ffn)) {
@@ -269,7 +273,7 @@ void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
         q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
         q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
         q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
-        q.nb = 2; q.rows_per_wg = 64; q.depth = 2;
+        q.nb = 2; q.rows_per_wg = M > 128 ? 128 : 64; q.depth = 2;
         Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
         launch_gemm_packed(q, st);
         return;
