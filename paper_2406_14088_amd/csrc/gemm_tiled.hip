@@ -35,6 +35,7 @@ struct TiledParams {
     int tiles_m, tiles_n;
     void *out;
     int64_t ldc;
+    RopeEpilogue rope;  // EPI_ROPE
 };
 
 // EPI (GemmEpilogue) is a template parameter: each epilogue gets a kernel of its own, so that the registers one of them
@@ -193,8 +194,70 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     const int rows_w = p.rows[seg_h[wn]];
     const int nb = nbase_h[wn], oc = ocol_h[wn];
     constexpr int CT = WN * 32 + 8;  // floats per row of a 32-row band in LDS (4 rows apart = 32 banks apart: no conflicts)
-    if (EPI == EPI_F32_ACC) __syncthreads();  // every wavefront is done with the operand tiles
-    if (EPI == EPI_F32) {
+    if (EPI == EPI_F32_ACC || EPI == EPI_ROPE) __syncthreads();  // every wavefront is done with the operand tiles
+    if (EPI == EPI_ROPE) {
+        // The wavefront's 128 columns are one head of q, k or v.  Element e pairs with e + 64: accumulator tiles j and
+        // j + 2 of the same lane.  The arithmetic is that of rope_append_kernel, operation for operation, so both paths
+        // store the same bits.  Rows leave through a per-wavefront LDS band as whole 256-byte head rows.
+        const RopeEpilogue &rp = p.rope;
+        const int seg = seg_h[wn];          // 0: q, 1: k, 2: v
+        const int head = nb >> 7;           // head within its matrix
+        const bool head_ok = nb < rows_w;   // (whole heads: the 128 columns exist or none does)
+        constexpr int HT = 128 + 8;         // halves per row of the band
+        f16_t *ht = reinterpret_cast<f16_t *>(smem) + w * 32 * HT;
+        if (head_ok) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i) {
+                const int mb = m0 + (wm * WM + i) * 32;  // first row of the band (uniform over the wavefront)
+                const int pos_b = mb % rp.T, seq_b = rp.b0 + mb / rp.T;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int r = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                    int pos = pos_b + r;
+                    if (pos >= rp.T) pos -= rp.T;  // T >= 32: at most one wrap inside a band
+                    pos = pos < rp.S ? pos : rp.S - 1;
+                    const float *tab = rp.rope_tab + (size_t)pos * 128;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int rr = j * 32 + (lane & 31);
+                        float a = acc[i][j][e], c = acc[i][j + 2][e];
+                        if (seg != 2) {
+                            const float cs = tab[2 * rr], sn = tab[2 * rr + 1];
+                            const float ra = __fmaf_rn(a, cs, -__fmul_rn(c, sn));
+                            const float rb = __fmaf_rn(c, cs, __fmul_rn(a, sn));
+                            a = ra; c = rb;
+                        }
+                        ht[r * HT + rr] = f32_to_f16(a);
+                        ht[r * HT + rr + 64] = f32_to_f16(c);
+                    }
+                }
+                // 16 lanes per row (16 bytes each), 4 rows per instruction
+                const int c8 = (lane & 15) * 8;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int r = k * 4 + (lane >> 4), m = mb + r;
+                    if (m >= p.M) continue;
+                    int pos = pos_b + r, seq = seq_b;
+                    if (pos >= rp.T) { pos -= rp.T; seq += 1; }
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(ht + r * HT + c8);
+                    if (seg == 0) {
+                        *reinterpret_cast<u32x4_t *>(rp.q_f16 + ((size_t)m * rp.Hq + head) * 128 + c8) = v;
+                    } else {
+                        bool store_kv = pos < rp.S;
+                        if (rp.d_valid) {
+                            int nv = rp.d_valid[seq];
+                            nv = nv < 1 ? 1 : (nv > rp.T ? rp.T : nv);
+                            store_kv = store_kv && pos < nv;
+                        }
+                        if (store_kv) {
+                            f16_t *dst = (seg == 1 ? rp.kc : rp.vc) + kv_row_index(rp.map, seq, head, rp.Hkv, rp.S, pos) * 128 + c8;
+                            *reinterpret_cast<u32x4_t *>(dst) = v;
+                        }
+                    }
+                }
+            }
+        }
+    } else if (EPI == EPI_F32) {
         // plain stores: a wavefront store instruction writes two runs of 128 bytes, which the memory system takes as
         // well as whole rows; no detour through LDS
         float *out = reinterpret_cast<float *>(p.out);
@@ -332,7 +395,7 @@ static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
 }
 
 static void launch_one(const GemmArgs &a, hipStream_t st) {
-    TiledParams p;
+    TiledParams p = {};
     p.A = a.A;
     p.lda = a.lda;
     p.a_bytes = (uint32_t)((((size_t)a.M - 1) * a.lda + a.K) * 2);
@@ -360,7 +423,19 @@ static void launch_one(const GemmArgs &a, hipStream_t st) {
     const bool big = a.M >= 1024 && big_tiles >= 256;
     if (a.epilogue == EPI_SWIGLU) { if (big) launch_t<4, 4, EPI_SWIGLU>(p, a, st); else launch_t<2, 2, EPI_SWIGLU>(p, a, st); }
     else if (a.epilogue == EPI_F32_ACC) { if (big) launch_t<4, 4, EPI_F32_ACC>(p, a, st); else launch_t<2, 2, EPI_F32_ACC>(p, a, st); }
+    else if (a.epilogue == EPI_ROPE) { p.rope = *a.rope; launch_t<4, 4, EPI_ROPE>(p, a, st); }  // 128-column wavefronts only
     else { if (big) launch_t<4, 4, EPI_F32>(p, a, st); else launch_t<2, 2, EPI_F32>(p, a, st); }
+}
+
+// Can launch_gemm_tiled run EPI_ROPE on this problem?  (Whole heads of 128 per matrix, bands that wrap at most once,
+// enough tiles for the 256 x 256 kernel, operands that need no cutting.)
+bool gemm_tiled_rope_supported(int M, int K, int64_t lda, int Hq, int Hkv, int hd, int rope_style, int T, bool two_terms) {
+    if (hd != 128 || rope_style != 1 || T < 32 || M < 1024) return false;
+    const long n_total = (long)(Hq + 2 * Hkv) * 128;
+    if ((long)ceil_div(M, 256) * ceil_div((int)n_total, 256) < 256) return false;
+    const size_t a_bytes = (((size_t)M - 1) * lda + K) * 2 * (two_terms ? 2 : 1) + (two_terms ? (size_t)M * lda * 2 : 0);
+    if (a_bytes >= 0xF0000000ull || (size_t)Hq * 128 * K * 2 >= 0xF0000000ull) return false;
+    return true;
 }
 
 // The kernel addresses each operand through a buffer descriptor with 32-bit byte offsets: operands of

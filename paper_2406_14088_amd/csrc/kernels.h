@@ -54,7 +54,19 @@ void launch_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
 enum GemmEpilogue {
     EPI_F32 = 0,    // out fp32: split s writes out + s*split_stride, element [m*ldc + col]
     EPI_SWIGLU = 1, // W_0 = gate, W_1 = up (same shape): out half [m*ldc + n] = silu(gate) * up; splits must be 1
-    EPI_F32_ACC = 2 // out fp32 [m*ldc + col] += result (residual add); splits must be 1
+    EPI_F32_ACC = 2, // out fp32 [m*ldc + col] += result (residual add); splits must be 1
+    EPI_ROPE = 3     // tiled kernel only: W_0, W_1, W_2 = Wq, Wk, Wv; the result is rotated and stored as launch_rope_append
+                     // would store it (q half, cache rows), without the fp32 round trip; see RopeEpilogue
+};
+// What the EPI_ROPE epilogue needs: row m of the product is sequence b0 + m / T at position m % T (a prefill from
+// position 0).  head_dim 128 and rotary style 1 (element e pairs with e + 64) only; every W_i holds whole heads.
+struct RopeEpilogue {
+    const float *rope_tab;  // [S, 64, 2] (cos, sin)
+    int T, b0, Hq, Hkv, S;
+    f16_t *q_f16;           // [M, Hq * 128]
+    f16_t *kc, *vc;         // this layer's K and V areas, laid out as `map` says
+    KvMap map;
+    const int32_t *d_valid; // optional, as in launch_rope_append
 };
 struct GemmArgs {
     const f16_t *A;       // [M, K] half, row stride lda (elements)
@@ -69,12 +81,14 @@ struct GemmArgs {
     size_t split_stride;  // elements between split partials (EPI_F32)
     int splits;           // split-K factor (>= 1)
     int epilogue;
+    const RopeEpilogue *rope = nullptr;  // EPI_ROPE
 };
 // M <= 256: weights stream through registers exactly once, activations are staged in LDS.
 void launch_gemm_skinny(const GemmArgs &a, hipStream_t st);
 // any M: both operands tiled through LDS (the prefill path).
 void launch_gemm_tiled(const GemmArgs &a, hipStream_t st);
 int gemm_skinny_default_splits(int M, int N, int K);
+bool gemm_tiled_rope_supported(int M, int K, int64_t lda, int Hq, int Hkv, int hd, int rope_style, int T, bool two_terms);
 
 // ---- gemm_packed.hip -----------------------------------------------------------------------------
 // Weights re-laid-out once in matrix-core fragment order: P[ceil(N/32)][ceil(K/16)][64 lanes][8] halves, lane l of

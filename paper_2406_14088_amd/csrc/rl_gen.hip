@@ -314,17 +314,35 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
     }
     for (int l = 0; l < L; ++l) {
         const bool pk = h->packed && M <= kSkinnyMaxM;
+        bool qkv_stored = false;  // q and the cache rows already written by the projection itself
         int ns;
         if (pk)  // both terms go through the same weight fragments into the same accumulators
             ns = project_packed(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->pw[W_Q][l], qd, h->pw[W_K][l], kvd, h->pw[W_V][l],
                                 kvd, st);
-        else if (M > kSkinnyMaxM)  // large-M kernel: one contraction over [h | h_lo] x [W | W]
+        else if (!decode && gemm_tiled_rope_supported(M, d, d, s.n_heads, s.n_kv_heads, s.head_dim, s.rope_style, T, h_lo != nullptr) &&
+                 (!h_lo || (size_t)(h_lo - h->h()) * 2 < 0x70000000ull)) {
+            // prefill: the projection's epilogue rotates q and k and stores q and the cache rows itself
+            RopeEpilogue rp;
+            rp.rope_tab = h->rope(); rp.T = T; rp.b0 = b0; rp.Hq = s.n_heads; rp.Hkv = s.n_kv_heads; rp.S = s.max_seq;
+            rp.q_f16 = h->qbf(); rp.kc = h->kslab(l); rp.vc = h->vslab(l); rp.map = map; rp.d_valid = d_valid;
+            GemmArgs a;
+            a.A = h->h(); a.A_lo = h_lo; a.lda = d; a.M = M; a.K = d;
+            a.W[0] = h->lw[W_Q][l]; a.W[1] = h->lw[W_K][l]; a.W[2] = h->lw[W_V][l];
+            a.rows[0] = qd; a.rows[1] = kvd; a.rows[2] = kvd;
+            a.out = nullptr; a.ldc = 0; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_ROPE; a.rope = &rp;
+            {
+                Scope sc(h, RL_GEN_K_GEMM_QKV, st);
+                launch_gemm_tiled(a, st);
+            }
+            qkv_stored = true;
+            ns = 0;
+        } else if (M > kSkinnyMaxM)  // large-M kernel: one contraction over [h | h_lo] x [W | W]
             ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
                          nullptr, 0, st);
         else  // row-major skinny kernel: stacked rows [h; h_lo], the consumer adds the two row blocks
             ns = terms * project(h, RL_GEN_K_GEMM_QKV, h->h(), nullptr, d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd,
                                  h->lw[W_V][l], kvd, nullptr, 0, st);
-        {
+        if (!qkv_stored) {
             Scope sc(h, RL_GEN_K_ROPE_APPEND, st);
             launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_lens() : h->d_zero(),
                                decode ? 1 : 0, h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
@@ -1115,6 +1133,26 @@ int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint1
     bool skinny = kernel == 1 || (kernel == 0 && M <= kSkinnyMaxM);
     if (skinny) launch_gemm_skinny(a, reinterpret_cast<hipStream_t>(st));
     else launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *Wq, const uint16_t *Wk, const uint16_t *Wv,
+                    int32_t Hq, int32_t Hkv, int32_t hd, int32_t M, int32_t K, int32_t T, int32_t b0, const float *rope_tab,
+                    int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *st) {
+    if (!A || !Wq || !Wk || !Wv || !rope_tab || !q_f16 || !kc || !vc) return RL_GEN_E_NULL;
+    if (M <= 0 || K <= 0 || K % 8 || lda % 8 || lda < K || Hq <= 0 || Hkv <= 0 || T <= 0 || b0 < 0 || S < T) return RL_GEN_E_SHAPE;
+    if (A_lo && A_lo <= A) return RL_GEN_E_SHAPE;
+    if (!gemm_tiled_rope_supported(M, K, lda, Hq, Hkv, hd, rope_style, T, A_lo != nullptr)) return RL_GEN_E_SHAPE;
+    if (A_lo && (size_t)(A_lo - A) * 2 >= 0x70000000ull) return RL_GEN_E_SHAPE;
+    RopeEpilogue rp;
+    rp.rope_tab = rope_tab; rp.T = T; rp.b0 = b0; rp.Hq = Hq; rp.Hkv = Hkv; rp.S = S;
+    rp.q_f16 = q_f16; rp.kc = kc; rp.vc = vc; rp.map = KvMap(); rp.d_valid = nullptr;
+    GemmArgs a;
+    a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
+    a.W[0] = Wq; a.W[1] = Wk; a.W[2] = Wv;
+    a.rows[0] = Hq * hd; a.rows[1] = Hkv * hd; a.rows[2] = Hkv * hd;
+    a.out = nullptr; a.ldc = 0; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_ROPE; a.rope = &rp;
+    launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

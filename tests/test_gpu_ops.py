@@ -586,3 +586,52 @@ def test_grouped_query_decode_attention_tile_tails(ops, Hq, Hkv, nsplit):
             ref = orc.attend(qn[b, u], kn[b, u // g, : n + 1], vn[b, u // g, : n + 1])
             err = np.abs(on[b, u] - ref)
             assert (err <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), (b, n, u, err.max())
+
+
+@pytest.mark.parametrize("Hq,Hkv,two_terms", [(8, 8, True), (16, 2, False), (9, 3, True)])
+def test_qkv_projection_with_rotary_epilogue_equals_the_two_kernels(ops, Hq, Hkv, two_terms):
+    """The prefill QKV projection that rotates and appends in its own epilogue stores, bit for bit, what the fp32
+    projection followed by rope_append stores (the oracle parity of those two is established by their own tests)."""
+    hd, K, T, nseq, b0, S = 128, 256, 40, 205, 3, 64        # 8200 rows: a ragged last tile, bands that wrap to the next sequence
+    M = nseq * T
+    n_all = (Hq + 2 * Hkv) * hd
+    A = randn_f16(((2 if two_terms else 1) * M, K), 401)
+    if two_terms:
+        A[M:] *= 2.0 ** -11                                   # a second term of the size it has in the generator
+    Wq, Wk, Wv = randn_bf16((Hq * hd, K), 402, 0.05), randn_bf16((Hkv * hd, K), 403, 0.05), randn_bf16((Hkv * hd, K), 404, 0.05)
+    tab = torch.empty((S, hd // 2, 2), dtype=torch.float32, device=DEV)
+    ops.build_rope_table(tab, S, hd, 10000.0)
+    A_lo = A[M:] if two_terms else None
+    # reference: fp32 projection, then rope_append
+    part = torch.empty((M, n_all), dtype=torch.float32, device=DEV)
+    ops.gemm(A[:M], [Wq, Wk, Wv], part, n_all, M=M, epilogue=0, kernel=2, A_lo=A_lo)
+    zero = torch.zeros((1,), dtype=torch.int32, device=DEV)
+    q_ref = torch.zeros((M, Hq * hd), dtype=torch.float16, device=DEV)
+    kc_ref = torch.zeros((b0 + nseq, Hkv, S, hd), dtype=torch.float16, device=DEV)
+    vc_ref = torch.zeros_like(kc_ref)
+    ops.rope_append(part, 1, M * n_all, M, T, b0, zero, tab, 1, Hq, Hkv, hd, S, None, q_ref, kc_ref, vc_ref)
+    q = torch.zeros_like(q_ref)
+    kc, vc = torch.zeros_like(kc_ref), torch.zeros_like(vc_ref)
+    ops.gemm_rope(A[:M], Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, tab, 1, S, q, kc, vc, A_lo=A_lo)
+    torch.cuda.synchronize()
+    assert q_ref.abs().max() > 0 and kc_ref.abs().max() > 0
+    assert torch.equal(q.view(torch.int16), q_ref.view(torch.int16))
+    assert torch.equal(kc.view(torch.int16), kc_ref.view(torch.int16))
+    assert torch.equal(vc.view(torch.int16), vc_ref.view(torch.int16))
+    # one row against the oracle directly (sequence b0 + 7, position 11)
+    m = 7 * T + 11
+    x = np64(A[m]) + (np64(A[M + m]) if two_terms else 0.0)
+    for name, W, H, got in (("q", Wq, Hq, np64(q[m]).reshape(Hq, hd)), ("k", Wk, Hkv, np64(kc[b0 + 7, :, 11])), ("v", Wv, Hkv, np64(vc[b0 + 7, :, 11]))):
+        y = (np64(W) @ x).reshape(H, hd)
+        want = y if name == "v" else orc.rope(y, 11, 10000.0, 1)
+        assert (np.abs(got - want) <= 0.5 * F16_EPS * np.abs(want) * 1.05 + 2e-4).all(), name
+
+
+def test_rotary_epilogue_is_refused_where_it_does_not_apply(ops):
+    from paper_2406_14088_amd import RlGenError
+    x = torch.zeros((4096, 256), dtype=torch.float16, device=DEV)
+    w = torch.zeros((1024, 256), dtype=torch.bfloat16, device=DEV)
+    t = torch.zeros((64, 64, 2), dtype=torch.float32, device=DEV)
+    for hd, style, T, M in ((64, 1, 40, 4000), (128, 0, 40, 4000), (128, 1, 16, 4000), (128, 1, 40, 512)):
+        with pytest.raises(RlGenError):
+            ops.gemm_rope(x, w, w, w, 8, 8, hd, M, T, 0, t, style, 64, x, x, x)
