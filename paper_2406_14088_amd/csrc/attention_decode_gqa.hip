@@ -86,6 +86,7 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
     // ---- every tile gets its own buffer descriptor (scalar registers): base = the tile's first row -- in a paged cache a
     //      tile never straddles pages, which hold a multiple of 16 rows and start at multiples of 16 -- and size = its
     //      visible rows, so rows at and beyond j1 are out of range.
+    const bool stream_kv = hgs == 1;
     const int32_t *pages = PAGED ? map.table + (size_t)b * map.table_stride : nullptr;
     // copy instruction i (0..3) of a tile moves rows 4 i .. 4 i + 3; this lane fills slot (lane & 15) of row 4 i + j
     uint32_t ksrc[4], vsrc[4];
@@ -113,8 +114,13 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
             unsigned char *kd = ring + stage * GA_STAGE_BYTES + i * 1024;
             unsigned char *vd = kd + GA_TILE_BYTES;
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, GA_LDS_PTR(kd), 16, (int)ksrc[i], 0, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, GA_LDS_PTR(vd), 16, (int)vsrc[i], 0, 0, 0);
+            if (stream_kv) {  // the only reader of these rows: non-temporal copies (they stream faster than cached ones)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, GA_LDS_PTR(kd), 16, (int)ksrc[i], 0, 0, 3);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, GA_LDS_PTR(vd), 16, (int)vsrc[i], 0, 0, 3);
+            } else {          // 16 heads per kv head: the second wavefront of the kv head finds the rows in L2
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(kr, GA_LDS_PTR(kd), 16, (int)ksrc[i], 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, GA_LDS_PTR(vd), 16, (int)vsrc[i], 0, 0, 0);
+            }
 #else
             (void)kd; (void)vd; (void)kr; (void)vr;
 #endif

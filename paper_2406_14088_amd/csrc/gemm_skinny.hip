@@ -115,6 +115,7 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
         x_off[i] = (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)c16 * 16u;
     }
     u32x4_t xr[2][MT];  // activation pieces in flight: xr[i & 1] belongs to chunk c0 + i
+    const bool stream_w = gridDim.z == 1;
     u32x4_t wq[8];      // raw bf16 weight pieces in flight: slots (i & 1) * 4 .. + 3 belong to chunk c0 + i
     f32x16_t acc[MT];
 #pragma unroll
@@ -138,7 +139,9 @@ __global__ __launch_bounds__(SK_THREADS, 2) void gemm_skinny_kernel(SkinnyParams
     };
     auto load_w1 = [&](int c, int slot, int i) {  // piece i of chunk c -> ring slot
         uint32_t cb = (uint32_t)c * (SK_BK * 2);
-        wq[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(c < c1 ? w_off[i] + cb : SK_OOB), 0, 0);
+        // one row block: every weight byte is used once and is loaded non-temporally (streams faster than a cached load)
+        if (stream_w) wq[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(c < c1 ? w_off[i] + cb : SK_OOB), 0, 3);
+        else wq[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr, (int)(c < c1 ? w_off[i] + cb : SK_OOB), 0, 0);
     };
     auto stage_w1 = [&](int slot, int buf, int i) {  // ring slot -> half -> LDS strip `buf`
         *reinterpret_cast<u32x4_t *>(wl + buf * 4096 + i * 1024 + wst[i]) = bf16x8_to_f16x8(wq[slot]);
