@@ -48,8 +48,15 @@ __global__ __launch_bounds__(THREADS) void add_rmsnorm_kernel(float *__restrict_
         int e4 = t + i * THREADS;
         if (e4 * 4 < d) {
             f32x4_t a = xr[e4];
-            // partials are added in split order (fixed, so results are reproducible); four loads in flight
+            // partials are added in split order (fixed, so results are reproducible); eight, then four loads in flight
             int s = 0;
+            for (; s + 8 <= nsplit; s += 8) {
+                f32x4_t q[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) q[u] = pr[(size_t)(s + u) * ps4 + e4];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) a += q[u];
+            }
             for (; s + 4 <= nsplit; s += 4) {
                 f32x4_t p0 = pr[(size_t)s * ps4 + e4], p1 = pr[(size_t)(s + 1) * ps4 + e4];
                 f32x4_t p2 = pr[(size_t)(s + 2) * ps4 + e4], p3 = pr[(size_t)(s + 3) * ps4 + e4];
