@@ -26,7 +26,7 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense 16-bit matrix cores (bf16 and fp16
 # HBM bytes per decode-attention launch (mean over the launches of one generation) measured with rocprofv3 counters:
 # FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the library's 1 GiB copy_kernel
 # (profiles/decode_attention_llama7b_hbm_traffic.md).  Only valid for the unmodified llama7b workload.
-MEASURED_TRAFFIC_BYTES = {"llama7b": 527414 * 1024}
+MEASURED_TRAFFIC_BYTES = {"llama7b": 527424 * 1024}
 
 
 def decode_bytes(shape, B, t):
