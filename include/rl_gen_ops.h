@@ -96,10 +96,11 @@ int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int
 /* Decode attention: for each sequence b < B and query head u, softmax(q_u . k_j / sqrt(hd)) v_j over
  * cache rows j = 0 .. d_len[b * len_stride] of kv head u / (Hq/Hkv) (len_stride 0: one length for all, 1: per sequence).  q fp32 [B, Hq*hd]; kc, vc f16; out f16 [B, Hq*hd].
  * nsplit >= 1 splits the rows over wavefronts; ws must then hold rl_op_decode_attention_ws_floats
- * floats (may be NULL for nsplit == 1).  hd in {64, 128}. */
+ * floats (may be NULL for nsplit == 1).  hd in {64, 128}.  d_done: DEVICE int32 [B] or NULL; sequences with a non-zero
+ * flag (ended, Section 2.1) are skipped: their cache is not read and their rows of out are left as they are. */
 int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
                            uint16_t *out, float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
-                           void *hip_stream);
+                           const int32_t *d_done, void *hip_stream);
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
 /* The same attention over a paged cache (Section 7 names paged attention as a technique the generation backend can

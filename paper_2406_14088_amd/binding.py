@@ -98,7 +98,7 @@ def lib():
         "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
-        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]),
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
         "rl_op_decode_attention_paged": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
@@ -474,9 +474,9 @@ class _Ops:
     def decode_attention_ws_floats(self, B, Hq, hd, nsplit):
         return int(lib().rl_op_decode_attention_ws_floats(B, Hq, hd, nsplit))
 
-    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0):
+    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0, d_done=None):
         self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(),
-                                              _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention")
+                                              _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _ptr(d_done), _stream()), "rl_op_decode_attention")
 
     def decode_attention_paged(self, q, k_pool, v_pool, table, page_size, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0):
         self._ck(lib().rl_op_decode_attention_paged(q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(), table.data_ptr(),

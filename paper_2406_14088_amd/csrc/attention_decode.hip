@@ -92,7 +92,8 @@ __device__ __forceinline__ void rotate8(float x[8], int c, const float *tab /* r
 template <int HD, int GT, bool FUSED, bool PAGED>
 __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     const float *__restrict__ q, f16_t *kc, f16_t *vc, const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
-    float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, int len_stride, FusedQkv fq, KvMap map) {
+    float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, int len_stride, FusedQkv fq, KvMap map,
+    const int32_t *__restrict__ d_done) {
     static_assert(!(FUSED && PAGED), "the fused form addresses contiguous slabs only");
     constexpr int LPR = HD / 8;     // lanes per cache row
     constexpr int RPW = 64 / LPR;   // rows per wavefront load instruction
@@ -106,6 +107,7 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     int kvh = rest % Hkv;
     int b = rest / Hkv;
     const int head0 = kvh * g + hg * GT;  // first query head of this wavefront
+    if (d_done && d_done[b]) return;  // an ended sequence: its cache is not read any more (its output row keeps old values)
 
     const int pos = d_len[(size_t)b * len_stride];  // position of the new token (len_stride 0: one length for all sequences)
     if (FUSED && pos >= S) return;  // capacity is checked on the host; never write outside the cache
@@ -328,28 +330,29 @@ int decode_attention_default_splits(int B, int Hkv, int S) {
 
 template <int HD, int GT>
 static void launch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B,
-                      int Hq, int Hkv, int S, int nsplit, const FusedQkv *fq, const KvMap &map, hipStream_t st) {
+                      int Hq, int Hkv, int S, int nsplit, const FusedQkv *fq, const KvMap &map, const int32_t *d_done, hipStream_t st) {
     int g = Hq / Hkv;
     int n_items = B * Hkv * (g / GT) * nsplit;
     int blocks = ceil_div(n_items, DA_THREADS / 64);
     if (fq)
         decode_attention_kernel<HD, GT, true, false><<<blocks, DA_THREADS, 0, st>>>(nullptr, kc, vc, d_len, out, ws, n_items, Hq,
-                                                                                  Hkv, S, nsplit, len_stride, *fq, KvMap());
+                                                                                  Hkv, S, nsplit, len_stride, *fq, KvMap(), nullptr);
     else if (map.table)
         decode_attention_kernel<HD, GT, false, true><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
-                                                                                  nsplit, len_stride, FusedQkv{}, map);
+                                                                                  nsplit, len_stride, FusedQkv{}, map, d_done);
     else
         decode_attention_kernel<HD, GT, false, false><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv,
-                                                                                   S, nsplit, len_stride, FusedQkv{}, KvMap());
+                                                                                   S, nsplit, len_stride, FusedQkv{}, KvMap(), d_done);
 }
 
 static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B,
-                        int Hq, int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, const KvMap &map, hipStream_t st) {
+                        int Hq, int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, const KvMap &map, const int32_t *d_done,
+                        hipStream_t st) {
     if (B <= 0) return;
     int g = Hq / Hkv;
     int gt = decode_attention_group(g);
 #define DA_CASE(HDV, GTV) \
-    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, fq, map, st); }
+    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, fq, map, d_done, st); }
     DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4)
     DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4)
 #undef DA_CASE
@@ -357,13 +360,14 @@ static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_l
 }
 
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
-                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map) {
+                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map,
+                             const int32_t *d_done) {
     if (decode_attention_gqa_supported(Hq, Hkv, hd)) {  // many query heads per cache row: the matrix-core kernel
-        launch_decode_attention_gqa(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, st, map);
+        launch_decode_attention_gqa(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, st, map, d_done);
         return;
     }
     dispatch_da(q, const_cast<f16_t *>(kc), const_cast<f16_t *>(vc), d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, nullptr,
-                map, st);
+                map, d_done, st);
 }
 
 void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
@@ -371,7 +375,7 @@ void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t spli
                                    int Hkv, int hd, int S, int nsplit, hipStream_t st) {
     FusedQkv fq;
     fq.part = qkv; fq.nsplit = nsplit_qkv; fq.split_stride = split_stride; fq.rope_tab = rope_tab; fq.rope_style = rope_style;
-    dispatch_da(nullptr, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, &fq, KvMap(), st);
+    dispatch_da(nullptr, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, &fq, KvMap(), nullptr, st);
 }
 
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {

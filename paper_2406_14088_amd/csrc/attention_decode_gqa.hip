@@ -38,7 +38,8 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
                                                                   const f16_t *__restrict__ vc,
                                                                   const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
                                                                   float *__restrict__ ws, int Hq, int Hkv, int S, int nsplit,
-                                                                  int len_stride, KvMap map) {
+                                                                  int len_stride, KvMap map,
+                                                                  const int32_t *__restrict__ d_done) {
     constexpr int HD = 128;
     __shared__ __attribute__((aligned(1024))) unsigned char ring[GA_STAGES * GA_STAGE_BYTES];
     const int lane = threadIdx.x;
@@ -52,6 +53,7 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
     const int kvh = item % Hkv;
     const int b = item / Hkv;
     const int head0 = kvh * g + hg * G8;
+    if (d_done && d_done[b]) return;  // an ended sequence: its cache is not read any more (its output row keeps old values)
 
     const int pos = __builtin_amdgcn_readfirstlane(d_len[(size_t)b * len_stride]);
     int n = pos + 1;  // visible cache rows
@@ -258,13 +260,14 @@ int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S) {
 }
 
 void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride,
-                                 f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st, KvMap map) {
+                                 f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st, KvMap map,
+                                 const int32_t *d_done) {
     if (B <= 0) return;
     const int g = Hq / Hkv;
     const int items = B * Hkv * (g < 8 ? 1 : g / 8) * nsplit;
     if (map.table)
-        decode_attention_gqa_kernel<true><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, ws, Hq, Hkv, S, nsplit, len_stride, map);
+        decode_attention_gqa_kernel<true><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, ws, Hq, Hkv, S, nsplit, len_stride, map, d_done);
     else
-        decode_attention_gqa_kernel<false><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, ws, Hq, Hkv, S, nsplit, len_stride, KvMap());
+        decode_attention_gqa_kernel<false><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, ws, Hq, Hkv, S, nsplit, len_stride, KvMap(), d_done);
     if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, 128, nsplit, st);
 }

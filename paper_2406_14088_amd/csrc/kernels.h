@@ -120,7 +120,8 @@ void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *split
 // q fp32 [B, Hq*hd] (already rotated); kc/vc this layer's K and V areas (half) laid out as `map` says; out half
 // [B, Hq*hd].  ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
-                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map = KvMap());
+                             float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map = KvMap(),
+                             const int32_t *d_done = nullptr);  // d_done (optional): sequences with a non-zero flag are skipped
 // Fused form: q, k, v of the new token are taken from the split-K partials of the QKV projection (each
 // [B, (Hq+2Hkv)*hd], q | k | v per row): partials added, q and k rotated at position *d_len, the k/v row appended to
 // the cache (kc/vc are written) and used from registers.  Replaces launch_rope_append + launch_decode_attention.
@@ -133,7 +134,7 @@ bool decode_attention_gqa_supported(int Hq, int Hkv, int hd);
 int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S);
 void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride,
                                  f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st,
-                                 KvMap map = KvMap());
+                                 KvMap map = KvMap(), const int32_t *d_done = nullptr);
 void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);

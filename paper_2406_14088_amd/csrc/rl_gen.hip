@@ -355,7 +355,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         if (decode) {
             Scope sc(h, RL_GEN_K_DECODE_ATTN, st);
             launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_lens(), 1, h->attn(), h->attn_ws(), nb,
-                                    s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st, map);
+                                    s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st, map,
+                                    h->eos >= 0 ? h->d_done() : nullptr);  // ended sequences cost no cache traffic
         } else {
             Scope sc(h, RL_GEN_K_PREFILL_ATTN, st);
             launch_prefill_attention(h->qbf(), h->kslab(l), h->vslab(l), h->attn(), nb, b0, T, s.n_heads, s.n_kv_heads,
@@ -1225,11 +1226,12 @@ size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32
 
 int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
                            uint16_t *out, float *ws,
-                           int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
+                           int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, const int32_t *d_done, void *st) {
     if (!q || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
     if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
-    launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st));
+    launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st), KvMap(),
+                            d_done);
     RL_OP_RETURN();
 }
 

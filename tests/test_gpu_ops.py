@@ -413,7 +413,7 @@ def test_empty_inputs_enqueue_nothing(ops):
         L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 2, None),
         L.rl_op_gemm_packed(p(A), None, d, p(P), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 0, 0, 0, None),
         L.rl_op_argmax(p(lg), 0, V, p(nxt), None),
-        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), 0, p(h), None, 0, 1, 1, 64, 8, 1, None),
+        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), 0, p(h), None, 0, 1, 1, 64, 8, 1, None, None),
         L.rl_op_prefill_attention(p(h), p(kc), p(kc), p(h), 0, 0, 1, 1, 1, 64, 8, None),
         L.rl_op_logprob_gather(p(lg), V, 0, V, p(toks), 4, 0, p(x), None),
     ]
@@ -635,3 +635,28 @@ def test_rotary_epilogue_is_refused_where_it_does_not_apply(ops):
     for hd, style, T, M in ((64, 1, 40, 4000), (128, 0, 40, 4000), (128, 1, 16, 4000), (128, 1, 40, 512)):
         with pytest.raises(RlGenError):
             ops.gemm_rope(x, w, w, w, 8, 8, hd, M, T, 0, t, style, 64, x, x, x)
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv,nsplit", [(128, 4, 4, 1), (128, 8, 1, 2), (64, 4, 2, 1)])
+def test_decode_attention_skips_ended_sequences(ops, hd, Hq, Hkv, nsplit):
+    """Sequences flagged as ended are not attended: their output rows keep what they held, the others are unaffected."""
+    B, S, n = 6, 128, 70
+    q = randn_f32((B, Hq * hd), 501)
+    kc, vc = randn_f16((B, Hkv, S, hd), 502), randn_f16((B, Hkv, S, hd), 503)
+    done = torch.tensor([0, 1, 0, 0, 1, 1], dtype=torch.int32, device=DEV)
+    kc[done.bool()] = float("nan")                        # an ended sequence's cache must not be touched
+    vc[done.bool()] = float("nan")
+    d_len = torch.tensor([n], dtype=torch.int32, device=DEV)
+    ws = torch.zeros(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ref = torch.full((B, Hq * hd), 7.0, dtype=torch.float16, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, ref, ws, B, Hq, Hkv, hd, S, nsplit)
+    out = torch.full((B, Hq * hd), 7.0, dtype=torch.float16, device=DEV)
+    ws.zero_()
+    ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, d_done=done)
+    torch.cuda.synchronize()
+    live = ~done.bool()
+    assert torch.equal(out[live].view(torch.int16), ref[live].view(torch.int16)) and not torch.isnan(out[live]).any()
+    if nsplit == 1:
+        assert (out[done.bool()] == 7.0).all()
+    else:                                                 # the merge of the (untouched, zeroed) partials writes the row
+        assert not torch.isinf(out[done.bool()]).any()
