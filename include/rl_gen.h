@@ -95,17 +95,18 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void
  * (DEVICE, 256-byte aligned, at least rl_gen_packed_bytes long, caller-owned, borrowed while the handle
  * lives) in the order the matrix cores read them (IEEE half; layout in rl_gen_ops.h), enqueued on
  * hip_stream.  Afterwards steps of at most 256 rows (decode, short prefills) read the copies of these
- * matrices; the gate/up pair and longer prefills keep reading the row-major weights.  Call it again after the weights changed (a training step
+ * matrices instead of the row-major weights; prefills of 1024 rows or more read them as the B operand of the large
+ * tile kernel (copied global -> LDS directly; same bits as without).  Call it again after the weights changed (a training step
  * between two generation phases); packed_arena == NULL detaches the copies.  Results are the same to fp32
  * summation order with and without the copies.  Use the same stream as for the following steps, or
  * synchronise in between. */
 size_t rl_gen_packed_bytes(const rl_gen_shape *shape);
 /* The same plus copies of the gate/up pair of every layer.  Whatever an arena holds beyond rl_gen_packed_bytes goes
  * to gate/up pairs, layer by layer from layer 0 ((full - base) / n_layers bytes each; rl_gen_packed_gate_up_layers tells
- * how many the last rl_gen_pack_weights re-laid), and steps of few rows then run the fused gate/up projection of those
- * layers from the copies where that is the faster kernel (more than 128 rows, an FFN width above 16384, or an FFN width
- * from 14336 with more than 64 rows -- rl_gen_prefers_packed_gate_up returns 1 when that holds for max_batch rows, 0
- * otherwise). */
+ * how many the last rl_gen_pack_weights re-laid).  Prefills of 1024 rows or more then run the fused gate/up projection
+ * of those layers from the copies, and steps of few rows do where that is the faster kernel (more than 128 rows, an FFN
+ * width above 16384, or an FFN width from 14336 with more than 64 rows).  rl_gen_prefers_packed_gate_up: 1 when the
+ * copies pay for this shape (always, for the prefill's sake: they cost their memory, nothing else), else 0. */
 size_t rl_gen_packed_bytes_full(const rl_gen_shape *shape);
 int rl_gen_prefers_packed_gate_up(const rl_gen_shape *shape);
 int rl_gen_packed_gate_up_layers(const rl_gen_t *h);

@@ -50,14 +50,23 @@ int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint1
                int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
                int32_t splits, int32_t epilogue, int32_t kernel, void *hip_stream);
 
+/* The large-M projection kernel fed fragment-order copies of its weights as well (P_i = rl_op_pack_weights of W_i, one per
+ * W_i): tiles of 256 x 256 then copy both operands global -> LDS with the load unit (no staging registers, no conversion in
+ * the loop); smaller problems run as rl_op_gemm with kernel 2 does.  epilogue 0, 1 or 2 as in rl_op_gemm; out as there.
+ * The products are the same; sums over K are formed in the same order, so results equal rl_op_gemm's bit for bit. */
+int rl_op_gemm_tiled_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *W0, const uint16_t *W1,
+                            const uint16_t *W2, const uint16_t *P0, const uint16_t *P1, const uint16_t *P2, int32_t rows0, int32_t rows1,
+                            int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, int32_t epilogue, void *hip_stream);
+
 /* QKV projection of a prefill with the rotary embedding and the cache append in its epilogue (what a prefill of a model
  * with head_dim 128 and rotary style 1 runs): [q | k | v] = (A + A_lo) [Wq; Wk; Wv]^T by the large-M kernel, row m being
  * sequence b0 + m / T at position m % T; q and k rotated with rope_tab (fp32 [S, 64, 2]); q stored as half [M, Hq*128],
  * k and v rows rounded to half and stored into kc / vc (half [n_seq][Hkv][S][128]).  Bit for bit what rl_op_gemm (fp32
  * output) followed by rl_op_rope_append stores.  RL_GEN_E_SHAPE where the fused form does not apply (head_dim, style,
- * T < 32, fewer than 256 tiles of 256 x 256). */
+ * T < 32, fewer than 256 tiles of 256 x 256).  Pq, Pk, Pv: optional fragment-order copies of the three matrices (all or
+ * none): with them both operands are copied global -> LDS directly, as in rl_op_gemm_tiled_packed; same stored bits. */
 int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *Wq, const uint16_t *Wk, const uint16_t *Wv,
-                    int32_t Hq, int32_t Hkv, int32_t hd, int32_t M, int32_t K, int32_t T, int32_t b0, const float *rope_tab,
+                    const uint16_t *Pq, const uint16_t *Pk, const uint16_t *Pv, int32_t Hq, int32_t Hkv, int32_t hd, int32_t M, int32_t K, int32_t T, int32_t b0, const float *rope_tab,
                     int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *hip_stream);
 
 /* Weights in matrix-core fragment order.  rl_op_pack_weights converts W bf16 [N, K] row-major (K % 8 == 0)

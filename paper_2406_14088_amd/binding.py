@@ -92,7 +92,8 @@ def lib():
         "rl_op_embed": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
         "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, vp, i32, i32, vp]),
         "rl_op_gemm": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
-        "rl_op_gemm_rope": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp]),
+        "rl_op_gemm_rope": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp]),
+        "rl_op_gemm_tiled_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, i32, vp]),
         "rl_op_packed_weight_bytes": (sz, [i32, i32]),
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
         "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp]),
@@ -122,7 +123,7 @@ EXPORTED_SYMBOLS = (
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_gemm_rope", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
+    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
@@ -440,9 +441,19 @@ class _Ops:
         self._ck(lib().rl_op_gemm(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K, out.data_ptr(),
                                   ldc, split_stride, splits, epilogue, kernel, _stream()), "rl_op_gemm")
 
-    def gemm_rope(self, A, Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, rope_tab, rope_style, S, q_f16, kc, vc, A_lo=None):
+    def gemm_tiled_packed(self, A, Ws, Ps, out, ldc, M=None, epilogue=0, A_lo=None):
+        K = Ws[0].shape[1]
+        wp = [w.data_ptr() for w in Ws] + [None] * (3 - len(Ws))
+        pp = [x.data_ptr() for x in Ps] + [None] * (3 - len(Ps))
+        rows = [w.shape[0] for w in Ws] + [0] * (3 - len(Ws))
+        M = A.shape[0] if M is None else M
+        self._ck(lib().rl_op_gemm_tiled_packed(A.data_ptr(), _ptr(A_lo), A.stride(0), wp[0], wp[1], wp[2], pp[0], pp[1], pp[2], rows[0],
+                                               rows[1], rows[2], M, K, out.data_ptr(), ldc, epilogue, _stream()), "rl_op_gemm_tiled_packed")
+
+    def gemm_rope(self, A, Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, rope_tab, rope_style, S, q_f16, kc, vc, A_lo=None, Ps=None):
         K = Wq.shape[1]
-        self._ck(lib().rl_op_gemm_rope(A.data_ptr(), _ptr(A_lo), A.stride(0), Wq.data_ptr(), Wk.data_ptr(), Wv.data_ptr(), Hq, Hkv, hd, M, K,
+        pq, pk, pv = (x.data_ptr() for x in Ps) if Ps else (None, None, None)
+        self._ck(lib().rl_op_gemm_rope(A.data_ptr(), _ptr(A_lo), A.stride(0), Wq.data_ptr(), Wk.data_ptr(), Wv.data_ptr(), pq, pk, pv, Hq, Hkv, hd, M, K,
                                        T, b0, rope_tab.data_ptr(), rope_style, S, q_f16.data_ptr(), kc.data_ptr(), vc.data_ptr(), _stream()),
                  "rl_op_gemm_rope")
 

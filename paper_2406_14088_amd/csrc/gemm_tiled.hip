@@ -36,20 +36,21 @@ struct TiledParams {
     void *out;
     int64_t ldc;
     RopeEpilogue rope;  // EPI_ROPE
+    const f16_t *P[3];  // fragment-order copies of W[0..2] (gemm_tiled_dma_kernel), or all NULL
+    int ksteps;         // 16-element k-steps of a packed weight row: ceil(K / 16)
 };
 
 // EPI (GemmEpilogue) is a template parameter: each epilogue gets a kernel of its own, so that the registers one of them
 // needs after the loop do not change the allocation inside the loop of the others.
-template <int WM, int WN, int EPI>
-__global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, HALF_N = WN * 32;
-    constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;  // 16-byte loads per thread per chunk
-    f16_t *as = reinterpret_cast<f16_t *>(smem);                    // [2][BM][72]
-    f16_t *bs = as + 2 * BM * TG_LDS_STRIDE;                         // [2][BN][72]
-    const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
-    const int K = p.K;
+// Which tile a workgroup computes, and where its two column halves come from.
+struct TileCtx {
+    int m0;                                 // first activation row
+    int seg_h[2], nbase_h[2], ocol_h[2];    // per column half: weight matrix, first weight row, first output column
+};
 
+template <int WM, int WN, int EPI>
+__device__ __forceinline__ TileCtx tile_setup(const TiledParams &p) {
+    constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, HALF_N = WN * 32;
     // ---- XCD-aware tile order: consecutive logical ids live on one XCD; walk tiles in groups of 8 rows
     int nwg = p.tiles_m * p.tiles_n;
     int bid = blockIdx.x;
@@ -65,130 +66,29 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
     int tile_n = in_group / gsize;
 
     // ---- weight rows of each half of the B tile (half h belongs to wavefront column h)
-    int seg_h[2], nbase_h[2], ocol_h[2];
+    TileCtx c;
     if (EPI == EPI_SWIGLU) {
-        for (int h = 0; h < 2; ++h) { seg_h[h] = h; nbase_h[h] = tile_n * HALF_N; ocol_h[h] = tile_n * HALF_N; }
+        for (int h = 0; h < 2; ++h) { c.seg_h[h] = h; c.nbase_h[h] = tile_n * HALF_N; c.ocol_h[h] = tile_n * HALF_N; }
     } else {
         int seg = tile_n >= p.tile_begin[2] ? 2 : (tile_n >= p.tile_begin[1] ? 1 : 0);
         for (int h = 0; h < 2; ++h) {
-            seg_h[h] = seg;
-            nbase_h[h] = (tile_n - p.tile_begin[seg]) * BN + h * HALF_N;
-            ocol_h[h] = p.col_off[seg] + nbase_h[h];
+            c.seg_h[h] = seg;
+            c.nbase_h[h] = (tile_n - p.tile_begin[seg]) * BN + h * HALF_N;
+            c.ocol_h[h] = p.col_off[seg] + c.nbase_h[h];
         }
     }
-    const int m0 = tile_m * BM;
+    c.m0 = tile_m * BM;
+    return c;
 
-    // loader mapping: thread -> (row t/8 + 32*i, 16-byte group t%8).  Range-checked buffer loads: rows past
-    // the matrix and K columns past the end get an offset outside the descriptor and come back as zeros,
-    // so the loop needs no branches and the count of outstanding loads is the same on every trip.
-    const int lc = t & 7, lr = t >> 3;
-    constexpr uint32_t OOB = 0xFFFFFF00u;
-    __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<f16_t *>(p.A), 0, (int)p.a_bytes, 0x00020000);
-    uint32_t a_off[A_LOADS];
-#pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) {
-        int row = m0 + lr + 32 * i;
-        a_off[i] = row < p.M ? (uint32_t)((size_t)row * p.lda * 2) + (uint32_t)lc * 16u : OOB;
-    }
-    // B rows of the two halves may come from different matrices: one descriptor per half
-    __amdgpu_buffer_rsrc_t b_rs[2];
-    uint32_t b_off[B_LOADS];
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh)
-        b_rs[hh] = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg_h[hh]]), 0,
-                                                      (int)(uint32_t)((size_t)p.rows[seg_h[hh]] * K * 2), 0x00020000);
-#pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) {
-        int r = lr + 32 * i;
-        int hh = r / HALF_N;
-        int row = nbase_h[hh] + (r - hh * HALF_N);
-        int rows = p.rows[seg_h[hh]];
-        b_off[i] = (uint32_t)(row < rows ? row : 0) * (uint32_t)K * 2u + (uint32_t)lc * 16u;  // clamped rows are never stored
-    }
-    u32x4_t ar[A_LOADS], br[B_LOADS];
-    f32x16_t acc[WM][WN];
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+}
 
-    // Trip c covers K chunk c % chunks of activation term c / chunks: with two terms the contraction runs over
-    // [A | A_lo] against [W | W], so both products land in the same accumulators.
-    const int trips = p.chunks * p.terms;
-    auto load_a1 = [&](int c, int i) {
-        int term = c >= p.chunks ? 1 : 0, ck = c - term * p.chunks;
-        uint32_t kb = (uint32_t)ck * (TG_BK * 2) + (term ? p.lo_delta : 0u);
-        bool kok = c < trips && ck * TG_BK + lc * 8 < K;
-        ar[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)(kok && a_off[i] != OOB ? a_off[i] + kb : OOB), 0, 0);
-    };
-    auto load_b1 = [&](int c, int i) {
-        int ck = c >= p.chunks ? c - p.chunks : c;
-        uint32_t kb = (uint32_t)ck * (TG_BK * 2);
-        bool kok = c < trips && ck * TG_BK + lc * 8 < K;
-        // piece i belongs to half (32 i) / HALF_N: a compile-time choice of descriptor
-        br[i] = __builtin_amdgcn_raw_buffer_load_b128((32 * i) / HALF_N == 0 ? b_rs[0] : b_rs[1], (int)(kok ? b_off[i] + kb : OOB), 0, 0);
-    };
-    auto store_a1 = [&](int buf, int i) {
-        *reinterpret_cast<u32x4_t *>(as + buf * BM * TG_LDS_STRIDE + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = ar[i];
-    };
-    auto store_b1 = [&](int buf, int i) {
-        *reinterpret_cast<u32x4_t *>(bs + buf * BN * TG_LDS_STRIDE + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = bf16x8_to_f16x8(br[i]);
-    };
-
-    // One K chunk: 4 k-steps of WM*WN MFMAs on the tiles staged one chunk ago.  Interleaved with them, piece by
-    // piece: LDS fragments of the next k-step, the next chunk's operands registers -> LDS (weights widened on the
-    // way), and the loads of the chunk after next into the registers just freed -- so the matrix cores, the LDS
-    // and the memory pipeline overlap although only one wavefront runs per SIMD.
-    constexpr int APS = A_LOADS / 4, BPS = B_LOADS / 4;  // pieces staged per k-step
-    auto body = [&](int c, auto par_tag) {
-        constexpr int PAR = decltype(par_tag)::value;
-        __syncthreads();  // tiles of chunk c are in LDS buffer PAR; buffer PAR^1 is free
-        const f16_t *ap = as + PAR * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
-        const f16_t *bp = bs + PAR * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
-        f16x8_t af[2][WM], bf[2][WN];
-#pragma unroll
-        for (int i = 0; i < WM; ++i) af[0][i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE);
-#pragma unroll
-        for (int j = 0; j < WN; ++j) bf[0][j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (s + 1 < 4) {
-#pragma unroll
-                for (int i = 0; i < WM; ++i)
-                    af[(s + 1) & 1][i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + (s + 1) * 16);
-#pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    bf[(s + 1) & 1][j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + (s + 1) * 16);
-            }
-#pragma unroll
-            for (int i = 0; i < WM; ++i)
-#pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s & 1][i], bf[s & 1][j], acc[i][j], 0, 0, 0);
-#pragma unroll
-            for (int q = 0; q < APS; ++q) { store_a1(PAR ^ 1, s * APS + q); load_a1(c + 2, s * APS + q); }
-#pragma unroll
-            for (int q = 0; q < BPS; ++q) { store_b1(PAR ^ 1, s * BPS + q); load_b1(c + 2, s * BPS + q); }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-#pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) load_a1(0, i);
-#pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) load_b1(0, i);
-#pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) { store_a1(0, i); load_a1(1, i); }
-#pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) { store_b1(0, i); load_b1(1, i); }
-    __builtin_amdgcn_sched_barrier(0);
-    for (int c = 0; c < trips; c += 2) {
-        body(c, std::integral_constant<int, 0>{});
-        body(c + 1, std::integral_constant<int, 1>{});  // past the end: multiplies zero tiles
-    }
-
+// Epilogue shared by the main-loop variants.  The four wavefronts form a 2 x 2 grid (wm, wn); acc[i][j] is the 32 x 32
+// tile (wm * WM + i, wn * WN + j) of the workgroup's output.
+template <int WM, int WN, int EPI>
+__device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileCtx &c, f32x16_t (&acc)[WM][WN], unsigned char *smem) {
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
+    const int m0 = c.m0;
+    const int *seg_h = c.seg_h, *nbase_h = c.nbase_h, *ocol_h = c.ocol_h;
     // ---- epilogue.  Lane holds column (lane & 31) of each 32x32 tile; register e is row
     //      (e/4)*8 + (lane>>5)*4 + (e%4).
     const int rows_w = p.rows[seg_h[wn]];
@@ -362,6 +262,314 @@ __global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p
 }
 
 template <int WM, int WN, int EPI>
+__global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_kernel(TiledParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, HALF_N = WN * 32;
+    constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;  // 16-byte loads per thread per chunk
+    f16_t *as = reinterpret_cast<f16_t *>(smem);                    // [2][BM][72]
+    f16_t *bs = as + 2 * BM * TG_LDS_STRIDE;                         // [2][BN][72]
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
+    const int K = p.K;
+
+    const TileCtx ctx = tile_setup<WM, WN, EPI>(p);
+    const int m0 = ctx.m0;
+    const int *seg_h = ctx.seg_h, *nbase_h = ctx.nbase_h;
+
+    // loader mapping: thread -> (row t/8 + 32*i, 16-byte group t%8).  Range-checked buffer loads: rows past
+    // the matrix and K columns past the end get an offset outside the descriptor and come back as zeros,
+    // so the loop needs no branches and the count of outstanding loads is the same on every trip.
+    const int lc = t & 7, lr = t >> 3;
+    constexpr uint32_t OOB = 0xFFFFFF00u;
+    __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<f16_t *>(p.A), 0, (int)p.a_bytes, 0x00020000);
+    uint32_t a_off[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        int row = m0 + lr + 32 * i;
+        a_off[i] = row < p.M ? (uint32_t)((size_t)row * p.lda * 2) + (uint32_t)lc * 16u : OOB;
+    }
+    // B rows of the two halves may come from different matrices: one descriptor per half
+    __amdgpu_buffer_rsrc_t b_rs[2];
+    uint32_t b_off[B_LOADS];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+        b_rs[hh] = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.W[seg_h[hh]]), 0,
+                                                      (int)(uint32_t)((size_t)p.rows[seg_h[hh]] * K * 2), 0x00020000);
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+        int r = lr + 32 * i;
+        int hh = r / HALF_N;
+        int row = nbase_h[hh] + (r - hh * HALF_N);
+        int rows = p.rows[seg_h[hh]];
+        b_off[i] = (uint32_t)(row < rows ? row : 0) * (uint32_t)K * 2u + (uint32_t)lc * 16u;  // clamped rows are never stored
+    }
+    u32x4_t ar[A_LOADS], br[B_LOADS];
+    f32x16_t acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // Trip c covers K chunk c % chunks of activation term c / chunks: with two terms the contraction runs over
+    // [A | A_lo] against [W | W], so both products land in the same accumulators.
+    const int trips = p.chunks * p.terms;
+    auto load_a1 = [&](int c, int i) {
+        int term = c >= p.chunks ? 1 : 0, ck = c - term * p.chunks;
+        uint32_t kb = (uint32_t)ck * (TG_BK * 2) + (term ? p.lo_delta : 0u);
+        bool kok = c < trips && ck * TG_BK + lc * 8 < K;
+        ar[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, (int)(kok && a_off[i] != OOB ? a_off[i] + kb : OOB), 0, 0);
+    };
+    auto load_b1 = [&](int c, int i) {
+        int ck = c >= p.chunks ? c - p.chunks : c;
+        uint32_t kb = (uint32_t)ck * (TG_BK * 2);
+        bool kok = c < trips && ck * TG_BK + lc * 8 < K;
+        // piece i belongs to half (32 i) / HALF_N: a compile-time choice of descriptor
+        br[i] = __builtin_amdgcn_raw_buffer_load_b128((32 * i) / HALF_N == 0 ? b_rs[0] : b_rs[1], (int)(kok ? b_off[i] + kb : OOB), 0, 0);
+    };
+    auto store_a1 = [&](int buf, int i) {
+        *reinterpret_cast<u32x4_t *>(as + buf * BM * TG_LDS_STRIDE + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = ar[i];
+    };
+    auto store_b1 = [&](int buf, int i) {
+        *reinterpret_cast<u32x4_t *>(bs + buf * BN * TG_LDS_STRIDE + (lr + 32 * i) * TG_LDS_STRIDE + lc * 8) = bf16x8_to_f16x8(br[i]);
+    };
+
+    // One K chunk: 4 k-steps of WM*WN MFMAs on the tiles staged one chunk ago.  Interleaved with them, piece by
+    // piece: LDS fragments of the next k-step, the next chunk's operands registers -> LDS (weights widened on the
+    // way), and the loads of the chunk after next into the registers just freed -- so the matrix cores, the LDS
+    // and the memory pipeline overlap although only one wavefront runs per SIMD.
+    constexpr int APS = A_LOADS / 4, BPS = B_LOADS / 4;  // pieces staged per k-step
+    auto body = [&](int c, auto par_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        __syncthreads();  // tiles of chunk c are in LDS buffer PAR; buffer PAR^1 is free
+        const f16_t *ap = as + PAR * BM * TG_LDS_STRIDE + (wm * WM * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        const f16_t *bp = bs + PAR * BN * TG_LDS_STRIDE + (wn * WN * 32 + (lane & 31)) * TG_LDS_STRIDE + (lane >> 5) * 8;
+        f16x8_t af[2][WM], bf[2][WN];
+#pragma unroll
+        for (int i = 0; i < WM; ++i) af[0][i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE);
+#pragma unroll
+        for (int j = 0; j < WN; ++j) bf[0][j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            if (s + 1 < 4) {
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+                    af[(s + 1) & 1][i] = *reinterpret_cast<const f16x8_t *>(ap + i * 32 * TG_LDS_STRIDE + (s + 1) * 16);
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    bf[(s + 1) & 1][j] = *reinterpret_cast<const f16x8_t *>(bp + j * 32 * TG_LDS_STRIDE + (s + 1) * 16);
+            }
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s & 1][i], bf[s & 1][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < APS; ++q) { store_a1(PAR ^ 1, s * APS + q); load_a1(c + 2, s * APS + q); }
+#pragma unroll
+            for (int q = 0; q < BPS; ++q) { store_b1(PAR ^ 1, s * BPS + q); load_b1(c + 2, s * BPS + q); }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) load_a1(0, i);
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) load_b1(0, i);
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) { store_a1(0, i); load_a1(1, i); }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) { store_b1(0, i); load_b1(1, i); }
+    __builtin_amdgcn_sched_barrier(0);
+    for (int c = 0; c < trips; c += 2) {
+        body(c, std::integral_constant<int, 0>{});
+        body(c + 1, std::integral_constant<int, 1>{});  // past the end: multiplies zero tiles
+    }
+
+    tiled_epilogue<WM, WN, EPI>(p, ctx, acc, smem);
+}
+
+// ---------------------------------------------------------------------------------------------------------------------
+// The same tile computation with both operands copied global -> LDS by the load unit itself (buffer_load ... lds): no
+// staging registers, no ds_write, no bf16 -> half conversion in the loop.  Needs the weights as half in matrix-core
+// fragment order (the copies the decode step streams): a B fragment is then 1 KB of consecutive bytes in memory and in
+// LDS.  K is walked in stages of 32 through a ring of four stages (three in flight while one is consumed): a wavefront
+// waits on its own load counter for the oldest stage, the barrier then makes every wavefront's part of it visible.
+// Activation rows are 64 bytes per stage; their 16-byte pieces are stored XOR-permuted (piece ^ (row / 4 & 3)), so a fragment
+// read -- 16 consecutive rows, same piece, in the 16 lanes served together -- covers all 64 banks.
+#define TD_STAGES 4
+#define TD_SK 32
+#define TD_A_BYTES (256 * TD_SK * 2)
+#define TD_STAGE_BYTES (2 * TD_A_BYTES)
+#define TD_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+template <int EPI>
+__global__ __launch_bounds__(TG_THREADS, 1) void gemm_tiled_dma_kernel(TiledParams p) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    constexpr int WM = 4, WN = 4;
+    const int t = threadIdx.x, lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 1, wn = w & 1;
+    const int K = p.K;
+    const TileCtx ctx = tile_setup<WM, WN, EPI>(p);
+    // A voffset at or above 2^31 is out of range for every descriptor used here (the launcher keeps them below 2 GB) and
+    // stays so with any scalar offset added: such a copy writes zeros.
+    constexpr uint32_t OOB = 0x80000000u;
+
+    // ---- copy plan.  A stage holds A[256 rows][32 k] (16 KB) and B as 8 column blocks x 2 k-steps of 1 KB fragments (16 KB).
+    //      Wavefront w issues copy instructions 4 w .. 4 w + 3 of each operand.  Per lane and instruction a fixed byte
+    //      offset (voffset); what moves with the stage is a scalar offset, the same for the whole wavefront.
+    __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<f16_t *>(p.A), 0, (int)p.a_bytes, 0x00020000);
+    uint32_t a_vo[4];  // this lane's 16-byte piece of its row, chunk 0, term 0
+    int a_lim[4];      // the piece holds data while 32 * chunk < a_lim (0 for rows past M: never)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int r = 16 * (4 * w + q) + (lane >> 2);  // row of the tile
+        const int piece = (lane & 3) ^ ((r >> 2) & 3);
+        a_vo[q] = (uint32_t)((size_t)(ctx.m0 + r) * p.lda * 2) + (uint32_t)piece * 16u;
+        a_lim[q] = ctx.m0 + r < p.M ? K - piece * 8 : 0;
+
+    }
+    // B: fragment f = 4 w + q of a stage is column block f / 2 of the tile (blocks 0..3: half 0, 4..7: half 1), k-step f % 2
+    __amdgpu_buffer_rsrc_t b_rs[4];
+    uint32_t b_vo[4];
+    int b_ks[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int f = 4 * w + q, blk = f >> 1, hh = blk >> 2;
+        const int seg = ctx.seg_h[hh];
+        const int nblk = ctx.nbase_h[hh] / 32 + (blk & 3);  // 32-row block within its matrix
+        const int nblocks = (p.rows[seg] + 31) / 32;
+        // (the descriptor must sit in scalar registers: say so, or every copy instruction is wrapped in a loop over distinct values)
+        const uint64_t pa = (uint64_t)p.P[seg];
+        const uint32_t pa_lo = __builtin_amdgcn_readfirstlane((uint32_t)pa), pa_hi = __builtin_amdgcn_readfirstlane((uint32_t)(pa >> 32));
+        const uint32_t pbytes = __builtin_amdgcn_readfirstlane((uint32_t)((size_t)nblocks * p.ksteps * 1024));
+        b_rs[q] = __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)pa_hi << 32) | pa_lo), 0, (int)pbytes, 0x00020000);
+        b_ks[q] = f & 1;
+        b_vo[q] = nblk < nblocks ? (uint32_t)(((size_t)nblk * p.ksteps + b_ks[q]) * 1024) + (uint32_t)lane * 16u : OOB;
+
+    }
+    const int chunks = (K + TD_SK - 1) / TD_SK;  // stages per activation term
+    const int trips = chunks * p.terms;
+    // what a stage's copies share: computed once per stage in scalar registers
+    struct StageScalars { int k32; int ks2; uint32_t a_so, b_so; };
+    auto stage_scalars = [&](int c) {
+        StageScalars z;
+        const int term = c >= chunks ? 1 : 0, ck = c - term * chunks;
+        const bool live = c < trips;
+        z.k32 = live ? ck * TD_SK : 0x7fffffff;   // past the last stage: every piece is "beyond K"
+        z.ks2 = live ? 2 * ck : 0x3fffffff;
+        z.a_so = live ? (uint32_t)ck * (TD_SK * 2) + (term ? p.lo_delta : 0u) : 0u;
+        z.b_so = live ? (uint32_t)ck * 2048u : 0u;
+        return z;
+    };
+    auto issue_a = [&](const StageScalars &z, int stage, int q) {
+        unsigned char *ad = smem + stage * TD_STAGE_BYTES + (4 * w + q) * 1024;
+        const uint32_t vo = z.k32 < a_lim[q] ? a_vo[q] : OOB;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, TD_LDS_PTR(ad), 16, (int)vo, (int)z.a_so, 0, 0);
+#else
+        (void)ad; (void)vo;
+#endif
+    };
+    auto issue_b = [&](const StageScalars &z, int stage, int q) {
+        unsigned char *bd = smem + stage * TD_STAGE_BYTES + TD_A_BYTES + (4 * w + q) * 1024;
+        const uint32_t vo = z.ks2 + b_ks[q] < p.ksteps ? b_vo[q] : OOB;
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rs[q], TD_LDS_PTR(bd), 16, (int)vo, (int)z.b_so, 0, 0);
+#else
+        (void)bd; (void)vo;
+#endif
+    };
+    auto issue = [&](int c, int stage) {
+        const StageScalars z = stage_scalars(c);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { issue_a(z, stage, q); issue_b(z, stage, q); }
+    };
+
+    // ---- fragment addresses within a stage
+    int a_ld[WM][2];  // row tile i, k-step s: row wm * 128 + 32 i + (lane & 31), piece 2 s + (lane >> 5)
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int row = wm * 128 + 32 * i + (lane & 31);
+            a_ld[i][s2] = row * 64 + (((2 * s2 + (lane >> 5)) ^ ((row >> 2) & 3)) << 4);
+        }
+    const int b_ld = TD_A_BYTES + wn * 8 * 1024 + lane * 16;  // column tile j, k-step s: + (2 j + s) * 1024
+
+    f32x16_t acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // One wavefront per SIMD: whatever it issues that is not a matrix-core instruction delays the next one, unless it sits
+    // in the shadow of one (32 cycles each).  So the loop is written as the instruction order it should have: after each
+    // of the 16 matrix instructions of a k-step one small piece of other work -- a fragment read for the next k-step (into
+    // the other half of a register ping-pong), or one copy instruction of the stage three ahead -- with scheduling
+    // fences between, so that the compiler keeps the order.
+    f16x8_t af[2][WM], bf[2][WN];
+    auto read_a = [&](int stage, int s2, int buf, int i) {
+        af[buf][i] = *reinterpret_cast<const f16x8_t *>(smem + stage * TD_STAGE_BYTES + a_ld[i][s2]);
+    };
+    auto read_b = [&](int stage, int s2, int buf, int j) {
+        bf[buf][j] = *reinterpret_cast<const f16x8_t *>(smem + stage * TD_STAGE_BYTES + b_ld + (2 * j + s2) * 1024);
+    };
+    auto multiply = [&](int buf, int n) {
+        const int i = n >> 2, j = n & 3;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[buf][i], bf[buf][j], acc[i][j], 0, 0, 0);
+    };
+    // (a bare barrier instruction: the workgroup barrier of the language also waits for every outstanding load, which
+    //  would end the overlap of the copies with the arithmetic; the explicit counter wait says what has to have landed)
+    constexpr int YOUNGER = 8 * (TD_STAGES - 2);  // copy instructions of the two stages younger than the one waited for
+    constexpr int WAIT_STAGE = (YOUNGER & 15) | (7 << 4) | (0 << 8) | ((YOUNGER >> 4) << 14);  // vmcnt(YOUNGER), lgkmcnt(0)
+#pragma unroll
+    for (int k = 0; k < TD_STAGES - 1; ++k) issue(k, k);
+    __builtin_amdgcn_s_waitcnt(WAIT_STAGE);
+    __builtin_amdgcn_s_barrier();  // chunk 0 is in stage 0 for every wavefront
+    issue(TD_STAGES - 1, TD_STAGES - 1);
+#pragma unroll
+    for (int n = 0; n < 4; ++n) { read_b(0, 0, 0, n); read_a(0, 0, 0, n); }
+    __builtin_amdgcn_sched_barrier(0);
+    for (int c0 = 0; c0 < trips; c0 += TD_STAGES) {
+#pragma unroll
+        for (int k = 0; k < TD_STAGES; ++k) {  // unrolled: stage offsets become immediates
+            if (c0 + k < trips) {               // uniform over the workgroup
+                // k-step 0 of stage k (fragments: ping), reading k-step 1 (pong)
+#pragma unroll
+                for (int n = 0; n < 16; ++n) {
+                    multiply(0, n);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (n < 4) read_b(k, 1, 1, n);
+                    else if (n < 8) read_a(k, 1, 1, n - 4);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // chunk c0 + k + 1 has landed for this wavefront, and its own reads of stage k are complete ...
+                __builtin_amdgcn_s_waitcnt(WAIT_STAGE);
+                __builtin_amdgcn_s_barrier();  // ... and for every wavefront: stage k is free, stage k + 1 is readable
+                __builtin_amdgcn_sched_barrier(0);
+                // k-step 1 (pong), reading k-step 0 of stage k + 1 (ping) and refilling stage k with chunk c0 + k + 4
+                const StageScalars z = stage_scalars(c0 + k + TD_STAGES);
+#pragma unroll
+                for (int n = 0; n < 16; ++n) {
+                    multiply(1, n);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (n < 4) read_b((k + 1) % TD_STAGES, 0, 0, n);
+                    else if (n < 8) read_a((k + 1) % TD_STAGES, 0, 0, n - 4);
+                    else if (n < 12) issue_a(z, k, n - 8);
+                    else issue_b(z, k, n - 12);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (15 << 8) | (0 << 14));  // no copy may still be writing LDS
+    __syncthreads();
+    tiled_epilogue<WM, WN, EPI>(p, ctx, acc, smem);
+}
+
+template <int WM, int WN, int EPI>
 static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
     constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
     int tiles = 0, col = 0;
@@ -391,6 +599,18 @@ static void launch_t(TiledParams &p, const GemmArgs &a, hipStream_t st) {
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
+    if (WM == 4 && WN == 4 && p.P[0]) {
+        size_t dlds = (size_t)TD_STAGES * TD_STAGE_BYTES;
+        if (lds > dlds) dlds = lds;
+        static bool dma_attr_set = false;
+        if (!dma_attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tiled_dma_kernel<EPI>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            dma_attr_set = true;
+        }
+        gemm_tiled_dma_kernel<EPI><<<p.tiles_m * p.tiles_n, TG_THREADS, dlds, st>>>(p);
+        return;
+    }
     gemm_tiled_kernel<WM, WN, EPI><<<p.tiles_m * p.tiles_n, TG_THREADS, lds, st>>>(p);
 }
 
@@ -413,11 +633,21 @@ static void launch_one(const GemmArgs &a, hipStream_t st) {
     p.out = a.out;
     p.ldc = a.ldc;
     int n_total = 0;
+    bool have_p = a.P[0] != nullptr;
     for (int i = 0; i < 3; ++i) {
         p.W[i] = a.W[i] ? a.W[i] : a.W[0];
         p.rows[i] = a.W[i] ? a.rows[i] : 0;
         n_total += p.rows[i];
+        if (a.W[i] && !a.P[i]) have_p = false;
     }
+    p.ksteps = ceil_div(a.K, 16);
+    if (p.a_bytes >= 0x80000000u) have_p = false;
+    for (int i = 0; i < 3; ++i) {
+        // fragment-order copies are used when every matrix has one and every operand stays below 2 GB (the kernel marks
+        // a copy as out of range with bit 31 of its offset)
+        if (a.W[i] && have_p && (size_t)ceil_div(p.rows[i], 32) * p.ksteps * 1024 >= 0x80000000ull) have_p = false;
+    }
+    for (int i = 0; i < 3; ++i) p.P[i] = have_p ? (a.P[i] ? a.P[i] : a.P[0]) : nullptr;
     // big tiles only when they still give every compute unit work
     long big_tiles = (long)ceil_div(a.M, 256) * ceil_div(n_total, 256);
     const bool big = a.M >= 1024 && big_tiles >= 256;
@@ -477,6 +707,7 @@ void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
     if (a.epilogue == EPI_SWIGLU) {  // gate and up blocks of the same output columns go together
         for (int n = 0; n < a.rows[0]; n += rows_max) {
             GemmArgs s = a;
+            s.P[0] = s.P[1] = s.P[2] = nullptr;  // row blocks of the weights: the fragment-order copies are not cut along
             int r = a.rows[0] - n < rows_max ? a.rows[0] - n : rows_max;
             s.W[0] = a.W[0] + (size_t)n * a.K;
             s.W[1] = a.W[1] + (size_t)n * a.K;
@@ -491,6 +722,7 @@ void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
         if (!a.W[i] || a.rows[i] <= 0) continue;
         for (int n = 0; n < a.rows[i]; n += rows_max) {
             GemmArgs s = a;
+            s.P[0] = s.P[1] = s.P[2] = nullptr;
             s.W[0] = a.W[i] + (size_t)n * a.K;
             s.rows[0] = a.rows[i] - n < rows_max ? a.rows[i] - n : rows_max;
             s.W[1] = s.W[2] = nullptr;

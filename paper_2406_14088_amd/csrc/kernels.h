@@ -82,6 +82,9 @@ struct GemmArgs {
     int splits;           // split-K factor (>= 1)
     int epilogue;
     const RopeEpilogue *rope = nullptr;  // EPI_ROPE
+    // tiled kernel only, optional: fragment-order half copies of W[0..2] (as written by launch_pack_weights).  When every
+    // W_i has one, large tiles copy both operands global -> LDS directly instead of staging them through registers.
+    const f16_t *P[3] = {nullptr, nullptr, nullptr};
 };
 // M <= 256: weights stream through registers exactly once, activations are staged in LDS.
 void launch_gemm_skinny(const GemmArgs &a, hipStream_t st);

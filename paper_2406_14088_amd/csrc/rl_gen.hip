@@ -232,12 +232,16 @@ int project_packed(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_
 
 // One projection.  Returns the number of fp32 partials written to h->part() (0 when the result was
 // accumulated straight into `acc_out`).
+// P0..P2: the matrices' fragment-order copies where they exist (the large-M kernel then copies both operands straight
+// into LDS; same results).
 int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, int M, int K, const bf16_t *W0, int r0,
-            const bf16_t *W1, int r1, const bf16_t *W2, int r2, float *acc_out, int64_t ld_acc, hipStream_t st) {
+            const bf16_t *W1, int r1, const bf16_t *W2, int r2, float *acc_out, int64_t ld_acc, hipStream_t st,
+            const f16_t *P0 = nullptr, const f16_t *P1 = nullptr, const f16_t *P2 = nullptr) {
     GemmArgs a;
     a.A = A; a.lda = lda; a.M = M; a.K = K;
     a.A_lo = M > kSkinnyMaxM ? A_lo : nullptr;  // second activation term: large-M kernel only
     a.W[0] = W0; a.W[1] = W1; a.W[2] = W2;
+    a.P[0] = P0; a.P[1] = P1; a.P[2] = P2;
     a.rows[0] = r0; a.rows[1] = r1; a.rows[2] = r2;
     int N = r0 + r1 + r2;
     Scope sc(h, cls, st);
@@ -281,6 +285,7 @@ void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
     GemmArgs a;
     a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
     a.W[0] = h->lw[W_GATE][l]; a.W[1] = h->lw[W_UP][l]; a.W[2] = nullptr;
+    if (h->packed && l < h->packed_gu_layers) { a.P[0] = h->pw[W_GATE][l]; a.P[1] = h->pw[W_UP][l]; }
     a.rows[0] = h->s.ffn; a.rows[1] = h->s.ffn; a.rows[2] = 0;
     a.out = h->act(); a.ldc = h->s.ffn; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
     Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
@@ -328,6 +333,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             GemmArgs a;
             a.A = h->h(); a.A_lo = h_lo; a.lda = d; a.M = M; a.K = d;
             a.W[0] = h->lw[W_Q][l]; a.W[1] = h->lw[W_K][l]; a.W[2] = h->lw[W_V][l];
+            if (h->packed) { a.P[0] = h->pw[W_Q][l]; a.P[1] = h->pw[W_K][l]; a.P[2] = h->pw[W_V][l]; }
             a.rows[0] = qd; a.rows[1] = kvd; a.rows[2] = kvd;
             a.out = nullptr; a.ldc = 0; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_ROPE; a.rope = &rp;
             {
@@ -338,7 +344,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             ns = 0;
         } else if (M > kSkinnyMaxM)  // large-M kernel: one contraction over [h | h_lo] x [W | W]
             ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
-                         nullptr, 0, st);
+                         nullptr, 0, st, h->packed ? h->pw[W_Q][l] : nullptr, h->packed ? h->pw[W_K][l] : nullptr,
+                         h->packed ? h->pw[W_V][l] : nullptr);
         else  // row-major skinny kernel: stacked rows [h; h_lo], the consumer adds the two row blocks
             ns = terms * project(h, RL_GEN_K_GEMM_QKV, h->h(), nullptr, d, terms * M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd,
                                  h->lw[W_V][l], kvd, nullptr, 0, st);
@@ -363,7 +370,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
                                      s.head_dim, s.max_seq, st, map, d_valid);
         }
         if (pk) ns = project_packed(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->pw[W_O][l], d, nullptr, 0, nullptr, 0, st);
-        else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
+        else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st,
+                          h->packed ? h->pw[W_O][l] : nullptr);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), nullptr, M, d, st);
@@ -372,7 +380,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         if (pk)
             ns = project_packed(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->pw[W_DOWN][l], d, nullptr, 0, nullptr, 0, st);
         else
-            ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d, st);
+            ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d, st,
+                         h->packed ? h->pw[W_DOWN][l] : nullptr);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, l + 1 < L ? h->lw[W_ATTN_NORM][l + 1] : h->final_norm,
@@ -491,7 +500,9 @@ size_t rl_gen_packed_bytes_full(const rl_gen_shape *s) {
 
 int rl_gen_prefers_packed_gate_up(const rl_gen_shape *s) {
     if (validate(s) != RL_GEN_OK) return RL_GEN_E_SHAPE;
-    return packed_swiglu_wins(s->max_batch, s->ffn) ? 1 : 0;
+    // The prefill projection (thousands of rows) is faster from the copies at every width measured (7B shape, 16384
+    // rows: 2.88 against 3.09 ms per layer); steps of few rows use them where packed_swiglu_wins says so.
+    return 1;
 }
 
 int rl_gen_pack_weights(rl_gen_t *h, void *packed_arena, size_t packed_bytes, void *hip_stream) {
@@ -1137,7 +1148,29 @@ int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint1
     RL_OP_RETURN();
 }
 
+int rl_op_gemm_tiled_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *W0, const uint16_t *W1,
+                            const uint16_t *W2, const uint16_t *P0, const uint16_t *P1, const uint16_t *P2, int32_t rows0, int32_t rows1,
+                            int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, int32_t epilogue, void *st) {
+    if (!A || !W0 || !P0 || !out) return RL_GEN_E_NULL;
+    if (A_lo && (epilogue == EPI_SWIGLU || A_lo <= A)) return RL_GEN_E_SHAPE;
+    if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
+    if (epilogue < 0 || epilogue > 2) return RL_GEN_E_SHAPE;
+    if ((rows1 > 0 && (!W1 || !P1)) || (rows2 > 0 && (!W2 || !P2))) return RL_GEN_E_NULL;
+    if (epilogue == EPI_SWIGLU && (rows1 != rows0 || rows2 != 0)) return RL_GEN_E_SHAPE;
+    if ((uint64_t)rows0 * K * 2 > 0xffffffffull || (uint64_t)rows1 * K * 2 > 0xffffffffull || (uint64_t)rows2 * K * 2 > 0xffffffffull)
+        return RL_GEN_E_SHAPE;
+    GemmArgs a;
+    a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
+    a.W[0] = W0; a.W[1] = rows1 > 0 ? W1 : nullptr; a.W[2] = rows2 > 0 ? W2 : nullptr;
+    a.P[0] = P0; a.P[1] = rows1 > 0 ? P1 : nullptr; a.P[2] = rows2 > 0 ? P2 : nullptr;
+    a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
+    a.out = out; a.ldc = ldc; a.split_stride = 0; a.splits = 1; a.epilogue = epilogue;
+    launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
 int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *Wq, const uint16_t *Wk, const uint16_t *Wv,
+                    const uint16_t *Pq, const uint16_t *Pk, const uint16_t *Pv,
                     int32_t Hq, int32_t Hkv, int32_t hd, int32_t M, int32_t K, int32_t T, int32_t b0, const float *rope_tab,
                     int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *st) {
     if (!A || !Wq || !Wk || !Wv || !rope_tab || !q_f16 || !kc || !vc) return RL_GEN_E_NULL;
@@ -1153,6 +1186,7 @@ int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const 
     a.W[0] = Wq; a.W[1] = Wk; a.W[2] = Wv;
     a.rows[0] = Hq * hd; a.rows[1] = Hkv * hd; a.rows[2] = Hkv * hd;
     a.out = nullptr; a.ldc = 0; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_ROPE; a.rope = &rp;
+    if (Pq && Pk && Pv) { a.P[0] = Pq; a.P[1] = Pk; a.P[2] = Pv; }
     launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }

@@ -134,6 +134,46 @@ def pack(ops, W):
     return P
 
 
+TILED_PACKED_CASES = [
+    # M, K, rows, epilogue, two activation terms: all at least 256 tiles of 256 x 256 (below that the call runs rl_op_gemm's kernel)
+    (1100, 136, (16400,), 0, False), (1024, 256, (8192, 4200, 4100), 0, False), (1030, 200, (13100,), 0, True),
+    (1100, 72, (16400,), 2, False), (1281, 104, (300, 13000), 2, True), (1024, 128, (8200, 8200), 1, False), (1300, 1000, (6600, 6600), 1, False),
+]
+
+
+@pytest.mark.parametrize("M,K,rows,epilogue,two_terms", TILED_PACKED_CASES)
+def test_gemm_tiled_from_fragment_order_copies_equals_the_register_staged_kernel(ops, M, K, rows, epilogue, two_terms):
+    """Same products, same order of the sums over K: the direct-to-LDS main loop stores the bits the register-staged one does
+    (whose oracle parity its own tests establish); one output row is also checked against the oracle directly."""
+    step(f"tiled packed M={M} K={K} rows={rows} epilogue={epilogue} two_terms={two_terms}")
+    A = randn_f16(((2 if two_terms else 1) * M, K), 60 + M)
+    if two_terms:
+        A[M:] *= 2.0 ** -11
+    A_lo = A[M:] if two_terms else None
+    Ws = [randn_bf16((r, K), 61 + i, std=0.05) for i, r in enumerate(rows)]
+    Ps = [pack(ops, W) for W in Ws]
+    N = rows[0] if epilogue == 1 else sum(rows)
+    if epilogue == 1:
+        ref, out = (torch.zeros((M, N), dtype=torch.float16, device=DEV) for _ in range(2))
+    else:
+        base = randn_f32((M, N), 62)
+        ref, out = base.clone(), base.clone()
+    ops.gemm(A[:M], Ws, ref, N, M=M, epilogue=epilogue, kernel=2, A_lo=A_lo)
+    ops.gemm_tiled_packed(A[:M], Ws, Ps, out, N, M=M, epilogue=epilogue, A_lo=A_lo)
+    torch.cuda.synchronize()
+    bits_of = (lambda x: x.view(torch.int16)) if epilogue == 1 else (lambda x: x.view(torch.int32))
+    assert torch.equal(bits_of(out), bits_of(ref))
+    m = M - 3
+    x = np64(A[m]) + (np64(A[M + m]) if two_terms else 0.0)
+    y = [np64(W) @ x for W in Ws]
+    if epilogue == 1:
+        want = y[0] / (1.0 + np.exp(-y[0])) * y[1]
+        assert (np.abs(np64(out[m]) - want) <= 0.5 * F16_EPS * np.abs(want) * 1.02 + 2e-5).all()
+    else:
+        want = np.concatenate(y) + (np64(base[m]) if epilogue == 2 else 0.0)
+        assert np.abs(np64(out[m]) - want).max() <= 2e-6 * np.sqrt(K) * (np.abs(want).max() + 1.0)
+
+
 def f16_toward_zero(x32):
     """float32 -> float16, rounded toward zero (what the weight widening does; exact for normal halves)."""
     h = x32.astype(np.float16)
@@ -618,6 +658,12 @@ def test_qkv_projection_with_rotary_epilogue_equals_the_two_kernels(ops, Hq, Hkv
     assert torch.equal(q.view(torch.int16), q_ref.view(torch.int16))
     assert torch.equal(kc.view(torch.int16), kc_ref.view(torch.int16))
     assert torch.equal(vc.view(torch.int16), vc_ref.view(torch.int16))
+    # the same with both operands copied global -> LDS directly (fragment-order weight copies)
+    q2, kc2, vc2 = torch.zeros_like(q_ref), torch.zeros_like(kc_ref), torch.zeros_like(vc_ref)
+    ops.gemm_rope(A[:M], Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, tab, 1, S, q2, kc2, vc2, A_lo=A_lo, Ps=[pack(ops, W) for W in (Wq, Wk, Wv)])
+    torch.cuda.synchronize()
+    for got, want in ((q2, q_ref), (kc2, kc_ref), (vc2, vc_ref)):
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16))
     # one row against the oracle directly (sequence b0 + 7, position 11)
     m = 7 * T + 11
     x = np64(A[m]) + (np64(A[M + m]) if two_terms else 0.0)
