@@ -226,7 +226,10 @@ __global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_pa
         constexpr int YOUNGER = NBF + (NBUF - 2) * (TERMS * MT + NBF);
         static_assert(YOUNGER < 64, "vmcnt is a 6-bit counter");
         __builtin_amdgcn_s_waitcnt((YOUNGER & 15) | (7 << 4) | (15 << 8) | ((YOUNGER >> 4) << 14));  // vmcnt(YOUNGER) only
-        __syncthreads();  // the tile of chunk c has landed for every wavefront; buffer of chunk c-1 is free
+        // (the bare barrier instruction: before the language's workgroup barrier the compiler waits for every copy into LDS
+        //  still in flight, i.e. also for the younger ones and for the weight loads issued before them, which would cut
+        //  the distance the loads run ahead to one trip)
+        __builtin_amdgcn_s_barrier();  // the tile of chunk c has landed for every wavefront; buffer of chunk c-1 is free
         int nbuf = buf + NBUF - 1;
         if (nbuf >= NBUF) nbuf -= NBUF;
         copy_x(c + NBUF - 1, nbuf);
