@@ -174,6 +174,24 @@ def test_gemm_tiled_from_fragment_order_copies_equals_the_register_staged_kernel
         assert np.abs(np64(out[m]) - want).max() <= 2e-6 * np.sqrt(K) * (np.abs(want).max() + 1.0)
 
 
+def test_gemm_tiled_from_fragment_order_copies_with_a_row_stride(ops):
+    """Activation rows wider than K (a column slice of a larger buffer) and a K that ends inside a 32-wide stage."""
+    M, K, N, pad = 1040, 168, 16640, 24
+    buf = randn_f16((M, K + pad), 70)
+    A = buf[:, :K]
+    assert A.stride(0) == K + pad
+    W = randn_bf16((N, K), 71, std=0.05)
+    P = pack(ops, W)
+    ref = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    out = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    ops.gemm(A, [W], ref, N, M=M, epilogue=0, kernel=2)
+    ops.gemm_tiled_packed(A, [W], [P], out, N, M=M, epilogue=0)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), ref.view(torch.int32))
+    want = np64(A[M - 1]) @ np64(W).T
+    assert np.abs(np64(out[M - 1]) - want).max() <= 2e-6 * np.sqrt(K) * (np.abs(want).max() + 1.0)
+
+
 def f16_toward_zero(x32):
     """float32 -> float16, rounded toward zero (what the weight widening does; exact for normal halves)."""
     h = x32.astype(np.float16)
