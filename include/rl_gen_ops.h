@@ -90,6 +90,14 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
                       int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg,
                       int32_t depth, void *hip_stream);
 
+/* Fused gate/up projection of few rows from fragment-order copies, the two 64-wide halves of every 128-wide K chunk on
+ * separate wavefronts: out[M, F] (DEVICE half, row stride ldc) = silu(A Pg^T) * (A Pu^T), A DEVICE half [M, K] with row stride lda,
+ * Pg and Pu = rl_op_pack_weights of the gate and up matrices [F, K].  The sums are formed in the order of rl_op_gemm's kernel 1 with
+ * epilogue 1, so the two calls store the same bits.  depth: 128-wide weight chunks in flight per wavefront, 2 or 4 (0: 4).
+ * K % 8 == 0, lda % 8 == 0, each packed matrix below 3.75 GB; RL_GEN_E_SHAPE otherwise. */
+int rl_op_gemm_packed_swiglu_halves(const uint16_t *A, int64_t lda, const uint16_t *Pg, const uint16_t *Pu, int32_t F, int32_t M,
+                                    int32_t K, uint16_t *out, int64_t ldc, int32_t depth, void *hip_stream);
+
 /* Builds the rotary table the library uses: tab fp32 [max_seq, head_dim/2, 2] = (cos, sin) of
  * pos * base^(-2r/head_dim), evaluated in fp64 on the host and copied (synchronously) to `tab`. */
 int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float base);

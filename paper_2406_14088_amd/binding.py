@@ -93,6 +93,7 @@ def lib():
         "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, vp, i32, i32, vp]),
         "rl_op_gemm": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
         "rl_op_gemm_rope": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp]),
+        "rl_op_gemm_packed_swiglu_halves": (C.c_int, [vp, i64, vp, vp, i32, i32, i32, vp, i64, i32, vp]),
         "rl_op_gemm_tiled_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, i32, vp]),
         "rl_op_packed_weight_bytes": (sz, [i32, i32]),
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
@@ -123,7 +124,7 @@ EXPORTED_SYMBOLS = (
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
+    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_gemm_packed_swiglu_halves", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
@@ -456,6 +457,11 @@ class _Ops:
         self._ck(lib().rl_op_gemm_rope(A.data_ptr(), _ptr(A_lo), A.stride(0), Wq.data_ptr(), Wk.data_ptr(), Wv.data_ptr(), pq, pk, pv, Hq, Hkv, hd, M, K,
                                        T, b0, rope_tab.data_ptr(), rope_style, S, q_f16.data_ptr(), kc.data_ptr(), vc.data_ptr(), _stream()),
                  "rl_op_gemm_rope")
+
+    def gemm_packed_swiglu_halves(self, A, Pg, Pu, F, K, out, ldc, M=None, depth=0):
+        M = A.shape[0] if M is None else M
+        self._ck(lib().rl_op_gemm_packed_swiglu_halves(A.data_ptr(), A.stride(0), Pg.data_ptr(), Pu.data_ptr(), F, M, K, out.data_ptr(),
+                                                       ldc, depth, _stream()), "rl_op_gemm_packed_swiglu_halves")
 
     def packed_weight_bytes(self, N, K):
         return int(lib().rl_op_packed_weight_bytes(N, K))

@@ -397,6 +397,237 @@ static void launch_pm(PackedParams &p, int mt, int depth, hipStream_t st) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Fused gate/up projection for few rows, K halves on separate wavefronts
+// ---------------------------------------------------------------------------------------------------
+// out[M, F] = silu(A Wg^T) * (A Wu^T) for M <= 128 rows per workgroup, from the fragment-order copies.  The row-major
+// kernel of the same projection (gemm_skinny.hip) spends its time in LDS: every weight passes through a wavefront-private
+// LDS strip and every activation fragment is read by four wavefronts -- 224 KB of LDS traffic per 128-wide K chunk and
+// workgroup.  Here a workgroup of four wavefronts owns 64 gate + 64 up columns as (column half cw) x (K half kg):
+// wavefront (cw, kg) holds the gate block and the up block of columns 32 cw .. 32 cw + 31, takes their fragments straight
+// from memory and multiplies the half kg (64 elements) of every 128-wide K chunk; the activation chunk is copied
+// global -> LDS by the load unit and each half is read by two wavefronts: 96 KB per chunk.  At the end the kg = 1
+// wavefronts hand their sums to kg = 0 through LDS, which applies the SwiGLU.  The order of every sum -- the K half of
+// each chunk in ascending chunks, then half 0 + half 1 -- is that of the row-major kernel, and so are the results, bit for
+// bit.  One workgroup per compute unit (the register ring holds RC chunks of weight fragments: 8 KB each).
+#define PS_BK 128
+template <int RC, bool SW>
+__global__ __launch_bounds__(PK_THREADS, 1) void gemm_packed_swiglu_halves_kernel(PackedParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int MT = 4, BM = 128, NBUF = 3;
+    constexpr int XTILE = BM * 64 * 2;   // one 64-wide half of an activation chunk
+    constexpr int XBUF = 2 * XTILE;
+    const int t = threadIdx.x, lane = t & 63;
+    const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int cw = w & 1, kg = w >> 1;
+    const int K = p.K;
+
+    // workgroup id -> (column tile, row block): ids congruent mod 8 share an XCD, the row blocks of a tile get ids 8 apart
+    const int id = blockIdx.x;
+    const int tile = (id / (8 * p.zblocks)) * 8 + (id & 7);
+    const int zb = (id % (8 * p.zblocks)) >> 3;
+    if (tile >= p.tiles) return;  // padding of the id space (whole workgroup, before any barrier)
+    const int m0 = zb * BM;
+    const int Mloc = p.M - m0 < BM ? p.M - m0 : BM;
+    const int rows = p.rows[0];
+    const int nblocks = (rows + 31) >> 5;
+    const int nb = tile * 2 + cw;  // 32-row block of gate and of up
+    __amdgpu_buffer_rsrc_t wr[2];
+    wr[0] = pk_rsrc(p.P[0], (uint32_t)((size_t)nblocks * p.ksteps * 1024));
+    wr[1] = pk_rsrc(p.P[1], (uint32_t)((size_t)nblocks * p.ksteps * 1024));
+    const bool w_ok = nb < nblocks;
+    const uint32_t w_off = ((uint32_t)nb * (uint32_t)p.ksteps * 64u + (uint32_t)lane) * 16u;
+    const int trips = (K + PS_BK - 1) / PS_BK;
+
+    // activation copy: instruction i of wavefront w fills rows 8 (4 w + i) .. + 7 of one half; piece g of row r sits in
+    // slot g ^ ((r >> 1) & 7), as in gemm_packed_kernel
+    __amdgpu_buffer_rsrc_t ar = pk_rsrc(p.A, p.a_bytes);
+    uint32_t x_off[MT];
+    int x_piece[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        int row = (w * MT + i) * 8 + (lane >> 3);
+        x_piece[i] = (lane & 7) ^ ((row >> 1) & 7);
+        x_off[i] = row < Mloc ? (uint32_t)(m0 + row) * (uint32_t)p.lda_bytes + (uint32_t)x_piece[i] * 16u : PK_OOB;
+    }
+    auto copy_x = [&](int c, int buf) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                unsigned char *dst = smem + buf * XBUF + hf * XTILE + (w * MT + i) * 1024;
+                bool ok = c < trips && (c * PS_BK + hf * 64 + x_piece[i] * 8 < K);
+                uint32_t off = ok && x_off[i] != PK_OOB ? x_off[i] + (uint32_t)c * (PS_BK * 2) + (uint32_t)hf * 128u : PK_OOB;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(ar, LDS_PTR(dst), 16, (int)off, 0, 0, 0);
+#else
+                (void)dst; (void)off;
+#endif
+            }
+    };
+    int xld[4];
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2) xld[s2] = (lane & 31) * 128 + (((2 * s2 + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+
+    u32x4_t ring[RC * 8];  // slots (c % RC) * 8 + 2 s + j: k-step s of this wavefront's half of chunk c, j = 0 gate, 1 up
+    auto load_w = [&](int c, int s2, int j, int slot) {
+        int ks = c * 8 + kg * 4 + s2;
+        uint32_t off = (ks < p.ksteps && w_ok) ? w_off + (uint32_t)ks * 1024u : PK_OOB;
+        ring[slot] = __builtin_amdgcn_raw_buffer_load_b128(wr[j], (int)off, 0, SW ? 3 : 0);
+    };
+
+    f32x16_t acc[2][MT];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+    auto body = [&](int c, int buf, auto slot_tag) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        // the copy of chunk c was issued two trips ago, before that trip's 8 weight loads and the 16 loads of the last trip
+        constexpr int YOUNGER = 8 + 16;
+        __builtin_amdgcn_s_waitcnt((YOUNGER & 15) | (7 << 4) | (15 << 8) | ((YOUNGER >> 4) << 14));  // vmcnt(YOUNGER) only
+        __builtin_amdgcn_s_barrier();  // chunk c has landed for every wavefront; the buffer of chunk c - 1 is free
+        int nbuf = buf + NBUF - 1;
+        if (nbuf >= NBUF) nbuf -= NBUF;
+        copy_x(c + NBUF - 1, nbuf);
+        __builtin_amdgcn_sched_barrier(0);  // the copies stay ahead of this trip's weight loads in issue order
+        const unsigned char *xb = smem + buf * XBUF + kg * XTILE;
+        f16x8_t a[2][MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a[0][mt] = *reinterpret_cast<const f16x8_t *>(xb + xld[0] + mt * 4096);
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) {
+            if (s2 + 1 < 4) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) a[(s2 + 1) & 1][mt] = *reinterpret_cast<const f16x8_t *>(xb + xld[s2 + 1] + mt * 4096);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[j][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[s2 & 1][mt], __builtin_bit_cast(f16x8_t, ring[SLOT * 8 + 2 * s2 + j]),
+                                                                      acc[j][mt], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) load_w(c + RC, s2, j, SLOT * 8 + 2 * s2 + j);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    if (trips > 0) {
+#pragma unroll
+        for (int i = 0; i < NBUF - 1; ++i) copy_x(i, i);
+#pragma unroll
+        for (int i = 0; i < RC; ++i)
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) load_w(i, s2, j, i * 8 + 2 * s2 + j);
+        __builtin_amdgcn_sched_barrier(0);
+        int buf = 0;
+        for (int c = 0; c < trips; c += RC) {  // trips past the end multiply zero tiles
+            body(c, buf, std::integral_constant<int, 0>{});
+            buf = buf + 1 == NBUF ? 0 : buf + 1;
+            body(c + 1, buf, std::integral_constant<int, 1 % RC>{});
+            buf = buf + 1 == NBUF ? 0 : buf + 1;
+            if constexpr (RC == 4) {
+                body(c + 2, buf, std::integral_constant<int, 2 % RC>{});
+                buf = buf + 1 == NBUF ? 0 : buf + 1;
+                body(c + 3, buf, std::integral_constant<int, 3 % RC>{});
+                buf = buf + 1 == NBUF ? 0 : buf + 1;
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);  // copies issued for chunks past the end (zeros) must have landed before the memory is reused
+    __syncthreads();
+
+    // ---- half 0 + half 1: kg = 1 hands its sums to kg = 0 (same operand order as the row-major kernel)
+    float *ex = reinterpret_cast<float *>(smem);  // [2 column halves][2 MT 16][64 lanes]
+    if (kg == 1) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) ex[((cw * 2 + j) * MT * 16 + mt * 16 + e) * 64 + lane] = acc[j][mt][e];
+    }
+    __syncthreads();
+    f16_t *ht = reinterpret_cast<f16_t *>(smem + 2 * 2 * MT * 16 * 64 * 4);  // [BM][72] halves, after the exchange area
+    if (kg == 0) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float g = acc[0][mt][e], u = acc[1][mt][e];
+                g += ex[((cw * 2 + 0) * MT * 16 + mt * 16 + e) * 64 + lane];
+                u += ex[((cw * 2 + 1) * MT * 16 + mt * 16 + e) * 64 + lane];
+                int m = mt * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                ht[m * 72 + cw * 32 + (lane & 31)] = f32_to_f16(g / (1.0f + expf(-g)) * u);
+            }
+    }
+    __syncthreads();
+    f16_t *out = reinterpret_cast<f16_t *>(p.out);
+    const int c8 = (t & 7) * 8, rr = t >> 3;  // 8 lanes x 16 B = one 128-byte output row; 32 rows per pass
+    const int ncols = rows - tile * 64;
+#pragma unroll
+    for (int i = 0; i < BM / 32; ++i) {
+        int m = rr + 32 * i;
+        if (m < Mloc && c8 < ncols) {
+            f16_t *dst = out + (size_t)(m0 + m) * p.ldc + tile * 64 + c8;
+            const f16_t *srcp = ht + m * 72 + c8;
+            if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+                *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
+            } else {
+                for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+            }
+        }
+    }
+}
+
+template <int RC, bool SW>
+static void launch_halves(PackedParams &p, hipStream_t st) {
+    size_t lds = (size_t)3 * 2 * 128 * 64 * 2;  // three chunk buffers; the epilogue's exchange area and tile fit inside
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_swiglu_halves_kernel<RC, SW>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    int ids = ceil_div(p.tiles, 8) * 8 * p.zblocks;
+    gemm_packed_swiglu_halves_kernel<RC, SW><<<ids, PK_THREADS, lds, st>>>(p);
+}
+
+bool gemm_packed_swiglu_halves_supported(int F, int K) {
+    return F > 0 && K > 0 && (size_t)ceil_div(F, 32) * ceil_div(K, 16) * 1024 < PK_MAX_BYTES;
+}
+
+void launch_gemm_packed_swiglu_halves(const PackedGemmArgs &a, hipStream_t st) {
+    if (a.M <= 0) return;
+    PackedParams p = {};
+    p.A = a.A;
+    p.A_lo = nullptr;
+    p.lda_bytes = (int)(a.lda * 2);
+    p.a_bytes = (uint32_t)((((size_t)a.M - 1) * a.lda + a.K) * 2);
+    p.M = a.M;
+    p.K = a.K;
+    p.ksteps = ceil_div(a.K, 16);
+    p.chunks = ceil_div(a.K, PK_BK);
+    p.epilogue = EPI_SWIGLU;
+    p.splits = 1;
+    p.out = a.out;
+    p.ldc = a.ldc;
+    p.P[0] = a.P[0]; p.P[1] = a.P[1]; p.P[2] = a.P[0];
+    p.rows[0] = a.rows[0]; p.rows[1] = a.rows[0]; p.rows[2] = 0;
+    p.tiles = ceil_div(a.rows[0], 64);
+    p.zblocks = ceil_div(a.M, 128);
+    if (p.tiles <= 0) return;
+    const bool deep = a.depth != 2;
+    if (p.zblocks == 1) { if (deep) launch_halves<4, true>(p, st); else launch_halves<2, true>(p, st); }
+    else { if (deep) launch_halves<4, false>(p, st); else launch_halves<2, false>(p, st); }
+}
+
 // Decomposition of a projection with fp32 partial outputs.  Measured inside whole decode steps of the 7B shape,
 // one 128-row workgroup per column tile and split-K up to about one workgroup per compute unit was as fast as
 // any mix of 64-row workgroups, two column blocks per wavefront and deeper splits (all within 3 %).

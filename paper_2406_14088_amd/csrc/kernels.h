@@ -116,6 +116,11 @@ struct PackedGemmArgs {
 };
 // M of any size (row blocks of 128 re-stream the weights; meant for M <= 256).
 void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st);
+// Fused gate/up projection (EPI_SWIGLU) of few rows from the copies, K halves on separate wavefronts: the sums are
+// formed in the order of launch_gemm_skinny's and equal them bit for bit.  a.P[0] = gate, a.P[1] = up, a.rows[0] = F;
+// a.depth: weight chunks (128 wide) in flight per wavefront, 2 or 4 (0: 4).
+bool gemm_packed_swiglu_halves_supported(int F, int K);
+void launch_gemm_packed_swiglu_halves(const PackedGemmArgs &a, hipStream_t st);
 void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *splits);
 
 // ---- attention_decode.hip ------------------------------------------------------------------------

@@ -282,6 +282,19 @@ void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
         launch_gemm_packed(q, st);
         return;
     }
+    if (h->packed && l < h->packed_gu_layers && M <= kSkinnyMaxM && gemm_packed_swiglu_halves_supported(h->s.ffn, h->s.hidden)) {
+        // few rows, copies present: the kernel that splits each K chunk over two wavefront groups -- the row-major kernel's
+        // sums in the row-major kernel's order (same bits), without its LDS traffic on the weight side
+        PackedGemmArgs q;
+        q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
+        q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
+        q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
+        q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
+        q.nb = 2; q.rows_per_wg = 128; q.depth = 2;
+        Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
+        launch_gemm_packed_swiglu_halves(q, st);
+        return;
+    }
     GemmArgs a;
     a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
     a.W[0] = h->lw[W_GATE][l]; a.W[1] = h->lw[W_UP][l]; a.W[2] = nullptr;
@@ -1225,6 +1238,23 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
     a.rows_per_wg = rows_per_wg;
     a.depth = depth;
     launch_gemm_packed(a, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+int rl_op_gemm_packed_swiglu_halves(const uint16_t *A, int64_t lda, const uint16_t *Pg, const uint16_t *Pu, int32_t F, int32_t M,
+                                    int32_t K, uint16_t *out, int64_t ldc, int32_t depth, void *st) {
+    if (!A || !Pg || !Pu || !out) return RL_GEN_E_NULL;
+    if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || F <= 0 || ldc < F) return RL_GEN_E_SHAPE;
+    if (depth != 0 && depth != 2 && depth != 4) return RL_GEN_E_SHAPE;
+    if (((uint64_t)M * (uint64_t)lda + (uint64_t)K) * 2 > 0xf0000000ull) return RL_GEN_E_SHAPE;
+    if (!gemm_packed_swiglu_halves_supported(F, K)) return RL_GEN_E_SHAPE;
+    PackedGemmArgs a;
+    a.A = A; a.A_lo = nullptr; a.lda = lda; a.M = M; a.K = K;
+    a.P[0] = Pg; a.P[1] = Pu; a.P[2] = nullptr;
+    a.rows[0] = F; a.rows[1] = F; a.rows[2] = 0;
+    a.out = out; a.ldc = ldc; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
+    a.nb = 2; a.rows_per_wg = 128; a.depth = depth;
+    launch_gemm_packed_swiglu_halves(a, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

@@ -45,7 +45,7 @@ def bench_gemm(args):
     copies = max(2, min(16, int(600e6 // (nmat * N * K * 2)))) if M <= 256 else 1
     Ws = [[(torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16) for _ in range(nmat)] for _ in range(copies)]
     Ps = None
-    if args.kernel in ("packed", "tiled_packed"):
+    if args.kernel in ("packed", "tiled_packed", "packed_halves"):
         Ps = []
         for ws in Ws:
             row = []
@@ -67,6 +67,8 @@ def bench_gemm(args):
         if args.kernel == "packed":
             ops.gemm_packed(A[:M], Ps[c], [N] * nmat, K, out, N, A_lo=A_lo, M=M, split_stride=M * N, splits=splits, epilogue=epi,
                             nb=args.nb, rows_per_wg=args.rows_per_wg, depth=args.depth)
+        elif args.kernel == "packed_halves":
+            ops.gemm_packed_swiglu_halves(A[:M], Ps[c][0], Ps[c][1], N, K, out, N, M=M, depth=args.depth)
         elif args.kernel == "tiled_packed":
             ops.gemm_tiled_packed(A[:M], Ws[c], Ps[c], out, N, M=M, epilogue=epi, A_lo=A_lo)
         else:
@@ -104,7 +106,7 @@ def main():
     g.add_argument("--m", type=int, default=128)
     g.add_argument("--n", type=int, default=4096)
     g.add_argument("--k", type=int, default=4096)
-    g.add_argument("--kernel", default="packed", choices=["skinny", "tiled", "tiled_packed", "packed"])
+    g.add_argument("--kernel", default="packed", choices=["skinny", "tiled", "tiled_packed", "packed", "packed_halves"])
     g.add_argument("--epilogue", default="f32", choices=list(EPILOGUES))
     g.add_argument("--terms", type=int, default=1, choices=[1, 2], help="2: activations as a two-term half split")
     g.add_argument("--splits", type=int, default=1, help="K splits (fp32 partial outputs; epilogue f32 only)")
@@ -125,6 +127,8 @@ def main():
     if args.what == "gemm":
         if args.epilogue == "swiglu" and args.terms == 2:
             ap.error("the SwiGLU projection takes one-term activations")
+        if args.kernel == "packed_halves" and args.epilogue != "swiglu":
+            ap.error("packed_halves is the fused gate/up projection: --epilogue swiglu")
         if args.terms == 2 and args.kernel == "skinny":
             ap.error("the row-major skinny kernel takes the second term as extra rows, not as --terms 2")
         bench_gemm(args)

@@ -192,6 +192,26 @@ def test_gemm_tiled_from_fragment_order_copies_with_a_row_stride(ops):
     assert np.abs(np64(out[M - 1]) - want).max() <= 2e-6 * np.sqrt(K) * (np.abs(want).max() + 1.0)
 
 
+@pytest.mark.parametrize("M,K,F,depth", [(4, 256, 688, 4), (128, 512, 1000, 2), (256, 256, 72, 4), (128, 4096, 1100, 4), (77, 1000, 200, 2),
+                                          (200, 136, 96, 0)])
+def test_gemm_packed_swiglu_on_k_halves_equals_the_row_major_kernel(ops, M, K, F, depth):
+    """Same column sums in the same order (K halves of each 128-wide chunk, ascending chunks, half 0 + half 1): the kernel
+    over fragment-order copies stores the bits the row-major kernel stores; one row also against the oracle."""
+    step(f"swiglu halves M={M} K={K} F={F} depth={depth}")
+    A = randn_f16((M, K), 80 + M)
+    Wg, Wu = randn_bf16((F, K), 81, std=0.1), randn_bf16((F, K), 82, std=0.1)
+    ref = torch.zeros((M, F), dtype=torch.float16, device=DEV)
+    out = torch.full((M, F), -1.0, dtype=torch.float16, device=DEV)
+    ops.gemm(A, [Wg, Wu], ref, F, epilogue=1, kernel=1)
+    ops.gemm_packed_swiglu_halves(A, pack(ops, Wg), pack(ops, Wu), F, K, out, F, depth=depth)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+    m = M - 1
+    g, u = np64(Wg) @ np64(A[m]), np64(Wu) @ np64(A[m])
+    want = g / (1.0 + np.exp(-g)) * u
+    assert (np.abs(np64(out[m]) - want) <= 0.5 * F16_EPS * np.abs(want) * 1.02 + 2e-5).all()
+
+
 def f16_toward_zero(x32):
     """float32 -> float16, rounded toward zero (what the weight widening does; exact for normal halves)."""
     h = x32.astype(np.float16)
