@@ -103,10 +103,11 @@ int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void
 size_t rl_gen_packed_bytes(const rl_gen_shape *shape);
 /* The same plus copies of the gate/up pair of every layer.  Whatever an arena holds beyond rl_gen_packed_bytes goes
  * to gate/up pairs, layer by layer from layer 0 ((full - base) / n_layers bytes each; rl_gen_packed_gate_up_layers tells
- * how many the last rl_gen_pack_weights re-laid).  Prefills of 1024 rows or more then run the fused gate/up projection
- * of those layers from the copies, and steps of few rows do where that is the faster kernel (more than 128 rows, an FFN
- * width above 16384, or an FFN width from 14336 with more than 64 rows).  rl_gen_prefers_packed_gate_up: 1 when the
- * copies pay for this shape (always, for the prefill's sake: they cost their memory, nothing else), else 0. */
+ * how many the last rl_gen_pack_weights re-laid).  Every step then runs the fused gate/up projection of those layers
+ * from the copies: up to 128 rows and FFN widths up to 16384 with a kernel whose sums are formed in the order of the
+ * row-major kernel's (the same bits as without copies), otherwise (more rows, wider FFNs, prefills) with the kernel of
+ * the other projections (the same values to fp32 summation order).  rl_gen_prefers_packed_gate_up: 1 when the copies
+ * pay for this shape (always: they cost their memory, nothing else), else 0. */
 size_t rl_gen_packed_bytes_full(const rl_gen_shape *shape);
 int rl_gen_prefers_packed_gate_up(const rl_gen_shape *shape);
 int rl_gen_packed_gate_up_layers(const rl_gen_t *h);

@@ -271,20 +271,12 @@ int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, 
 bool packed_swiglu_wins(int M, int ffn) { return M > 128 || ffn > 256 * 64 || (ffn >= 14336 && M > 64); }
 
 void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
-    if (h->packed && l < h->packed_gu_layers && packed_swiglu_wins(M, h->s.ffn)) {
-        PackedGemmArgs q;
-        q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
-        q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
-        q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
-        q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
-        q.nb = 2; q.rows_per_wg = M > 128 ? 128 : 64; q.depth = 2;
-        Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
-        launch_gemm_packed(q, st);
-        return;
-    }
-    if (h->packed && l < h->packed_gu_layers && M <= kSkinnyMaxM && gemm_packed_swiglu_halves_supported(h->s.ffn, h->s.hidden)) {
-        // few rows, copies present: the kernel that splits each K chunk over two wavefront groups -- the row-major kernel's
-        // sums in the row-major kernel's order (same bits), without its LDS traffic on the weight side
+    const bool copies = h->packed && l < h->packed_gu_layers;
+    // Up to 128 rows and FFN widths up to 16384: the kernel that puts the K halves of each chunk on separate wavefronts (the
+    // row-major kernel's sums in its order, from the copies).  Measured against the other two at 128 / 64 rows: FFN 11008
+    // 46.6 us (row-major 52.2, packed 61); FFN 14336 54.0 / 49.7 us (packed 61 / 54.6, row-major 63 / 55.7).  Wider
+    // FFNs (K = 8192 shapes) and more rows stay with the packed kernel (34B shape at 64 rows: 137 against 160 us).
+    if (copies && M <= 128 && h->s.ffn <= 256 * 64 && gemm_packed_swiglu_halves_supported(h->s.ffn, h->s.hidden)) {
         PackedGemmArgs q;
         q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
         q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
@@ -295,10 +287,21 @@ void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
         launch_gemm_packed_swiglu_halves(q, st);
         return;
     }
+    if (copies && packed_swiglu_wins(M, h->s.ffn)) {
+        PackedGemmArgs q;
+        q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
+        q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
+        q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
+        q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
+        q.nb = 2; q.rows_per_wg = M > 128 ? 128 : 64; q.depth = 2;
+        Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
+        launch_gemm_packed(q, st);
+        return;
+    }
     GemmArgs a;
     a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
     a.W[0] = h->lw[W_GATE][l]; a.W[1] = h->lw[W_UP][l]; a.W[2] = nullptr;
-    if (h->packed && l < h->packed_gu_layers) { a.P[0] = h->pw[W_GATE][l]; a.P[1] = h->pw[W_UP][l]; }
+    if (copies) { a.P[0] = h->pw[W_GATE][l]; a.P[1] = h->pw[W_UP][l]; }
     a.rows[0] = h->s.ffn; a.rows[1] = h->s.ffn; a.rows[2] = 0;
     a.out = h->act(); a.ldc = h->s.ffn; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
     Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
