@@ -21,9 +21,14 @@
  *     state (batch, length) unchanged.  No exception crosses this boundary.
  *   - Number formats: weights are bf16 (as given) and are widened to IEEE half inside the kernels, or
  *     once per generation phase into the fragment-order copies of rl_gen_pack_weights (exact for
- *     |w| >= 2^-14); activations that feed a projection and the KV cache are IEEE half (same size as
- *     bf16, 11 instead of 8 significant bits); the residual stream, normalisation statistics, softmax,
- *     accumulators and logits are fp32.
+ *     |w| >= 2^-14); activations that feed a projection are IEEE half (same size as bf16, 11 instead of
+ *     8 significant bits), as one term or as a two-term sum hi + lo (see rl_gen_shape.precision); the KV
+ *     cache holds 16-bit elements, IEEE half or block-scaled fixed point (see rl_gen_shape.precision);
+ *     the residual stream, normalisation statistics, softmax, accumulators and logits are fp32.
+ *   - Range: fp32 -> half conversions saturate at +-65504 (never inf).  Activations that feed a
+ *     projection (normalised rows times gain, attention outputs, SwiGLU outputs) are exact to half
+ *     precision while their magnitude stays below 65504 and saturate beyond; NaN is never produced from
+ *     finite inputs.  Block-scaled cache rows have no such limit (the scale is fp32).
  *   - Matrices are row-major [out_features, in_features]; token ids are int32 in [0, vocab) --
  *     ids outside that range are clamped on the device (no fault), the result is then unspecified.
  */
@@ -56,7 +61,25 @@ typedef struct {
     int32_t weight_dtype; /* 0: fp32 (converted once to bf16 at create), 1: bf16 */
     int32_t max_batch;    /* KV capacity in sequences */
     int32_t max_seq;      /* KV capacity in tokens per sequence (prompt + generated) */
+    int32_t precision;    /* which 16-bit roundings the path keeps; the logit error against an fp64 evaluation grows with
+                           * depth and width, and the stated tolerance (max-abs 3e-2) needs more care for deeper models:
+                           *  1  activations enter the QKV projection as a two-term half sum; everything else that is
+                           *     stored in 16 bits is one IEEE half; KV cache IEEE half
+                           *  2  as 1, and the attention output enters the O projection and the SwiGLU output the down
+                           *     projection as two-term sums; the KV cache rows are 16-bit block-scaled fixed point
+                           *     (int16 elements, one fp32 scale per position and kv head: about 15 significant bits at the
+                           *     same 2 bytes per element) for shapes with fewer than 4 query heads per kv head, IEEE half
+                           *     for grouped-query shapes (whose decode attention runs on the matrix cores)
+                           *  3  as 2, and the FFN-norm output enters gate/up and the final-norm output the LM head as
+                           *     two-term sums; block-scaled KV cache for every shape (grouped-query decode attention then
+                           *     runs on the vector units)
+                           *  0  automatic: 3 for more than 32 layers or hidden above 4096, else 2 */
 } rl_gen_shape;
+
+/* The level a shape's `precision` field resolves to (1, 2 or 3; negative status on an invalid shape), and whether the KV
+ * cache of such a handle holds block-scaled rows (1) or IEEE half rows (0). */
+int rl_gen_precision_level(const rl_gen_shape *shape);
+int rl_gen_kv_block_scaled(const rl_gen_shape *shape);
 
 /* Supported shapes: hidden == n_heads*head_dim, n_heads % n_kv_heads == 0, n_heads/n_kv_heads <= 16,
  * head_dim in {64, 128}, hidden % 8 == 0, ffn % 8 == 0, all counts positive (n_layers may be 0). */
@@ -78,14 +101,16 @@ typedef struct {                 /* all DEVICE, borrowed, dtype given by weight_
 
 /* Closed forms (host only, no GPU needed).  Return 0 / negative on an invalid shape. */
 int64_t rl_gen_param_count(const rl_gen_shape *shape); /* parameters of the model-configuration table's inventory */
-size_t rl_gen_kv_bytes(const rl_gen_shape *shape);     /* bytes of the KV arena: 2*L*max_batch*Hkv*max_seq*head_dim*2 */
+size_t rl_gen_kv_bytes(const rl_gen_shape *shape);     /* bytes of the KV arena: 2*L*max_batch*Hkv*max_seq*head_dim*2, plus 4
+                                                          per cache row (head_dim elements) when rows are block-scaled */
 size_t rl_gen_work_bytes(const rl_gen_shape *shape);   /* bytes of the activation workspace arena */
 int rl_gen_validate_shape(const rl_gen_shape *shape);  /* RL_GEN_OK or RL_GEN_E_SHAPE */
 
 /* Creates a handle.  kv_arena / work_arena: DEVICE, 256-byte aligned, at least rl_gen_kv_bytes /
  * rl_gen_work_bytes long (else RL_GEN_E_CAPACITY), contents need not be initialised.  The host
  * arrays inside `weights` are copied; the device tensors they point to are borrowed.
- * KV layout inside the arena: [layer][K|V][sequence][kv_head][position][head_dim], IEEE half. */
+ * KV layout inside the arena: [layer][K|V][sequence][kv_head][position][head_dim], 16-bit elements (IEEE half or int16);
+ * block-scaled caches keep their fp32 row scales behind all rows, [layer][K|V][sequence][kv_head][position]. */
 int rl_gen_create(const rl_gen_shape *shape, const rl_gen_weights *weights, void *kv_arena, size_t kv_bytes,
                   void *work_arena, size_t work_bytes, rl_gen_t **out);
 

@@ -9,6 +9,14 @@
  * activations and cache slabs (h, A, q_f16, kc, vc, attention outputs) are IEEE half, called "f16"
  * below; `hip_stream` is a hipStream_t (NULL =
  * default stream).  Return: 0, or a negative rl_gen_status (rl_gen.h); nothing is enqueued on error.
+ *
+ * Two optional argument groups recur (both follow rl_gen_shape.precision, rl_gen.h):
+ *   kscale, vscale (both or neither; NULL = the cache rows are IEEE half): fp32 row scales of a block-scaled cache.  kc / vc
+ *     then hold int16 elements, element e of row i standing for kc[i][e] * kscale[i]; a row is one (position, kv head)
+ *     vector of hd elements and the scales are indexed like the rows ([n_seq][Hkv][S], or [n_pages][Hkv][page_size]).
+ *     A writer sets scale = max|x| / 32767 over the row and stores round(x / scale).
+ *   out_lo (NULL = not wanted): second term of a two-term half output, out_lo = f16(y - f16(y)) where out = f16(y), laid out
+ *     like out; a projection that multiplies both terms sees y with about 22 significant bits.
  */
 #ifndef RL_GEN_OPS_H
 #define RL_GEN_OPS_H
@@ -45,10 +53,11 @@ int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_s
  * splits applies to the skinny kernel with epilogue 0 only.  kernel: 0 = choose by M, 1 = skinny
  * (weights streamed once through registers; M <= 256), 2 = tiled (both operands through LDS).
  * A_lo (kernel 2, epilogues 0 and 2; else NULL): second term of the activations, f16 [M, K] with the same stride,
- * located above A in the same allocation: out = (A + A_lo) W^T as one contraction over [A | A_lo] x [W | W]. */
+ * located above A in the same allocation: out = (A + A_lo) W^T as one contraction over [A | A_lo] x [W | W].
+ * out_lo (kernel 2 with epilogue 1; else NULL): second half term of the SwiGLU result. */
 int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2,
                int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
-               int32_t splits, int32_t epilogue, int32_t kernel, void *hip_stream);
+               int32_t splits, int32_t epilogue, int32_t kernel, uint16_t *out_lo, void *hip_stream);
 
 /* The large-M projection kernel fed fragment-order copies of its weights as well (P_i = rl_op_pack_weights of W_i, one per
  * W_i): tiles of 256 x 256 then copy both operands global -> LDS with the load unit (no staging registers, no conversion in
@@ -64,10 +73,12 @@ int rl_op_gemm_tiled_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda
  * k and v rows rounded to half and stored into kc / vc (half [n_seq][Hkv][S][128]).  Bit for bit what rl_op_gemm (fp32
  * output) followed by rl_op_rope_append stores.  RL_GEN_E_SHAPE where the fused form does not apply (head_dim, style,
  * T < 32, fewer than 256 tiles of 256 x 256).  Pq, Pk, Pv: optional fragment-order copies of the three matrices (all or
- * none): with them both operands are copied global -> LDS directly, as in rl_op_gemm_tiled_packed; same stored bits. */
+ * none): with them both operands are copied global -> LDS directly, as in rl_op_gemm_tiled_packed; same stored bits.
+ * q_f16_lo (optional): second half term of q, f16(q - f16(q)), laid out like q_f16. */
 int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *Wq, const uint16_t *Wk, const uint16_t *Wv,
                     const uint16_t *Pq, const uint16_t *Pk, const uint16_t *Pv, int32_t Hq, int32_t Hkv, int32_t hd, int32_t M, int32_t K, int32_t T, int32_t b0, const float *rope_tab,
-                    int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *hip_stream);
+                    int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, float *kscale, float *vscale,
+                    uint16_t *q_f16_lo, void *hip_stream);
 
 /* Weights in matrix-core fragment order.  rl_op_pack_weights converts W bf16 [N, K] row-major (K % 8 == 0)
  * into P, rl_op_packed_weight_bytes(N, K) bytes of f16: P[ceil(N/32)][ceil(K/16)][64][8], where element e of
@@ -84,11 +95,12 @@ int rl_op_pack_weights(const uint16_t *W, uint16_t *P, int32_t N, int32_t K, voi
  * 1 or 2 (0: chosen from the number of columns); epilogue 1 (SwiGLU) always uses gate block + up block.
  * rows_per_wg: activation rows per workgroup, 32, 64 or 128 (0: 128): smaller row blocks give more workgroups
  * without split-K partials; the row blocks of one column tile stream the same weights (HBM once, L2 after).
- * depth: 64-wide K chunks of weights each wavefront keeps in flight, 2 or 4 (0: 2). */
+ * depth: 64-wide K chunks of weights each wavefront keeps in flight, 2 or 4 (0: 2).
+ * out_lo (epilogue 1 only; else NULL): second half term of the SwiGLU result. */
 int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P0, const uint16_t *P1,
                       const uint16_t *P2, int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out,
                       int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg,
-                      int32_t depth, void *hip_stream);
+                      int32_t depth, uint16_t *out_lo, void *hip_stream);
 
 /* Fused gate/up projection of few rows from fragment-order copies, the two 64-wide halves of every 128-wide K chunk on
  * separate wavefronts: out[M, F] (DEVICE half, row stride ldc) = silu(A Pg^T) * (A Pu^T), A DEVICE half [M, K] with row stride lda,
@@ -96,7 +108,7 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
  * epilogue 1, so the two calls store the same bits.  depth: 128-wide weight chunks in flight per wavefront, 2 or 4 (0: 4).
  * K % 8 == 0, lda % 8 == 0, each packed matrix below 3.75 GB; RL_GEN_E_SHAPE otherwise. */
 int rl_op_gemm_packed_swiglu_halves(const uint16_t *A, int64_t lda, const uint16_t *Pg, const uint16_t *Pu, int32_t F, int32_t M,
-                                    int32_t K, uint16_t *out, int64_t ldc, int32_t depth, void *hip_stream);
+                                    int32_t K, uint16_t *out, int64_t ldc, int32_t depth, uint16_t *out_lo, void *hip_stream);
 
 /* Builds the rotary table the library uses: tab fp32 [max_seq, head_dim/2, 2] = (cos, sin) of
  * pos * base^(-2r/head_dim), evaluated in fp64 on the host and copied (synchronously) to `tab`. */
@@ -105,19 +117,22 @@ int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float 
 /* Rotary embedding + KV-cache append.  qkv fp32: nsplit partials, each [M, (Hq+2Hkv)*hd] laid out
  * q | k | v per row, split_stride elements apart.  Row m is sequence b0 + m / T at position
  * d_pos0[(m / T) * pos_stride] + m % T (d_pos0: DEVICE int32; pos_stride 0: one start position, 1: one per sequence).  Writes q_f32 and/or q_f16 ([M, Hq*hd], either may
- * be NULL) and the cache rows of kc / vc (f16 [n_seq][Hkv][S][hd]).  Positions >= S are skipped. */
+ * be NULL) and the cache rows of kc / vc (f16 [n_seq][Hkv][S][hd], or block-scaled rows with their scales in kscale / vscale:
+ * then hd must be 64 or 128).  q_f16_lo (optional, needs q_f16): second half term of q.  Positions >= S are skipped. */
 int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
                       const int32_t *d_pos0, int32_t pos_stride, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv,
-                      int32_t hd, int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *hip_stream);
+                      int32_t hd, int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, float *kscale, float *vscale,
+                      uint16_t *q_f16_lo, void *hip_stream);
 
 /* Decode attention: for each sequence b < B and query head u, softmax(q_u . k_j / sqrt(hd)) v_j over
  * cache rows j = 0 .. d_len[b * len_stride] of kv head u / (Hq/Hkv) (len_stride 0: one length for all, 1: per sequence).  q fp32 [B, Hq*hd]; kc, vc f16; out f16 [B, Hq*hd].
  * nsplit >= 1 splits the rows over wavefronts; ws must then hold rl_op_decode_attention_ws_floats
  * floats (may be NULL for nsplit == 1).  hd in {64, 128}.  d_done: DEVICE int32 [B] or NULL; sequences with a non-zero
- * flag (ended, Section 2.1) are skipped: their cache is not read and their rows of out are left as they are. */
+ * flag (ended, Section 2.1) are skipped: their cache is not read and their rows of out are left as they are.
+ * With kscale / vscale the vector kernel serves every head grouping (the matrix-core kernel reads half rows only). */
 int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
                            uint16_t *out, float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
-                           const int32_t *d_done, void *hip_stream);
+                           const int32_t *d_done, const float *kscale, const float *vscale, uint16_t *out_lo, void *hip_stream);
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
 /* The same attention over a paged cache (Section 7 names paged attention as a technique the generation backend can
@@ -128,7 +143,7 @@ size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32
 int rl_op_decode_attention_paged(const float *q, const uint16_t *k_pool, const uint16_t *v_pool, const int32_t *table,
                                  int32_t table_stride, int32_t page_size, const int32_t *d_len, int32_t len_stride, uint16_t *out,
                                  float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
-                                 void *hip_stream);
+                                 const float *kscale, const float *vscale, void *hip_stream);
 
 /* Rotary embedding + KV-cache append + decode attention in one kernel (what a decode step runs): q, k and v of the
  * new token of every sequence are taken from qkv -- nsplit_qkv fp32 partials, each [B, (Hq+2Hkv)*hd] laid out
@@ -142,9 +157,12 @@ int rl_op_decode_attention_fused(const float *qkv, int32_t nsplit_qkv, size_t sp
                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *hip_stream);
 
 /* Prefill attention: causal attention of positions 0..T-1 of nb sequences; sequence i reads cache
- * sequence b0 + i.  q f16 [nb*T, Hq*hd] (rotated), kc, vc f16, out f16 [nb*T, Hq*hd].  hd in {64, 128}. */
+ * sequence b0 + i.  q f16 [nb*T, Hq*hd] (rotated), kc, vc f16 (or block-scaled: each element then enters the matrix cores
+ * as a two-term half sum, and so do the probabilities; q_lo, optional and for block-scaled rows only, is the second half term
+ * of q, laid out like q), out f16 [nb*T, Hq*hd].  hd in {64, 128}. */
 int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_t *vc, uint16_t *out, int32_t nb,
-                            int32_t b0, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, void *hip_stream);
+                            int32_t b0, int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, const float *kscale,
+                            const float *vscale, uint16_t *out_lo, const uint16_t *q_lo, void *hip_stream);
 
 /* Greedy token: next[b] = lowest index of the largest of logits[b, 0..V-1]; -1 if the row has a NaN. */
 int rl_op_argmax(const float *logits, int32_t B, int32_t V, int32_t *next, void *hip_stream);

@@ -430,6 +430,22 @@ int orc_decode_step(orc_model *m, const int32_t *tokens, double *logits, int32_t
     return ORC_OK;
 }
 
+/* tokens [B, T]: T further tokens of each of the current sequences (B must equal the batch of the last orc_prefill), entering
+ * at positions cur_len .. cur_len + T - 1 against the cache (Section 2.1: the decode phase consumes tokens against the cache;
+ * a span of T > 1 tokens is T consecutive decode steps whose inputs are known beforehand, e.g. a long prompt fed in pieces).
+ * logits (may be NULL): [B, V] for the last position of the span. */
+int orc_extend(orc_model *m, const int32_t *tokens, int T, double *logits) {
+    if (!m || !tokens) return ORC_E_NULL;
+    if (m->cur_batch <= 0) return ORC_E_STATE;
+    if (T <= 0) return ORC_E_SHAPE;
+    if (m->cur_len + T > m->s.max_seq) return ORC_E_CAPACITY;
+    if (!tokens_ok(m, tokens, (size_t)m->cur_batch * T)) return ORC_E_SHAPE;
+    int rc = run_span(m, tokens, m->cur_batch, T, m->cur_len, logits);
+    if (rc != ORC_OK) return rc;
+    m->cur_len += T;
+    return ORC_OK;
+}
+
 int orc_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

@@ -72,6 +72,8 @@ def lib():
         L.orc_prefill.restype = C.c_int
         L.orc_decode_step.argtypes = [vp, ip, dp, ip]
         L.orc_decode_step.restype = C.c_int
+        L.orc_extend.argtypes = [vp, ip, C.c_int, dp]
+        L.orc_extend.restype = C.c_int
         L.orc_num_threads.argtypes = []
         L.orc_num_threads.restype = C.c_int
         _LIB = L
@@ -263,6 +265,16 @@ class OracleModel:
             raise OracleError(rc, "orc_prefill")
         self._B = B
         return logits, nxt
+
+    def extend(self, tokens: np.ndarray, want_logits: bool = True):
+        """tokens [B, T]: T further tokens per sequence against the cache; returns the logits [B, V] of the last one (or None)."""
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        B, T = tokens.shape
+        logits = np.empty((B, self.shape.vocab), dtype=np.float64) if want_logits else None
+        rc = lib().orc_extend(self._h, _ip(tokens), T, _dp(logits) if want_logits else None)
+        if rc != 0:
+            raise OracleError(rc, "orc_extend")
+        return logits
 
     def decode_step(self, tokens: np.ndarray):
         tokens = np.ascontiguousarray(tokens, dtype=np.int32)

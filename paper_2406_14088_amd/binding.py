@@ -28,12 +28,12 @@ class RlGenError(RuntimeError):
 class RlGenShape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + [
         ("rope_base", C.c_float), ("rms_eps", C.c_float), ("rope_style", C.c_int32), ("weight_dtype", C.c_int32),
-        ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+        ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("precision", C.c_int32)]
 
     @classmethod
-    def from_model(cls, shape, max_batch: int, max_seq: int, weight_dtype: int = 1) -> "RlGenShape":
+    def from_model(cls, shape, max_batch: int, max_seq: int, weight_dtype: int = 1, precision: int = 0) -> "RlGenShape":
         return cls(shape.n_layers, shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab,
-                   shape.rope_base, shape.rms_eps, shape.rope_style, weight_dtype, max_batch, max_seq)
+                   shape.rope_base, shape.rms_eps, shape.rope_style, weight_dtype, max_batch, max_seq, precision)
 
 
 class RlGenWeights(C.Structure):
@@ -59,6 +59,8 @@ def lib():
         "rl_gen_validate_shape": (C.c_int, [sp]),
         "rl_gen_param_count": (i64, [sp]),
         "rl_gen_kv_bytes": (sz, [sp]),
+        "rl_gen_precision_level": (C.c_int, [sp]),
+        "rl_gen_kv_block_scaled": (C.c_int, [sp]),
         "rl_gen_work_bytes": (sz, [sp]),
         "rl_gen_create": (C.c_int, [sp, C.POINTER(RlGenWeights), vp, sz, vp, sz, C.POINTER(vp)]),
         "rl_gen_page_bytes": (sz, [sp, i32]),
@@ -91,20 +93,20 @@ def lib():
         "rl_gen_kernel_class_name": (C.c_char_p, [i32]),
         "rl_op_embed": (C.c_int, [vp, vp, vp, i32, i32, i32, vp]),
         "rl_op_add_rmsnorm": (C.c_int, [vp, vp, i32, sz, vp, f32, vp, vp, i32, i32, vp]),
-        "rl_op_gemm": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp]),
-        "rl_op_gemm_rope": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp]),
-        "rl_op_gemm_packed_swiglu_halves": (C.c_int, [vp, i64, vp, vp, i32, i32, i32, vp, i64, i32, vp]),
+        "rl_op_gemm": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, vp, vp]),
+        "rl_op_gemm_rope": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "rl_op_gemm_packed_swiglu_halves": (C.c_int, [vp, i64, vp, vp, i32, i32, i32, vp, i64, i32, vp, vp]),
         "rl_op_gemm_tiled_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, i32, vp]),
         "rl_op_packed_weight_bytes": (sz, [i32, i32]),
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
-        "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp]),
+        "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
-        "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
-        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]),
+        "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
-        "rl_op_decode_attention_paged": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_decode_attention_paged": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
-        "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
+        "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_argmax": (C.c_int, [vp, i32, i32, vp, vp]),
         "rl_op_sample": (C.c_int, [vp, i32, i32, f32, vp, vp, vp]),
         "rl_op_logprob_gather": (C.c_int, [vp, i64, i32, i32, vp, i32, i64, vp, vp]),
@@ -120,7 +122,7 @@ def lib():
 
 
 EXPORTED_SYMBOLS = (
-    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes", "rl_gen_packed_bytes_full", "rl_gen_prefers_packed_gate_up", "rl_gen_packed_gate_up_layers",
+    "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_precision_level", "rl_gen_kv_block_scaled", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes", "rl_gen_packed_bytes_full", "rl_gen_prefers_packed_gate_up", "rl_gen_packed_gate_up_layers",
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
@@ -128,8 +130,16 @@ EXPORTED_SYMBOLS = (
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
-def _shape_of(shape, max_batch=1, max_seq=1, weight_dtype=1) -> RlGenShape:
-    return shape if isinstance(shape, RlGenShape) else RlGenShape.from_model(shape, max_batch, max_seq, weight_dtype)
+def _shape_of(shape, max_batch=1, max_seq=1, weight_dtype=1, precision=0) -> RlGenShape:
+    return shape if isinstance(shape, RlGenShape) else RlGenShape.from_model(shape, max_batch, max_seq, weight_dtype, precision)
+
+
+def precision_level(shape, precision=0) -> int:
+    return int(lib().rl_gen_precision_level(C.byref(_shape_of(shape, precision=precision))))
+
+
+def kv_block_scaled(shape, precision=0) -> bool:
+    return int(lib().rl_gen_kv_block_scaled(C.byref(_shape_of(shape, precision=precision)))) == 1
 
 
 def validate_shape(shape, max_batch=1, max_seq=1) -> int:
@@ -140,16 +150,16 @@ def param_count(shape) -> int:
     return int(lib().rl_gen_param_count(C.byref(_shape_of(shape))))
 
 
-def kv_bytes(shape, max_batch=1, max_seq=1) -> int:
-    return int(lib().rl_gen_kv_bytes(C.byref(_shape_of(shape, max_batch, max_seq))))
+def kv_bytes(shape, max_batch=1, max_seq=1, precision=0) -> int:
+    return int(lib().rl_gen_kv_bytes(C.byref(_shape_of(shape, max_batch, max_seq, precision=precision))))
 
 
 def work_bytes(shape, max_batch=1, max_seq=1) -> int:
     return int(lib().rl_gen_work_bytes(C.byref(_shape_of(shape, max_batch, max_seq))))
 
 
-def page_bytes(shape, page_size: int) -> int:
-    return int(lib().rl_gen_page_bytes(C.byref(_shape_of(shape)), int(page_size)))
+def page_bytes(shape, page_size: int, precision=0) -> int:
+    return int(lib().rl_gen_page_bytes(C.byref(_shape_of(shape, precision=precision)), int(page_size)))
 
 
 def plan_pages(capacity, page_size: int, n_pages: int, pages_per_seq: int):
@@ -182,7 +192,7 @@ class Generator:
     """
 
     def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int, packed: bool = True,
-                 page_size: int = 0, n_pages: int = 0, pack_gate_up: Optional[bool] = None):
+                 page_size: int = 0, n_pages: int = 0, pack_gate_up: Optional[bool] = None, precision: int = 0):
         import torch
         self._h = None
         any_w = weights["tok_emb"]
@@ -190,7 +200,7 @@ class Generator:
         if wd == 0 and any_w.dtype != torch.float32:
             raise TypeError("weights must be bf16 or fp32")
         self.shape = shape
-        self.cshape = RlGenShape.from_model(shape, max_batch, max_seq, wd)
+        self.cshape = RlGenShape.from_model(shape, max_batch, max_seq, wd, precision)
         self._keep: List[object] = []
 
         def hold(t):
@@ -433,14 +443,14 @@ class _Ops:
         self._ck(lib().rl_op_add_rmsnorm(x.data_ptr(), _ptr(part), nsplit, part_stride, gain.data_ptr(), eps, h.data_ptr(), _ptr(h_lo), M, d,
                                          _stream()), "rl_op_add_rmsnorm")
 
-    def gemm(self, A, Ws, out, ldc, M=None, lda=None, split_stride=0, splits=1, epilogue=0, kernel=0, A_lo=None):
+    def gemm(self, A, Ws, out, ldc, M=None, lda=None, split_stride=0, splits=1, epilogue=0, kernel=0, A_lo=None, out_lo=None):
         K = Ws[0].shape[1]
         ptrs = [w.data_ptr() for w in Ws] + [None] * (3 - len(Ws))
         rows = [w.shape[0] for w in Ws] + [0] * (3 - len(Ws))
         M = A.shape[0] if M is None else M
         lda = A.stride(0) if lda is None else lda
         self._ck(lib().rl_op_gemm(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K, out.data_ptr(),
-                                  ldc, split_stride, splits, epilogue, kernel, _stream()), "rl_op_gemm")
+                                  ldc, split_stride, splits, epilogue, kernel, _ptr(out_lo), _stream()), "rl_op_gemm")
 
     def gemm_tiled_packed(self, A, Ws, Ps, out, ldc, M=None, epilogue=0, A_lo=None):
         K = Ws[0].shape[1]
@@ -451,17 +461,19 @@ class _Ops:
         self._ck(lib().rl_op_gemm_tiled_packed(A.data_ptr(), _ptr(A_lo), A.stride(0), wp[0], wp[1], wp[2], pp[0], pp[1], pp[2], rows[0],
                                                rows[1], rows[2], M, K, out.data_ptr(), ldc, epilogue, _stream()), "rl_op_gemm_tiled_packed")
 
-    def gemm_rope(self, A, Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, rope_tab, rope_style, S, q_f16, kc, vc, A_lo=None, Ps=None):
+    def gemm_rope(self, A, Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, rope_tab, rope_style, S, q_f16, kc, vc, A_lo=None, Ps=None,
+                  kscale=None, vscale=None, q_f16_lo=None):
         K = Wq.shape[1]
         pq, pk, pv = (x.data_ptr() for x in Ps) if Ps else (None, None, None)
         self._ck(lib().rl_op_gemm_rope(A.data_ptr(), _ptr(A_lo), A.stride(0), Wq.data_ptr(), Wk.data_ptr(), Wv.data_ptr(), pq, pk, pv, Hq, Hkv, hd, M, K,
-                                       T, b0, rope_tab.data_ptr(), rope_style, S, q_f16.data_ptr(), kc.data_ptr(), vc.data_ptr(), _stream()),
+                                       T, b0, rope_tab.data_ptr(), rope_style, S, q_f16.data_ptr(), kc.data_ptr(), vc.data_ptr(), _ptr(kscale), _ptr(vscale),
+                                       _ptr(q_f16_lo), _stream()),
                  "rl_op_gemm_rope")
 
-    def gemm_packed_swiglu_halves(self, A, Pg, Pu, F, K, out, ldc, M=None, depth=0):
+    def gemm_packed_swiglu_halves(self, A, Pg, Pu, F, K, out, ldc, M=None, depth=0, out_lo=None):
         M = A.shape[0] if M is None else M
         self._ck(lib().rl_op_gemm_packed_swiglu_halves(A.data_ptr(), A.stride(0), Pg.data_ptr(), Pu.data_ptr(), F, M, K, out.data_ptr(),
-                                                       ldc, depth, _stream()), "rl_op_gemm_packed_swiglu_halves")
+                                                       ldc, depth, _ptr(out_lo), _stream()), "rl_op_gemm_packed_swiglu_halves")
 
     def packed_weight_bytes(self, N, K):
         return int(lib().rl_op_packed_weight_bytes(N, K))
@@ -471,34 +483,38 @@ class _Ops:
         self._ck(lib().rl_op_pack_weights(W.data_ptr(), P.data_ptr(), N, K, _stream()), "rl_op_pack_weights")
 
     def gemm_packed(self, A, Ps, rows, K, out, ldc, A_lo=None, M=None, lda=None, split_stride=0, splits=1, epilogue=0, nb=0,
-                    rows_per_wg=0, depth=0):
+                    rows_per_wg=0, depth=0, out_lo=None):
         ptrs = [q.data_ptr() for q in Ps] + [None] * (3 - len(Ps))
         rows = list(rows) + [0] * (3 - len(rows))
         M = A.shape[0] if M is None else M
         lda = A.stride(0) if lda is None else lda
         self._ck(lib().rl_op_gemm_packed(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K,
-                                         out.data_ptr(), ldc, split_stride, splits, epilogue, nb, rows_per_wg, depth, _stream()), "rl_op_gemm_packed")
+                                         out.data_ptr(), ldc, split_stride, splits, epilogue, nb, rows_per_wg, depth, _ptr(out_lo), _stream()), "rl_op_gemm_packed")
 
     def build_rope_table(self, tab, max_seq, head_dim, base):
         self._ck(lib().rl_op_build_rope_table(tab.data_ptr(), max_seq, head_dim, base), "rl_op_build_rope_table")
 
     def rope_append(self, qkv, nsplit, split_stride, M, T, b0, d_pos0, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_bf16, kc, vc,
-                    pos_stride=0):
+                    pos_stride=0, kscale=None, vscale=None, q_f16_lo=None):
         self._ck(lib().rl_op_rope_append(qkv.data_ptr(), nsplit, split_stride, M, T, b0, d_pos0.data_ptr(), pos_stride, rope_tab.data_ptr(),
                                          rope_style, Hq, Hkv, hd, S, _ptr(q_f32), _ptr(q_bf16), kc.data_ptr(), vc.data_ptr(),
-                                         _stream()), "rl_op_rope_append")
+                                         _ptr(kscale), _ptr(vscale), _ptr(q_f16_lo), _stream()), "rl_op_rope_append")
 
     def decode_attention_ws_floats(self, B, Hq, hd, nsplit):
         return int(lib().rl_op_decode_attention_ws_floats(B, Hq, hd, nsplit))
 
-    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0, d_done=None):
+    def decode_attention(self, q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0, d_done=None, kscale=None,
+                         vscale=None, out_lo=None):
         self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(),
-                                              _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _ptr(d_done), _stream()), "rl_op_decode_attention")
+                                              _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _ptr(d_done), _ptr(kscale), _ptr(vscale), _ptr(out_lo),
+                                              _stream()), "rl_op_decode_attention")
 
-    def decode_attention_paged(self, q, k_pool, v_pool, table, page_size, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0):
+    def decode_attention_paged(self, q, k_pool, v_pool, table, page_size, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0,
+                               kscale=None, vscale=None):
         self._ck(lib().rl_op_decode_attention_paged(q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(), table.data_ptr(),
                                                     table.shape[1], page_size, d_len.data_ptr(), len_stride, out.data_ptr(), _ptr(ws),
-                                                    B, Hq, Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention_paged")
+                                                    B, Hq, Hkv, hd, S, nsplit, _ptr(kscale), _ptr(vscale), _stream()),
+                 "rl_op_decode_attention_paged")
 
     def decode_attention_fused(self, qkv, nsplit_qkv, split_stride, rope_tab, rope_style, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S,
                                nsplit, len_stride=0):
@@ -506,9 +522,9 @@ class _Ops:
                                                     kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(), _ptr(ws), B, Hq,
                                                     Hkv, hd, S, nsplit, _stream()), "rl_op_decode_attention_fused")
 
-    def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S):
+    def prefill_attention(self, q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, kscale=None, vscale=None, out_lo=None, q_lo=None):
         self._ck(lib().rl_op_prefill_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), out.data_ptr(), nb, b0, T, Hq, Hkv,
-                                               hd, S, _stream()), "rl_op_prefill_attention")
+                                               hd, S, _ptr(kscale), _ptr(vscale), _ptr(out_lo), _ptr(q_lo), _stream()), "rl_op_prefill_attention")
 
     def sample(self, logits, temperature, u, nxt):
         B, V = logits.shape

@@ -1,6 +1,6 @@
 // Decode attention: one new query per (sequence, query head) against the KV cache.
 //
-// Every decode step re-reads the whole cache (the paper, Section 8.4, calls this iterative KV-cache
+// Every decode step re-reads the whole cache (the paper, Section 8.5 (strong scaling trend), calls this iterative KV-cache
 // loading the irreducible overhead of generation), so this kernel is a pure HBM stream: each cache
 // element is used once per query head that shares it.  Design for gfx950:
 //   * one WAVEFRONT per (sequence, kv head, group of GT query heads, sequence split); no LDS and no
@@ -89,12 +89,16 @@ __device__ __forceinline__ void rotate8(float x[8], int c, const float *tab /* r
     }
 }
 
-template <int HD, int GT, bool FUSED, bool PAGED>
+// I16: the cache rows are 16-bit block-scaled fixed point (KvMap::kscale / vscale) instead of half: the elements are
+// widened from integers and the row's scale multiplies the finished dot product (K) or the probability (V).
+// out_lo (optional): second half term of the output, half(o - half(o)), for a two-term output projection.
+template <int HD, int GT, bool FUSED, bool PAGED, bool I16>
 __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     const float *__restrict__ q, f16_t *kc, f16_t *vc, const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
-    float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, int len_stride, FusedQkv fq, KvMap map,
-    const int32_t *__restrict__ d_done) {
+    f16_t *__restrict__ out_lo, float *__restrict__ ws, int n_items, int Hq, int Hkv, int S, int nsplit, int len_stride,
+    FusedQkv fq, KvMap map, const int32_t *__restrict__ d_done) {
     static_assert(!(FUSED && PAGED), "the fused form addresses contiguous slabs only");
+    static_assert(!(FUSED && I16), "the fused form stores half rows");
     constexpr int LPR = HD / 8;     // lanes per cache row
     constexpr int RPW = 64 / LPR;   // rows per wavefront load instruction
     const int lane = threadIdx.x & 63;
@@ -155,6 +159,8 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
     // contiguous: the slab of this (sequence, kv head); paged: the pool, rows found through the sequence's page list
     const f16_t *kb = kc + (PAGED ? (size_t)0 : ((size_t)b * Hkv + kvh) * S * HD) + c * 8;
     const f16_t *vb = vc + (PAGED ? (size_t)0 : ((size_t)b * Hkv + kvh) * S * HD) + c * 8;
+    const float *ksb = I16 ? map.kscale + (PAGED ? (size_t)0 : ((size_t)b * Hkv + kvh) * S) : nullptr;
+    const float *vsb = I16 ? map.vscale + (PAGED ? (size_t)0 : ((size_t)b * Hkv + kvh) * S) : nullptr;
     const int32_t *pages = PAGED ? map.table + (size_t)b * map.table_stride : nullptr;
     const int pmask = (1 << map.page_shift) - 1;
     // page numbers are fetched one iteration ahead, so the cache loads never wait for the page list
@@ -178,6 +184,7 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
 
     for (int base = j0; base < j1; base += RPW * DA_U) {
         u32x4_t kr[DA_U], vr[DA_U];
+        float ksc[DA_U], vsc[DA_U];
         int jj[DA_U];
         bool is_new[DA_U];
 #pragma unroll
@@ -191,6 +198,8 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
             // streaming of 8 GiB: 7.05 TB/s against 6.2 TB/s with ordinary loads)
             kr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(kb + row * HD));
             vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(vb + row * HD));
+            ksc[u] = I16 ? ksb[row] : 1.f;
+            vsc[u] = I16 ? vsb[row] : 1.f;
         }
         if (PAGED) {
 #pragma unroll
@@ -208,10 +217,17 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
         float kf[DA_U][8];
 #pragma unroll
         for (int u = 0; u < DA_U; ++u) {
-            kf[u][0] = f16lo_to_f32(kr[u].x); kf[u][1] = f16hi_to_f32(kr[u].x);
-            kf[u][2] = f16lo_to_f32(kr[u].y); kf[u][3] = f16hi_to_f32(kr[u].y);
-            kf[u][4] = f16lo_to_f32(kr[u].z); kf[u][5] = f16hi_to_f32(kr[u].z);
-            kf[u][6] = f16lo_to_f32(kr[u].w); kf[u][7] = f16hi_to_f32(kr[u].w);
+            if (I16) {
+                kf[u][0] = i16lo_to_f32(kr[u].x); kf[u][1] = i16hi_to_f32(kr[u].x);
+                kf[u][2] = i16lo_to_f32(kr[u].y); kf[u][3] = i16hi_to_f32(kr[u].y);
+                kf[u][4] = i16lo_to_f32(kr[u].z); kf[u][5] = i16hi_to_f32(kr[u].z);
+                kf[u][6] = i16lo_to_f32(kr[u].w); kf[u][7] = i16hi_to_f32(kr[u].w);
+            } else {
+                kf[u][0] = f16lo_to_f32(kr[u].x); kf[u][1] = f16hi_to_f32(kr[u].x);
+                kf[u][2] = f16lo_to_f32(kr[u].y); kf[u][3] = f16hi_to_f32(kr[u].y);
+                kf[u][4] = f16lo_to_f32(kr[u].z); kf[u][5] = f16hi_to_f32(kr[u].z);
+                kf[u][6] = f16lo_to_f32(kr[u].w); kf[u][7] = f16hi_to_f32(kr[u].w);
+            }
         }
         float sc[GT][DA_U];
 #pragma unroll
@@ -222,15 +238,23 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
 #pragma unroll
                 for (int i = 0; i < 8; ++i) d = fmaf(qr[gh][i], kf[u][i], d);
                 d = group_sum<LPR>(d) * scale;
+                if (I16) d *= ksc[u];
                 sc[gh][u] = jj[u] < j1 ? d : -INFINITY;
             }
         float vf[DA_U][8];
 #pragma unroll
         for (int u = 0; u < DA_U; ++u) {
-            vf[u][0] = f16lo_to_f32(vr[u].x); vf[u][1] = f16hi_to_f32(vr[u].x);
-            vf[u][2] = f16lo_to_f32(vr[u].y); vf[u][3] = f16hi_to_f32(vr[u].y);
-            vf[u][4] = f16lo_to_f32(vr[u].z); vf[u][5] = f16hi_to_f32(vr[u].z);
-            vf[u][6] = f16lo_to_f32(vr[u].w); vf[u][7] = f16hi_to_f32(vr[u].w);
+            if (I16) {
+                vf[u][0] = i16lo_to_f32(vr[u].x); vf[u][1] = i16hi_to_f32(vr[u].x);
+                vf[u][2] = i16lo_to_f32(vr[u].y); vf[u][3] = i16hi_to_f32(vr[u].y);
+                vf[u][4] = i16lo_to_f32(vr[u].z); vf[u][5] = i16hi_to_f32(vr[u].z);
+                vf[u][6] = i16lo_to_f32(vr[u].w); vf[u][7] = i16hi_to_f32(vr[u].w);
+            } else {
+                vf[u][0] = f16lo_to_f32(vr[u].x); vf[u][1] = f16hi_to_f32(vr[u].x);
+                vf[u][2] = f16lo_to_f32(vr[u].y); vf[u][3] = f16hi_to_f32(vr[u].y);
+                vf[u][4] = f16lo_to_f32(vr[u].z); vf[u][5] = f16hi_to_f32(vr[u].z);
+                vf[u][6] = f16lo_to_f32(vr[u].w); vf[u][7] = f16hi_to_f32(vr[u].w);
+            }
         }
 #pragma unroll
         for (int gh = 0; gh < GT; ++gh) {
@@ -247,8 +271,9 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
             for (int u = 0; u < DA_U; ++u) {
                 float p = __expf(sc[gh][u] - mnew);  // exp(-inf) = 0 for rows past the end
                 den[gh] += p;
+                const float pv = I16 ? p * vsc[u] : p;  // the row's scale rides on the probability
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[gh][i] = fmaf(p, vf[u][i], acc[gh][i]);
+                for (int i = 0; i < 8; ++i) acc[gh][i] = fmaf(pv, vf[u][i], acc[gh][i]);
             }
         }
     }
@@ -280,6 +305,14 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
                 o4.z = pack_f16x2(acc[gh][4] * inv, acc[gh][5] * inv);
                 o4.w = pack_f16x2(acc[gh][6] * inv, acc[gh][7] * inv);
                 *reinterpret_cast<u32x4_t *>(out + ((size_t)b * Hq + head) * HD + c * 8) = o4;
+                if (out_lo) {
+                    u32x4_t l4;
+                    l4.x = pack_f16x2_lo(acc[gh][0] * inv, acc[gh][1] * inv, o4.x);
+                    l4.y = pack_f16x2_lo(acc[gh][2] * inv, acc[gh][3] * inv, o4.y);
+                    l4.z = pack_f16x2_lo(acc[gh][4] * inv, acc[gh][5] * inv, o4.z);
+                    l4.w = pack_f16x2_lo(acc[gh][6] * inv, acc[gh][7] * inv, o4.w);
+                    *reinterpret_cast<u32x4_t *>(out_lo + ((size_t)b * Hq + head) * HD + c * 8) = l4;
+                }
             } else {
                 float *p = ws + (((size_t)b * Hq + head) * nsplit + split) * (HD + 2);
                 if (c == 0) { p[0] = m; p[1] = l; }
@@ -293,7 +326,7 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
 
 // Combines the split partials: o = sum_s o_s e^(m_s - M) / sum_s l_s e^(m_s - M)
 __global__ __launch_bounds__(128) void decode_attention_merge_kernel(const float *__restrict__ ws, f16_t *__restrict__ out,
-                                                                     int hd, int nsplit) {
+                                                                     f16_t *__restrict__ out_lo, int hd, int nsplit) {
     int bh = blockIdx.x, e = threadIdx.x;
     if (e >= hd) return;
     const float *p = ws + (size_t)bh * nsplit * (hd + 2);
@@ -306,7 +339,10 @@ __global__ __launch_bounds__(128) void decode_attention_merge_kernel(const float
         L += p[s * (hd + 2) + 1] * wgt;
         o += p[s * (hd + 2) + 2 + e] * wgt;
     }
-    out[(size_t)bh * hd + e] = f32_to_f16(o / L);
+    const float y = o / L;
+    const f16_t hi = f32_to_f16(y);
+    out[(size_t)bh * hd + e] = hi;
+    if (out_lo) out_lo[(size_t)bh * hd + e] = f32_to_f16(y - f16_to_f32(hi));
 }
 
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit) {
@@ -329,45 +365,48 @@ int decode_attention_default_splits(int B, int Hkv, int S) {
 }
 
 template <int HD, int GT>
-static void launch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B,
-                      int Hq, int Hkv, int S, int nsplit, const FusedQkv *fq, const KvMap &map, const int32_t *d_done, hipStream_t st) {
+static void launch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, f16_t *out_lo, float *ws,
+                      int B, int Hq, int Hkv, int S, int nsplit, const FusedQkv *fq, const KvMap &map, const int32_t *d_done,
+                      hipStream_t st) {
     int g = Hq / Hkv;
     int n_items = B * Hkv * (g / GT) * nsplit;
     int blocks = ceil_div(n_items, DA_THREADS / 64);
-    if (fq)
-        decode_attention_kernel<HD, GT, true, false><<<blocks, DA_THREADS, 0, st>>>(nullptr, kc, vc, d_len, out, ws, n_items, Hq,
-                                                                                  Hkv, S, nsplit, len_stride, *fq, KvMap(), nullptr);
-    else if (map.table)
-        decode_attention_kernel<HD, GT, false, true><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv, S,
-                                                                                  nsplit, len_stride, FusedQkv{}, map, d_done);
-    else
-        decode_attention_kernel<HD, GT, false, false><<<blocks, DA_THREADS, 0, st>>>(q, kc, vc, d_len, out, ws, n_items, Hq, Hkv,
-                                                                                   S, nsplit, len_stride, FusedQkv{}, KvMap(), d_done);
+    const bool i16 = map.kscale != nullptr;
+#define DA_LAUNCH(FUSEDV, PAGEDV, I16V, QV, FQV, MAPV, DONEV)                                                                   \
+    decode_attention_kernel<HD, GT, FUSEDV, PAGEDV, I16V><<<blocks, DA_THREADS, 0, st>>>(QV, kc, vc, d_len, out, out_lo, ws, n_items, \
+                                                                                         Hq, Hkv, S, nsplit, len_stride, FQV, MAPV, DONEV)
+    if (fq) DA_LAUNCH(true, false, false, nullptr, *fq, KvMap(), nullptr);
+    else if (map.table && i16) DA_LAUNCH(false, true, true, q, FusedQkv{}, map, d_done);
+    else if (map.table) DA_LAUNCH(false, true, false, q, FusedQkv{}, map, d_done);
+    else if (i16) DA_LAUNCH(false, false, true, q, FusedQkv{}, map, d_done);
+    else DA_LAUNCH(false, false, false, q, FusedQkv{}, KvMap(), d_done);
+#undef DA_LAUNCH
 }
 
-static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, float *ws, int B,
-                        int Hq, int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, const KvMap &map, const int32_t *d_done,
+static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out, f16_t *out_lo, float *ws,
+                        int B, int Hq, int Hkv, int hd, int S, int nsplit, const FusedQkv *fq, const KvMap &map, const int32_t *d_done,
                         hipStream_t st) {
     if (B <= 0) return;
     int g = Hq / Hkv;
     int gt = decode_attention_group(g);
 #define DA_CASE(HDV, GTV) \
-    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, fq, map, d_done, st); }
+    if (hd == HDV && gt == GTV) { launch_da<HDV, GTV>(q, kc, vc, d_len, len_stride, out, out_lo, ws, B, Hq, Hkv, S, nsplit, fq, map, d_done, st); }
     DA_CASE(128, 1) DA_CASE(128, 2) DA_CASE(128, 4)
     DA_CASE(64, 1) DA_CASE(64, 2) DA_CASE(64, 4)
 #undef DA_CASE
-    if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, hd, nsplit, st);
+    if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, hd, nsplit, st, out_lo);
 }
 
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map,
-                             const int32_t *d_done) {
-    if (decode_attention_gqa_supported(Hq, Hkv, hd)) {  // many query heads per cache row: the matrix-core kernel
-        launch_decode_attention_gqa(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, st, map, d_done);
+                             const int32_t *d_done, f16_t *out_lo) {
+    // many query heads per cache row of halves: the matrix-core kernel (16-bit block-scaled rows are read by the vector kernel)
+    if (!map.kscale && decode_attention_gqa_supported(Hq, Hkv, hd)) {
+        launch_decode_attention_gqa(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, st, map, d_done, out_lo);
         return;
     }
-    dispatch_da(q, const_cast<f16_t *>(kc), const_cast<f16_t *>(vc), d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, nullptr,
-                map, d_done, st);
+    dispatch_da(q, const_cast<f16_t *>(kc), const_cast<f16_t *>(vc), d_len, len_stride, out, out_lo, ws, B, Hq, Hkv, hd, S, nsplit,
+                nullptr, map, d_done, st);
 }
 
 void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t split_stride, const float *rope_tab, int rope_style,
@@ -375,9 +414,9 @@ void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t spli
                                    int Hkv, int hd, int S, int nsplit, hipStream_t st) {
     FusedQkv fq;
     fq.part = qkv; fq.nsplit = nsplit_qkv; fq.split_stride = split_stride; fq.rope_tab = rope_tab; fq.rope_style = rope_style;
-    dispatch_da(nullptr, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, &fq, KvMap(), nullptr, st);
+    dispatch_da(nullptr, kc, vc, d_len, len_stride, out, nullptr, ws, B, Hq, Hkv, hd, S, nsplit, &fq, KvMap(), nullptr, st);
 }
 
-void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st) {
-    decode_attention_merge_kernel<<<B * Hq, 128, 0, st>>>(ws, out, hd, nsplit);
+void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st, f16_t *out_lo) {
+    decode_attention_merge_kernel<<<B * Hq, 128, 0, st>>>(ws, out, out_lo, hd, nsplit);
 }

@@ -37,6 +37,7 @@ template <bool PAGED>
 __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *__restrict__ q, const f16_t *__restrict__ kc,
                                                                   const f16_t *__restrict__ vc,
                                                                   const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
+                                                                  f16_t *__restrict__ out_lo,
                                                                   float *__restrict__ ws, int Hq, int Hkv, int S, int nsplit,
                                                                   int len_stride, KvMap map,
                                                                   const int32_t *__restrict__ d_done) {
@@ -230,6 +231,12 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
                 o2.x = pack_f16x2(oacc[t][0] * inv, oacc[t][1] * inv);
                 o2.y = pack_f16x2(oacc[t][2] * inv, oacc[t][3] * inv);
                 *reinterpret_cast<u32x2_t *>(op + 16 * t) = o2;
+                if (out_lo) {  // second half term of the output (two-term output projection)
+                    u32x2_t l2;
+                    l2.x = pack_f16x2_lo(oacc[t][0] * inv, oacc[t][1] * inv, o2.x);
+                    l2.y = pack_f16x2_lo(oacc[t][2] * inv, oacc[t][3] * inv, o2.y);
+                    *reinterpret_cast<u32x2_t *>(out_lo + ((size_t)b * Hq + hq) * HD + 4 * j + 16 * t) = l2;
+                }
             }
         } else {
             float *p = ws + (((size_t)b * Hq + hq) * nsplit + split) * (HD + 2);
@@ -261,13 +268,13 @@ int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S) {
 
 void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride,
                                  f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st, KvMap map,
-                                 const int32_t *d_done) {
+                                 const int32_t *d_done, f16_t *out_lo) {
     if (B <= 0) return;
     const int g = Hq / Hkv;
     const int items = B * Hkv * (g < 8 ? 1 : g / 8) * nsplit;
     if (map.table)
-        decode_attention_gqa_kernel<true><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, ws, Hq, Hkv, S, nsplit, len_stride, map, d_done);
+        decode_attention_gqa_kernel<true><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, out_lo, ws, Hq, Hkv, S, nsplit, len_stride, map, d_done);
     else
-        decode_attention_gqa_kernel<false><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, ws, Hq, Hkv, S, nsplit, len_stride, KvMap(), d_done);
-    if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, 128, nsplit, st);
+        decode_attention_gqa_kernel<false><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, out_lo, ws, Hq, Hkv, S, nsplit, len_stride, KvMap(), d_done);
+    if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, 128, nsplit, st, out_lo);
 }

@@ -69,15 +69,39 @@ __device__ __forceinline__ float wave_max(float v) {
 // K (or V) area.  table == NULL: contiguous slabs [max_batch][Hkv][S][hd].  Otherwise the area is a pool of pages
 // [n_pages][Hkv][page][hd] with page = 1 << page_shift positions, and table[b * table_stride + (j >> page_shift)]
 // names the page that holds position j of sequence b.
+// kscale / vscale (both or neither): the cache rows are 16-bit block-scaled fixed point instead of IEEE half -- element e of
+// row i is q[i][e] * scale[i] with q int16 and one fp32 scale per row (= per position and kv head), scale = max|x| / 32767.
+// At the same 2 bytes per element a row of head_dim values of similar magnitude keeps about 15 significant bits instead of
+// half's 11.  The scales of a layer's K (or V) area are indexed like its rows (kv_row_index).
 struct KvMap {
     const int32_t *table = nullptr;
     int table_stride = 0;
     int page_shift = 0;
+    float *kscale = nullptr;
+    float *vscale = nullptr;
 };
 __device__ __forceinline__ size_t kv_row_index(const KvMap &m, int b, int kvh, int Hkv, int S, int j) {
     if (!m.table) return ((size_t)b * Hkv + kvh) * S + j;
     const int page = m.table[(size_t)b * m.table_stride + (j >> m.page_shift)];
     return (((size_t)page * Hkv + kvh) << m.page_shift) + (j & ((1 << m.page_shift) - 1));
+}
+
+// ---- 16-bit block-scaled rows (see KvMap)
+__device__ __forceinline__ float i16lo_to_f32(uint32_t pair) { return (float)((int32_t)(pair << 16) >> 16); }
+__device__ __forceinline__ float i16hi_to_f32(uint32_t pair) { return (float)((int32_t)pair >> 16); }
+// inv = 32767 / max|x| of the row (0 for an all-zero row): nearest integer, kept inside +-32767
+__device__ __forceinline__ int kv_quant(float x, float inv) {
+    float r = rintf(x * inv);
+    r = __builtin_amdgcn_fmed3f(r, -32767.f, 32767.f);
+    return (int)r;
+}
+__device__ __forceinline__ uint32_t pack_i16x2(int lo, int hi) { return ((uint32_t)lo & 0xffffu) | ((uint32_t)hi << 16); }
+__device__ __forceinline__ float kv_inv_of(float amax) { return amax > 0.f ? 32767.f / amax : 0.f; }
+__device__ __forceinline__ float kv_scale_of(float amax) { return amax * (1.0f / 32767.f); }
+
+// Two-term half split of a value: hi = half(x), lo = half(x - hi); hi + lo carries about 22 significant bits of x.
+__device__ __forceinline__ uint32_t pack_f16x2_lo(float x0, float x1, uint32_t hi) {
+    return pack_f16x2(x0 - f16lo_to_f32(hi), x1 - f16hi_to_f32(hi));
 }
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

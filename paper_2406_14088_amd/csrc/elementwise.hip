@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
                                                           f16_t *__restrict__ q_f16, f16_t *__restrict__ kc,
                                                           f16_t *__restrict__ vc, KvMap map,
                                                           const int32_t *__restrict__ d_valid,
-                                                          const int32_t *__restrict__ d_done) {
+                                                          const int32_t *__restrict__ d_done, f16_t *__restrict__ q_f16_lo) {
     int m = blockIdx.x;
     int b = b0 + m / T;
     bool store_kv = true;  // rows past a sequence's own length never reach the cache
@@ -139,14 +139,16 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     const float *row = qkv + (size_t)m * ld;
     const float *tab = rope_tab + (size_t)pos * hd;  // [half][2]
     int it = blockIdx.y * blockDim.x + threadIdx.x;
-    if (it < nq + 2 * nk) {
-        int kind = it < nq ? 0 : (it < nq + nk ? 1 : 2);
+    const bool valid = it < nq + 2 * nk;
+    int kind = 0, head = 0, r = 0, ia = 0, ib = 1;
+    float a = 0.f, c = 0.f;
+    if (valid) {
+        kind = it < nq ? 0 : (it < nq + nk ? 1 : 2);
         int local = kind == 0 ? it : (kind == 1 ? it - nq : it - nq - nk);
-        int head = local / half, r = local % half;
+        head = local / half;
+        r = local % half;
         int col0 = (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd)) + head * hd;
-        int ia, ib;
         if (kind == 2 || rope_style == 0) { ia = 2 * r; ib = 2 * r + 1; } else { ia = r; ib = r + half; }
-        float a = 0.f, c = 0.f;
         for (int s = 0; s < nsplit; ++s) {
             a += row[(size_t)s * split_stride + col0 + ia];
             c += row[(size_t)s * split_stride + col0 + ib];
@@ -159,24 +161,43 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
         if (kind == 0) {
             size_t o = (size_t)m * Hq * hd + (size_t)head * hd;
             if (q_f32) { q_f32[o + ia] = a; q_f32[o + ib] = c; }
-            if (q_f16) { q_f16[o + ia] = f32_to_f16(a); q_f16[o + ib] = f32_to_f16(c); }
-        } else if (store_kv) {
-            f16_t *dst = (kind == 1 ? kc : vc) + kv_row_index(map, b, head, Hkv, S, pos) * hd;
-            dst[ia] = f32_to_f16(a);
-            dst[ib] = f32_to_f16(c);
+            if (q_f16) {
+                const f16_t ha = f32_to_f16(a), hc = f32_to_f16(c);
+                q_f16[o + ia] = ha; q_f16[o + ib] = hc;
+                if (q_f16_lo) { q_f16_lo[o + ia] = f32_to_f16(a - f16_to_f32(ha)); q_f16_lo[o + ib] = f32_to_f16(c - f16_to_f32(hc)); }
+            }
         }
+    }
+    const bool kv_item = valid && kind != 0 && store_kv;
+    if (map.kscale) {
+        // 16-bit block-scaled rows: the hd / 2 threads of a head are consecutive lanes (hd is 64 or 128 here and every
+        // offset of the item space is a multiple of hd / 2), so the row maximum is an xor-shuffle reduction among them
+        float am = valid && kind != 0 ? fmaxf(fabsf(a), fabsf(c)) : 0.f;
+        for (int o = 1; o < half; o <<= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
+        if (kv_item) {
+            const size_t rowi = kv_row_index(map, b, head, Hkv, S, pos);
+            const float inv = kv_inv_of(am);
+            int16_t *dst = reinterpret_cast<int16_t *>(kind == 1 ? kc : vc) + rowi * hd;
+            dst[ia] = (int16_t)kv_quant(a, inv);
+            dst[ib] = (int16_t)kv_quant(c, inv);
+            if (r == 0) (kind == 1 ? map.kscale : map.vscale)[rowi] = kv_scale_of(am);
+        }
+    } else if (kv_item) {
+        f16_t *dst = (kind == 1 ? kc : vc) + kv_row_index(map, b, head, Hkv, S, pos) * hd;
+        dst[ia] = f32_to_f16(a);
+        dst[ib] = f32_to_f16(c);
     }
 }
 
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
                         int pos_stride, const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
                         f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st, KvMap map, const int32_t *d_valid,
-                        const int32_t *d_done) {
+                        const int32_t *d_done, f16_t *q_f16_lo) {
     if (M <= 0) return;
     int items = (Hq + 2 * Hkv) * (hd / 2);
     dim3 grid(M, ceil_div(items, 256));
     rope_append_kernel<<<grid, 256, 0, st>>>(qkv, nsplit, split_stride, T, b0, d_pos0, pos_stride, rope_tab, rope_style, Hq, Hkv, hd, S,
-                                          q_f32, q_f16, kc, vc, map, d_valid, d_done);
+                                          q_f32, q_f16, kc, vc, map, d_valid, d_done, q_f16_lo);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -330,19 +351,20 @@ void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, fl
 // Temperature sampling by inversion: e_v = exp((x_v - max) / temperature), next = smallest v with
 // e_0 + ... + e_v > u * sum(e); -1 if the row holds a NaN.  One workgroup per row.  Every thread owns a contiguous
 // segment of the row, the segment sums are scanned in thread order (fixed summation order: deterministic), and the
-// one thread whose prefix range contains the target walks its segment.
+// first thread (with weight) whose prefix exceeds the target walks its segment.
 #define SP_THREADS 1024
 __global__ __launch_bounds__(SP_THREADS) void sample_kernel(const float *__restrict__ logits, int V, float inv_temp,
                                                             const float *__restrict__ u, int32_t *__restrict__ next,
                                                             int32_t *lens, int32_t *done, int eos) {
     __shared__ float red[SP_THREADS / RL_WAVE];
     __shared__ float bcast;
-    __shared__ int snan, stoken;
+    __shared__ float pre[SP_THREADS];
+    __shared__ int snan, stoken, sowner;
     const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
     const float *row = logits + (size_t)b * V;
     const int seg = (V + SP_THREADS - 1) / SP_THREADS;
     const int i0 = t * seg < V ? t * seg : V, i1 = i0 + seg < V ? i0 + seg : V;
-    if (t == 0) { snan = 0; stoken = -1; }
+    if (t == 0) { snan = 0; stoken = -1; sowner = SP_THREADS; }
     __syncthreads();
     // ---- row maximum
     float m = -INFINITY;
@@ -377,17 +399,25 @@ __global__ __launch_bounds__(SP_THREADS) void sample_kernel(const float *__restr
     float total = 0.f;
     for (int w = 0; w < SP_THREADS / RL_WAVE; ++w) total += red[w];
     incl += base;
-    const float excl = incl - s;
+    pre[t] = incl;
+    __syncthreads();
+    // A thread's range starts exactly where its predecessor's ends (the stored prefix, not incl - s, which differs from it
+    // by rounding): the ranges tile [0, last prefix) without gaps.  The prefixes come out of a tree-shaped scan and may
+    // step back by an ulp, so the owner is the FIRST thread with weight whose prefix exceeds the target.
+    const float excl = t == 0 ? 0.f : pre[t - 1];
     const float target = u[b] * total;
-    // ---- the thread whose range [excl, incl) holds the target walks its segment
-    if (!bad && s > 0.f && excl <= target && target < incl) {
+    if (!bad && s > 0.f && incl > target) atomicMin(&sowner, t);
+    __syncthreads();
+    if (t == sowner) {
         float run = excl;
-        int tok = i1 - 1;
+        int tok = -1, last = i0;
         for (int i = i0; i < i1; ++i) {
-            run += expf((row[i] - mx) * inv_temp);
-            if (run > target) { tok = i; break; }
+            float e = expf((row[i] - mx) * inv_temp);
+            if (e > 0.f) last = i;
+            run += e;
+            if (e > 0.f && run > target) { tok = i; break; }
         }
-        stoken = tok;
+        stoken = tok >= 0 ? tok : last;  // the serial walk may round below the scanned prefix: the segment's last weighted index
     }
     __syncthreads();
     if (t == 0) {

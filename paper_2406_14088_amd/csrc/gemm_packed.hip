@@ -94,6 +94,7 @@ struct PackedParams {
     int M, K, ksteps, chunks, splits, epilogue;
     int tiles, zblocks;  // n-tiles, row blocks
     void *out;
+    f16_t *out_lo;       // SwiGLU epilogue, optional: second half term of the result, half(y - half(y)), same layout as out
     int64_t ldc;
     size_t split_stride;
 };
@@ -327,29 +328,35 @@ __global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_pa
             }
         }
     } else if (NB == 2) {
-        f16_t *ht = reinterpret_cast<f16_t *>(smem);  // [BM][PK_HT_STRIDE]
+        f16_t *ht = reinterpret_cast<f16_t *>(smem);  // [BM][PK_HT_STRIDE], and a second tile for the low term
+        const bool two_out = p.out_lo != nullptr;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 int m = mt * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
                 float g = acc[0][mt][e], u = acc[NB - 1][mt][e];
-                ht[m * PK_HT_STRIDE + w * 32 + (lane & 31)] = f32_to_f16(g / (1.0f + expf(-g)) * u);
+                const float y = g / (1.0f + expf(-g)) * u;
+                const f16_t hi = f32_to_f16(y);
+                ht[m * PK_HT_STRIDE + w * 32 + (lane & 31)] = hi;
+                if (two_out) ht[(BM + m) * PK_HT_STRIDE + w * 32 + (lane & 31)] = f32_to_f16(y - f16_to_f32(hi));
             }
         __syncthreads();
-        f16_t *out = reinterpret_cast<f16_t *>(p.out);
         const int c8 = (t & 15) * 8, rr = t >> 4;  // 16 lanes x 16 B = one 256-byte output row; 16 rows per pass
         const int ncols = rows - ltile * 128;
+        for (int tm = 0; tm < (two_out ? 2 : 1); ++tm) {
+            f16_t *out = tm == 0 ? reinterpret_cast<f16_t *>(p.out) : p.out_lo;
 #pragma unroll
-        for (int i = 0; i < BM / 16; ++i) {
-            int m = rr + 16 * i;
-            if (m < Mloc && c8 < ncols) {
-                f16_t *dst = out + (size_t)(m0 + m) * p.ldc + ltile * 128 + c8;
-                const f16_t *srcp = ht + m * PK_HT_STRIDE + c8;
-                if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-                    *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
-                } else {
-                    for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+            for (int i = 0; i < BM / 16; ++i) {
+                int m = rr + 16 * i;
+                if (m < Mloc && c8 < ncols) {
+                    f16_t *dst = out + (size_t)(m0 + m) * p.ldc + ltile * 128 + c8;
+                    const f16_t *srcp = ht + (tm * BM + m) * PK_HT_STRIDE + c8;
+                    if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+                        *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
+                    } else {
+                        for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+                    }
                 }
             }
         }
@@ -363,6 +370,7 @@ static void launch_p2(PackedParams &p, hipStream_t st) {
     size_t lds = (size_t)NBUF * TERMS * BM * PK_BK * 2;
     size_t epi = (size_t)BM * PK_CT_STRIDE * sizeof(float);
     if (epi > lds) lds = epi;
+    if (p.out_lo && (size_t)2 * BM * PK_HT_STRIDE * sizeof(f16_t) > lds) lds = (size_t)2 * BM * PK_HT_STRIDE * sizeof(f16_t);
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_kernel<NB, TERMS, MT, RC, SW>),
@@ -554,7 +562,8 @@ __global__ __launch_bounds__(PK_THREADS, 1) void gemm_packed_swiglu_halves_kerne
                 for (int e = 0; e < 16; ++e) ex[((cw * 2 + j) * MT * 16 + mt * 16 + e) * 64 + lane] = acc[j][mt][e];
     }
     __syncthreads();
-    f16_t *ht = reinterpret_cast<f16_t *>(smem + 2 * 2 * MT * 16 * 64 * 4);  // [BM][72] halves, after the exchange area
+    f16_t *ht = reinterpret_cast<f16_t *>(smem + 2 * 2 * MT * 16 * 64 * 4);  // 2 x [BM][72] halves (both terms), after the exchange area
+    const bool two_out = p.out_lo != nullptr;
     if (kg == 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -564,23 +573,28 @@ __global__ __launch_bounds__(PK_THREADS, 1) void gemm_packed_swiglu_halves_kerne
                 g += ex[((cw * 2 + 0) * MT * 16 + mt * 16 + e) * 64 + lane];
                 u += ex[((cw * 2 + 1) * MT * 16 + mt * 16 + e) * 64 + lane];
                 int m = mt * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                ht[m * 72 + cw * 32 + (lane & 31)] = f32_to_f16(g / (1.0f + expf(-g)) * u);
+                const float y = g / (1.0f + expf(-g)) * u;
+                const f16_t hi = f32_to_f16(y);
+                ht[m * 72 + cw * 32 + (lane & 31)] = hi;
+                if (two_out) ht[(BM + m) * 72 + cw * 32 + (lane & 31)] = f32_to_f16(y - f16_to_f32(hi));
             }
     }
     __syncthreads();
-    f16_t *out = reinterpret_cast<f16_t *>(p.out);
     const int c8 = (t & 7) * 8, rr = t >> 3;  // 8 lanes x 16 B = one 128-byte output row; 32 rows per pass
     const int ncols = rows - tile * 64;
+    for (int tm = 0; tm < (two_out ? 2 : 1); ++tm) {
+        f16_t *out = tm == 0 ? reinterpret_cast<f16_t *>(p.out) : p.out_lo;
 #pragma unroll
-    for (int i = 0; i < BM / 32; ++i) {
-        int m = rr + 32 * i;
-        if (m < Mloc && c8 < ncols) {
-            f16_t *dst = out + (size_t)(m0 + m) * p.ldc + tile * 64 + c8;
-            const f16_t *srcp = ht + m * 72 + c8;
-            if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-                *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
-            } else {
-                for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+        for (int i = 0; i < BM / 32; ++i) {
+            int m = rr + 32 * i;
+            if (m < Mloc && c8 < ncols) {
+                f16_t *dst = out + (size_t)(m0 + m) * p.ldc + tile * 64 + c8;
+                const f16_t *srcp = ht + (tm * BM + m) * 72 + c8;
+                if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
+                    *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
+                } else {
+                    for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+                }
             }
         }
     }
@@ -588,7 +602,9 @@ __global__ __launch_bounds__(PK_THREADS, 1) void gemm_packed_swiglu_halves_kerne
 
 template <int RC, bool SW>
 static void launch_halves(PackedParams &p, hipStream_t st) {
-    size_t lds = (size_t)3 * 2 * 128 * 64 * 2;  // three chunk buffers; the epilogue's exchange area and tile fit inside
+    size_t lds = (size_t)3 * 2 * 128 * 64 * 2;  // three chunk buffers; the epilogue's exchange area and first tile fit inside
+    const size_t epi = (size_t)2 * 2 * 4 * 16 * 64 * 4 + (size_t)2 * 128 * 72 * 2;  // exchange area + both output tiles
+    if (epi > lds) lds = epi;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_swiglu_halves_kernel<RC, SW>),
@@ -617,6 +633,7 @@ void launch_gemm_packed_swiglu_halves(const PackedGemmArgs &a, hipStream_t st) {
     p.epilogue = EPI_SWIGLU;
     p.splits = 1;
     p.out = a.out;
+    p.out_lo = a.out_lo;
     p.ldc = a.ldc;
     p.P[0] = a.P[0]; p.P[1] = a.P[1]; p.P[2] = a.P[0];
     p.rows[0] = a.rows[0]; p.rows[1] = a.rows[0]; p.rows[2] = 0;
@@ -666,6 +683,7 @@ void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
                 s.rows[1] = s.rows[2] = 0;
                 if (a.epilogue == EPI_SWIGLU) { s.P[1] = a.P[1] + skip; s.rows[1] = s.rows[0]; }
                 s.out = static_cast<char *>(a.out) + (size_t)(col + n) * out_elem;
+                if (a.out_lo) s.out_lo = a.out_lo + (col + n);
                 launch_gemm_packed(s, st);
             }
             col += a.rows[i];
@@ -685,6 +703,7 @@ void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
     p.splits = a.epilogue != EPI_F32 ? 1 : (a.splits < 1 ? 1 : a.splits);
     if (p.splits > p.chunks) p.splits = p.chunks;
     p.out = a.out;
+    p.out_lo = a.epilogue == EPI_SWIGLU ? a.out_lo : nullptr;
     p.ldc = a.ldc;
     p.split_stride = a.split_stride;
     const bool swiglu = a.epilogue == EPI_SWIGLU;

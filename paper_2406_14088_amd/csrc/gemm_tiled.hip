@@ -34,6 +34,7 @@ struct TiledParams {
     int M, K, chunks, terms, epilogue;
     int tiles_m, tiles_n;
     void *out;
+    f16_t *out_lo;      // EPI_SWIGLU, optional: second half term of the result
     int64_t ldc;
     RopeEpilogue rope;  // EPI_ROPE
     const f16_t *P[3];  // fragment-order copies of W[0..2] (gemm_tiled_dma_kernel), or all NULL
@@ -105,6 +106,9 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
         const bool head_ok = nb < rows_w;   // (whole heads: the 128 columns exist or none does)
         constexpr int HT = 128 + 8;         // halves per row of the band
         f16_t *ht = reinterpret_cast<f16_t *>(smem) + w * 32 * HT;
+        float *hs = reinterpret_cast<float *>(smem + 4 * 32 * HT * 2) + w * 32;  // row scales of the band (block-scaled cache)
+        f16_t *hl = reinterpret_cast<f16_t *>(smem + 4 * 32 * HT * 2 + 4 * 32 * 4) + w * 32 * HT;  // low half terms of q rows
+        const bool i16 = seg != 0 && rp.map.kscale != nullptr;  // cache rows as 16-bit block-scaled fixed point
         if (head_ok) {
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
@@ -117,6 +121,7 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
                     if (pos >= rp.T) pos -= rp.T;  // T >= 32: at most one wrap inside a band
                     pos = pos < rp.S ? pos : rp.S - 1;
                     const float *tab = rp.rope_tab + (size_t)pos * 128;
+                    float va[2], vc2[2];
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         const int rr = j * 32 + (lane & 31);
@@ -127,8 +132,33 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
                             const float rb = __fmaf_rn(c, cs, __fmul_rn(a, sn));
                             a = ra; c = rb;
                         }
-                        ht[r * HT + rr] = f32_to_f16(a);
-                        ht[r * HT + rr + 64] = f32_to_f16(c);
+                        va[j] = a; vc2[j] = c;
+                    }
+                    if (i16) {
+                        // the 32 lanes of a half-wavefront hold the 128 elements of row r: row maximum by xor shuffles
+                        float am = fmaxf(fmaxf(fabsf(va[0]), fabsf(va[1])), fmaxf(fabsf(vc2[0]), fabsf(vc2[1])));
+#pragma unroll
+                        for (int o = 1; o < 32; o <<= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
+                        const float inv = kv_inv_of(am);
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const int rr = j * 32 + (lane & 31);
+                            ht[r * HT + rr] = (f16_t)(kv_quant(va[j], inv) & 0xffff);
+                            ht[r * HT + rr + 64] = (f16_t)(kv_quant(vc2[j], inv) & 0xffff);
+                        }
+                        if ((lane & 31) == 0) hs[r] = kv_scale_of(am);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const int rr = j * 32 + (lane & 31);
+                            const f16_t ha = f32_to_f16(va[j]), hc = f32_to_f16(vc2[j]);
+                            ht[r * HT + rr] = ha;
+                            ht[r * HT + rr + 64] = hc;
+                            if (seg == 0 && rp.q_f16_lo) {
+                                hl[r * HT + rr] = f32_to_f16(va[j] - f16_to_f32(ha));
+                                hl[r * HT + rr + 64] = f32_to_f16(vc2[j] - f16_to_f32(hc));
+                            }
+                        }
                     }
                 }
                 // 16 lanes per row (16 bytes each), 4 rows per instruction
@@ -142,6 +172,10 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
                     const u32x4_t v = *reinterpret_cast<const u32x4_t *>(ht + r * HT + c8);
                     if (seg == 0) {
                         *reinterpret_cast<u32x4_t *>(rp.q_f16 + ((size_t)m * rp.Hq + head) * 128 + c8) = v;
+                        if (rp.q_f16_lo) {  // second half term of q: the band's low rows sit behind its 32 high rows
+                            const u32x4_t vl = *reinterpret_cast<const u32x4_t *>(hl + r * HT + c8);
+                            *reinterpret_cast<u32x4_t *>(rp.q_f16_lo + ((size_t)m * rp.Hq + head) * 128 + c8) = vl;
+                        }
                     } else {
                         bool store_kv = pos < rp.S;
                         if (rp.d_valid) {
@@ -150,8 +184,10 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
                             store_kv = store_kv && pos < nv;
                         }
                         if (store_kv) {
-                            f16_t *dst = (seg == 1 ? rp.kc : rp.vc) + kv_row_index(rp.map, seq, head, rp.Hkv, rp.S, pos) * 128 + c8;
+                            const size_t rowi = kv_row_index(rp.map, seq, head, rp.Hkv, rp.S, pos);
+                            f16_t *dst = (seg == 1 ? rp.kc : rp.vc) + rowi * 128 + c8;
                             *reinterpret_cast<u32x4_t *>(dst) = v;
+                            if (i16 && (lane & 15) == 0) (seg == 1 ? rp.map.kscale : rp.map.vscale)[rowi] = hs[r];
                         }
                     }
                 }
@@ -234,26 +270,33 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
             }
             __syncthreads();
             if (wn == 0) {
+                // the band is private to this wavefront: the high term leaves first, then the band is refilled with the
+                // low term half(y - half(y)) when the caller asked for it
+                for (int tm = 0; tm < (p.out_lo ? 2 : 1); ++tm) {
 #pragma unroll
-                for (int j = 0; j < WN; ++j)
+                    for (int j = 0; j < WN; ++j)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        float g = acc[i][j][e], u = ex[(j * 16 + e) * 64 + lane];
-                        float a = g / (1.0f + expf(-g)) * u;
-                        ht[((e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * (2 * CT) + j * 32 + (lane & 31)] = f32_to_f16(a);
-                    }
-                const int mb = m0 + (wm * WM + i) * 32;
+                        for (int e = 0; e < 16; ++e) {
+                            float g = acc[i][j][e], u = ex[(j * 16 + e) * 64 + lane];
+                            float a = g / (1.0f + expf(-g)) * u;
+                            const f16_t hi = f32_to_f16(a);
+                            ht[((e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * (2 * CT) + j * 32 + (lane & 31)] =
+                                tm == 0 ? hi : f32_to_f16(a - f16_to_f32(hi));
+                        }
+                    f16_t *outp = tm == 0 ? out : p.out_lo;
+                    const int mb = m0 + (wm * WM + i) * 32;
 #pragma unroll
-                for (int k = 0; k < 32 / RPI; ++k) {
-                    const int r = k * RPI + r_in, m = mb + r;
-                    if (m >= p.M || c8 >= ncols) continue;
-                    u32x4_t v = *reinterpret_cast<const u32x4_t *>(ht + r * (2 * CT) + c8);
-                    f16_t *dst = out + (size_t)m * p.ldc + oc + c8;
-                    if (c8 + 8 <= ncols && (((size_t)m * p.ldc + oc) & 7) == 0) {
-                        *reinterpret_cast<u32x4_t *>(dst) = v;
-                    } else {
-                        const f16_t *src = ht + r * (2 * CT) + c8;
-                        for (int q = 0; q < 8 && c8 + q < ncols; ++q) dst[q] = src[q];
+                    for (int k = 0; k < 32 / RPI; ++k) {
+                        const int r = k * RPI + r_in, m = mb + r;
+                        if (m >= p.M || c8 >= ncols) continue;
+                        u32x4_t v = *reinterpret_cast<const u32x4_t *>(ht + r * (2 * CT) + c8);
+                        f16_t *dst = outp + (size_t)m * p.ldc + oc + c8;
+                        if (c8 + 8 <= ncols && (((size_t)m * p.ldc + oc) & 7) == 0) {
+                            *reinterpret_cast<u32x4_t *>(dst) = v;
+                        } else {
+                            const f16_t *src = ht + r * (2 * CT) + c8;
+                            for (int q = 0; q < 8 && c8 + q < ncols; ++q) dst[q] = src[q];
+                        }
                     }
                 }
             }
@@ -631,6 +674,7 @@ static void launch_one(const GemmArgs &a, hipStream_t st) {
     p.chunks = ceil_div(a.K, TG_BK);
     p.epilogue = a.epilogue;
     p.out = a.out;
+    p.out_lo = a.epilogue == EPI_SWIGLU ? a.out_lo : nullptr;
     p.ldc = a.ldc;
     int n_total = 0;
     bool have_p = a.P[0] != nullptr;
@@ -695,6 +739,7 @@ void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
             if (a.A_lo) s.A_lo = a.A_lo + (size_t)m * a.lda;
             s.M = a.M - m < rows_max ? a.M - m : rows_max;
             s.out = static_cast<char *>(a.out) + (size_t)m * a.ldc * out_elem;
+            if (a.out_lo) s.out_lo = a.out_lo + (size_t)m * a.ldc;
             launch_gemm_tiled(s, st);
         }
         return;
@@ -713,6 +758,7 @@ void launch_gemm_tiled(const GemmArgs &a, hipStream_t st) {
             s.W[1] = a.W[1] + (size_t)n * a.K;
             s.rows[0] = s.rows[1] = r;
             s.out = static_cast<char *>(a.out) + (size_t)n * out_elem;
+            if (a.out_lo) s.out_lo = a.out_lo + n;
             launch_one(s, st);
         }
         return;

@@ -19,7 +19,8 @@ void launch_add_rmsnorm(float *x, const float *part, int nsplit, size_t part_str
 void launch_rope_append(const float *qkv, int nsplit, size_t split_stride, int M, int T, int b0, const int32_t *d_pos0,
                         int pos_stride, const float *rope_tab, int rope_style, int Hq, int Hkv, int hd, int S, float *q_f32,
                         f16_t *q_f16, f16_t *kc, f16_t *vc, hipStream_t st, KvMap map = KvMap(),
-                        const int32_t *d_valid = nullptr, const int32_t *d_done = nullptr);
+                        const int32_t *d_valid = nullptr, const int32_t *d_done = nullptr,
+                        f16_t *q_f16_lo = nullptr);  // optional: second half term of q, half(q - half(q)), laid out like q_f16
 // next[b] = lowest index of the largest logit of row b (-1 if the row holds a NaN).  Optional bookkeeping per sequence
 // (lens, done may be NULL; eos < 0: no end token): a sequence with done[b] returns eos and does not grow; otherwise
 // lens[b] += 1 and done[b] = (next[b] == eos).
@@ -64,6 +65,7 @@ struct RopeEpilogue {
     const float *rope_tab;  // [S, 64, 2] (cos, sin)
     int T, b0, Hq, Hkv, S;
     f16_t *q_f16;           // [M, Hq * 128]
+    f16_t *q_f16_lo = nullptr;  // optional: second half term of q, half(q - half(q)), same layout
     f16_t *kc, *vc;         // this layer's K and V areas, laid out as `map` says
     KvMap map;
     const int32_t *d_valid; // optional, as in launch_rope_append
@@ -85,6 +87,7 @@ struct GemmArgs {
     // tiled kernel only, optional: fragment-order half copies of W[0..2] (as written by launch_pack_weights).  When every
     // W_i has one, large tiles copy both operands global -> LDS directly instead of staging them through registers.
     const f16_t *P[3] = {nullptr, nullptr, nullptr};
+    f16_t *out_lo = nullptr;  // EPI_SWIGLU of the tiled kernel, optional: second half term of the result, laid out like out
 };
 // M <= 256: weights stream through registers exactly once, activations are staged in LDS.
 void launch_gemm_skinny(const GemmArgs &a, hipStream_t st);
@@ -113,6 +116,7 @@ struct PackedGemmArgs {
     int nb;               // 32-column blocks per wavefront, 1 or 2 (fp32 epilogues; SwiGLU always uses 2)
     int depth;            // weight chunks in flight per wavefront: 2 or 4 (0: 2)
     int rows_per_wg;      // activation rows per workgroup: 32, 64 or 128 (0: 128); the row blocks of one tile re-read its weights from L2
+    f16_t *out_lo = nullptr;  // EPI_SWIGLU, optional: second half term of the result, half(y - half(y)), laid out like out
 };
 // M of any size (row blocks of 128 re-stream the weights; meant for M <= 256).
 void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st);
@@ -129,7 +133,8 @@ void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *split
 // [B, Hq*hd].  ws: fp32 workspace of decode_attention_ws_floats(...) elements when nsplit > 1.
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map = KvMap(),
-                             const int32_t *d_done = nullptr);  // d_done (optional): sequences with a non-zero flag are skipped
+                             const int32_t *d_done = nullptr,   // d_done (optional): sequences with a non-zero flag are skipped
+                             f16_t *out_lo = nullptr);          // out_lo (optional): half(o - half(o)), second term of the output
 // Fused form: q, k, v of the new token are taken from the split-K partials of the QKV projection (each
 // [B, (Hq+2Hkv)*hd], q | k | v per row): partials added, q and k rotated at position *d_len, the k/v row appended to
 // the cache (kc/vc are written) and used from registers.  Replaces launch_rope_append + launch_decode_attention.
@@ -142,8 +147,9 @@ bool decode_attention_gqa_supported(int Hq, int Hkv, int hd);
 int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S);
 void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride,
                                  f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st,
-                                 KvMap map = KvMap(), const int32_t *d_done = nullptr);
-void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st);
+                                 KvMap map = KvMap(), const int32_t *d_done = nullptr, f16_t *out_lo = nullptr);
+void launch_decode_attention_merge(const float *ws, f16_t *out, int B, int Hq, int hd, int nsplit, hipStream_t st,
+                                   f16_t *out_lo = nullptr);
 size_t decode_attention_ws_floats(int B, int Hq, int hd, int nsplit);
 int decode_attention_default_splits(int B, int Hkv, int S);
 int decode_attention_group(int g);  // query heads per wavefront for Hq/Hkv = g
@@ -155,4 +161,4 @@ int decode_attention_group(int g);  // query heads per wavefront for Hq/Hkv = g
 // zero rows with zero weight, and the output rows of later queries are unspecified (finite).
 void launch_prefill_attention(const f16_t *q, const f16_t *kc, const f16_t *vc, f16_t *out, int nb, int b0, int T,
                               int Hq, int Hkv, int hd, int S, hipStream_t st, KvMap map = KvMap(),
-                              const int32_t *d_valid = nullptr);
+                              const int32_t *d_valid = nullptr, f16_t *out_lo = nullptr, const f16_t *q_lo = nullptr);

@@ -42,11 +42,28 @@ int validate(const rl_gen_shape *s) {
     if (s->rope_style != 0 && s->rope_style != 1) return RL_GEN_E_SHAPE;
     if (s->weight_dtype != 0 && s->weight_dtype != 1) return RL_GEN_E_SHAPE;
     if (!(s->rope_base > 0.f) || !(s->rms_eps >= 0.f)) return RL_GEN_E_SHAPE;
+    if (s->precision < 0 || s->precision > 3) return RL_GEN_E_SHAPE;
     // every weight matrix is addressed through a 32-bit range-checked buffer descriptor
     const uint64_t lim = 0xffffffffull;
     if ((uint64_t)s->vocab * s->hidden * 2 > lim || (uint64_t)s->ffn * s->hidden * 2 > lim) return RL_GEN_E_SHAPE;
     return RL_GEN_OK;
 }
+
+// Which 16-bit roundings the path keeps (rl_gen_shape.precision).  The logit error against an fp64 evaluation grows
+// roughly with the square root of the depth and with the width (measured, random-init weights: rms 4.7e-3 at 32 layers
+// x 4096, 7.5e-3 at 40 x 5120, 2.0e-2 at 80 x 8192 on level 1; on level 2: 2.7e-3, 4.6e-3 -- the latter with a worst logit
+// of 2.8e-2 --), so models deeper or wider than the 7B shape default to the most careful level.
+int prec_level(const rl_gen_shape *s) {
+    if (s->precision != 0) return s->precision;
+    return s->n_layers > 32 || s->hidden > 4096 ? 3 : 2;
+}
+// Block-scaled cache rows are read by the vector attention kernel; grouped-query shapes keep half rows for the matrix-core
+// kernel unless the level asks for the more exact cache everywhere.
+bool kv_block_scaled(const rl_gen_shape *s) {
+    const int p = prec_level(s);
+    return p >= 3 || (p == 2 && !decode_attention_gqa_supported(s->n_heads, s->n_kv_heads, s->head_dim));
+}
+size_t kv_row_bytes(const rl_gen_shape *s) { return (size_t)s->head_dim * sizeof(f16_t) + (kv_block_scaled(s) ? sizeof(float) : 0); }
 
 int page_shift_of(int page_size) {
     for (int sh = 4; (1 << sh) <= kMaxPage; ++sh)
@@ -55,7 +72,7 @@ int page_shift_of(int page_size) {
 }
 
 int attn_splits(const rl_gen_shape *s) {
-    if (decode_attention_gqa_supported(s->n_heads, s->n_kv_heads, s->head_dim))
+    if (!kv_block_scaled(s) && decode_attention_gqa_supported(s->n_heads, s->n_kv_heads, s->head_dim))
         return decode_attention_gqa_default_splits(s->max_batch, s->n_heads, s->n_kv_heads, s->max_seq);
     int g = s->n_heads / s->n_kv_heads;
     int gt = decode_attention_group(g);
@@ -82,9 +99,9 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.part = take(part_elems * 4);
     p.part_elems = part_elems;
     p.qf32 = take((size_t)s->max_batch * qd * 4);
-    p.qbf = take((size_t)rows * qd * 2);
-    p.attn = take((size_t)rows * qd * 2);
-    p.act = take((size_t)rows * s->ffn * 2);
+    p.qbf = take((size_t)2 * rows * qd * 2);    // rotated q of a prefill, and its low term behind the rows in use
+    p.attn = take((size_t)2 * rows * qd * 2);   // attention output, and its low term behind the rows in use
+    p.act = take((size_t)2 * rows * s->ffn * 2);  // SwiGLU output, likewise
     p.attn_ws = take(decode_attention_ws_floats(s->max_batch, s->n_heads, s->head_dim, attn_splits(s)) * 4 + 16);
     p.logits = take((size_t)s->max_batch * s->vocab * 4);
     p.next = take((size_t)s->max_batch * 4);
@@ -125,6 +142,8 @@ struct rl_gen {
     unsigned char *work;
     WorkPlan wp;
     int nsplit_attn;
+    int prec;      // resolved precision level (1..3)
+    bool kv_i16;   // cache rows are 16-bit block-scaled fixed point; their fp32 scales follow all rows in the arena
     int B, len;
     bool graph_on, prof_on, qkv_two_term;
     // paged cache (rl_gen_create_paged): the kv arena is a pool of n_pages pages of 1 << page_shift positions
@@ -168,9 +187,15 @@ struct rl_gen {
     }
     f16_t *kslab(int l) const { return kv + (size_t)(2 * l) * area_elems(); }
     f16_t *vslab(int l) const { return kv + (size_t)(2 * l + 1) * area_elems(); }
-    KvMap kvmap() const {
+    float *scales() const { return reinterpret_cast<float *>(kv + (size_t)2 * s.n_layers * area_elems()); }
+    KvMap kvmap(int l) const {  // how layer l's K and V areas are addressed
         KvMap m;
         if (page_shift) { m.table = d_table(); m.table_stride = table_stride; m.page_shift = page_shift; }
+        if (kv_i16) {
+            const size_t area_rows = area_elems() / s.head_dim;
+            m.kscale = scales() + (size_t)(2 * l) * area_rows;
+            m.vscale = scales() + (size_t)(2 * l + 1) * area_rows;
+        }
         return m;
     }
 };
@@ -270,33 +295,36 @@ int project(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int64_t lda, 
 // shape at up to 128 rows -- it is level or slightly ahead (48 against 52 us at 32 rows, 54 against 55 us at 128).
 bool packed_swiglu_wins(int M, int ffn) { return M > 128 || ffn > 256 * 64 || (ffn >= 14336 && M > 64); }
 
-void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
+// Fused gate/up projection + SwiGLU of M rows into h->act().  A_lo (optional): second half term of the input; honoured by
+// the kernel that reads fragment-order copies, dropped otherwise.  out_lo (optional): where the second half term of the
+// result goes.  Returns whether out_lo was written (the row-major kernel for few rows has no such output).
+bool swiglu_project(rl_gen *h, const f16_t *A, const f16_t *A_lo, f16_t *out_lo, int M, int l, hipStream_t st) {
     const bool copies = h->packed && l < h->packed_gu_layers;
     // Up to 128 rows and FFN widths up to 16384: the kernel that puts the K halves of each chunk on separate wavefronts (the
     // row-major kernel's sums in its order, from the copies).  Measured against the other two at 128 / 64 rows: FFN 11008
     // 46.6 us (row-major 52.2, packed 61); FFN 14336 54.0 / 49.7 us (packed 61 / 54.6, row-major 63 / 55.7).  Wider
     // FFNs (K = 8192 shapes) and more rows stay with the packed kernel (34B shape at 64 rows: 137 against 160 us).
-    if (copies && M <= 128 && h->s.ffn <= 256 * 64 && gemm_packed_swiglu_halves_supported(h->s.ffn, h->s.hidden)) {
+    if (copies && !A_lo && M <= 128 && h->s.ffn <= 256 * 64 && gemm_packed_swiglu_halves_supported(h->s.ffn, h->s.hidden)) {
         PackedGemmArgs q;
         q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
         q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
         q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
-        q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
+        q.out = h->act(); q.out_lo = out_lo; q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
         q.nb = 2; q.rows_per_wg = 128; q.depth = 2;
         Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
         launch_gemm_packed_swiglu_halves(q, st);
-        return;
+        return out_lo != nullptr;
     }
-    if (copies && packed_swiglu_wins(M, h->s.ffn)) {
+    if (copies && (A_lo || packed_swiglu_wins(M, h->s.ffn))) {
         PackedGemmArgs q;
-        q.A = A; q.A_lo = nullptr; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
+        q.A = A; q.A_lo = A_lo; q.lda = h->s.hidden; q.M = M; q.K = h->s.hidden;
         q.P[0] = h->pw[W_GATE][l]; q.P[1] = h->pw[W_UP][l]; q.P[2] = nullptr;
         q.rows[0] = h->s.ffn; q.rows[1] = h->s.ffn; q.rows[2] = 0;
-        q.out = h->act(); q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
+        q.out = h->act(); q.out_lo = out_lo; q.ldc = h->s.ffn; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_SWIGLU;
         q.nb = 2; q.rows_per_wg = M > 128 ? 128 : 64; q.depth = 2;
         Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
         launch_gemm_packed(q, st);
-        return;
+        return out_lo != nullptr;
     }
     GemmArgs a;
     a.A = A; a.lda = h->s.hidden; a.M = M; a.K = h->s.hidden;
@@ -305,16 +333,30 @@ void swiglu_project(rl_gen *h, const f16_t *A, int M, int l, hipStream_t st) {
     a.rows[0] = h->s.ffn; a.rows[1] = h->s.ffn; a.rows[2] = 0;
     a.out = h->act(); a.ldc = h->s.ffn; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
     Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
-    if (M <= kSkinnyMaxM) launch_gemm_skinny(a, st);
-    else launch_gemm_tiled(a, st);
+    if (M <= kSkinnyMaxM) { launch_gemm_skinny(a, st); return false; }
+    a.out_lo = out_lo;
+    launch_gemm_tiled(a, st);
+    return out_lo != nullptr;
+}
+
+// x += (A + A_lo) W^T for the O and down projections (N = hidden columns): through fp32 partials that the following
+// add_rmsnorm adds (few rows; returns their number) or accumulated by the kernel itself (many rows; returns 0).
+int project_resid(rl_gen *h, int cls, const f16_t *A, const f16_t *A_lo, int M, int K, const bf16_t *W, const f16_t *P, hipStream_t st) {
+    const int d = h->s.hidden;
+    if (h->packed && M <= kSkinnyMaxM) return project_packed(h, cls, A, A_lo, K, M, K, P, d, nullptr, 0, nullptr, 0, st);
+    if (M > kSkinnyMaxM) return project(h, cls, A, A_lo, K, M, K, W, d, nullptr, 0, nullptr, 0, h->x(), d, st, h->packed ? P : nullptr);
+    // row-major kernel for few rows: the low term sits in the rows right behind the high term ([A; A_lo], 2 M rows) and the
+    // consumer adds the two row blocks of every partial like two partials
+    const int terms = A_lo ? 2 : 1;
+    return terms * project(h, cls, A, nullptr, K, terms * M, K, W, d, nullptr, 0, nullptr, 0, nullptr, 0, st);
 }
 
 // All layers for M = nb*T rows (sequences b0 .. b0+nb-1, T new positions each starting at *d_pos0),
 // then final norm; leaves the normalised rows in h->h().  decode == (T == 1 and attention over the cache).
 // d_valid (prefill of ragged prompts): per-sequence count of rows that exist; later rows never reach the cache.
-void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool decode, hipStream_t st,
+// Returns whether the rows behind the first M of h->h() hold the low term of the final-norm output.
+bool run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool decode, hipStream_t st,
                 const int32_t *d_valid = nullptr) {
-    const KvMap map = h->kvmap();
     const rl_gen_shape &s = h->s;
     const int M = nb * T, d = s.hidden, qd = s.n_heads * s.head_dim, kvd = s.n_kv_heads * s.head_dim;
     const int L = s.n_layers;
@@ -322,32 +364,41 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
         Scope sc(h, RL_GEN_K_EMBED, st);
         launch_embed(tokens, h->tok_emb, h->x(), M, d, s.vocab, st);
     }
-    // The normalised activations that feed the QKV projection are kept as a two-term half split [h; h_lo]
-    // (rows M..2M-1 hold what the first rounding lost): q, k and v errors are what the logits are most
-    // sensitive to, because k and v stay in the cache for every later token.  The projection then runs on 2M
-    // rows and its consumer adds the two row blocks like two more split-K partials.
+    // Two-term activations.  What feeds a projection is stored as IEEE half; where the level asks for it the value is kept
+    // as a two-term half sum hi + lo (lo = half(y - half(y)): about 22 significant bits), the low term in the rows right
+    // behind the M rows in use, and the projection multiplies both terms with the same weights.  Level 1: the attention-norm
+    // output (q, k and v errors are what the logits are most sensitive to: k and v stay in the cache for every later
+    // token); level 2: also the attention output and the SwiGLU output; level 3: also the FFN-norm and final-norm outputs.
     const int terms = h->qkv_two_term ? 2 : 1;
-    f16_t *h_lo = terms == 2 ? h->h() + (size_t)M * d : nullptr;
+    const bool two_o = h->prec >= 2, two_f = h->prec >= 3;
+    f16_t *h_lo = h->h() + (size_t)M * d;
+    f16_t *attn_lo = two_o ? h->attn() + (size_t)M * qd : nullptr;
+    f16_t *act_lo = two_o ? h->act() + (size_t)M * s.ffn : nullptr;
+    // a prefill over block-scaled cache rows multiplies two-term keys with two-term queries
+    f16_t *q_lo = !decode && h->kv_i16 ? h->qbf() + (size_t)M * qd : nullptr;
     {
         Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
+        const bool lo = L > 0 ? terms == 2 : two_f;
         launch_add_rmsnorm(h->x(), nullptr, 0, 0, L > 0 ? h->lw[W_ATTN_NORM][0] : h->final_norm, s.rms_eps, h->h(),
-                           L > 0 ? h_lo : nullptr, M, d, st);
+                           lo ? h_lo : nullptr, M, d, st);
     }
     for (int l = 0; l < L; ++l) {
+        const KvMap map = h->kvmap(l);
         const bool pk = h->packed && M <= kSkinnyMaxM;
+        const f16_t *hq_lo = terms == 2 ? h_lo : nullptr;
         bool qkv_stored = false;  // q and the cache rows already written by the projection itself
         int ns;
         if (pk)  // both terms go through the same weight fragments into the same accumulators
-            ns = project_packed(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->pw[W_Q][l], qd, h->pw[W_K][l], kvd, h->pw[W_V][l],
+            ns = project_packed(h, RL_GEN_K_GEMM_QKV, h->h(), hq_lo, d, M, d, h->pw[W_Q][l], qd, h->pw[W_K][l], kvd, h->pw[W_V][l],
                                 kvd, st);
-        else if (!decode && gemm_tiled_rope_supported(M, d, d, s.n_heads, s.n_kv_heads, s.head_dim, s.rope_style, T, h_lo != nullptr) &&
-                 (!h_lo || (size_t)(h_lo - h->h()) * 2 < 0x70000000ull)) {
+        else if (!decode && gemm_tiled_rope_supported(M, d, d, s.n_heads, s.n_kv_heads, s.head_dim, s.rope_style, T, hq_lo != nullptr) &&
+                 (!hq_lo || (size_t)(hq_lo - h->h()) * 2 < 0x70000000ull)) {
             // prefill: the projection's epilogue rotates q and k and stores q and the cache rows itself
             RopeEpilogue rp;
             rp.rope_tab = h->rope(); rp.T = T; rp.b0 = b0; rp.Hq = s.n_heads; rp.Hkv = s.n_kv_heads; rp.S = s.max_seq;
-            rp.q_f16 = h->qbf(); rp.kc = h->kslab(l); rp.vc = h->vslab(l); rp.map = map; rp.d_valid = d_valid;
+            rp.q_f16 = h->qbf(); rp.q_f16_lo = q_lo; rp.kc = h->kslab(l); rp.vc = h->vslab(l); rp.map = map; rp.d_valid = d_valid;
             GemmArgs a;
-            a.A = h->h(); a.A_lo = h_lo; a.lda = d; a.M = M; a.K = d;
+            a.A = h->h(); a.A_lo = hq_lo; a.lda = d; a.M = M; a.K = d;
             a.W[0] = h->lw[W_Q][l]; a.W[1] = h->lw[W_K][l]; a.W[2] = h->lw[W_V][l];
             if (h->packed) { a.P[0] = h->pw[W_Q][l]; a.P[1] = h->pw[W_K][l]; a.P[2] = h->pw[W_V][l]; }
             a.rows[0] = qd; a.rows[1] = kvd; a.rows[2] = kvd;
@@ -359,7 +410,7 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             qkv_stored = true;
             ns = 0;
         } else if (M > kSkinnyMaxM)  // large-M kernel: one contraction over [h | h_lo] x [W | W]
-            ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), h_lo, d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
+            ns = project(h, RL_GEN_K_GEMM_QKV, h->h(), hq_lo, d, M, d, h->lw[W_Q][l], qd, h->lw[W_K][l], kvd, h->lw[W_V][l], kvd,
                          nullptr, 0, st, h->packed ? h->pw[W_Q][l] : nullptr, h->packed ? h->pw[W_K][l] : nullptr,
                          h->packed ? h->pw[W_V][l] : nullptr);
         else  // row-major skinny kernel: stacked rows [h; h_lo], the consumer adds the two row blocks
@@ -370,7 +421,8 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             launch_rope_append(h->part(), ns, (size_t)M * (qd + 2 * kvd), M, T, b0, decode ? h->d_lens() : h->d_zero(),
                                decode ? 1 : 0, h->rope(), s.rope_style, s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq,
                                decode ? h->qf32() : nullptr, decode ? nullptr : h->qbf(), h->kslab(l), h->vslab(l), st, map,
-                               d_valid, decode && h->eos >= 0 ? h->d_done() : nullptr);  // without an end token no sequence ever ends
+                               d_valid, decode && h->eos >= 0 ? h->d_done() : nullptr,  // without an end token no sequence ever ends
+                               q_lo);
         }
         // (A single kernel that takes q, k, v from the partials, rotates, appends and attends exists --
         // launch_decode_attention_fused -- but measured no faster per step: what the separate kernel costs, the
@@ -379,36 +431,35 @@ void run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
             Scope sc(h, RL_GEN_K_DECODE_ATTN, st);
             launch_decode_attention(h->qf32(), h->kslab(l), h->vslab(l), h->d_lens(), 1, h->attn(), h->attn_ws(), nb,
                                     s.n_heads, s.n_kv_heads, s.head_dim, s.max_seq, h->nsplit_attn, st, map,
-                                    h->eos >= 0 ? h->d_done() : nullptr);  // ended sequences cost no cache traffic
+                                    h->eos >= 0 ? h->d_done() : nullptr, attn_lo);  // ended sequences cost no cache traffic
         } else {
             Scope sc(h, RL_GEN_K_PREFILL_ATTN, st);
             launch_prefill_attention(h->qbf(), h->kslab(l), h->vslab(l), h->attn(), nb, b0, T, s.n_heads, s.n_kv_heads,
-                                     s.head_dim, s.max_seq, st, map, d_valid);
+                                     s.head_dim, s.max_seq, st, map, d_valid, attn_lo, q_lo);
         }
-        if (pk) ns = project_packed(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->pw[W_O][l], d, nullptr, 0, nullptr, 0, st);
-        else ns = project(h, RL_GEN_K_GEMM_O, h->attn(), nullptr, qd, M, qd, h->lw[W_O][l], d, nullptr, 0, nullptr, 0, h->x(), d, st,
-                          h->packed ? h->pw[W_O][l] : nullptr);
+        ns = project_resid(h, RL_GEN_K_GEMM_O, h->attn(), attn_lo, M, qd, h->lw[W_O][l], h->packed ? h->pw[W_O][l] : nullptr, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
-            launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), nullptr, M, d, st);
+            launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, h->lw[W_FFN_NORM][l], s.rms_eps, h->h(), two_f ? h_lo : nullptr, M, d, st);
         }
-        swiglu_project(h, h->h(), M, l, st);
-        if (pk)
-            ns = project_packed(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->pw[W_DOWN][l], d, nullptr, 0, nullptr, 0, st);
-        else
-            ns = project(h, RL_GEN_K_GEMM_DOWN, h->act(), nullptr, s.ffn, M, s.ffn, h->lw[W_DOWN][l], d, nullptr, 0, nullptr, 0, h->x(), d, st,
-                         h->packed ? h->pw[W_DOWN][l] : nullptr);
+        const bool have_act_lo = swiglu_project(h, h->h(), two_f ? h_lo : nullptr, act_lo, M, l, st);
+        ns = project_resid(h, RL_GEN_K_GEMM_DOWN, h->act(), have_act_lo ? act_lo : nullptr, M, s.ffn, h->lw[W_DOWN][l],
+                           h->packed ? h->pw[W_DOWN][l] : nullptr, st);
         {
             Scope sc(h, RL_GEN_K_ADD_RMSNORM, st);
+            const bool lo = l + 1 < L ? terms == 2 : two_f;
             launch_add_rmsnorm(h->x(), h->part(), ns, (size_t)M * d, l + 1 < L ? h->lw[W_ATTN_NORM][l + 1] : h->final_norm,
-                               s.rms_eps, h->h(), l + 1 < L ? h_lo : nullptr, M, d, st);
+                               s.rms_eps, h->h(), lo ? h_lo : nullptr, M, d, st);
         }
     }
+    return two_f;
 }
 
 // logits[b0 + i, :] = lm_head * h[row i*T + T-1]  for i < nb
 // (rows: optional compact [nb, hidden] rows to use instead -- the last valid position of ragged sequences)
-void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, const f16_t *rows = nullptr) {
+// lo: the rows behind the nb*T rows of h->h() hold the low term of the normalised rows (level 3); the kernel that reads the
+// fragment-order copy multiplies both terms, the row-major kernels use the high term alone.
+void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, const f16_t *rows = nullptr, bool lo = false) {
     const rl_gen_shape &s = h->s;
     GemmArgs a;
     a.A = h->h() + (size_t)(T - 1) * s.hidden; a.lda = (int64_t)T * s.hidden; a.M = nb; a.K = s.hidden;
@@ -419,7 +470,7 @@ void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, co
     Scope sc(h, RL_GEN_K_GEMM_LM_HEAD, st);
     if (h->packed && nb <= kSkinnyMaxM) {
         PackedGemmArgs q;
-        q.A = a.A; q.A_lo = nullptr; q.lda = a.lda; q.M = nb; q.K = s.hidden;
+        q.A = a.A; q.A_lo = lo && !rows ? a.A + (size_t)nb * T * s.hidden : nullptr; q.lda = a.lda; q.M = nb; q.K = s.hidden;
         q.P[0] = h->p_lm_head; q.P[1] = nullptr; q.P[2] = nullptr;
         q.rows[0] = s.vocab; q.rows[1] = 0; q.rows[2] = 0;
         q.out = a.out; q.ldc = s.vocab; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_F32; q.nb = 1; q.rows_per_wg = 128; q.depth = 2;
@@ -429,8 +480,8 @@ void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, co
 }
 
 void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, int32_t *next, hipStream_t st) {
-    run_layers(h, tokens, h->B, 1, 0, true, st);
-    lm_head(h, h->B, 1, 0, logits, st);
+    const bool lo = run_layers(h, tokens, h->B, 1, 0, true, st);
+    lm_head(h, h->B, 1, 0, logits, st, nullptr, lo);
     Scope sc(h, RL_GEN_K_ARGMAX, st);
     if (h->temperature > 0.f)
         launch_sample(logits, h->B, h->s.vocab, h->temperature, h->sample_u, next, h->d_lens(), h->d_done(), h->eos, st);
@@ -447,9 +498,14 @@ int check_hip(rl_gen *h, const char *where) {
     return RL_GEN_OK;
 }
 
+// Retires every captured decode step.  Replays may still be queued on the stream they were launched on, and nothing
+// promises that an executable graph outlives its destruction while in flight: wait for that stream first.
 void drop_graphs(rl_gen *h) {
     for (auto &g : h->graphs)
-        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+        if (g.exec) {
+            (void)hipStreamSynchronize(g.stream);
+            (void)hipGraphExecDestroy(g.exec);
+        }
     h->graphs.clear();
 }
 
@@ -473,8 +529,11 @@ int64_t rl_gen_param_count(const rl_gen_shape *s) {
 
 size_t rl_gen_kv_bytes(const rl_gen_shape *s) {
     if (validate(s) != RL_GEN_OK) return 0;
-    return (size_t)2 * s->n_layers * s->max_batch * s->n_kv_heads * s->max_seq * s->head_dim * sizeof(bf16_t);
+    return (size_t)2 * s->n_layers * s->max_batch * s->n_kv_heads * s->max_seq * kv_row_bytes(s);
 }
+
+int rl_gen_precision_level(const rl_gen_shape *s) { return validate(s) != RL_GEN_OK ? RL_GEN_E_SHAPE : prec_level(s); }
+int rl_gen_kv_block_scaled(const rl_gen_shape *s) { return validate(s) != RL_GEN_OK ? RL_GEN_E_SHAPE : (kv_block_scaled(s) ? 1 : 0); }
 
 size_t rl_gen_work_bytes(const rl_gen_shape *s) {
     if (validate(s) != RL_GEN_OK) return 0;
@@ -574,7 +633,7 @@ int rl_gen_packed_gate_up_layers(const rl_gen_t *h) { return h ? h->packed_gu_la
 
 size_t rl_gen_page_bytes(const rl_gen_shape *s, int32_t page_size) {
     if (validate(s) != RL_GEN_OK || !page_shift_of(page_size)) return 0;
-    return (size_t)2 * s->n_layers * s->n_kv_heads * page_size * s->head_dim * sizeof(f16_t);
+    return (size_t)2 * s->n_layers * s->n_kv_heads * page_size * kv_row_bytes(s);
 }
 
 int32_t rl_gen_plan_pages(const int32_t *capacity, int32_t B, int32_t page_size, int32_t n_pages, int32_t pages_per_seq,
@@ -627,6 +686,8 @@ static int create_impl(const rl_gen_shape *shape, const rl_gen_weights *w, void 
     h->work = reinterpret_cast<unsigned char *>(work_arena);
     h->wp = wp;
     h->nsplit_attn = attn_splits(shape);
+    h->prec = prec_level(shape);
+    h->kv_i16 = kv_block_scaled(shape);
     h->B = 0; h->len = 0;
     h->graph_on = true; h->prof_on = false; h->qkv_two_term = true;
     h->packed = false; h->packed_gu_layers = 0; h->p_lm_head = nullptr;
@@ -803,7 +864,7 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
     if (per_chunk < 1) per_chunk = 1;
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
         int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
-        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st, lens ? h->d_lens() : nullptr);
+        const bool lo = run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st, lens ? h->d_lens() : nullptr);
         if (lens) {
             // ragged prompts: the row that feeds the LM head is each sequence's own last position; the attention
             // output area is idle by now and takes the gathered rows
@@ -813,7 +874,7 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
             }
             lm_head(h, nb, T, b0, lg, st, h->attn());
         } else {
-            lm_head(h, nb, T, b0, lg, st);
+            lm_head(h, nb, T, b0, lg, st, nullptr, lo);
         }
     }
     {
@@ -1142,8 +1203,9 @@ int rl_op_add_rmsnorm(float *x, const float *part, int32_t nsplit, size_t part_s
 
 int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *W0, const uint16_t *W1, const uint16_t *W2,
                int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out, int64_t ldc, size_t split_stride,
-               int32_t splits, int32_t epilogue, int32_t kernel, void *st) {
+               int32_t splits, int32_t epilogue, int32_t kernel, uint16_t *out_lo, void *st) {
     if (!A || !W0 || !out) return RL_GEN_E_NULL;
+    if (out_lo && (epilogue != EPI_SWIGLU || kernel != 2)) return RL_GEN_E_SHAPE;
     if (A_lo && (kernel != 2 || epilogue == EPI_SWIGLU || A_lo <= A)) return RL_GEN_E_SHAPE;
     if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
     if (epilogue < 0 || epilogue > 2 || kernel < 0 || kernel > 2 || splits < 1) return RL_GEN_E_SHAPE;
@@ -1157,7 +1219,7 @@ int rl_op_gemm(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint1
     a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
     a.W[0] = W0; a.W[1] = rows1 > 0 ? W1 : nullptr; a.W[2] = rows2 > 0 ? W2 : nullptr;
     a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
-    a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue;
+    a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue; a.out_lo = out_lo;
     bool skinny = kernel == 1 || (kernel == 0 && M <= kSkinnyMaxM);
     if (skinny) launch_gemm_skinny(a, reinterpret_cast<hipStream_t>(st));
     else launch_gemm_tiled(a, reinterpret_cast<hipStream_t>(st));
@@ -1188,8 +1250,10 @@ int rl_op_gemm_tiled_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda
 int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *Wq, const uint16_t *Wk, const uint16_t *Wv,
                     const uint16_t *Pq, const uint16_t *Pk, const uint16_t *Pv,
                     int32_t Hq, int32_t Hkv, int32_t hd, int32_t M, int32_t K, int32_t T, int32_t b0, const float *rope_tab,
-                    int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *st) {
+                    int32_t rope_style, int32_t S, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, float *kscale, float *vscale,
+                    uint16_t *q_f16_lo, void *st) {
     if (!A || !Wq || !Wk || !Wv || !rope_tab || !q_f16 || !kc || !vc) return RL_GEN_E_NULL;
+    if ((kscale == nullptr) != (vscale == nullptr)) return RL_GEN_E_NULL;
     if (M <= 0 || K <= 0 || K % 8 || lda % 8 || lda < K || Hq <= 0 || Hkv <= 0 || T <= 0 || b0 < 0 || S < T) return RL_GEN_E_SHAPE;
     if (A_lo && A_lo <= A) return RL_GEN_E_SHAPE;
     if (!gemm_tiled_rope_supported(M, K, lda, Hq, Hkv, hd, rope_style, T, A_lo != nullptr)) return RL_GEN_E_SHAPE;
@@ -1197,6 +1261,7 @@ int rl_op_gemm_rope(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const 
     RopeEpilogue rp;
     rp.rope_tab = rope_tab; rp.T = T; rp.b0 = b0; rp.Hq = Hq; rp.Hkv = Hkv; rp.S = S;
     rp.q_f16 = q_f16; rp.kc = kc; rp.vc = vc; rp.map = KvMap(); rp.d_valid = nullptr;
+    rp.map.kscale = kscale; rp.map.vscale = vscale; rp.q_f16_lo = q_f16_lo;
     GemmArgs a;
     a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
     a.W[0] = Wq; a.W[1] = Wk; a.W[2] = Wv;
@@ -1221,8 +1286,10 @@ int rl_op_pack_weights(const uint16_t *W, uint16_t *P, int32_t N, int32_t K, voi
 
 int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P0, const uint16_t *P1,
                       const uint16_t *P2, int32_t rows0, int32_t rows1, int32_t rows2, int32_t M, int32_t K, void *out,
-                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg, int32_t depth, void *st) {
+                      int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg, int32_t depth,
+                      uint16_t *out_lo, void *st) {
     if (!A || !P0 || !out) return RL_GEN_E_NULL;
+    if (out_lo && epilogue != EPI_SWIGLU) return RL_GEN_E_SHAPE;
     if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || rows0 <= 0 || rows1 < 0 || rows2 < 0) return RL_GEN_E_SHAPE;
     if (epilogue < 0 || epilogue > 2 || splits < 1 || nb < 0 || nb > 2) return RL_GEN_E_SHAPE;
     if (rows_per_wg != 0 && rows_per_wg != 32 && rows_per_wg != 64 && rows_per_wg != 128) return RL_GEN_E_SHAPE;
@@ -1234,7 +1301,7 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
     a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
     a.P[0] = P0; a.P[1] = rows1 > 0 ? P1 : nullptr; a.P[2] = rows2 > 0 ? P2 : nullptr;
     a.rows[0] = rows0; a.rows[1] = rows1; a.rows[2] = rows2;
-    a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue;
+    a.out = out; a.ldc = ldc; a.split_stride = split_stride; a.splits = splits; a.epilogue = epilogue; a.out_lo = out_lo;
     int pnb, prows, psplits;
     gemm_packed_plan(rows0 + rows1 + rows2, K, M, &pnb, &prows, &psplits);
     a.nb = nb == 0 ? pnb : nb;
@@ -1245,7 +1312,7 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
 }
 
 int rl_op_gemm_packed_swiglu_halves(const uint16_t *A, int64_t lda, const uint16_t *Pg, const uint16_t *Pu, int32_t F, int32_t M,
-                                    int32_t K, uint16_t *out, int64_t ldc, int32_t depth, void *st) {
+                                    int32_t K, uint16_t *out, int64_t ldc, int32_t depth, uint16_t *out_lo, void *st) {
     if (!A || !Pg || !Pu || !out) return RL_GEN_E_NULL;
     if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || F <= 0 || ldc < F) return RL_GEN_E_SHAPE;
     if (depth != 0 && depth != 2 && depth != 4) return RL_GEN_E_SHAPE;
@@ -1255,7 +1322,7 @@ int rl_op_gemm_packed_swiglu_halves(const uint16_t *A, int64_t lda, const uint16
     a.A = A; a.A_lo = nullptr; a.lda = lda; a.M = M; a.K = K;
     a.P[0] = Pg; a.P[1] = Pu; a.P[2] = nullptr;
     a.rows[0] = F; a.rows[1] = F; a.rows[2] = 0;
-    a.out = out; a.ldc = ldc; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
+    a.out = out; a.ldc = ldc; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU; a.out_lo = out_lo;
     a.nb = 2; a.rows_per_wg = 128; a.depth = depth;
     launch_gemm_packed_swiglu_halves(a, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
@@ -1277,13 +1344,19 @@ int rl_op_build_rope_table(float *tab, int32_t max_seq, int32_t head_dim, float 
 
 int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int32_t M, int32_t T, int32_t b0,
                       const int32_t *d_pos0, int32_t pos_stride, const float *rope_tab, int32_t rope_style, int32_t Hq, int32_t Hkv, int32_t hd,
-                      int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, void *st) {
+                      int32_t S, float *q_f32, uint16_t *q_f16, uint16_t *kc, uint16_t *vc, float *kscale, float *vscale,
+                      uint16_t *q_f16_lo, void *st) {
     if (!qkv || !d_pos0 || !rope_tab || !kc || !vc) return RL_GEN_E_NULL;
+    if ((kscale == nullptr) != (vscale == nullptr)) return RL_GEN_E_NULL;
+    if (kscale && hd != 64 && hd != 128) return RL_GEN_E_SHAPE;
+    if (q_f16_lo && !q_f16) return RL_GEN_E_NULL;
     if (nsplit < 1 || M < 0 || T <= 0 || b0 < 0 || Hq <= 0 || Hkv <= 0 || hd <= 0 || hd % 2 || S <= 0 || (rope_style != 0 && rope_style != 1))
         return RL_GEN_E_SHAPE;
     if (pos_stride != 0 && pos_stride != 1) return RL_GEN_E_SHAPE;
+    KvMap map;
+    map.kscale = kscale; map.vscale = vscale;
     launch_rope_append(qkv, nsplit, split_stride, M, T, b0, d_pos0, pos_stride, rope_tab, rope_style, Hq, Hkv, hd, S, q_f32, q_f16, kc, vc,
-                       reinterpret_cast<hipStream_t>(st));
+                       reinterpret_cast<hipStream_t>(st), map, nullptr, nullptr, q_f16_lo);
     RL_OP_RETURN();
 }
 
@@ -1293,25 +1366,32 @@ size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32
 
 int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
                            uint16_t *out, float *ws,
-                           int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, const int32_t *d_done, void *st) {
+                           int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, const int32_t *d_done,
+                           const float *kscale, const float *vscale, uint16_t *out_lo, void *st) {
     if (!q || !kc || !vc || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
+    if ((kscale == nullptr) != (vscale == nullptr)) return RL_GEN_E_NULL;
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
     if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
-    launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st), KvMap(),
-                            d_done);
+    KvMap map;
+    map.kscale = const_cast<float *>(kscale); map.vscale = const_cast<float *>(vscale);
+    launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st), map,
+                            d_done, out_lo);
     RL_OP_RETURN();
 }
 
 int rl_op_decode_attention_paged(const float *q, const uint16_t *k_pool, const uint16_t *v_pool, const int32_t *table,
                                  int32_t table_stride, int32_t page_size, const int32_t *d_len, int32_t len_stride, uint16_t *out,
-                                 float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit, void *st) {
+                                 float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
+                                 const float *kscale, const float *vscale, void *st) {
     if (!q || !k_pool || !v_pool || !table || !d_len || !out || (nsplit > 1 && !ws)) return RL_GEN_E_NULL;
+    if ((kscale == nullptr) != (vscale == nullptr)) return RL_GEN_E_NULL;
     if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
     if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
     const int shift = page_shift_of(page_size);
     if (!shift || (int64_t)table_stride * page_size < S) return RL_GEN_E_SHAPE;
     KvMap map;
     map.table = table; map.table_stride = table_stride; map.page_shift = shift;
+    map.kscale = const_cast<float *>(kscale); map.vscale = const_cast<float *>(vscale);
     launch_decode_attention(q, k_pool, v_pool, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st),
                             map);
     RL_OP_RETURN();
@@ -1332,11 +1412,16 @@ int rl_op_decode_attention_fused(const float *qkv, int32_t nsplit_qkv, size_t sp
 }
 
 int rl_op_prefill_attention(const uint16_t *q, const uint16_t *kc, const uint16_t *vc, uint16_t *out, int32_t nb, int32_t b0,
-                            int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, void *st) {
+                            int32_t T, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, const float *kscale, const float *vscale,
+                            uint16_t *out_lo, const uint16_t *q_lo, void *st) {
     if (!q || !kc || !vc || !out) return RL_GEN_E_NULL;
+    if ((kscale == nullptr) != (vscale == nullptr)) return RL_GEN_E_NULL;
+    if (q_lo && !kscale) return RL_GEN_E_SHAPE;
     if (nb < 0 || b0 < 0 || T <= 0 || T > S || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || nb > 65535)
         return RL_GEN_E_SHAPE;
-    launch_prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, reinterpret_cast<hipStream_t>(st));
+    KvMap map;
+    map.kscale = const_cast<float *>(kscale); map.vscale = const_cast<float *>(vscale);
+    launch_prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, reinterpret_cast<hipStream_t>(st), map, nullptr, out_lo, q_lo);
     RL_OP_RETURN();
 }
 

@@ -21,14 +21,15 @@ LOGIT_TOL = 3e-2
 TOTALS = {"agree": 0, "total": 0}
 
 
-def run_teacher_forced(shape, seed_index, B, P, G, graph=True, max_batch=None, max_seq=None, std=0.02, packed=True):
+def run_teacher_forced(shape, seed_index, B, P, G, graph=True, max_batch=None, max_seq=None, std=0.02, packed=True, gain_std=0.0,
+                       precision=0):
     from paper_2406_14088_amd import Generator
     wl = Workload("t", seed_index, shape, B, P, G)
-    W = make_weights(shape, seed_index, device="cpu", std=std)
+    W = make_weights(shape, seed_index, device="cpu", std=std, gain_std=gain_std)
     Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
     prompts = make_prompts(wl)
     om = orc.OracleModel(shape, orc.weights_to_numpy(W), B, P + G)
-    gen = Generator(shape, Wg, max_batch or B, max_seq or (P + G), packed=packed)
+    gen = Generator(shape, Wg, max_batch or B, max_seq or (P + G), packed=packed, precision=precision)
     gen.set_graph(graph)
     o_logits, o_next = om.prefill(prompts.numpy())
     g_logits, g_next = gen.prefill(prompts.to(DEV))
@@ -84,6 +85,40 @@ def test_tiny_interleaved_rope_and_spare_capacity():
     from dataclasses import replace
     wl = PRESETS["tiny"]
     check(replace(wl.shape, rope_style=0), 11, 3, 9, 5, max_batch=5, max_seq=40)
+
+
+@pytest.mark.parametrize("packed", [True, False])
+@pytest.mark.parametrize("shape", [ModelShape(4, 512, 4, 4, 128, 1384, 2048), ModelShape(3, 512, 8, 2, 64, 1000, 2048)])
+def test_distinct_random_gains_reach_their_own_norms(shape, packed):
+    """Every RMSNorm gain vector drawn as 1 + 0.3 N(0, 1) (attention norm and FFN norm of each layer, final norm): with
+    unit gains any two of them could be swapped unnoticed; with these, a gain reaching the wrong norm moves the logits far
+    beyond the tolerance (a swapped pair changes them by ~0.3 relative)."""
+    worst, _ = check(shape, 16, 5, 40, 6, packed=packed, gain_std=0.3)
+    # the test has teeth: the oracle itself, fed weights with two gain vectors exchanged, is far from the product
+    from paper_2406_14088_amd import Generator
+    W = make_weights(shape, 16, device="cpu", gain_std=0.3)
+    Ws = dict(W)
+    Ws["ffn_norm"] = list(W["ffn_norm"])
+    Ws["attn_norm"] = list(W["attn_norm"])
+    Ws["ffn_norm"][1], Ws["attn_norm"][2] = W["attn_norm"][2], W["ffn_norm"][1]
+    prompts = make_prompts(Workload("t", 16, shape, 5, 40, 6))
+    wrong, _ = orc.OracleModel(shape, orc.weights_to_numpy(Ws), 5, 46).prefill(prompts.numpy())
+    gen = Generator(shape, {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}, 5, 46, packed=packed)
+    g_logits, _ = gen.prefill(prompts.to(DEV))
+    torch.cuda.synchronize()
+    gen.close()
+    assert np.abs(np64(g_logits) - wrong).max() > 10 * LOGIT_TOL
+
+
+@pytest.mark.parametrize("precision", [1, 2, 3])
+@pytest.mark.parametrize("shape", [ModelShape(3, 512, 4, 4, 128, 1384, 2048), ModelShape(3, 1024, 8, 1, 128, 1000, 2048)])
+def test_precision_levels(shape, precision):
+    """Each level of rl_gen_shape.precision on a multi-head and a grouped-query shape, packed and row-major decode paths,
+    more than 128 rows per step included (all within the tolerance; the levels differ in how far inside)."""
+    step(f"precision {precision}, Hq/Hkv {shape.n_heads}/{shape.n_kv_heads}")
+    check(shape, 17, 6, 33, 5, precision=precision)
+    check(shape, 17, 6, 33, 5, precision=precision, packed=False)
+    check(shape, 17, 130, 5, 3, precision=precision)
 
 
 def test_gqa_small_model():
@@ -827,59 +862,3 @@ def test_zz_overall_agreement():
     rate = TOTALS["agree"] / TOTALS["total"]
     step(f"overall greedy agreement {rate:.4f} over {TOTALS['total']} tokens")
     assert rate >= 0.99
-
-
-def test_benchmark_workload_full_size_sampled():
-    """The benchmark configuration itself (LLaMA-7B shape, all 32 layers, batch 128, prompt 128, 256 generated tokens,
-    packed weights, HIP-graph decode): the GPU runs the whole batch exactly as bench.py does; the oracle recomputes sampled
-    sequences one by one (sequences are independent) and is fed the GPU's own greedy tokens, so both sides see identical
-    inputs at every one of the 256 steps."""
-    from paper_2406_14088_amd import Generator
-    wl = PRESETS["llama7b"]
-    shape, B, P, G = wl.shape, wl.batch, wl.prompt_len, wl.gen_len
-    sample = [5, 77]
-    step("7B full depth: drawing weights on the GPU")
-    W = make_weights(shape, wl.index, device=DEV)
-    prompts = make_prompts(wl, device=DEV)
-    gen = Generator(shape, W, B, wl.max_seq)
-    bufs = [torch.empty((B,), dtype=torch.int32, device=DEV) for _ in range(2)]
-    lowest_argmax = lambda lg: (lg == lg.max(-1, keepdim=True).values).int().argmax(-1)   # first index of the maximum
-    lg = gen.prefill(prompts, next_tokens=bufs[0])[0]
-    g_logits, g_tokens = [lg[sample].clone()], [bufs[0][sample].clone()]
-    assert torch.isfinite(lg).all() and torch.equal(bufs[0].long(), lowest_argmax(lg))
-    cur = 0
-    for i in range(G - 1):
-        lg, _ = gen.decode_step(bufs[cur], next_tokens=bufs[1 - cur])
-        cur = 1 - cur
-        g_logits.append(lg[sample].clone())
-        g_tokens.append(bufs[cur][sample].clone())
-        if i % 32 == 0 or i == G - 2:        # whole-batch properties that hold at any size
-            assert torch.isfinite(lg).all() and torch.equal(bufs[cur].long(), lowest_argmax(lg))
-    torch.cuda.synchronize()
-    assert gen.state() == (B, P + G - 1)
-    gen.close()
-    step("copying weights to the host for the oracle")
-    Wn = orc.weights_to_numpy(W)
-    del W
-    om = orc.OracleModel(shape, Wn, len(sample), P + G)
-    step("oracle prefill of the sampled sequences")
-    o_logits, o_next = om.prefill(prompts[sample].cpu().numpy())
-    worst, agree, total = 0.0, 0, 0
-    for i in range(G):
-        gl = np64(g_logits[i])
-        gn = g_tokens[i].cpu().numpy()
-        err = np.abs(gl - o_logits).max()
-        worst = max(worst, err)
-        if i < 4 or i % 32 == 0 or i == G - 1:
-            step(f"  step {i}: max-abs logit error {err:.3e}, rms {np.sqrt(((gl - o_logits) ** 2).mean()):.3e}")
-        assert err <= LOGIT_TOL, (i, err)
-        assert np.array_equal(gn, np.array([orc.argmax(r) for r in gl]))
-        for b in np.nonzero(gn != o_next)[0]:
-            assert o_logits[b, o_next[b]] - o_logits[b, gn[b]] <= 2.0 * err
-        agree += int((gn == o_next).sum())
-        total += len(gn)
-        if i < G - 1:
-            o_logits, o_next = om.decode_step(gn)      # the oracle is fed the GPU's tokens
-    om.close()
-    step(f"  worst {worst:.3e}, greedy agreement {agree}/{total}")
-    assert agree >= 0.99 * total

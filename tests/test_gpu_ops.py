@@ -487,12 +487,12 @@ def test_empty_inputs_enqueue_nothing(ops):
     rcs = [
         L.rl_op_embed(p(toks), p(emb), p(x), 0, d, V, None),
         L.rl_op_add_rmsnorm(p(x), None, 0, 0, p(gain), 1e-5, p(h), None, 0, d, None),
-        L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 1, None),
-        L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 2, None),
-        L.rl_op_gemm_packed(p(A), None, d, p(P), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 0, 0, 0, None),
+        L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 1, None, None),
+        L.rl_op_gemm(p(A), None, d, p(W), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 2, None, None),
+        L.rl_op_gemm_packed(p(A), None, d, p(P), None, None, 96, 0, 0, 0, d, p(out), 96, 0, 1, 0, 0, 0, 0, None, None),
         L.rl_op_argmax(p(lg), 0, V, p(nxt), None),
-        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), 0, p(h), None, 0, 1, 1, 64, 8, 1, None, None),
-        L.rl_op_prefill_attention(p(h), p(kc), p(kc), p(h), 0, 0, 1, 1, 1, 64, 8, None),
+        L.rl_op_decode_attention(p(x), p(kc), p(kc), p(toks), 0, p(h), None, 0, 1, 1, 64, 8, 1, None, None, None, None, None),
+        L.rl_op_prefill_attention(p(h), p(kc), p(kc), p(h), 0, 0, 1, 1, 1, 64, 8, None, None, None, None, None),
         L.rl_op_logprob_gather(p(lg), V, 0, V, p(toks), 4, 0, p(x), None),
     ]
     torch.cuda.synchronize()
@@ -744,3 +744,210 @@ def test_decode_attention_skips_ended_sequences(ops, hd, Hq, Hkv, nsplit):
         assert (out[done.bool()] == 7.0).all()
     else:                                                 # the merge of the (untouched, zeroed) partials writes the row
         assert not torch.isinf(out[done.bool()]).any()
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# Block-scaled cache rows (int16 elements, one fp32 scale per row) and two-term half outputs
+# ---------------------------------------------------------------------------------------------------------------------
+def _random_block_scaled(shape, seed):
+    """A cache area as the kernels store it: random int16 elements and positive fp32 row scales, plus the fp64 values
+    q * scale they stand for (exactly representable, so both sides read identical numbers)."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    qi = torch.randint(-32767, 32768, shape, generator=g, dtype=torch.int32).to(torch.int16)
+    sc = (torch.rand(shape[:-1], generator=g) * 2.0 + 0.5) * (1.0 / 32767.0)
+    vals = qi.to(torch.float64) * sc.to(torch.float32).to(torch.float64)[..., None]
+    return qi.to(DEV), sc.to(torch.float32).to(DEV), vals.numpy()
+
+
+@pytest.mark.parametrize("style", [0, 1])
+@pytest.mark.parametrize("hd,Hq,Hkv", [(64, 4, 4), (128, 8, 2), (128, 3, 3)])
+def test_rope_append_block_scaled_rows(ops, style, hd, Hq, Hkv):
+    """The appended rows as int16 * scale: scale = max|x| / 32767 of the (position, kv head) row, elements within half a
+    step of the oracle's rotated values; the largest element of a row is +-32767; nothing else is touched."""
+    S, nseq, nsplit = 40, 3, 2
+    tab = torch.empty((S, hd // 2, 2), dtype=torch.float32, device=DEV)
+    ops.build_rope_table(tab, S, hd, 10000.0)
+    ld = (Hq + 2 * Hkv) * hd
+    for (T, b0, pos0, nb) in [(7, 1, 0, 2), (1, 0, 23, 3)]:
+        M = nb * T
+        qkv = randn_f32((nsplit, M, ld), 160 + T)
+        qkv[:, 0, Hq * hd: Hq * hd + hd] = 0.0           # one all-zero K row: scale 0, elements 0
+        kc = torch.zeros((nseq, Hkv, S, hd), dtype=torch.int16, device=DEV)
+        vc = torch.zeros_like(kc)
+        ks = torch.full((nseq, Hkv, S), -1.0, dtype=torch.float32, device=DEV)
+        vs = torch.full((nseq, Hkv, S), -1.0, dtype=torch.float32, device=DEV)
+        qf = torch.empty((M, Hq * hd), dtype=torch.float32, device=DEV)
+        d_pos = torch.tensor([pos0], dtype=torch.int32, device=DEV)
+        qh = torch.zeros((M, Hq * hd), dtype=torch.float16, device=DEV)
+        ql = torch.zeros_like(qh)
+        ops.rope_append(qkv, nsplit, M * ld, M, T, b0, d_pos, tab, style, Hq, Hkv, hd, S, qf, qh, kc, vc, kscale=ks, vscale=vs, q_f16_lo=ql)
+        torch.cuda.synchronize()
+        assert torch.equal(qh, qf.to(torch.float16)) and torch.equal(ql, (qf - qh.float()).to(torch.float16))
+        tot = np64(qkv).sum(0)
+        kq, vq, ksn, vsn = kc.cpu().numpy().astype(np.float64), vc.cpu().numpy().astype(np.float64), np64(ks), np64(vs)
+        seen = np.zeros((nseq, S), bool)
+        for m in range(M):
+            b, pos = b0 + m // T, pos0 + m % T
+            seen[b, pos] = True
+            k = orc.rope(tot[m, Hq * hd: (Hq + Hkv) * hd].reshape(Hkv, hd), pos, 10000.0, style)
+            v = tot[m, (Hq + Hkv) * hd:].reshape(Hkv, hd)
+            for ref, qv, sc in ((k, kq[b, :, pos], ksn[b, :, pos]), (v, vq[b, :, pos], vsn[b, :, pos])):
+                amax = np.abs(ref).max(-1)
+                assert (np.abs(sc - amax / 32767.0) <= 3e-6 * amax / 32767.0 + 1e-30).all()
+                assert (np.abs(qv * sc[:, None] - ref) <= 0.5 * sc[:, None] * 1.001 + 1e-6 * np.abs(ref)).all()
+                assert ((np.abs(qv).max(-1) == 32767) | (amax == 0)).all()
+        untouched = ~seen[:, None, :]
+        assert (np.where(untouched[..., None], kq, 0) == 0).all() and (np.where(untouched[..., None], vq, 0) == 0).all()
+        assert (np.where(untouched, ksn, -1.0) == -1.0).all() and (np.where(untouched, vsn, -1.0) == -1.0).all()
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv", [(128, 8, 8), (128, 8, 2), (128, 16, 2), (64, 4, 4), (64, 6, 2)])
+@pytest.mark.parametrize("length,nsplit", [(0, 1), (5, 1), (130, 3), (1000, 8), (2, 4)])
+def test_decode_attention_block_scaled_rows_and_two_term_output(ops, hd, Hq, Hkv, length, nsplit):
+    """Decode attention over int16 * scale rows (every head grouping runs on the vector kernel then), with the second
+    half term of the output: out alone is the oracle's value to half precision, out + out_lo to fp32 arithmetic."""
+    B, S = 3, 1024
+    q = randn_f32((B, Hq * hd), 170, std=1.5)
+    kc, ks, kn = _random_block_scaled((B, Hkv, S, hd), 171)
+    vc, vs, vn = _random_block_scaled((B, Hkv, S, hd), 172)
+    ks[:, :, length + 1:] = float("nan")          # rows past the visible range must never be used
+    vs[:, :, length + 1:] = float("nan")
+    d_len = torch.tensor([length], dtype=torch.int32, device=DEV)
+    out = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    out_lo = torch.zeros_like(out)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, kscale=ks, vscale=vs, out_lo=out_lo)
+    torch.cuda.synchronize()
+    qn, on, ln = np64(q).reshape(B, Hq, hd), np64(out).reshape(B, Hq, hd), np64(out_lo).reshape(B, Hq, hd)
+    g = Hq // Hkv
+    for b in range(B):
+        for u in range(Hq):
+            ref = orc.attend(qn[b, u], kn[b, u // g, : length + 1], vn[b, u // g, : length + 1])
+            assert (np.abs(on[b, u] - ref) <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 2e-5).all(), (b, u)
+            assert (np.abs(on[b, u] + ln[b, u] - ref) <= 2e-5 * (1 + np.abs(ref))).all(), (b, u, np.abs(on[b, u] + ln[b, u] - ref).max())
+
+
+@pytest.mark.parametrize("kind", ["vector", "matrix", "block_scaled"])
+@pytest.mark.parametrize("length", [2047, 4095])
+def test_decode_attention_at_long_context_lengths(ops, kind, length):
+    """Cached lengths of the long-context workload (prompt 2048, generation to 4096 positions): the vector kernel (one query
+    head per kv head, IEEE half rows), the matrix-core kernel (8 query heads per kv head) and the vector kernel over
+    block-scaled rows, each split over the sequence as the generator splits it, against the oracle row by row."""
+    hd, S = 128, 4096
+    B, Hq, Hkv = (2, 4, 4) if kind != "matrix" else (2, 16, 2)
+    nsplit = 4
+    step(f"decode attention, {kind} kernel, {length + 1} cached rows")
+    q = randn_f32((B, Hq * hd), 180, std=1.5)
+    if kind == "block_scaled":
+        kc, ks, kn = _random_block_scaled((B, Hkv, S, hd), 181)
+        vc, vs, vn = _random_block_scaled((B, Hkv, S, hd), 182)
+    else:
+        kc, vc, ks, vs = randn_f16((B, Hkv, S, hd), 181), randn_f16((B, Hkv, S, hd), 182), None, None
+        kn, vn = np64(kc), np64(vc)
+    d_len = torch.tensor([length], dtype=torch.int32, device=DEV)
+    out = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, kscale=ks, vscale=vs)
+    torch.cuda.synchronize()
+    qn, on = np64(q).reshape(B, Hq, hd), np64(out).reshape(B, Hq, hd)
+    g = Hq // Hkv
+    for b in range(B):
+        for u in range(Hq):
+            ref = orc.attend(qn[b, u], kn[b, u // g, : length + 1], vn[b, u // g, : length + 1])
+            assert (np.abs(on[b, u] - ref) <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + 3e-5).all(), (b, u, np.abs(on[b, u] - ref).max())
+
+
+@pytest.mark.parametrize("hd,Hq,Hkv", [(128, 4, 4), (128, 8, 2), (64, 4, 1)])
+@pytest.mark.parametrize("T", [1, 16, 100, 300])
+def test_prefill_attention_block_scaled_rows_and_two_term_output(ops, hd, Hq, Hkv, T):
+    """Prefill attention over int16 * scale rows: every element enters the matrix cores as hi + lo, so only q and the
+    probabilities carry a half rounding."""
+    nb, b0, S, nseq = 2, 1, 320, 3
+    qf = randn_f32((nb * T, Hq * hd), 190, std=1.5)
+    q = qf.to(torch.float16)
+    q_lo = (qf - q.float()).to(torch.float16)             # the two terms the projection's epilogue stores
+    kc, ks, kn = _random_block_scaled((nseq, Hkv, S, hd), 191)
+    vc, vs, vn = _random_block_scaled((nseq, Hkv, S, hd), 192)
+    ks[:, :, T:] = float("nan")
+    vs[:, :, T:] = float("nan")
+    out = torch.zeros((nb * T, Hq * hd), dtype=torch.float16, device=DEV)
+    out_lo = torch.zeros_like(out)
+    ops.prefill_attention(q, kc, vc, out, nb, b0, T, Hq, Hkv, hd, S, kscale=ks, vscale=vs, out_lo=out_lo, q_lo=q_lo)
+    torch.cuda.synchronize()
+    qn = (np64(q) + np64(q_lo)).reshape(nb, T, Hq, hd)
+    on, ln = np64(out).reshape(nb, T, Hq, hd), np64(out_lo).reshape(nb, T, Hq, hd)
+    g = Hq // Hkv
+    for b in range(nb):
+        for u in range(Hq):
+            for i in sorted(set(min(i, T - 1) for i in [0, 1, T // 2, T - 1] + list(range(0, T, 7)))):
+                ref = orc.attend(qn[b, i, u], kn[b0 + b, u // g, : i + 1], vn[b0 + b, u // g, : i + 1])
+                # every operand is a two-term sum: what is left is fp32 arithmetic and the fast exponential
+                small = 3e-5 * (1 + np.abs(vn[b0 + b, u // g, : i + 1]).max())
+                assert (np.abs(on[b, i, u] - ref) <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + small).all(), (b, u, i)
+                assert (np.abs(on[b, i, u] + ln[b, i, u] - ref) <= small + 2e-6 * np.abs(ref)).all(), (b, u, i, np.abs(on[b, i, u] + ln[b, i, u] - ref).max())
+
+
+@pytest.mark.parametrize("M,K,F,kind", [(4, 256, 688, "halves"), (128, 512, 1000, "halves"), (77, 1000, 200, "packed"),
+                                        (300, 256, 688, "packed"), (600, 264, 520, "tiled")])
+def test_swiglu_two_term_output(ops, M, K, F, kind):
+    """The SwiGLU epilogues' second half term: out is the oracle's value to half precision, out + out_lo to fp32 arithmetic."""
+    A = randn_f16((M, K), 200)
+    Wg, Wu = randn_bf16((F, K), 201, std=0.05), randn_bf16((F, K), 202, std=0.05)
+    out = torch.zeros((M, F), dtype=torch.float16, device=DEV)
+    out_lo = torch.zeros_like(out)
+    if kind == "tiled":
+        ops.gemm(A, [Wg, Wu], out, F, epilogue=1, kernel=2, out_lo=out_lo)
+    else:
+        Pg = torch.zeros(ops.packed_weight_bytes(F, K) // 2, dtype=torch.int16, device=DEV)
+        Pu = torch.zeros_like(Pg)
+        ops.pack_weights(Wg, Pg)
+        ops.pack_weights(Wu, Pu)
+        if kind == "halves":
+            ops.gemm_packed_swiglu_halves(A, Pg, Pu, F, K, out, F, out_lo=out_lo)
+        else:
+            ops.gemm_packed(A, [Pg, Pu], [F, F], K, out, F, epilogue=1, out_lo=out_lo)
+    torch.cuda.synchronize()
+    gate = orc.linear(bits(Wg), np64(A))
+    up = orc.linear(bits(Wu), np64(A))
+    ref = np.vectorize(orc.silu)(gate) * up
+    tol = 3e-6 * np.sqrt(K) * (np.abs(np64(A)).max() * 0.05 * np.sqrt(K)) * (1 + np.abs(up)) + 1e-6
+    assert (np.abs(np64(out) - ref) <= 0.5 * F16_EPS * np.abs(ref) * 1.02 + tol).all()
+    assert (np.abs(np64(out) + np64(out_lo) - ref) <= tol + 2e-6 * np.abs(ref)).all(), np.abs(np64(out) + np64(out_lo) - ref).max()
+
+
+@pytest.mark.parametrize("Hq,Hkv,two_terms", [(8, 8, True), (16, 2, False)])
+def test_qkv_projection_with_rotary_epilogue_block_scaled_equals_the_two_kernels(ops, Hq, Hkv, two_terms):
+    """The prefill projection that rotates and stores in its epilogue writes the same int16 rows and scales as the fp32
+    projection followed by rope_append (the row maximum and the quantisation are the same operations on the same bits);
+    one row is checked against the oracle directly."""
+    hd, K, T, nseq, b0, S = 128, 256, 40, 205, 3, 64        # 8200 rows: a ragged last tile, bands that wrap to the next sequence
+    M = nseq * T
+    n_all = (Hq + 2 * Hkv) * hd
+    A = randn_f16(((2 if two_terms else 1) * M, K), 411)
+    if two_terms:
+        A[M:] *= 2.0 ** -11
+    A_lo = A[M:] if two_terms else None
+    Wq, Wk, Wv = randn_bf16((Hq * hd, K), 412, 0.05), randn_bf16((Hkv * hd, K), 413, 0.05), randn_bf16((Hkv * hd, K), 414, 0.05)
+    tab = torch.empty((S, hd // 2, 2), dtype=torch.float32, device=DEV)
+    ops.build_rope_table(tab, S, hd, 10000.0)
+    mk = lambda: (torch.zeros((b0 + nseq, Hkv, S, hd), dtype=torch.int16, device=DEV),
+                  torch.zeros((b0 + nseq, Hkv, S), dtype=torch.float32, device=DEV))
+    (kc1, ks1), (vc1, vs1), (kc2, ks2), (vc2, vs2) = mk(), mk(), mk(), mk()
+    q1 = torch.zeros((M, Hq * hd), dtype=torch.float16, device=DEV)
+    q2, l1, l2 = torch.zeros_like(q1), torch.zeros_like(q1), torch.zeros_like(q1)
+    ops.gemm_rope(A[:M], Wq, Wk, Wv, Hq, Hkv, hd, M, T, b0, tab, 1, S, q1, kc1, vc1, A_lo=A_lo, kscale=ks1, vscale=vs1, q_f16_lo=l1)
+    part = torch.zeros((M, n_all), dtype=torch.float32, device=DEV)
+    ops.gemm(A[:M], [Wq, Wk, Wv], part, n_all, M=M, kernel=2, A_lo=A_lo)
+    zero = torch.zeros((1,), dtype=torch.int32, device=DEV)
+    ops.rope_append(part, 1, M * n_all, M, T, b0, zero, tab, 1, Hq, Hkv, hd, S, None, q2, kc2, vc2, kscale=ks2, vscale=vs2, q_f16_lo=l2)
+    torch.cuda.synchronize()
+    assert torch.equal(l1, l2) and l1.abs().max() > 0
+    assert torch.equal(q1, q2) and torch.equal(kc1, kc2) and torch.equal(vc1, vc2) and torch.equal(ks1, ks2) and torch.equal(vs1, vs2)
+    assert ks1[b0:, :, :T].min() > 0 and ks1[:b0].abs().max() == 0 and ks1[:, :, T:].abs().max() == 0
+    m = 7 * T + 11
+    x = np64(A[m]) + (np64(A[M + m]) if two_terms else 0.0)
+    for name, W, got, sc in (("k", Wk, kc1[b0 + 7, :, 11], ks1[b0 + 7, :, 11]), ("v", Wv, vc1[b0 + 7, :, 11], vs1[b0 + 7, :, 11])):
+        y = (np64(W) @ x).reshape(Hkv, hd)
+        want = y if name == "v" else orc.rope(y, 11, 10000.0, 1)
+        deq = got.cpu().numpy().astype(np.float64) * np64(sc)[:, None]
+        assert (np.abs(deq - want) <= 0.51 * np64(sc)[:, None] + 2e-4).all(), name

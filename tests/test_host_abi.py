@@ -50,9 +50,20 @@ def test_param_count_matches_paper_table_and_presets(binding):
 
 def test_kv_bytes_closed_form(binding):
     s = PRESETS["llama7b"].shape
-    assert binding.kv_bytes(s, 1, 1) == 524288                      # 0.5 MiB per token and sequence in bf16
-    assert binding.kv_bytes(s, 128, 384) == 524288 * 128 * 384
-    assert binding.kv_bytes(PRESETS["llama70b"].shape, 64, 384) == 2 * 80 * 8 * 128 * 2 * 64 * 384
+    # 16-bit elements: 0.5 MiB per token and sequence; level 1 keeps IEEE half rows
+    assert binding.kv_bytes(s, 1, 1, precision=1) == 524288
+    assert binding.kv_bytes(s, 128, 384, precision=1) == 524288 * 128 * 384
+    # block-scaled rows (the default level of this shape): one fp32 scale per (layer, K|V, kv head) row of 128 elements
+    assert binding.precision_level(s) == 2 and binding.kv_block_scaled(s)
+    assert binding.kv_bytes(s, 1, 1) == 524288 + 2 * 32 * 32 * 4
+    assert binding.kv_bytes(s, 128, 384) == (524288 + 2 * 32 * 32 * 4) * 128 * 384
+    s70 = PRESETS["llama70b"].shape
+    assert binding.precision_level(s70) == 3 and binding.kv_block_scaled(s70)
+    assert binding.kv_bytes(s70, 64, 384) == 2 * 80 * 8 * (128 * 2 + 4) * 64 * 384
+    assert binding.kv_bytes(s70, 64, 384, precision=2) == 2 * 80 * 8 * 128 * 2 * 64 * 384   # grouped-query shape: half rows at level 2
+    assert not binding.kv_block_scaled(s70, precision=2) and not binding.kv_block_scaled(s, precision=1)
+    assert binding.precision_level(s, precision=3) == 3
+    assert binding.validate_shape(binding.RlGenShape.from_model(s, 1, 1, precision=4)) == -2
     assert binding.work_bytes(s, 128, 384) > 0
 
 
@@ -78,15 +89,16 @@ def test_null_arguments_are_rejected_without_a_gpu(binding):
     assert L.rl_gen_reset(None) == -1
     L.rl_gen_destroy(None)
     assert L.rl_op_argmax(None, 1, 1, None, None) == -1
-    assert L.rl_op_gemm(None, None, 8, None, None, None, 1, 0, 0, 1, 8, None, 1, 0, 1, 0, 0, None) == -1
+    assert L.rl_op_gemm(None, None, 8, None, None, None, 1, 0, 0, 1, 8, None, 1, 0, 1, 0, 0, None, None) == -1
     assert L.rl_gen_kernel_class_name(4) == b"decode_attention"
     assert len(binding.KERNEL_CLASSES) == 13
 
 
 def test_page_bytes_and_page_planning_on_the_host(binding):
     s = PRESETS["llama7b"].shape
-    assert binding.page_bytes(s, 16) == 16 * 524288                 # a page of 16 positions: 16 x the per-token bytes
+    assert binding.page_bytes(s, 16, precision=1) == 16 * 524288    # a page of 16 positions: 16 x the per-token bytes
     assert binding.page_bytes(s, 64) * 6 == binding.kv_bytes(s, 1, 384)
+    assert binding.page_bytes(s, 16) == 16 * binding.kv_bytes(s, 1, 1)
     for bad in (0, 8, 24, 100, 8192, -16):
         assert binding.page_bytes(s, bad) == 0
     # consecutive pages, ceil(capacity / page) per sequence, -1 in the unused entries

@@ -294,6 +294,30 @@ def test_cached_route_equals_plain_definition():
     assert np.abs(logits - full[:, P - 1]).max() < 1e-12
 
 
+def test_feeding_a_sequence_in_spans_equals_plain_definition():
+    """prefill(first piece) + extend(further pieces of any length) reaches the logits of the plain, cache-free forward pass
+    at every span end, and decode steps continue from there (the route the long-context GPU tests take on the oracle)."""
+    s = small_shape(n_kv_heads=2)
+    W = rand_weights(s, seed=31)
+    B, T = 2, 17
+    tok = rand_tokens(s, B, T)
+    m = orc.OracleModel(s, W, B, T)
+    full = m.forward_all(tok)
+    logits, _ = m.prefill(tok[:, :4])
+    assert np.abs(logits - full[:, 3]).max() < 1e-12
+    at = 4
+    for n in (1, 5, 3, 2):
+        logits = m.extend(tok[:, at: at + n])
+        at += n
+        assert np.abs(logits - full[:, at - 1]).max() < 1e-12
+    assert m.extend(tok[:, at: at + 1], want_logits=False) is None
+    logits, nxt = m.decode_step(tok[:, at + 1])
+    assert np.abs(logits - full[:, at + 1]).max() < 1e-12 and np.array_equal(nxt, full[:, at + 1].argmax(-1))
+    with pytest.raises(orc.OracleError) as e:          # capacity
+        m.extend(tok[:, :1])
+    assert e.value.code == -3
+
+
 def test_gqa_equals_mha_with_replicated_kv_rows():
     s = small_shape(n_kv_heads=2)
     W = rand_weights(s, seed=28)

@@ -5,7 +5,7 @@ tensor slot), so a reduced-depth model is exactly a prefix of the full one and a
 tensor's values do not depend on which other tensors were generated.
 
 Recipe: embedding and all projection matrices ~ N(0, 0.02^2); RMSNorm gains are
-1.0.  Values are rounded once (round-to-nearest-even, torch's conversion) to
+1.0 (gain_std > 0: every gain vector drawn as 1 + gain_std * N(0, 1) instead).  Values are rounded once (round-to-nearest-even, torch's conversion) to
 bf16 so that the CPU oracle and the GPU path consume identical weights; the
 oracle widens them, the GPU path uses them as they are.
 """
@@ -32,17 +32,21 @@ def _tensor_shape(s: ModelShape, name: str):
     }[name]
 
 
-def _draw(seed_index: int, layer: int, name: str, shape, device, dtype, std: float):
-    if name.endswith("norm"):
-        return torch.ones(shape, dtype=dtype, device=device)
+def _draw(seed_index: int, layer: int, name: str, shape, device, dtype, std: float, gain_std: float = 0.0):
     g = torch.Generator(device=device)
     g.manual_seed((1000 + seed_index) * 1_000_003 + (layer + 1) * 101 + _SLOT[name])
+    if name.endswith("norm"):
+        if gain_std == 0.0:
+            return torch.ones(shape, dtype=dtype, device=device)
+        # distinct gains per norm (tests of which gain reaches which norm): 1 + gain_std * N(0, 1), rounded to bf16
+        t = 1.0 + gain_std * torch.randn(shape, generator=g, device=device, dtype=torch.float32)
+        return t.to(torch.bfloat16).to(dtype)
     t = torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std
     return t.to(torch.bfloat16).to(dtype)
 
 
 def make_weights(shape: ModelShape, seed_index: int, device="cpu", dtype=torch.bfloat16,
-                 std: float = 0.02) -> Dict[str, object]:
+                 std: float = 0.02, gain_std: float = 0.0) -> Dict[str, object]:
     """Returns {"tok_emb": T, "final_norm": T, "lm_head": T, <layer tensor>: [T]*L}.
 
     All values are exactly representable in bf16 whatever `dtype` is.  The CPU
@@ -51,11 +55,11 @@ def make_weights(shape: ModelShape, seed_index: int, device="cpu", dtype=torch.b
     """
     out: Dict[str, object] = {}
     for name in ("tok_emb", "final_norm", "lm_head"):
-        out[name] = _draw(seed_index, -1, name, _tensor_shape(shape, name), device, dtype, std)
+        out[name] = _draw(seed_index, -1, name, _tensor_shape(shape, name), device, dtype, std, gain_std)
     for name in LAYER_TENSORS:
         lst: List[torch.Tensor] = []
         for layer in range(shape.n_layers):
-            lst.append(_draw(seed_index, layer, name, _tensor_shape(shape, name), device, dtype, std))
+            lst.append(_draw(seed_index, layer, name, _tensor_shape(shape, name), device, dtype, std, gain_std))
         out[name] = lst
     return out
 
