@@ -95,8 +95,10 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
     const int rows_w = p.rows[seg_h[wn]];
     const int nb = nbase_h[wn], oc = ocol_h[wn];
     constexpr int CT = WN * 32 + 8;  // floats per row of a 32-row band in LDS (4 rows apart = 32 banks apart: no conflicts)
-    if (EPI == EPI_F32_ACC || EPI == EPI_ROPE) __syncthreads();  // every wavefront is done with the operand tiles
-    if (EPI == EPI_ROPE) {
+    constexpr bool ROPE = EPI == EPI_ROPE || EPI == EPI_ROPE_BS;
+    constexpr bool BS = EPI == EPI_ROPE_BS;  // cache rows as 16-bit block-scaled fixed point, q with its low half term
+    if (EPI == EPI_F32_ACC || ROPE) __syncthreads();  // every wavefront is done with the operand tiles
+    if (ROPE) {
         // The wavefront's 128 columns are one head of q, k or v.  Element e pairs with e + 64: accumulator tiles j and
         // j + 2 of the same lane.  The arithmetic is that of rope_append_kernel, operation for operation, so both paths
         // store the same bits.  Rows leave through a per-wavefront LDS band as whole 256-byte head rows.
@@ -108,59 +110,69 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
         f16_t *ht = reinterpret_cast<f16_t *>(smem) + w * 32 * HT;
         float *hs = reinterpret_cast<float *>(smem + 4 * 32 * HT * 2) + w * 32;  // row scales of the band (block-scaled cache)
         f16_t *hl = reinterpret_cast<f16_t *>(smem + 4 * 32 * HT * 2 + 4 * 32 * 4) + w * 32 * HT;  // low half terms of q rows
-        const bool i16 = seg != 0 && rp.map.kscale != nullptr;  // cache rows as 16-bit block-scaled fixed point
         if (head_ok) {
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int mb = m0 + (wm * WM + i) * 32;  // first row of the band (uniform over the wavefront)
                 const int pos_b = mb % rp.T, seq_b = rp.b0 + mb / rp.T;
+                // KIND 0: half rows; 1: half rows and their low terms (q next to a block-scaled cache); 2: block-scaled k/v rows.
+                // One fully unrolled copy of the band per kind (accumulators must be indexed with constants), chosen per wavefront.
+                auto band = [&](auto kind_tag) {
+                    constexpr int KIND = decltype(kind_tag)::value;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int r = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-                    int pos = pos_b + r;
-                    if (pos >= rp.T) pos -= rp.T;  // T >= 32: at most one wrap inside a band
-                    pos = pos < rp.S ? pos : rp.S - 1;
-                    const float *tab = rp.rope_tab + (size_t)pos * 128;
-                    float va[2], vc2[2];
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int rr = j * 32 + (lane & 31);
-                        float a = acc[i][j][e], c = acc[i][j + 2][e];
-                        if (seg != 2) {
-                            const float cs = tab[2 * rr], sn = tab[2 * rr + 1];
-                            const float ra = __fmaf_rn(a, cs, -__fmul_rn(c, sn));
-                            const float rb = __fmaf_rn(c, cs, __fmul_rn(a, sn));
-                            a = ra; c = rb;
-                        }
-                        va[j] = a; vc2[j] = c;
-                    }
-                    if (i16) {
-                        // the 32 lanes of a half-wavefront hold the 128 elements of row r: row maximum by xor shuffles
-                        float am = fmaxf(fmaxf(fabsf(va[0]), fabsf(va[1])), fmaxf(fabsf(vc2[0]), fabsf(vc2[1])));
-#pragma unroll
-                        for (int o = 1; o < 32; o <<= 1) am = fmaxf(am, __shfl_xor(am, o, 64));
-                        const float inv = kv_inv_of(am);
+                    for (int e = 0; e < 16; ++e) {
+                        const int r = (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+                        int pos = pos_b + r;
+                        if (pos >= rp.T) pos -= rp.T;  // T >= 32: at most one wrap inside a band
+                        pos = pos < rp.S ? pos : rp.S - 1;
+                        const float *tab = rp.rope_tab + (size_t)pos * 128;
+                        float va[2], vc2[2];
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
                             const int rr = j * 32 + (lane & 31);
-                            ht[r * HT + rr] = (f16_t)(kv_quant(va[j], inv) & 0xffff);
-                            ht[r * HT + rr + 64] = (f16_t)(kv_quant(vc2[j], inv) & 0xffff);
+                            float a = acc[i][j][e], c = acc[i][j + 2][e];
+                            if (seg != 2) {
+                                const float cs = tab[2 * rr], sn = tab[2 * rr + 1];
+                                const float ra = __fmaf_rn(a, cs, -__fmul_rn(c, sn));
+                                const float rb = __fmaf_rn(c, cs, __fmul_rn(a, sn));
+                                a = ra; c = rb;
+                            }
+                            va[j] = a; vc2[j] = c;
                         }
-                        if ((lane & 31) == 0) hs[r] = kv_scale_of(am);
-                    } else {
+                        if (KIND == 2) {
+                            // the 32 lanes of a half-wavefront hold the 128 elements of row r: row maximum by xor shuffles
+                            float am = fmaxf(fmaxf(fabsf(va[0]), fabsf(va[1])), fmaxf(fabsf(vc2[0]), fabsf(vc2[1])));
+                            am = fmaxf(am, __shfl_xor(am, 1, 64));
+                            am = fmaxf(am, __shfl_xor(am, 2, 64));
+                            am = fmaxf(am, __shfl_xor(am, 4, 64));
+                            am = fmaxf(am, __shfl_xor(am, 8, 64));
+                            am = fmaxf(am, __shfl_xor(am, 16, 64));
+                            const float inv = kv_inv_of(am);
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            const int rr = j * 32 + (lane & 31);
-                            const f16_t ha = f32_to_f16(va[j]), hc = f32_to_f16(vc2[j]);
-                            ht[r * HT + rr] = ha;
-                            ht[r * HT + rr + 64] = hc;
-                            if (seg == 0 && rp.q_f16_lo) {
-                                hl[r * HT + rr] = f32_to_f16(va[j] - f16_to_f32(ha));
-                                hl[r * HT + rr + 64] = f32_to_f16(vc2[j] - f16_to_f32(hc));
+                            for (int j = 0; j < 2; ++j) {
+                                const int rr = j * 32 + (lane & 31);
+                                ht[r * HT + rr] = (f16_t)(kv_quant(va[j], inv) & 0xffff);
+                                ht[r * HT + rr + 64] = (f16_t)(kv_quant(vc2[j], inv) & 0xffff);
+                            }
+                            if ((lane & 31) == 0) hs[r] = kv_scale_of(am);
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < 2; ++j) {
+                                const int rr = j * 32 + (lane & 31);
+                                const f16_t ha = f32_to_f16(va[j]), hc = f32_to_f16(vc2[j]);
+                                ht[r * HT + rr] = ha;
+                                ht[r * HT + rr + 64] = hc;
+                                if (KIND == 1) {
+                                    hl[r * HT + rr] = f32_to_f16(va[j] - f16_to_f32(ha));
+                                    hl[r * HT + rr + 64] = f32_to_f16(vc2[j] - f16_to_f32(hc));
+                                }
                             }
                         }
                     }
-                }
+                };
+                if (!BS) band(std::integral_constant<int, 0>{});
+                else if (seg == 0) band(std::integral_constant<int, 1>{});
+                else band(std::integral_constant<int, 2>{});
                 // 16 lanes per row (16 bytes each), 4 rows per instruction
                 const int c8 = (lane & 15) * 8;
 #pragma unroll
@@ -172,7 +184,7 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
                     const u32x4_t v = *reinterpret_cast<const u32x4_t *>(ht + r * HT + c8);
                     if (seg == 0) {
                         *reinterpret_cast<u32x4_t *>(rp.q_f16 + ((size_t)m * rp.Hq + head) * 128 + c8) = v;
-                        if (rp.q_f16_lo) {  // second half term of q: the band's low rows sit behind its 32 high rows
+                        if (BS && rp.q_f16_lo) {  // second half term of q, from the band of low terms
                             const u32x4_t vl = *reinterpret_cast<const u32x4_t *>(hl + r * HT + c8);
                             *reinterpret_cast<u32x4_t *>(rp.q_f16_lo + ((size_t)m * rp.Hq + head) * 128 + c8) = vl;
                         }
@@ -187,7 +199,7 @@ __device__ __forceinline__ void tiled_epilogue(const TiledParams &p, const TileC
                             const size_t rowi = kv_row_index(rp.map, seq, head, rp.Hkv, rp.S, pos);
                             f16_t *dst = (seg == 1 ? rp.kc : rp.vc) + rowi * 128 + c8;
                             *reinterpret_cast<u32x4_t *>(dst) = v;
-                            if (i16 && (lane & 15) == 0) (seg == 1 ? rp.map.kscale : rp.map.vscale)[rowi] = hs[r];
+                            if (BS && (lane & 15) == 0) (seg == 1 ? rp.map.kscale : rp.map.vscale)[rowi] = hs[r];
                         }
                     }
                 }
@@ -697,7 +709,11 @@ static void launch_one(const GemmArgs &a, hipStream_t st) {
     const bool big = a.M >= 1024 && big_tiles >= 256;
     if (a.epilogue == EPI_SWIGLU) { if (big) launch_t<4, 4, EPI_SWIGLU>(p, a, st); else launch_t<2, 2, EPI_SWIGLU>(p, a, st); }
     else if (a.epilogue == EPI_F32_ACC) { if (big) launch_t<4, 4, EPI_F32_ACC>(p, a, st); else launch_t<2, 2, EPI_F32_ACC>(p, a, st); }
-    else if (a.epilogue == EPI_ROPE) { p.rope = *a.rope; launch_t<4, 4, EPI_ROPE>(p, a, st); }  // 128-column wavefronts only
+    else if (a.epilogue == EPI_ROPE) {  // 128-column wavefronts only
+        p.rope = *a.rope;
+        if (p.rope.map.kscale) { p.epilogue = EPI_ROPE_BS; launch_t<4, 4, EPI_ROPE_BS>(p, a, st); }
+        else launch_t<4, 4, EPI_ROPE>(p, a, st);
+    }
     else { if (big) launch_t<4, 4, EPI_F32>(p, a, st); else launch_t<2, 2, EPI_F32>(p, a, st); }
 }
 

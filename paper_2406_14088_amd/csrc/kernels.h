@@ -56,8 +56,10 @@ enum GemmEpilogue {
     EPI_F32 = 0,    // out fp32: split s writes out + s*split_stride, element [m*ldc + col]
     EPI_SWIGLU = 1, // W_0 = gate, W_1 = up (same shape): out half [m*ldc + n] = silu(gate) * up; splits must be 1
     EPI_F32_ACC = 2, // out fp32 [m*ldc + col] += result (residual add); splits must be 1
-    EPI_ROPE = 3     // tiled kernel only: W_0, W_1, W_2 = Wq, Wk, Wv; the result is rotated and stored as launch_rope_append
+    EPI_ROPE = 3,    // tiled kernel only: W_0, W_1, W_2 = Wq, Wk, Wv; the result is rotated and stored as launch_rope_append
                      // would store it (q half, cache rows), without the fp32 round trip; see RopeEpilogue
+    EPI_ROPE_BS = 4  // chosen by the launcher for EPI_ROPE when RopeEpilogue::map names row scales: block-scaled cache rows, and
+                     // q with its low half term
 };
 // What the EPI_ROPE epilogue needs: row m of the product is sequence b0 + m / T at position m % T (a prefill from
 // position 0).  head_dim 128 and rotary style 1 (element e pairs with e + 64) only; every W_i holds whole heads.
