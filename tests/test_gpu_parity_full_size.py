@@ -136,6 +136,7 @@ def test_13b_workload_full_depth_sampled():
     om.prefill(pn[:, :64])
     for at in range(64, P - 64, 64):
         om.extend(pn[:, at: at + 64], want_logits=False)
+    step("  oracle prompt done")
     o_logits = om.extend(pn[:, P - 64:])
     o_next = np.array([orc.argmax(r) for r in o_logits], dtype=np.int32)
     tally = Tally("13B, 40 layers, batch 256")
@@ -167,6 +168,8 @@ def test_long_context_workload_full_depth_prompt():
     om.prefill(pn[:, :128])
     for at in range(128, P - 128, 128):
         om.extend(pn[:, at: at + 128], want_logits=False)
+        if at % 512 == 0:
+            step(f"  oracle at position {at}")
     o_logits = om.extend(pn[:, P - 128:])
     o_next = np.array([orc.argmax(r) for r in o_logits], dtype=np.int32)
     tally = Tally("7B, 32 layers, prompt 2048")
@@ -180,11 +183,11 @@ def test_long_context_workload_full_depth_prompt():
 
 def test_long_context_workload_to_the_last_position():
     """The long-context workload's lengths (prompt 2048, generation to position 4094, batch 32, the cache at 4096 positions) at
-    the 7B width and 8 of the 32 layers, so that the oracle can follow one sequence all the way: logits compared at the
+    the 7B width and 4 of the 32 layers, so that the oracle can follow one sequence all the way: logits compared at the
     first decode step, around position 3000 and at the last positions."""
     from paper_2406_14088_amd import Generator
     wl = PRESETS["llama7b_long"]
-    shape, B, P, G = wl.shape.with_layers(8), wl.batch, wl.prompt_len, wl.gen_len
+    shape, B, P, G = wl.shape.with_layers(4), wl.batch, wl.prompt_len, wl.gen_len
     sample = [20]
     keep = {0, 1, 2, 952, 953, G - 3, G - 2, G - 1}       # step i decodes at position P + i - 1
     W = make_weights(shape, wl.index, device=DEV)
@@ -197,7 +200,7 @@ def test_long_context_workload_to_the_last_position():
     del W
     om = orc.OracleModel(shape, Wn, 1, P + G)
     seq = np.concatenate([prompts[sample].cpu().numpy(), torch.stack(g_tokens, 1).cpu().numpy()], axis=1)   # [1, P + G]
-    tally = Tally("7B width, 8 layers, positions to 4094")
+    tally = Tally("7B width, 4 layers, positions to 4094")
     at = 0
     for i in sorted(keep):          # logits of step i follow the token at position P + i - 1
         end = P + i
@@ -206,6 +209,8 @@ def test_long_context_workload_to_the_last_position():
             last = at + n == end
             o_logits = om.extend(seq[:, at: at + n], want_logits=last) if at else om.prefill(seq[:, :n])[0]
             at += n
+            if at % 1024 == 0:
+                step(f"  oracle at position {at}")
         o_next = np.array([orc.argmax(r) for r in o_logits], dtype=np.int32)
         tally.add(i, g_logits[i], g_tokens[i], o_logits, o_next)
     om.close()
@@ -217,7 +222,7 @@ def test_70b_workload_full_depth_sampled():
     short prompt; the oracle recomputes two sequences."""
     from paper_2406_14088_amd import Generator
     wl = PRESETS["llama70b"]
-    shape, B, P, G = wl.shape, wl.batch, 24, 6
+    shape, B, P, G = wl.shape, wl.batch, 24, 4
     sample = [3, 50]
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
@@ -229,16 +234,21 @@ def test_70b_workload_full_depth_sampled():
     gen = Generator(shape, W, B, P + G)
     g_logits, g_tokens = generate_on_gpu(gen, prompts, G, sample)
     gen.close()
-    step("copying weights to the host for the oracle")
-    Wn = orc.weights_to_numpy(W)
+    step("copying weights to the host for the oracle, tensor by tensor")
+    Wn = {}
+    for k in list(W.keys()):       # 138 GB: keep the runner informed while it moves
+        Wn.update(orc.weights_to_numpy({k: W.pop(k)}))
+        step(f"  {k} on the host")
     del W
     torch.cuda.empty_cache()
     om = orc.OracleModel(shape, Wn, len(sample), P + G)
+    step("oracle prefill of the sampled sequences")
     o_logits, o_next = om.prefill(prompts[sample].cpu().numpy())
     tally = Tally("70B, 80 layers, batch 64")
     for i in range(G):
         gn = tally.add(i, g_logits[i], g_tokens[i], o_logits, o_next)
         if i < G - 1:
             o_logits, o_next = om.decode_step(gn)
+            step(f"  oracle decode step {i + 1}")
     om.close()
     tally.finish(need_rate=False)
