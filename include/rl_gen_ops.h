@@ -135,6 +135,20 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
                            const int32_t *d_done, const float *kscale, const float *vscale, uint16_t *out_lo, void *hip_stream);
 size_t rl_op_decode_attention_ws_floats(int32_t B, int32_t Hq, int32_t hd, int32_t nsplit);
 
+/* rl_op_decode_attention for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same operation, same kernels and same results; the split partials (the `ws` of
+ * rl_op_decode_attention) live in a scratch array of RL_OP_NOALLOC_SCRATCH_BYTES that is part of the library's code object on
+ * every GPU (held until the process ends).  The call allocates nothing and calls no allocating routine; on its first use
+ * on a device it looks the array's address up (hipGetSymbolAddress) -- make that first call outside a stream capture.
+ * RL_GEN_E_CAPACITY (text in rl_gen_last_error(NULL)) when rl_op_decode_attention_ws_floats(B, Hq, hd, nsplit) * 4 exceeds the
+ * scratch size.  All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different streams
+ * or host threads) race on it; calls that follow each other on one stream do not. */
+#define RL_OP_NOALLOC_SCRATCH_BYTES (16u << 20)
+int rl_op_decode_attention_noalloc(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
+                                   uint16_t *out, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
+                                   const int32_t *d_done, const float *kscale, const float *vscale, uint16_t *out_lo,
+                                   void *hip_stream);
+
 /* The same attention over a paged cache (Section 7 names paged attention as a technique the generation backend can
  * take in).  k_pool / v_pool: DEVICE f16 [n_pages][Hkv][page_size][hd]; table: DEVICE int32 [B, table_stride], entry
  * (b, i) = pool page that holds positions i*page_size .. of sequence b; page_size a power of two in [16, 4096],

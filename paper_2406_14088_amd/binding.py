@@ -104,6 +104,7 @@ def lib():
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention_ws_floats": (sz, [i32, i32, i32, i32]),
+        "rl_op_decode_attention_noalloc": (C.c_int, [vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention_paged": (C.c_int, [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "rl_op_decode_attention_fused": (C.c_int, [vp, i32, sz, vp, i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp]),
         "rl_op_prefill_attention": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
@@ -126,7 +127,7 @@ EXPORTED_SYMBOLS = (
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_gemm_packed_swiglu_halves", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
+    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_gemm_packed_swiglu_halves", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_noalloc", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
@@ -508,6 +509,12 @@ class _Ops:
         self._ck(lib().rl_op_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride, out.data_ptr(),
                                               _ptr(ws), B, Hq, Hkv, hd, S, nsplit, _ptr(d_done), _ptr(kscale), _ptr(vscale), _ptr(out_lo),
                                               _stream()), "rl_op_decode_attention")
+
+    def decode_attention_noalloc(self, q, kc, vc, d_len, out, B, Hq, Hkv, hd, S, nsplit, len_stride=0, d_done=None, kscale=None,
+                                 vscale=None, out_lo=None):
+        self._ck(lib().rl_op_decode_attention_noalloc(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), d_len.data_ptr(), len_stride,
+                                                      out.data_ptr(), B, Hq, Hkv, hd, S, nsplit, _ptr(d_done), _ptr(kscale),
+                                                      _ptr(vscale), _ptr(out_lo), _stream()), "rl_op_decode_attention_noalloc")
 
     def decode_attention_paged(self, q, k_pool, v_pool, table, page_size, d_len, out, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=0,
                                kscale=None, vscale=None):

@@ -6,15 +6,43 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "../../include/rl_gen.h"
 #include "../../include/rl_gen_ops.h"
 #include "kernels.h"
 
+// Scratch memory of the entry point that allocates nothing (rl_op_decode_attention_noalloc): one array per GPU, part of the
+// library's code object, held until the process ends.  In host code the array's name is a stand-in, not a device address:
+// the address on the current device comes from hipGetSymbolAddress (scratch_of_current_device) and only that pointer is
+// handed to kernels.
+static __device__ __align__(256) unsigned char scratch[RL_OP_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 char g_create_error[512] = "";
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, looked up once per device.
+int scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RL_GEN_E_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return RL_GEN_E_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RL_GEN_OK;
+}
 
 constexpr int kPrefillChunkTokens = 16384;  // prompt tokens pushed through the layers at once
 constexpr int kSkinnyMaxM = 256;
@@ -1376,6 +1404,32 @@ int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *v
     map.kscale = const_cast<float *>(kscale); map.vscale = const_cast<float *>(vscale);
     launch_decode_attention(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, hd, S, nsplit, reinterpret_cast<hipStream_t>(st), map,
                             d_done, out_lo);
+    RL_OP_RETURN();
+}
+
+int rl_op_decode_attention_noalloc(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
+                                   uint16_t *out, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
+                                   const int32_t *d_done, const float *kscale, const float *vscale, uint16_t *out_lo, void *st) {
+    if (!q || !kc || !vc || !d_len || !out) return RL_GEN_E_NULL;
+    if ((kscale == nullptr) != (vscale == nullptr)) return RL_GEN_E_NULL;
+    if (B < 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || (hd != 64 && hd != 128) || S <= 0 || nsplit < 1) return RL_GEN_E_SHAPE;
+    if (len_stride != 0 && len_stride != 1) return RL_GEN_E_SHAPE;
+    const size_t need = decode_attention_ws_floats(B, Hq, hd, nsplit) * sizeof(float);
+    if (need > (size_t)RL_OP_NOALLOC_SCRATCH_BYTES) {
+        set_err(nullptr, "rl_op_decode_attention_noalloc: the split partials need %zu bytes, the built-in scratch holds %zu", need,
+                (size_t)RL_OP_NOALLOC_SCRATCH_BYTES);
+        return RL_GEN_E_CAPACITY;
+    }
+    void *ws = nullptr;
+    if (int rc = scratch_of_current_device(&ws)) {
+        set_err(nullptr, "rl_op_decode_attention_noalloc: hipGetSymbolAddress(scratch) failed");
+        return rc;
+    }
+    // every partial a merge reads is written by this call's attention kernel first: nothing to clear
+    KvMap map;
+    map.kscale = const_cast<float *>(kscale); map.vscale = const_cast<float *>(vscale);
+    launch_decode_attention(q, kc, vc, d_len, len_stride, out, reinterpret_cast<float *>(ws), B, Hq, Hkv, hd, S, nsplit,
+                            reinterpret_cast<hipStream_t>(st), map, d_done, out_lo);
     RL_OP_RETURN();
 }
 
