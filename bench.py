@@ -21,28 +21,58 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+DTYPE = "f16 x bf16 -> fp32 on the matrix cores (f16 activations, as two-term sums where the precision level asks; 16-bit KV cache)"
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense 16-bit matrix cores (bf16 and fp16), published
-# HBM bytes per decode-attention launch (mean over the launches of one generation) measured with rocprofv3 counters:
-# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the library's 1 GiB copy_kernel
-# (profiles/decode_attention_llama7b_hbm_traffic.md).  Only valid for the unmodified llama7b workload.
-MEASURED_TRAFFIC_BYTES = {"llama7b": 527424 * 1024}
+# HBM bytes per decode-attention launch (mean over the launches of one generation) as rocprofv3 counters saw them in a
+# separate profiling run of this benchmark: FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for the
+# library's 1 GiB copy_kernel.  A RECORDED figure (the counters cannot be read from inside this process): it is reported
+# with its source file, and only for the unmodified workload it was recorded on.
+RECORDED_TRAFFIC = {"llama7b": {"bytes": None, "source": "profiles/decode_attention_llama7b_hbm_traffic.md"}}
 
 
-def decode_bytes(shape, B, t):
+def kv_row_bytes(shape, block_scaled):
+    """Bytes of one cache row (head_dim 16-bit elements, plus the fp32 scale of a block-scaled row)."""
+    return shape.head_dim * 2 + (4 if block_scaled else 0)
+
+
+def decode_bytes(shape, B, t, block_scaled=False):
     """Algorithmic HBM bytes of one decode step at position t (the new token attends to t+1 cache rows):
     every weight once, the KV cache rows read, the appended K/V rows, the fp32 logits, the embedding rows."""
     d, hd, Hq, Hkv, F, V, L = shape.hidden, shape.head_dim, shape.n_heads, shape.n_kv_heads, shape.ffn, shape.vocab, shape.n_layers
     w = 2 * (L * ((Hq + 2 * Hkv) * hd * d + Hq * hd * d + 3 * d * F + 2 * d) + d + V * d)
-    kv_row = 2 * L * Hkv * hd * 2
+    kv_row = 2 * L * Hkv * kv_row_bytes(shape, block_scaled)
     return w + B * (t + 1) * kv_row + B * kv_row + B * V * 4 + B * d * 2
 
 
-def attention_bytes(shape, B, t):
+def attention_bytes(shape, B, t, block_scaled=False):
     """Algorithmic bytes of ONE decode-attention launch (one layer) at position t: K and V rows 0..t of every
     (sequence, kv head), the fp32 queries and the 16-bit outputs."""
     hd, Hq, Hkv = shape.head_dim, shape.n_heads, shape.n_kv_heads
-    return B * (t + 1) * 2 * Hkv * hd * 2 + B * Hq * hd * (4 + 2)
+    return B * (t + 1) * 2 * Hkv * kv_row_bytes(shape, block_scaled) + B * Hq * hd * (4 + 2)
+
+
+def decode_kernel_models(shape, B, P, G, block_scaled, level):
+    """Per kernel class of a decode step: algorithmic bytes per launch (weights once + activations in + results out; for
+    attention the mean over the positions of the generation) and executed flops per launch (second activation terms
+    included).  M = B rows."""
+    d, hd, Hq, Hkv, F, V = shape.hidden, shape.head_dim, shape.n_heads, shape.n_kv_heads, shape.ffn, shape.vocab
+    qd, kvd, M = Hq * hd, Hkv * hd, B
+    nqkv = qd + 2 * kvd
+    t_o, t_act, t_ffn = (2 if level >= 2 else 1), (2 if level >= 2 else 1), (2 if level >= 3 else 1)
+    att = sum(attention_bytes(shape, B, t, block_scaled) for t in range(P, P + G - 1)) / max(G - 1, 1)
+    return {
+        "gemm_qkv": {"bytes": nqkv * d * 2 + 2 * M * d * 2 + M * nqkv * 4, "flops": 2 * 2 * M * nqkv * d},
+        "gemm_o": {"bytes": d * qd * 2 + t_o * M * qd * 2 + M * d * 4, "flops": 2 * t_o * M * d * qd},
+        "gemm_gate_up": {"bytes": 2 * F * d * 2 + t_ffn * M * d * 2 + t_act * M * F * 2, "flops": 2 * t_ffn * M * 2 * F * d},
+        "gemm_down": {"bytes": d * F * 2 + t_act * M * F * 2 + M * d * 4, "flops": 2 * t_act * M * d * F},
+        "gemm_lm_head": {"bytes": V * d * 2 + t_ffn * M * d * 2 + M * V * 4, "flops": 2 * t_ffn * M * V * d},
+        "add_rmsnorm": {"bytes": M * d * (4 + 4 + 2 * 2), "flops": 0},
+        "rope_append": {"bytes": M * nqkv * 4 + M * qd * 4 + 2 * M * Hkv * kv_row_bytes(shape, block_scaled), "flops": 0},
+        "decode_attention": {"bytes": att, "flops": 0},
+        "argmax": {"bytes": M * V * 4, "flops": 0},
+        "embed": {"bytes": M * d * (2 + 4), "flops": 0},
+    }
 
 
 def prefill_flops(shape, B, P):
@@ -76,7 +106,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2406_14088_amd import Generator
+    from paper_2406_14088_amd import Generator, kv_block_scaled, precision_level
     from workload import PRESETS, make_prompts, make_weights
 
     if not torch.cuda.is_available():
@@ -86,6 +116,7 @@ def main():
     wl = PRESETS[args.workload]
     shape = wl.shape.with_layers(args.layers) if args.layers else wl.shape
     B, P, G = wl.batch, wl.prompt_len, wl.gen_len
+    level, bs = precision_level(shape), kv_block_scaled(shape)
 
     t0 = time.perf_counter()
     W = make_weights(shape, wl.index, device=dev)
@@ -118,7 +149,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    def generate(timing=None):
+    def generate(timing=None, after_prefill=None):
         """weight re-layout + prefill + (G-1) decode steps; tokens stay on the device.  The fragment-order weight copies
         are rebuilt inside every step: in the RLHF loop each generation phase starts from freshly trained weights."""
         if timing is not None:
@@ -130,6 +161,8 @@ def main():
             ta = time.perf_counter()
             timing["pack_s"] = timing.get("pack_s", 0.0) + ta - tp
         gen.prefill(prompts, next_tokens=buf[0])
+        if after_prefill is not None:
+            after_prefill()
         if timing is not None:
             torch.cuda.synchronize()
             tb = time.perf_counter()
@@ -166,7 +199,7 @@ def main():
     # split of one generation into prefill and decode (separate, synchronised pass; not part of `value`)
     split = {}
     generate(split)
-    dec_bytes = sum(decode_bytes(shape, B, t) for t in range(P, P + G - 1))
+    dec_bytes = sum(decode_bytes(shape, B, t, bs) for t in range(P, P + G - 1))
     pf = prefill_flops(shape, B, P)
     phases = {
         "pack_weights_ms": split["pack_s"] * 1e3,
@@ -178,7 +211,7 @@ def main():
         "decode_frac_of_hbm_peak": dec_bytes / split["decode_s"] / 1e9 / HBM_PEAK_GBS,
         "decode_tokens_per_s": B * (G - 1) / split["decode_s"],
         # single decode steps (events on the launch stream): position, ms, algorithmic GB/s
-        "decode_steps": [{"position": P + i, "ms": ms, "algorithmic_GBs": decode_bytes(shape, B, P + i) / (ms * 1e-3) / 1e9}
+        "decode_steps": [{"position": P + i, "ms": ms, "algorithmic_GBs": decode_bytes(shape, B, P + i, bs) / (ms * 1e-3) / 1e9}
                          for i, ms in sorted(split["step_ms"].items())],
     }
 
@@ -187,11 +220,12 @@ def main():
         else f"generated tokens/sec on 1 GPU + decode-step HBM GB/s (% peak), {args.workload}",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"{wl.name}: L{shape.n_layers} d{shape.hidden} H{shape.n_heads}/{shape.n_kv_heads} F{shape.ffn} "
                                f"V{shape.vocab}, batch {B}, prompt {P}, generate {G}",
                    "global_batch": B, "prompt_len": P, "gen_len": G, "hip_graph": not args.no_graph,
-                   "packed_gate_up_layers": gen.packed_gate_up_layers()},
+                   "packed_gate_up_layers": gen.packed_gate_up_layers(), "precision_level": level,
+                   "kv_cache": "int16 rows with one fp32 scale each" if bs else "IEEE half rows"},
         "phases": phases, "setup_s": setup_s,
     }
 
@@ -199,19 +233,43 @@ def main():
         # per-kernel durations, measured with HIP events on the launch stream during one more generation
         gen.profile(True)
         gen.profile_read()
-        generate()
+        pre = {}
+        generate(after_prefill=lambda: pre.update(gen.profile_read()))   # the prefill's launches are read (and reset) apart
         prof = gen.profile_read()
         gen.profile(False)
         att = prof["decode_attention"]
-        att_bytes = sum(attention_bytes(shape, B, t) for t in range(P, P + G - 1)) * shape.n_layers
+        att_bytes = sum(attention_bytes(shape, B, t, bs) for t in range(P, P + G - 1)) * shape.n_layers
         if att["launches"] > 0 and att["ms"] > 0:
             achieved = att_bytes / (att["ms"] * 1e-3) / 1e9
+            rec = RECORDED_TRAFFIC.get(args.workload) if not args.layers else None
             out["roofline"] = {"kernel": "decode_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                               "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if not args.layers else None,
+                               "traffic": rec["bytes"] if rec else None,
+                               "traffic_source": (rec["source"] + " (rocprofv3 counters of a separate run of this command; not "
+                                                  "measured by this run)") if rec and rec["bytes"] else None,
                                "launches": att["launches"], "avg_launch_us": att["ms"] * 1e3 / att["launches"],
                                "bytes_per_launch_mean": att_bytes / att["launches"]}
-        out["kernels"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 3)} for k, v in prof.items() if v["launches"]}
+        # every kernel class of the decode step against its own roofline: algorithmic bytes per launch / event-timed duration
+        # (HIP events around every launch on the launch stream; graph replay is off in this pass, which adds 2-4 us per launch)
+        models = decode_kernel_models(shape, B, P, G, bs, level)
+        ra = []
+        for k, mdl in models.items():
+            v = prof.get(k)
+            if not v or not v["launches"] or v["ms"] <= 0:
+                continue
+            us = v["ms"] * 1e3 / v["launches"]
+            e = {"class": k, "bound": "hbm", "launches": v["launches"], "avg_launch_us": us, "bytes_per_launch": mdl["bytes"],
+                 "achieved": mdl["bytes"] / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": mdl["bytes"] / us / 1e3 / HBM_PEAK_GBS,
+                 "share_of_decode_kernel_time": None}
+            if mdl["flops"]:
+                e["executed_tflops"] = mdl["flops"] / us / 1e6
+            ra.append(e)
+        tot = sum(e["avg_launch_us"] * e["launches"] for e in ra)
+        for e in ra:
+            e["share_of_decode_kernel_time"] = e["avg_launch_us"] * e["launches"] / tot
+        out["roofline_all"] = sorted(ra, key=lambda e: -e["share_of_decode_kernel_time"])
+        out["kernels"] = {"prefill": {k: {"launches": v["launches"], "ms": round(v["ms"], 3)} for k, v in pre.items() if v["launches"]},
+                          "decode": {k: {"launches": v["launches"], "ms": round(v["ms"], 3)} for k, v in prof.items() if v["launches"]}}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, wl, W)
@@ -244,7 +302,7 @@ def bench_portions(args, gen, wl, shape, prompts, setup_s):
     return {"metric": f"generated tokens/sec on 1 GPU, {wl.name}, batch in {args.mbs} sequential portions",
             "value": B * G * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
+            "dtype": DTYPE, "data": "synthetic",
             "config": {"workload": f"{wl.name}: L{shape.n_layers} d{shape.hidden} H{shape.n_heads}/{shape.n_kv_heads} F{shape.ffn} "
                                    f"V{shape.vocab}, batch {B} as {args.mbs} portions of {B // args.mbs}, prompt {P}, generate {G}",
                        "global_batch": B, "prompt_len": P, "gen_len": G, "mbs": args.mbs, "hip_graph": not args.no_graph},
@@ -275,7 +333,7 @@ def bench_logprobs(args, gen, wl, shape, dev, setup_s):
     out = {"metric": f"inference call (token log-probabilities), scored tokens/sec on 1 GPU, {wl.name}", "value": B * T * args.steps / elapsed,
            "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f16 activations and KV cache x bf16 weights, fp32 accumulate", "data": "synthetic",
+           "dtype": DTYPE, "data": "synthetic",
            "config": {"workload": f"{wl.name}: L{L} d{d} H{Hq}/{Hkv} F{F} V{V}, batch {B}, sequence {T}", "global_batch": B, "seq_len": T},
            "phases": {"tflops": flops / (elapsed / args.steps) / 1e12, "frac_of_mfma_peak": flops / (elapsed / args.steps) / 1e12 / MFMA_PEAK_TFLOPS},
            "setup_s": setup_s, "checksum_logp": float(logp.double().sum().item())}

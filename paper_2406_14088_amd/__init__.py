@@ -5,7 +5,7 @@ thin Python binding: argument marshalling only.  There is no CPU fallback: impor
 without the built library raises.
 """
 from .binding import (RlGenError, RlGenShape, Generator, lib, ops, param_count, kv_bytes, work_bytes,
-                      validate_shape, KERNEL_CLASSES)
+                      validate_shape, precision_level, kv_block_scaled, KERNEL_CLASSES)
 
 __all__ = ["RlGenError", "RlGenShape", "Generator", "lib", "ops", "param_count", "kv_bytes", "work_bytes",
-           "validate_shape", "KERNEL_CLASSES"]
+           "validate_shape", "precision_level", "kv_block_scaled", "KERNEL_CLASSES"]

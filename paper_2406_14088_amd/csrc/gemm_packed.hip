@@ -582,18 +582,25 @@ __global__ __launch_bounds__(PK_THREADS, 1) void gemm_packed_swiglu_halves_kerne
     __syncthreads();
     const int c8 = (t & 7) * 8, rr = t >> 3;  // 8 lanes x 16 B = one 128-byte output row; 32 rows per pass
     const int ncols = rows - tile * 64;
-    for (int tm = 0; tm < (two_out ? 2 : 1); ++tm) {
-        f16_t *out = tm == 0 ? reinterpret_cast<f16_t *>(p.out) : p.out_lo;
+    f16_t *const outs[2] = {reinterpret_cast<f16_t *>(p.out), p.out_lo};
 #pragma unroll
-        for (int i = 0; i < BM / 32; ++i) {
-            int m = rr + 32 * i;
-            if (m < Mloc && c8 < ncols) {
-                f16_t *dst = out + (size_t)(m0 + m) * p.ldc + tile * 64 + c8;
-                const f16_t *srcp = ht + (tm * BM + m) * 72 + c8;
-                if (c8 + 8 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
-                    *reinterpret_cast<u32x4_t *>(dst) = *reinterpret_cast<const u32x4_t *>(srcp);
-                } else {
-                    for (int e = 0; e < 8 && c8 + e < ncols; ++e) dst[e] = srcp[e];
+    for (int i = 0; i < BM / 32; ++i) {
+        int m = rr + 32 * i;
+        if (m < Mloc && c8 < ncols) {
+            const size_t at = (size_t)(m0 + m) * p.ldc + tile * 64 + c8;
+            const bool vec = c8 + 8 <= ncols && ((at * sizeof(f16_t)) & 15) == 0 && ((reinterpret_cast<uintptr_t>(outs[0]) | reinterpret_cast<uintptr_t>(outs[1])) & 15) == 0;
+            // both terms of a row piece leave together: their LDS reads first, then the two stores
+            const f16_t *src0 = ht + m * 72 + c8, *src1 = ht + (BM + m) * 72 + c8;
+            if (vec) {
+                const u32x4_t v0 = *reinterpret_cast<const u32x4_t *>(src0);
+                u32x4_t v1 = v0;
+                if (two_out) v1 = *reinterpret_cast<const u32x4_t *>(src1);
+                *reinterpret_cast<u32x4_t *>(outs[0] + at) = v0;
+                if (two_out) *reinterpret_cast<u32x4_t *>(outs[1] + at) = v1;
+            } else {
+                for (int e = 0; e < 8 && c8 + e < ncols; ++e) {
+                    outs[0][at + e] = src0[e];
+                    if (two_out) outs[1][at + e] = src1[e];
                 }
             }
         }
