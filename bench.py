@@ -28,7 +28,7 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense 16-bit matrix cores (bf16 and fp16
 # separate profiling run of this benchmark: FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for the
 # library's 1 GiB copy_kernel.  A RECORDED figure (the counters cannot be read from inside this process): it is reported
 # with its source file, and only for the unmodified workload it was recorded on.
-RECORDED_TRAFFIC = {"llama7b": {"bytes": None, "source": "profiles/decode_attention_llama7b_hbm_traffic.md"}}
+RECORDED_TRAFFIC = {"llama7b": {"bytes": 537160 * 1024, "source": "profiles/decode_attention_llama7b_hbm_traffic.md"}}
 
 
 def kv_row_bytes(shape, block_scaled):
