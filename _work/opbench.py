@@ -89,12 +89,19 @@ def bench_attention(args):
     S = args.max_seq or pos + 129
     torch.manual_seed(0)
     q = torch.randn((B, Hq, hd), device=dev)
-    kc = torch.randn((B, Hkv, S, hd), device=dev).to(torch.float16)
-    vc = torch.randn((B, Hkv, S, hd), device=dev).to(torch.float16)
+    ks = vs = None
+    if args.block_scaled:
+        kc = torch.randint(-32767, 32768, (B, Hkv, S, hd), device=dev, dtype=torch.int32).to(torch.int16)
+        vc = torch.randint(-32767, 32768, (B, Hkv, S, hd), device=dev, dtype=torch.int32).to(torch.int16)
+        ks = torch.rand((B, Hkv, S), device=dev) / 32767 + 1e-5
+        vs = torch.rand((B, Hkv, S), device=dev) / 32767 + 1e-5
+    else:
+        kc = torch.randn((B, Hkv, S, hd), device=dev).to(torch.float16)
+        vc = torch.randn((B, Hkv, S, hd), device=dev).to(torch.float16)
     d_len = torch.full((1,), pos, dtype=torch.int32, device=dev)
     out = torch.empty((B, Hq * hd), dtype=torch.float16, device=dev)
     ws = torch.empty((max(1, ops.decode_attention_ws_floats(B, Hq, hd, args.nsplit)),), device=dev)
-    us = _time(lambda: ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, args.nsplit), args.iters)
+    us = _time(lambda: ops.decode_attention(q, kc, vc, d_len, out, ws, B, Hq, Hkv, hd, S, args.nsplit, kscale=ks, vscale=vs), args.iters)
     kv = 2.0 * B * Hkv * (pos + 1) * hd * 2
     print(f"decode attention B={B} heads={Hq}/{Hkv} hd={hd} position={pos} nsplit={args.nsplit}: {us:.1f} us  KV {kv / us / 1e3:.0f} GB/s")
 
@@ -123,6 +130,7 @@ def main():
     a.add_argument("--max-seq", type=int, default=0)
     a.add_argument("--nsplit", type=int, default=1)
     a.add_argument("--iters", type=int, default=20)
+    a.add_argument("--block-scaled", action="store_true")
     args = ap.parse_args()
     if args.what == "gemm":
         if args.epilogue == "swiglu" and args.terms == 2:

@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--mbs", type=int, default=1,
                     help="generation only: run the batch as this many sequential portions through rl_gen_generate on a "
                          "generator (and KV cache) of batch/mbs sequences; not the headline configuration")
+    ap.add_argument("--precision", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="rl_gen_shape.precision: 0 = the library's default for the shape (the benchmark; what the parity tests "
+                         "cover at full depth), 1-3 force a level (1 is faster and misses the parity bar at full depth)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (copy_kernel: a known-size kernel to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -116,7 +119,7 @@ def main():
     wl = PRESETS[args.workload]
     shape = wl.shape.with_layers(args.layers) if args.layers else wl.shape
     B, P, G = wl.batch, wl.prompt_len, wl.gen_len
-    level, bs = precision_level(shape), kv_block_scaled(shape)
+    level, bs = precision_level(shape, args.precision), kv_block_scaled(shape, args.precision)
 
     t0 = time.perf_counter()
     W = make_weights(shape, wl.index, device=dev)
@@ -124,7 +127,8 @@ def main():
     if args.mbs < 1 or B % args.mbs:
         print(f"bench.py: --mbs must divide the batch ({B})", file=sys.stderr)
         sys.exit(2)
-    gen = Generator(shape, W, B // args.mbs, P + G, pack_gate_up={"auto": None, "on": True, "off": False}[args.pack_gate_up])
+    gen = Generator(shape, W, B // args.mbs, P + G, pack_gate_up={"auto": None, "on": True, "off": False}[args.pack_gate_up],
+                    precision=args.precision)
     gen.set_graph(not args.no_graph)
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
@@ -225,6 +229,7 @@ def main():
                                f"V{shape.vocab}, batch {B}, prompt {P}, generate {G}",
                    "global_batch": B, "prompt_len": P, "gen_len": G, "hip_graph": not args.no_graph,
                    "packed_gate_up_layers": gen.packed_gate_up_layers(), "precision_level": level,
+                   "precision_forced": args.precision != 0,
                    "kv_cache": "int16 rows with one fp32 scale each" if bs else "IEEE half rows"},
         "phases": phases, "setup_s": setup_s,
     }
@@ -241,7 +246,7 @@ def main():
         att_bytes = sum(attention_bytes(shape, B, t, bs) for t in range(P, P + G - 1)) * shape.n_layers
         if att["launches"] > 0 and att["ms"] > 0:
             achieved = att_bytes / (att["ms"] * 1e-3) / 1e9
-            rec = RECORDED_TRAFFIC.get(args.workload) if not args.layers else None
+            rec = RECORDED_TRAFFIC.get(args.workload) if not args.layers and not args.precision else None
             out["roofline"] = {"kernel": "decode_attention", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                                "traffic": rec["bytes"] if rec else None,

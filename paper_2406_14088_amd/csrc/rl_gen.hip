@@ -361,7 +361,10 @@ bool swiglu_project(rl_gen *h, const f16_t *A, const f16_t *A_lo, f16_t *out_lo,
     a.rows[0] = h->s.ffn; a.rows[1] = h->s.ffn; a.rows[2] = 0;
     a.out = h->act(); a.ldc = h->s.ffn; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_SWIGLU;
     Scope sc(h, RL_GEN_K_GEMM_GATE_UP, st);
-    if (M <= kSkinnyMaxM) { launch_gemm_skinny(a, st); return false; }
+    // the row-major kernel for few rows takes one activation term and writes one output term: with a second input term
+    // the tile kernel (both terms in one contraction) serves every row count
+    if (M <= kSkinnyMaxM && !A_lo) { launch_gemm_skinny(a, st); return false; }
+    a.A_lo = A_lo;
     a.out_lo = out_lo;
     launch_gemm_tiled(a, st);
     return out_lo != nullptr;
@@ -499,16 +502,18 @@ void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, co
     a.W[0] = h->lm_head; a.W[1] = nullptr; a.W[2] = nullptr;
     a.rows[0] = s.vocab; a.rows[1] = 0; a.rows[2] = 0;
     a.out = logits + (size_t)b0 * s.vocab; a.ldc = s.vocab; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
+    // low term of the final-norm output: behind the nb * T rows of h, or behind the nb gathered rows
+    const f16_t *A_lo = !lo ? nullptr : rows ? rows + (size_t)nb * s.hidden : a.A + (size_t)nb * T * s.hidden;
     Scope sc(h, RL_GEN_K_GEMM_LM_HEAD, st);
     if (h->packed && nb <= kSkinnyMaxM) {
         PackedGemmArgs q;
-        q.A = a.A; q.A_lo = lo && !rows ? a.A + (size_t)nb * T * s.hidden : nullptr; q.lda = a.lda; q.M = nb; q.K = s.hidden;
+        q.A = a.A; q.A_lo = A_lo; q.lda = a.lda; q.M = nb; q.K = s.hidden;
         q.P[0] = h->p_lm_head; q.P[1] = nullptr; q.P[2] = nullptr;
         q.rows[0] = s.vocab; q.rows[1] = 0; q.rows[2] = 0;
         q.out = a.out; q.ldc = s.vocab; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_F32; q.nb = 1; q.rows_per_wg = 128; q.depth = 2;
         launch_gemm_packed(q, st);
-    } else if (nb <= kSkinnyMaxM) launch_gemm_skinny(a, st);
-    else launch_gemm_tiled(a, st);
+    } else if (nb <= kSkinnyMaxM && !A_lo) launch_gemm_skinny(a, st);
+    else { a.A_lo = A_lo; launch_gemm_tiled(a, st); }
 }
 
 void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, int32_t *next, hipStream_t st) {
@@ -903,8 +908,11 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
             {
                 Scope sc(h, RL_GEN_K_MISC, st);
                 launch_gather_last_rows(h->h(), h->d_lens(), b0, nb, T, h->s.hidden, h->attn(), st);
+                if (lo)
+                    launch_gather_last_rows(h->h() + (size_t)nb * T * h->s.hidden, h->d_lens(), b0, nb, T, h->s.hidden,
+                                            h->attn() + (size_t)nb * h->s.hidden, st);
             }
-            lm_head(h, nb, T, b0, lg, st, h->attn());
+            lm_head(h, nb, T, b0, lg, st, h->attn(), lo);
         } else {
             lm_head(h, nb, T, b0, lg, st, nullptr, lo);
         }
@@ -978,7 +986,7 @@ int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, fl
     if (rows_fit < 1) { set_err(h, "rl_gen_logprobs: workspace holds no logit row"); return RL_GEN_E_CAPACITY; }
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
         int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
-        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
+        const bool lo = run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
         const int M = nb * T;
         for (int m0 = 0; m0 < M; m0 += (int)rows_fit) {
             int mm = M - m0 < rows_fit ? M - m0 : (int)rows_fit;
@@ -989,7 +997,8 @@ int rl_gen_logprobs(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, fl
             a.out = h->part(); a.ldc = s.vocab; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
             {
                 Scope sc(h, RL_GEN_K_GEMM_LM_HEAD, st);
-                if (mm <= kSkinnyMaxM) launch_gemm_skinny(a, st);
+                if (lo) a.A_lo = a.A + (size_t)M * s.hidden;
+                if (mm <= kSkinnyMaxM && !lo) launch_gemm_skinny(a, st);
                 else launch_gemm_tiled(a, st);
             }
             Scope sc(h, RL_GEN_K_MISC, st);

@@ -198,13 +198,18 @@ def test_width_of_the_papers_llama3_34b_row_reduced_depth():
     check(s, 7, 2, 12, 3)
 
 
-@pytest.mark.parametrize("case", ["tiny", "7b_width", "chunked_head"])
+@pytest.mark.parametrize("case", ["tiny", "7b_width", "chunked_head", "tiny_level3", "7b_width_level3_row_major"])
 def test_inference_call_logprobs(case):
     """rl_gen_logprobs: one forward pass over whole sequences, log-probability of every following token.
     |d logp| <= |d logit_target| + |d logsumexp| <= 2 * LOGIT_TOL (the logits themselves are within LOGIT_TOL)."""
     from paper_2406_14088_amd import Generator
-    if case == "tiny":
+    kw = {}
+    if case.startswith("tiny"):
         shape, idx, B, T = PRESETS["tiny"].shape, 1, 5, 90       # 450 rows: the large-M projection kernel serves the LM head
+        if case == "tiny_level3":                                # the LM head takes the final norm's low term as well
+            kw = {"precision": 3}
+    elif case == "7b_width_level3_row_major":                    # 72 rows and no fragment-order copies: tile kernel, two terms
+        shape, idx, B, T, kw = PRESETS["llama7b"].shape.with_layers(2), 2, 3, 24, {"precision": 3, "packed": False}
     elif case == "7b_width":
         shape, idx, B, T = PRESETS["llama7b"].shape.with_layers(2), 2, 3, 24
     else:   # more rows than one block of the LM head holds (vocabulary large against the workspace)
@@ -217,7 +222,7 @@ def test_inference_call_logprobs(case):
     om = orc.OracleModel(shape, orc.weights_to_numpy(W), B, T)
     want = orc.sequence_logprobs(om.forward_all(toks.numpy()), toks.numpy())
     om.close()
-    gen = Generator(shape, Wg, B, T + 1)
+    gen = Generator(shape, Wg, B, T + 1, **kw)
     got = gen.logprobs(toks.to(DEV))
     torch.cuda.synchronize()
     gn = np64(got)
@@ -227,7 +232,7 @@ def test_inference_call_logprobs(case):
     assert err <= 2 * LOGIT_TOL
     # the call leaves the cache as a prefill of the same tokens would: a decode step may follow
     assert gen.state() == (B, T)
-    ref = Generator(shape, Wg, B, T + 1)
+    ref = Generator(shape, Wg, B, T + 1, **kw)
     ref.prefill(toks.to(DEV))
     nxt = torch.zeros((B,), dtype=torch.int32, device=DEV)
     a, _ = gen.decode_step(nxt)
@@ -459,7 +464,8 @@ def test_per_kernel_timing_counts_every_launch():
     gen.close()
 
 
-def test_ragged_prompts_against_the_oracle():
+@pytest.mark.parametrize("precision,packed", [(0, True), (3, True), (3, False)])
+def test_ragged_prompts_against_the_oracle(precision, packed):
     """Prompts of different lengths in one batch: every sequence must behave exactly as if it were alone (the oracle runs
     them one by one at their own lengths), through prefill and teacher-forced decode steps at per-sequence positions."""
     from paper_2406_14088_amd import Generator
@@ -469,7 +475,7 @@ def test_ragged_prompts_against_the_oracle():
     W = make_weights(shape, 41, device="cpu")
     Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
     toks = make_prompts(Workload("t", 41, shape, B, T, 0))
-    gen = Generator(shape, Wg, B, T + steps)
+    gen = Generator(shape, Wg, B, T + steps, precision=precision, packed=packed)
     g_logits, g_next = gen.prefill_ragged(toks.to(DEV), torch.tensor(lens, dtype=torch.int32, device=DEV))
     torch.cuda.synchronize()
     assert gen.read_state() == (lens, [0] * B)
@@ -493,7 +499,7 @@ def test_ragged_prompts_against_the_oracle():
         assert gen.read_state()[0] == [n + i + 1 for n in lens]
     for om in oms:
         om.close()
-    step(f"  ragged batch: max-abs logit error {worst:.3e}")
+    step(f"  ragged batch, level {precision}, packed={packed}: max-abs logit error {worst:.3e}")
     assert worst <= LOGIT_TOL
     gen.close()
 
