@@ -400,8 +400,8 @@ static void dispatch_da(const float *q, f16_t *kc, f16_t *vc, const int32_t *d_l
 void launch_decode_attention(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride, f16_t *out,
                              float *ws, int B, int Hq, int Hkv, int hd, int S, int nsplit, hipStream_t st, KvMap map,
                              const int32_t *d_done, f16_t *out_lo) {
-    // many query heads per cache row of halves: the matrix-core kernel (16-bit block-scaled rows are read by the vector kernel)
-    if (!map.kscale && decode_attention_gqa_supported(Hq, Hkv, hd)) {
+    // many query heads per cache row: the matrix-core kernel (half and block-scaled rows)
+    if (decode_attention_gqa_takes(Hq, Hkv, hd, map.kscale != nullptr)) {
         launch_decode_attention_gqa(q, kc, vc, d_len, len_stride, out, ws, B, Hq, Hkv, S, nsplit, st, map, d_done, out_lo);
         return;
     }

@@ -16,6 +16,12 @@
 // stored XOR-permuted so that both read patterns are bank-conflict free: K rows as 16-byte operand fragments (piece ^ row),
 // V transposed through 16-bit reads (piece ^ 4 * (row / 4)).  Rows past the end are cut off by the buffer descriptor
 // (they arrive as zeros) and masked to weight 0.
+//
+// I16: the cache rows are block-scaled 16-bit fixed point (int16 elements times one fp32 scale per row, KvMap::kscale /
+// vscale).  An int16 n is split exactly into two integer-valued halves, n = (n & ~31) + (n & 31): a multiple of 32 of
+// magnitude <= 32768 and an integer in [0, 31] are both IEEE half values, so K and V enter the matrix cores without any
+// rounding at the price of a second matrix instruction per operand.  The row scales travel with their tile (two more
+// copy instructions into the stage) and are applied to the scores (K) and to the probabilities (V).
 #include "kernels.h"
 
 #define GA_TILE 16                 // cache rows per tile
@@ -27,13 +33,17 @@
 
 #define GA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
+#define GA_SCALE_BYTES 512              // I16: K scales at +0, V scales at +256 behind the two tiles of a stage (16 floats each in use)
+
 typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float ga_ror8(float v) {  // lane l of a row of 16 receives lane (l + 8) % 16
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xf, 0xf, true));
 }
 
-template <bool PAGED>
+template <bool PAGED, bool I16>
 __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *__restrict__ q, const f16_t *__restrict__ kc,
                                                                   const f16_t *__restrict__ vc,
                                                                   const int32_t *__restrict__ d_len, f16_t *__restrict__ out,
@@ -42,7 +52,8 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
                                                                   int len_stride, KvMap map,
                                                                   const int32_t *__restrict__ d_done) {
     constexpr int HD = 128;
-    __shared__ __attribute__((aligned(1024))) unsigned char ring[GA_STAGES * GA_STAGE_BYTES];
+    constexpr int STAGE = GA_STAGE_BYTES + (I16 ? GA_SCALE_BYTES : 0);
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[GA_STAGES * STAGE];
     const int lane = threadIdx.x;
     const int c = lane & 15, j = lane >> 4;  // column (head and term) / group of 4 keys
     const int g = Hq / Hkv;
@@ -79,8 +90,8 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float v = col_ok ? x[e] : 0.f;  // columns without a head contribute nothing
-                const _Float16 hi = (_Float16)v;
-                const _Float16 lo = (_Float16)(v - (float)hi);
+                const _Float16 hi = (_Float16)__builtin_amdgcn_fmed3f(v, -65504.f, 65504.f);  // saturating, like every half here
+                const _Float16 lo = (_Float16)__builtin_amdgcn_fmed3f(v - (float)hi, -65504.f, 65504.f);
                 qf[s][e] = c < 8 ? hi : lo;
             }
         }
@@ -112,9 +123,20 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
         }
         __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<f16_t *>(kc + first * HD), 0, rows * (HD * 2), 0x00020000);
         __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<f16_t *>(vc + first * HD), 0, rows * (HD * 2), 0x00020000);
+        if (I16) {  // the scales of the tile's rows: lane r < rows fetches scale r, every other lane is out of range (zero)
+            __amdgpu_buffer_rsrc_t ksr = __builtin_amdgcn_make_buffer_rsrc(map.kscale + first, 0, rows * 4, 0x00020000);
+            __amdgpu_buffer_rsrc_t vsr = __builtin_amdgcn_make_buffer_rsrc(map.vscale + first, 0, rows * 4, 0x00020000);
+            unsigned char *sd = ring + stage * STAGE + GA_STAGE_BYTES;
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ksr, GA_LDS_PTR(sd), 4, lane * 4, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vsr, GA_LDS_PTR(sd + 256), 4, lane * 4, 0, 0, 0);
+#else
+            (void)sd; (void)ksr; (void)vsr;
+#endif
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            unsigned char *kd = ring + stage * GA_STAGE_BYTES + i * 1024;
+            unsigned char *kd = ring + stage * STAGE + i * 1024;
             unsigned char *vd = kd + GA_TILE_BYTES;
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass does not know this builtin
             if (stream_kv) {  // the only reader of these rows: non-temporal copies (they stream faster than cached ones)
@@ -153,8 +175,24 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
         f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            f16x8_t kf = *reinterpret_cast<const f16x8_t *>(st + kaddr[s]);
-            sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[s], sacc, 0, 0, 0);
+            if (I16) {
+                const u32x4_t kw = *reinterpret_cast<const u32x4_t *>(st + kaddr[s]);
+                const u32x4_t wh = {kw.x & 0xFFE0FFE0u, kw.y & 0xFFE0FFE0u, kw.z & 0xFFE0FFE0u, kw.w & 0xFFE0FFE0u};
+                const u32x4_t wl = {kw.x & 0x001F001Fu, kw.y & 0x001F001Fu, kw.z & 0x001F001Fu, kw.w & 0x001F001Fu};
+                const f16x8_t kh = __builtin_convertvector(__builtin_bit_cast(s16x8_t, wh), f16x8_t);
+                const f16x8_t kl = __builtin_convertvector(__builtin_bit_cast(s16x8_t, wl), f16x8_t);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qf[s], sacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qf[s], sacc, 0, 0, 0);
+            } else {
+                f16x8_t kf = *reinterpret_cast<const f16x8_t *>(st + kaddr[s]);
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, qf[s], sacc, 0, 0, 0);
+            }
+        }
+        // I16: the scales of keys 4 j + 0..3 (K) and of the same rows of V
+        f32x4_t ksc = {1.f, 1.f, 1.f, 1.f}, vsc = {1.f, 1.f, 1.f, 1.f};
+        if (I16) {
+            ksc = *reinterpret_cast<const f32x4_t *>(st + GA_STAGE_BYTES + 16 * j);
+            vsc = *reinterpret_cast<const f32x4_t *>(st + GA_STAGE_BYTES + 256 + 16 * j);
         }
         // register i: key 4 j + i of the tile, column c.  High and low term of a head sit 8 columns apart.
         float sc[4];
@@ -162,6 +200,7 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float v = sacc[i] + ga_ror8(sacc[i]);
+            if (I16) v *= ksc[i];
             const int key = j0 + tile * GA_TILE + 4 * j + i;
             sc[i] = key < j1 ? v * scale : -INFINITY;
             tmax = fmaxf(tmax, sc[i]);
@@ -179,24 +218,65 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
                 for (int i = 0; i < 4; ++i) oacc[t][i] *= alpha;
         }
         f16x4_t pf;
+        float wref = 1.f;  // I16: what the weights of this tile are measured in
+        if (I16) {
+            // The row scale of V rides on the probability: weight = p * scale.  A scale is of order 1e-5 .. 1e-4, below the
+            // normal range of a half, so the tile's weights are normalised by their largest (per column) before they are
+            // split into half terms, and the tile's product is accumulated times that factor.
+            float w[4];
+            float wmax = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float p = __expf(sc[i] - mnew);  // 0 for keys past the end
-            den += p;
-            const _Float16 hi = (_Float16)p;
-            pf[i] = c < 8 ? hi : (_Float16)(p - (float)hi);
+            for (int i = 0; i < 4; ++i) {
+                const float p = __expf(sc[i] - mnew);  // 0 for keys past the end
+                den += p;
+                w[i] = p * vsc[i];
+                wmax = fmaxf(wmax, w[i]);
+            }
+            wmax = fmaxf(wmax, __shfl_xor(wmax, 16, 64));
+            wmax = fmaxf(wmax, __shfl_xor(wmax, 32, 64));
+            const float inv = wmax > 0.f ? 1.0f / wmax : 0.f;
+            wref = wmax;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float x = w[i] * inv;  // in [0, 1]
+                const _Float16 hi = (_Float16)x;
+                pf[i] = c < 8 ? hi : (_Float16)(x - (float)hi);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = __expf(sc[i] - mnew);  // 0 for keys past the end
+                den += p;
+                const _Float16 hi = (_Float16)p;
+                pf[i] = c < 8 ? hi : (_Float16)(p - (float)hi);
+            }
         }
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            f16x4_t vf;
+            if (I16) {
+                s16x4_t nh, nl;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) vf[i] = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t *>(st + vaddr[t] + i * 256));
-            oacc[t] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf, pf, oacc[t], 0, 0, 0);
+                for (int i = 0; i < 4; ++i) {
+                    const uint16_t n = *reinterpret_cast<const uint16_t *>(st + vaddr[t] + i * 256);
+                    nh[i] = (short)(n & 0xFFE0u);
+                    nl[i] = (short)(n & 0x001Fu);
+                }
+                f32x4_t part = {0.f, 0.f, 0.f, 0.f};
+                part = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_convertvector(nh, f16x4_t), pf, part, 0, 0, 0);
+                part = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_convertvector(nl, f16x4_t), pf, part, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) oacc[t][i] = fmaf(wref, part[i], oacc[t][i]);
+            } else {
+                f16x4_t vf;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) vf[i] = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t *>(st + vaddr[t] + i * 256));
+                oacc[t] = __builtin_amdgcn_mfma_f32_16x16x16f16(vf, pf, oacc[t], 0, 0, 0);
+            }
         }
     };
 
-    // tile t has landed once at most the GA_STAGES - 2 younger tiles (8 copy instructions each) are pending
-    constexpr int YOUNGER = 8 * (GA_STAGES - 2);
+    // tile t has landed once at most the GA_STAGES - 2 younger tiles (8 copy instructions each, 10 with scales) are pending
+    constexpr int YOUNGER = (I16 ? 10 : 8) * (GA_STAGES - 2);
     static_assert(YOUNGER < 64, "vmcnt is a 6-bit counter");
     for (int tile0 = 0; tile0 < ntiles; tile0 += GA_STAGES) {
 #pragma unroll
@@ -206,7 +286,7 @@ __global__ __launch_bounds__(64) void decode_attention_gqa_kernel(const float *_
                 __builtin_amdgcn_sched_barrier(0);
                 issue_tile(tile0 + k + GA_STAGES - 1, (k + GA_STAGES - 1) % GA_STAGES);  // into the stage consumed one step ago
                 __builtin_amdgcn_sched_barrier(0);
-                consume(tile0 + k, ring + k * GA_STAGE_BYTES);
+                consume(tile0 + k, ring + k * STAGE);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -255,10 +335,20 @@ bool decode_attention_gqa_supported(int Hq, int Hkv, int hd) {
     return g == 4 || (g >= 8 && g % 8 == 0);
 }
 
-int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S) {
+// Block-scaled rows are served when 8 heads share a cache row; with 4 the integer conversions outweigh what the matrix
+// cores save and the vector kernel is faster (32/8 heads, 1536 cached rows, batch 128: 190-200 us here).
+bool decode_attention_gqa_takes(int Hq, int Hkv, int hd, bool block_scaled) {
+    return decode_attention_gqa_supported(Hq, Hkv, hd) && (!block_scaled || Hq / Hkv >= 8);
+}
+
+int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S, bool block_scaled) {
     const int g = Hq / Hkv;
     long items = (long)B * Hkv * (g < 8 ? 1 : g / 8);
-    int s = (int)((1024 + items - 1) / items);  // one wavefront per SIMD over 256 compute units, at least
+    // one wavefront per SIMD over 256 compute units, at least; block-scaled rows: three per two SIMDs (the conversions make a
+    // tile's critical path longer, and six wavefronts per compute unit is what the LDS ring allows: batch 64, 64/8 heads, 1536
+    // rows: 126 us with 2 splits, 101 with 3, 123 with 4)
+    const long want = block_scaled ? 1536 : 1024;
+    int s = (int)((want + items - 1) / items);
     int cap = S / 128;                          // but keep >= 128 positions per split at full length
     if (s > cap) s = cap;
     if (s > 16) s = 16;
@@ -272,9 +362,12 @@ void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *v
     if (B <= 0) return;
     const int g = Hq / Hkv;
     const int items = B * Hkv * (g < 8 ? 1 : g / 8) * nsplit;
-    if (map.table)
-        decode_attention_gqa_kernel<true><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, out_lo, ws, Hq, Hkv, S, nsplit, len_stride, map, d_done);
-    else
-        decode_attention_gqa_kernel<false><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, out_lo, ws, Hq, Hkv, S, nsplit, len_stride, KvMap(), d_done);
+#define GA_LAUNCH(PAGEDV, I16V) \
+    decode_attention_gqa_kernel<PAGEDV, I16V><<<items, 64, 0, st>>>(q, kc, vc, d_len, out, out_lo, ws, Hq, Hkv, S, nsplit, len_stride, map, d_done)
+    if (map.table && map.kscale) GA_LAUNCH(true, true);
+    else if (map.table) GA_LAUNCH(true, false);
+    else if (map.kscale) GA_LAUNCH(false, true);
+    else GA_LAUNCH(false, false);
+#undef GA_LAUNCH
     if (nsplit > 1) launch_decode_attention_merge(ws, out, B, Hq, 128, nsplit, st, out_lo);
 }

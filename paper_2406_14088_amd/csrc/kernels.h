@@ -146,7 +146,8 @@ void launch_decode_attention_fused(const float *qkv, int nsplit_qkv, size_t spli
 // ---- attention_decode_gqa.hip: the same operation on the matrix cores for grouped-query shapes (head_dim 128 and 4, 8, 16,
 // ... query heads per kv head); launch_decode_attention forwards to it when decode_attention_gqa_supported().
 bool decode_attention_gqa_supported(int Hq, int Hkv, int hd);
-int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S);
+bool decode_attention_gqa_takes(int Hq, int Hkv, int hd, bool block_scaled);  // supported, and faster than the vector kernel
+int decode_attention_gqa_default_splits(int B, int Hq, int Hkv, int S, bool block_scaled);
 void launch_decode_attention_gqa(const float *q, const f16_t *kc, const f16_t *vc, const int32_t *d_len, int len_stride,
                                  f16_t *out, float *ws, int B, int Hq, int Hkv, int S, int nsplit, hipStream_t st,
                                  KvMap map = KvMap(), const int32_t *d_done = nullptr, f16_t *out_lo = nullptr);

@@ -100,8 +100,8 @@ int page_shift_of(int page_size) {
 }
 
 int attn_splits(const rl_gen_shape *s) {
-    if (!kv_block_scaled(s) && decode_attention_gqa_supported(s->n_heads, s->n_kv_heads, s->head_dim))
-        return decode_attention_gqa_default_splits(s->max_batch, s->n_heads, s->n_kv_heads, s->max_seq);
+    if (decode_attention_gqa_takes(s->n_heads, s->n_kv_heads, s->head_dim, kv_block_scaled(s)))
+        return decode_attention_gqa_default_splits(s->max_batch, s->n_heads, s->n_kv_heads, s->max_seq, kv_block_scaled(s));
     int g = s->n_heads / s->n_kv_heads;
     int gt = decode_attention_group(g);
     return decode_attention_default_splits(s->max_batch, s->n_kv_heads * (g / gt), s->max_seq);

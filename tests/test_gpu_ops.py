@@ -628,6 +628,53 @@ def test_paged_decode_attention_equals_contiguous(ops, hd, Hq, Hkv, nsplit, page
         assert (np.abs(on[b, u] - want) <= 0.5 * F16_EPS * np.abs(want) * 1.02 + 3e-5).all()
 
 
+@pytest.mark.parametrize("hd,Hq,Hkv,nsplit,page", [(128, 4, 4, 1, 16), (128, 8, 2, 3, 64), (64, 4, 2, 2, 32), (128, 16, 2, 1, 128),
+                                                   (128, 32, 4, 2, 16)])
+def test_paged_decode_attention_over_block_scaled_rows(ops, hd, Hq, Hkv, nsplit, page):
+    """Block-scaled rows (int16 elements, one fp32 scale per row) through shuffled page lists: bit-equal to the contiguous
+    cache for the vector kernel and for the matrix-core kernel of grouped-query shapes, and the oracle's attention."""
+    B, S = 5, 320
+    lens = [0, 15, 16, 200, 319]
+    kc, ks, kn = _random_block_scaled((B, Hkv, S, hd), 211)
+    vc, vs, vn = _random_block_scaled((B, Hkv, S, hd), 212)
+    q = randn_f32((B, Hq * hd), 213, std=0.7)
+    d_len = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    pps = (S + page - 1) // page
+    n_pages = B * pps + 3
+    perm = np.random.default_rng(214).permutation(n_pages)[: B * pps].reshape(B, pps)
+    # rows a sequence has not reached hold the largest elements and NaN scales: they must not reach the result
+    k_pool = torch.full((n_pages, Hkv, page, hd), 32767, dtype=torch.int16, device=DEV)
+    v_pool = torch.full((n_pages, Hkv, page, hd), 32767, dtype=torch.int16, device=DEV)
+    ks_pool = torch.full((n_pages, Hkv, page), float("nan"), dtype=torch.float32, device=DEV)
+    vs_pool = torch.full((n_pages, Hkv, page), float("nan"), dtype=torch.float32, device=DEV)
+    for b in range(B):
+        for i in range(pps):
+            lo, hi = i * page, min((i + 1) * page, S)
+            n = min(hi, lens[b] + 1) - lo
+            if n <= 0:
+                continue
+            k_pool[perm[b, i], :, :n] = kc[b, :, lo: lo + n]
+            v_pool[perm[b, i], :, :n] = vc[b, :, lo: lo + n]
+            ks_pool[perm[b, i], :, :n] = ks[b, :, lo: lo + n]
+            vs_pool[perm[b, i], :, :n] = vs[b, :, lo: lo + n]
+    table = torch.tensor(perm, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(ops.decode_attention_ws_floats(B, Hq, hd, nsplit), 1), dtype=torch.float32, device=DEV)
+    ref = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ops.decode_attention(q, kc, vc, d_len, ref, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=1, kscale=ks, vscale=vs)
+    got = torch.zeros((B, Hq * hd), dtype=torch.float16, device=DEV)
+    ops.decode_attention_paged(q, k_pool, v_pool, table, page, d_len, got, ws, B, Hq, Hkv, hd, S, nsplit, len_stride=1,
+                               kscale=ks_pool, vscale=vs_pool)
+    torch.cuda.synchronize()
+    assert not torch.isnan(got).any() and not torch.isnan(ref).any()
+    assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+    g = Hq // Hkv
+    on = np64(got).reshape(B, Hq, hd)
+    for b in (1, 3):
+        for u in range(Hq):
+            want = orc.attend(np64(q).reshape(B, Hq, hd)[b, u], kn[b, u // g, : lens[b] + 1], vn[b, u // g, : lens[b] + 1])
+            assert (np.abs(on[b, u] - want) <= 0.5 * F16_EPS * np.abs(want) * 1.02 + 3e-5).all()
+
+
 def test_paged_decode_attention_rejects_bad_page_sizes(ops):
     t = torch.zeros((1, 64), dtype=torch.int32, device=DEV)
     x = torch.zeros((4096,), dtype=torch.float16, device=DEV)
@@ -827,18 +874,18 @@ def test_decode_attention_block_scaled_rows_and_two_term_output(ops, hd, Hq, Hkv
             assert (np.abs(on[b, u] + ln[b, u] - ref) <= 2e-5 * (1 + np.abs(ref))).all(), (b, u, np.abs(on[b, u] + ln[b, u] - ref).max())
 
 
-@pytest.mark.parametrize("kind", ["vector", "matrix", "block_scaled"])
+@pytest.mark.parametrize("kind", ["vector", "matrix", "block_scaled", "matrix_block_scaled"])
 @pytest.mark.parametrize("length", [2047, 4095])
 def test_decode_attention_at_long_context_lengths(ops, kind, length):
     """Cached lengths of the long-context workload (prompt 2048, generation to 4096 positions): the vector kernel (one query
-    head per kv head, IEEE half rows), the matrix-core kernel (8 query heads per kv head) and the vector kernel over
+    head per kv head, IEEE half rows), the matrix-core kernel (8 query heads per kv head) and both kernels over
     block-scaled rows, each split over the sequence as the generator splits it, against the oracle row by row."""
     hd, S = 128, 4096
-    B, Hq, Hkv = (2, 4, 4) if kind != "matrix" else (2, 16, 2)
+    B, Hq, Hkv = (2, 16, 2) if kind.startswith("matrix") else (2, 4, 4)
     nsplit = 4
     step(f"decode attention, {kind} kernel, {length + 1} cached rows")
     q = randn_f32((B, Hq * hd), 180, std=1.5)
-    if kind == "block_scaled":
+    if kind.endswith("block_scaled"):
         kc, ks, kn = _random_block_scaled((B, Hkv, S, hd), 181)
         vc, vs, vn = _random_block_scaled((B, Hkv, S, hd), 182)
     else:
