@@ -68,11 +68,10 @@ typedef struct {
                            *  2  as 1, and the attention output enters the O projection and the SwiGLU output the down
                            *     projection as two-term sums; the KV cache rows are 16-bit block-scaled fixed point
                            *     (int16 elements, one fp32 scale per position and kv head: about 15 significant bits at the
-                           *     same 2 bytes per element) for shapes with fewer than 4 query heads per kv head, IEEE half
-                           *     for grouped-query shapes (whose decode attention runs on the matrix cores)
+                           *     same 2 bytes per element); grouped-query shapes that the matrix-core decode attention
+                           *     serves (head_dim 128 with 4 or a multiple of 8 query heads per kv head) keep IEEE half
                            *  3  as 2, and the FFN-norm output enters gate/up and the final-norm output the LM head as
-                           *     two-term sums; block-scaled KV cache for every shape (grouped-query decode attention then
-                           *     runs on the vector units)
+                           *     two-term sums; block-scaled KV cache for every shape
                            *  0  automatic: 3 for more than 32 layers or hidden above 4096, else 2 */
 } rl_gen_shape;
 

@@ -129,7 +129,8 @@ int rl_op_rope_append(const float *qkv, int32_t nsplit, size_t split_stride, int
  * nsplit >= 1 splits the rows over wavefronts; ws must then hold rl_op_decode_attention_ws_floats
  * floats (may be NULL for nsplit == 1).  hd in {64, 128}.  d_done: DEVICE int32 [B] or NULL; sequences with a non-zero
  * flag (ended, Section 2.1) are skipped: their cache is not read and their rows of out are left as they are.
- * With kscale / vscale the vector kernel serves every head grouping (the matrix-core kernel reads half rows only). */
+ * With kscale / vscale the matrix-core kernel serves head_dim 128 with a multiple of 8 query heads per kv head, the vector
+ * kernel everything else. */
 int rl_op_decode_attention(const float *q, const uint16_t *kc, const uint16_t *vc, const int32_t *d_len, int32_t len_stride,
                            uint16_t *out, float *ws, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd, int32_t S, int32_t nsplit,
                            const int32_t *d_done, const float *kscale, const float *vscale, uint16_t *out_lo, void *hip_stream);

@@ -85,8 +85,8 @@ int prec_level(const rl_gen_shape *s) {
     if (s->precision != 0) return s->precision;
     return s->n_layers > 32 || s->hidden > 4096 ? 3 : 2;
 }
-// Block-scaled cache rows are read by the vector attention kernel; grouped-query shapes keep half rows for the matrix-core
-// kernel unless the level asks for the more exact cache everywhere.
+// Level 2 keeps half rows for the grouped-query shapes that the matrix-core decode attention serves (with 4 heads per kv
+// head block-scaled rows would move them to the slower vector kernel); level 3 asks for the more exact cache everywhere.
 bool kv_block_scaled(const rl_gen_shape *s) {
     const int p = prec_level(s);
     return p >= 3 || (p == 2 && !decode_attention_gqa_supported(s->n_heads, s->n_kv_heads, s->head_dim));

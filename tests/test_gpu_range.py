@@ -135,10 +135,11 @@ def test_appended_rows_beyond_the_half_limit(ops, block_scaled):
     assert n_over > 0
 
 
-def test_decode_attention_over_rows_at_the_half_limit(ops):
+@pytest.mark.parametrize("Hq,Hkv", [(4, 2), (16, 2)])
+def test_decode_attention_over_rows_at_the_half_limit(ops, Hq, Hkv):
     """Half cache rows holding +-65504 and queries of order 100: scores of order 1e8, a one-hot softmax; the output is a
-    cache row, finite, and the oracle's."""
-    B, Hq, Hkv, hd, S, length = 2, 4, 2, 128, 160, 150
+    cache row, finite, and the oracle's (vector kernel, and the matrix-core kernel of grouped-query shapes)."""
+    B, hd, S, length = 2, 128, 160, 150
     q = randn_f32((B, Hq * hd), 930, std=100.0)
     kc = randn_f16((B, Hkv, S, hd), 931, std=3e4)          # torch's conversion gives inf beyond the range: bring those back
     vc = randn_f16((B, Hkv, S, hd), 932, std=3e4)
@@ -154,7 +155,7 @@ def test_decode_attention_over_rows_at_the_half_limit(ops):
         qn, kn, vn = np64(q).reshape(B, Hq, hd), np64(kc), np64(vc)
         for b in range(B):
             for u in range(Hq):
-                ref = orc.attend(qn[b, u], kn[b, u // 2, : length + 1], vn[b, u // 2, : length + 1])
+                ref = orc.attend(qn[b, u], kn[b, u // (Hq // Hkv), : length + 1], vn[b, u // (Hq // Hkv), : length + 1])
                 check_terms(out[b].reshape(Hq, hd)[u], out_lo[b].reshape(Hq, hd)[u], ref, 1e-6 * np.abs(ref).max() + 1e-6)
 
 
@@ -209,15 +210,15 @@ def test_generation_with_large_activations_inside_the_range(precision, packed):
 
 @pytest.mark.parametrize("packed", [True, False])
 @pytest.mark.parametrize("precision", [1, 2, 3])
-@pytest.mark.parametrize("which", ["attention", "ffn", "all"])
+@pytest.mark.parametrize("which", ["attention", "ffn", "all", "all_grouped_query"])
 def test_generation_beyond_the_range_stays_finite(which, precision, packed):
     """Gains of 2^17 on the attention norms (normalised rows, q, k and v past 65504), on the FFN norms (SwiGLU outputs of order
     1e9), on everything: outputs saturate, so the oracle (no limit) is no reference any more; what must hold is what the
     header promises: finite logits, tokens that are the argmax of those logits, no fault."""
-    shape = ModelShape(3, 512, 4, 4, 128, 1384, 2048)
+    shape = ModelShape(3, 1024, 8, 1, 128, 1000, 2048) if which == "all_grouped_query" else ModelShape(3, 512, 4, 4, 128, 1384, 2048)
     big = 2.0 ** 17
     W = scaled_gains(make_weights(shape, 32, device="cpu", std=0.05), attn=big if which != "ffn" else 1.0,
-                     ffn=big if which != "attention" else 1.0, final=big if which == "all" else 1.0)
+                     ffn=big if which != "attention" else 1.0, final=big if which.startswith("all") else 1.0)
     seen = [0]
 
     def compare(gl, gn, ol):
