@@ -18,5 +18,16 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+def build_sanitize_check() -> str:
+    """orc.c + sanitize_check.c as one executable under AddressSanitizer and UndefinedBehaviorSanitizer (CPU only).
+    The sanitizer runtime is linked statically so that it does not depend on the order of preloaded libraries."""
+    exe = os.path.join(HERE, "orc_sanitize_check")
+    cmd = ["gcc", "-std=c99", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-fopenmp", "-Wall", "-Wextra", "-o", exe,
+           SRC, os.path.join(HERE, "sanitize_check.c"), "-lm"]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 if __name__ == "__main__":
     print(build())

@@ -54,6 +54,37 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitize_check() -> str:
+    """csrc/rl_gen.hip -- the host logic of the C ABI: validation, sizing, page planning, sequencing -- compiled with
+    AddressSanitizer and UndefinedBehaviorSanitizer on the host side, plus csrc/host_sanitize_check.cpp, linked into one
+    executable; the kernel launchers of the other sources come from the regular librl_gen.so (built first).  CPU only: the
+    check launches nothing.  Takes a few seconds."""
+    if not os.path.exists(LIB):
+        build(force=False)
+    out_dir = os.path.join(OBJ_DIR, "host_sanitize")
+    os.makedirs(out_dir, exist_ok=True)
+    inc = os.path.join(os.path.dirname(HERE), "include")
+    san = ["-O1", "-g", "-std=c++17", "-fno-omit-frame-pointer", "-fno-sanitize-recover=all"]
+    host_san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined"]
+    rl = os.path.join(out_dir, "rl_gen.o")
+    chk = os.path.join(out_dir, "host_sanitize_check.o")
+    exe = os.path.join(out_dir, "host_sanitize_check")
+    cmds = [
+        ["hipcc", "--offload-arch=gfx950", *san, *host_san, "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-c", os.path.join(CSRC, "rl_gen.hip"), "-o", rl],
+        # plain C++ (hipcc would treat it as HIP): the host compiler that hipcc drives
+        ["/opt/rocm/lib/llvm/bin/clang++", *san, "-fsanitize=address", "-fsanitize=undefined", "-I", inc, "-c",
+         os.path.join(CSRC, "host_sanitize_check.cpp"), "-o", chk],
+        ["hipcc", "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-Wno-option-ignored", "-o", exe, rl, chk,
+         LIB, "-Wl,-rpath," + HERE],
+    ]
+    for cmd in cmds:
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("failed: " + " ".join(cmd) + "\n" + r.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     import sys
     print(build(force="--incremental" not in sys.argv, verbose=True))

@@ -120,3 +120,17 @@ def test_page_bytes_and_page_planning_on_the_host(binding):
     cs = binding.RlGenShape.from_model(PRESETS["tiny"].shape, 4, 32)
     out = C.c_void_p()
     assert L.rl_gen_create_paged(C.byref(cs), None, None, 0, None, 0, 16, C.byref(out)) == -1
+
+
+def test_host_logic_under_address_and_undefined_behaviour_sanitizers():
+    """The host side of the C ABI (validation, arena sizing up to byte counts that need 64 bits, page planning into
+    exactly-sized tables, argument checks of the entry points) in a build with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the host code; nothing in it needs a GPU."""
+    import os
+    import subprocess
+    from paper_2406_14088_amd import build as lib_build
+    exe = lib_build.build_host_sanitize_check()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120,
+                       env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0"})   # the HIP runtime's own start-up allocations are not ours
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "host sanitize check: ok" in r.stdout

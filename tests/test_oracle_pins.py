@@ -455,3 +455,16 @@ def test_sampling_by_inversion_pins():
     assert np.abs(counts / 20000 - p).max() <= 1.5 / 20000
     # invalid input
     assert orc.sample(x, 0.0, 0.5) == -1 and orc.sample(np.array([0.0, np.nan]), 1.0, 0.5) == -1
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers():
+    """Every entry point of orc.c driven on tiny, exactly-sized models (grouped-query, both weight formats, both rotary
+    styles, no layers, refusals) in a build with AddressSanitizer, LeakSanitizer and UndefinedBehaviorSanitizer: any access
+    out of bounds, leak on an error path or undefined arithmetic aborts the run."""
+    import subprocess
+    from oracle import build as orc_build
+    exe = orc_build.build_sanitize_check()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120,
+                       env={**os.environ, "ASAN_OPTIONS": "detect_leaks=1:abort_on_error=0", "OMP_NUM_THREADS": "4"})
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "orc sanitize check: ok" in r.stdout
