@@ -199,6 +199,20 @@ int rl_gen_set_eos(rl_gen_t *h, int32_t eos);
  * stream. */
 int rl_gen_read_state(rl_gen_t *h, int32_t *lens, int32_t *done, void *hip_stream);
 
+/* Batch compaction after early termination (Appendix A: prompt and generation lengths vary; Section 2.1: a sequence is
+ * generated until it terminates).  Sequences that have produced the end token (rl_gen_set_eos) leave the batch; the others
+ * move up, in their order, to rows 0 .. n-1, and every later rl_gen_decode_step works on n rows: an ended sequence then
+ * costs nothing any more.  kept: HOST int32 [current batch], receives the old row of every new row (ascending);
+ * n_kept: HOST, receives n.  tokens: DEVICE int32 [current batch] or NULL -- a buffer of per-sequence values (typically the
+ * `next` of the last step) permuted in place along with the batch, so that it can feed the next step.  Synchronises the
+ * stream (it has to read the end flags).  A contiguous cache moves the rows of every sequence that changes its slot
+ * (bytes of its tokens so far); a paged cache moves nothing: the page lists move, the caller's own copy of them has to follow
+ * `kept`, and the pages of the dropped sequences are the caller's again.  With n == current batch nothing changes; with
+ * n == 0 the generator is left without sequences, as after rl_gen_reset.  Per-sequence results of later steps are
+ * the same as without compaction (rows of a batch do not interact).
+ * Errors: RL_GEN_E_NULL, RL_GEN_E_STATE (no sequences), RL_GEN_E_CAPACITY (more than 8192 sequences), RL_GEN_E_HIP. */
+int rl_gen_compact(rl_gen_t *h, int32_t *tokens, int32_t *kept, int32_t *n_kept, void *hip_stream);
+
 /* One decode step (Section 2.1: input the single latest token of each sequence, produce the next).
  * tokens: DEVICE int32 [B] with B as given to the last prefill -- the caller chooses what to feed
  * (the previous `next` buffer for free-running greedy generation, or reference tokens for teacher

@@ -77,6 +77,7 @@ def lib():
         "rl_gen_prefill_ragged": (C.c_int, [vp, vp, vp, i32, i32, vp, vp, vp]),
         "rl_gen_set_eos": (C.c_int, [vp, i32]),
         "rl_gen_read_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
+        "rl_gen_compact": (C.c_int, [vp, vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "rl_gen_decode_step": (C.c_int, [vp, vp, vp, vp, vp]),
         "rl_gen_generate": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
         "rl_gen_logprobs": (C.c_int, [vp, vp, i32, i32, vp, vp]),
@@ -124,7 +125,7 @@ def lib():
 
 EXPORTED_SYMBOLS = (
     "rl_gen_validate_shape", "rl_gen_param_count", "rl_gen_kv_bytes", "rl_gen_precision_level", "rl_gen_kv_block_scaled", "rl_gen_work_bytes", "rl_gen_create", "rl_gen_page_bytes", "rl_gen_create_paged", "rl_gen_pool_pages", "rl_gen_set_block_table", "rl_gen_plan_pages", "rl_gen_packed_bytes", "rl_gen_packed_bytes_full", "rl_gen_prefers_packed_gate_up", "rl_gen_packed_gate_up_layers",
-    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_logprobs", "rl_gen_values",
+    "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_compact", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
     "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_gemm_packed_swiglu_halves", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_noalloc", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
@@ -338,6 +339,14 @@ class Generator:
         lens, done = (C.c_int32 * max(b, 1))(), (C.c_int32 * max(b, 1))()
         self._check(lib().rl_gen_read_state(self._h, lens, done, _stream()), "rl_gen_read_state")
         return list(lens)[:b], list(done)[:b]
+
+    def compact(self, tokens=None):
+        """Drops the ended sequences from the batch (rl_gen_compact).  tokens: optional int32 GPU tensor [B], permuted in place;
+        returns the old row of every remaining row as a list (the first len(list) entries of `tokens` are the new batch)."""
+        b, _ = self.state()
+        kept, n = (C.c_int32 * max(b, 1))(), C.c_int32(0)
+        self._check(lib().rl_gen_compact(self._h, _ptr(tokens), kept, C.byref(n), _stream()), "rl_gen_compact")
+        return list(kept)[: n.value]
 
     def decode_step(self, tokens, logits=None, next_tokens=None, want_logits=True):
         """tokens: int32 GPU tensor [B].  Returns (logits or None, next)."""

@@ -448,6 +448,65 @@ void launch_copy_strided(const void *src, int64_t src_stride, void *dst, int64_t
                                                           reinterpret_cast<uint32_t *>(dst), dst_stride, n);
 }
 
+// Batch compaction: row i of the compacted batch is row kept[i] of the old one (kept ascending, kept[i] >= i).  One
+// workgroup; every thread reads all of its values before anyone writes, so the arrays are permuted in place.
+#define CS_THREADS 1024
+#define CS_PER_THREAD 8
+__global__ __launch_bounds__(CS_THREADS) void compact_state_kernel(int32_t *lens, int32_t *done, int32_t *tokens,
+                                                                 const int32_t *__restrict__ kept, int n) {
+    int32_t l[CS_PER_THREAD], t[CS_PER_THREAD];
+#pragma unroll
+    for (int k = 0; k < CS_PER_THREAD; ++k) {
+        const int i = threadIdx.x + k * CS_THREADS;
+        l[k] = 0; t[k] = 0;
+        if (i < n) {
+            const int src = kept[i];
+            l[k] = lens[src];
+            if (tokens) t[k] = tokens[src];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < CS_PER_THREAD; ++k) {
+        const int i = threadIdx.x + k * CS_THREADS;
+        if (i < n) {
+            lens[i] = l[k];
+            done[i] = 0;  // only sequences that have not ended are kept
+            if (tokens) tokens[i] = t[k];
+        }
+    }
+}
+int compact_state_max_batch() { return CS_THREADS * CS_PER_THREAD; }
+void launch_compact_state(int32_t *lens, int32_t *done, int32_t *tokens, const int32_t *kept, int n, hipStream_t st) {
+    if (n <= 0) return;
+    compact_state_kernel<<<1, CS_THREADS, 0, st>>>(lens, done, tokens, kept, n);
+}
+
+// One sequence's cache rows (contiguous cache) move to another sequence slot: for every (layer, K|V, kv head) the first
+// `rows` rows of slab src are copied to slab dst -- 16-bit elements, and the fp32 row scales when the rows are block-scaled.
+// Source and destination slabs are different sequences, so the ranges never overlap.
+__global__ __launch_bounds__(256) void kv_move_kernel(f16_t *kv, float *scales, size_t area_elems, int Hkv, int S, int hd, int src,
+                                                      int dst, int rows) {
+    const int area = blockIdx.y;               // 2 * layer + (0: K, 1: V)
+    const int kvh = blockIdx.x;
+    f16_t *base = kv + (size_t)area * area_elems;
+    const u32x4_t *from = reinterpret_cast<const u32x4_t *>(base + ((size_t)src * Hkv + kvh) * S * hd);
+    u32x4_t *to = reinterpret_cast<u32x4_t *>(base + ((size_t)dst * Hkv + kvh) * S * hd);
+    const size_t n16 = (size_t)rows * hd / 8;  // hd is 64 or 128: whole 16-byte pieces
+    for (size_t i = threadIdx.x; i < n16; i += 256) to[i] = from[i];
+    if (scales) {
+        const size_t area_rows = area_elems / hd;
+        const float *sf = scales + (size_t)area * area_rows + ((size_t)src * Hkv + kvh) * S;
+        float *sd = scales + (size_t)area * area_rows + ((size_t)dst * Hkv + kvh) * S;
+        for (int i = threadIdx.x; i < rows; i += 256) sd[i] = sf[i];
+    }
+}
+void launch_kv_move(f16_t *kv, float *scales, size_t area_elems, int n_areas, int Hkv, int S, int hd, int src, int dst, int rows,
+                    hipStream_t st) {
+    if (rows <= 0 || n_areas <= 0 || src == dst) return;
+    kv_move_kernel<<<dim3(Hkv, n_areas), 256, 0, st>>>(kv, scales, area_elems, Hkv, S, hd, src, dst, rows);
+}
+
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { p[0] = v; }
 void launch_set_i32(int32_t *p, int32_t v, hipStream_t st) { set_i32_kernel<<<1, 1, 0, st>>>(p, v); }
 

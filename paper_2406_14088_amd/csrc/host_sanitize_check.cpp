@@ -92,6 +92,7 @@ int main() {
         CHECK(rl_gen_set_eos(nullptr, 1) == RL_GEN_E_NULL && rl_gen_set_graph(nullptr, 1) == RL_GEN_E_NULL);
         CHECK(rl_gen_set_sampling(nullptr, 1.0f, nullptr) == RL_GEN_E_NULL && rl_gen_set_qkv_terms(nullptr, 1) == RL_GEN_E_NULL);
         CHECK(rl_gen_read_state(nullptr, nullptr, nullptr, nullptr) == RL_GEN_E_NULL);
+        CHECK(rl_gen_compact(nullptr, nullptr, nullptr, nullptr, nullptr) == RL_GEN_E_NULL);
         CHECK(rl_gen_state(nullptr, nullptr, nullptr) == RL_GEN_E_NULL && rl_gen_reset(nullptr) == RL_GEN_E_NULL);
         CHECK(rl_gen_profile(nullptr, 1) == RL_GEN_E_NULL && rl_gen_profile_read(nullptr, nullptr, nullptr, nullptr) == RL_GEN_E_NULL);
         rl_gen_destroy(nullptr);

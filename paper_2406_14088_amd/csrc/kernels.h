@@ -28,6 +28,12 @@ void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *le
 // lens[b] = clamp(lens_in[b], 1, T) (T if lens_in is NULL), done[b] = 0
 void launch_init_state(int32_t *lens, int32_t *done, int B, const int32_t *lens_in, int T, hipStream_t st);
 // out[i, :] = h[i * T + clamp(lens[b0 + i], 1, T) - 1, :]  (half rows of d elements, d % 8 == 0)
+// Batch compaction (ended sequences leave the batch): the per-sequence state and, optionally, a token buffer permuted in
+// place (row i <- row kept[i], kept ascending), and one sequence's cache rows copied to another slot of a contiguous cache.
+int compact_state_max_batch();
+void launch_compact_state(int32_t *lens, int32_t *done, int32_t *tokens, const int32_t *kept, int n, hipStream_t st);
+void launch_kv_move(f16_t *kv, float *scales, size_t area_elems, int n_areas, int Hkv, int S, int hd, int src, int dst, int rows,
+                    hipStream_t st);
 void launch_gather_last_rows(const f16_t *h, const int32_t *lens, int b0, int nb, int T, int d, f16_t *out, hipStream_t st);
 // next[b] = smallest v with cumulative softmax(logits[b] / temperature) above u[b] (-1 on NaN); bookkeeping as launch_argmax.
 void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *lens,

@@ -53,7 +53,7 @@ constexpr int kMinPage = 16, kMaxPage = 4096;  // positions per page of a paged 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct WorkPlan {
-    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, draws, rope, state, table, total;
+    size_t x, h, part, qf32, qbf, attn, act, attn_ws, logits, next, draws, rope, state, table, kept, total;
     size_t part_elems;  // floats in the split-K partial area
     int rows;  // activation rows the workspace can hold
 };
@@ -137,6 +137,7 @@ WorkPlan plan_work(const rl_gen_shape *s) {
     p.rope = take((size_t)s->max_seq * s->head_dim * 4);
     p.state = take(((size_t)2 * s->max_batch + 16) * 4);  // per-sequence lengths, per-sequence end flags, a constant 0
     p.table = take((size_t)s->max_batch * ceil_div(s->max_seq, kMinPage) * 4);  // page lists of a paged cache
+    p.kept = take((size_t)s->max_batch * 4);   // batch compaction: old row of every kept sequence
     p.total = off;
     return p;
 }
@@ -182,6 +183,7 @@ struct rl_gen {
     std::vector<int32_t> host_len;   // HOST: upper bound of each sequence's length
     std::vector<int32_t> host_done;  // HOST: end flags as last read back
     std::vector<int32_t> table_img;  // HOST: image of the device page lists
+    std::vector<int32_t> kept_img;   // HOST: source of the last compaction's copy to the device
     int eos;                 // end token (rl_gen_set_eos), -1: none
     float temperature;       // > 0: the next token is sampled (rl_gen_set_sampling); else greedy
     const float *sample_u;   // DEVICE [max_batch] uniform draws, borrowed, refreshed by the caller between steps
@@ -209,6 +211,7 @@ struct rl_gen {
     int32_t *d_done() const { return d_lens() + s.max_batch; }
     int32_t *d_zero() const { return d_lens() + 2 * s.max_batch; }
     int32_t *d_table() const { return reinterpret_cast<int32_t *>(work + wp.table); }
+    int32_t *d_kept() const { return reinterpret_cast<int32_t *>(work + wp.kept); }
     size_t area_elems() const {  // one layer's K (or V) area
         return page_shift ? ((size_t)n_pages * s.n_kv_heads << page_shift) * s.head_dim
                           : (size_t)s.max_batch * s.n_kv_heads * s.max_seq * s.head_dim;
@@ -964,6 +967,63 @@ int rl_gen_read_state(rl_gen_t *h, int32_t *lens, int32_t *done, void *hip_strea
     if (lens && hipMemcpyAsync(lens, h->d_lens(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return RL_GEN_E_HIP;
     if (done && hipMemcpyAsync(done, h->d_done(), (size_t)h->B * 4, hipMemcpyDeviceToHost, st) != hipSuccess) return RL_GEN_E_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) { set_err(h, "rl_gen_read_state: stream error"); return RL_GEN_E_HIP; }
+    return RL_GEN_OK;
+}
+
+int rl_gen_compact(rl_gen_t *h, int32_t *tokens, int32_t *kept, int32_t *n_kept, void *hip_stream) {
+    if (!h) return RL_GEN_E_NULL;
+    if (!kept || !n_kept) { set_err(h, "rl_gen_compact: NULL argument"); return RL_GEN_E_NULL; }
+    if (h->B <= 0) { set_err(h, "rl_gen_compact: no sequences (prefill first)"); return RL_GEN_E_STATE; }
+    if (h->B > compact_state_max_batch()) {
+        set_err(h, "rl_gen_compact: batches of up to %d sequences are served, this one has %d", compact_state_max_batch(), h->B);
+        return RL_GEN_E_CAPACITY;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+    const int B = h->B;
+    std::vector<int32_t> lens((size_t)B), done((size_t)B);
+    if (hipMemcpyAsync(lens.data(), h->d_lens(), (size_t)B * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemcpyAsync(done.data(), h->d_done(), (size_t)B * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) { set_err(h, "rl_gen_compact: stream error"); return RL_GEN_E_HIP; }
+    int n = 0;
+    for (int b = 0; b < B; ++b)
+        if (!done[b]) kept[n++] = b;
+    *n_kept = n;
+    if (n == B) {  // nobody has ended; the host-side bounds of a paged cache become exact on the way
+        if (h->page_shift) { h->host_len = lens; h->host_done = done; }
+        return RL_GEN_OK;
+    }
+    if (n == 0) {  // everybody has ended: an empty batch, as before the first prefill
+        h->B = 0; h->len = 0;
+        return RL_GEN_OK;
+    }
+    h->kept_img.assign(kept, kept + n);  // the copy source must outlive the copy
+    bool ok = hipMemcpyAsync(h->d_kept(), h->kept_img.data(), (size_t)n * 4, hipMemcpyHostToDevice, st) == hipSuccess;
+    if (h->page_shift) {
+        // a paged cache moves no rows: the page lists of the kept sequences move up
+        const size_t stride = (size_t)h->table_stride;
+        std::vector<int32_t> img(h->table_img.size(), 0), cap((size_t)n), hl((size_t)n);
+        for (int i = 0; i < n; ++i) {
+            memcpy(&img[(size_t)i * stride], &h->table_img[(size_t)kept[i] * stride], stride * 4);
+            cap[(size_t)i] = h->cap[(size_t)kept[i]];
+            hl[(size_t)i] = lens[(size_t)kept[i]];
+        }
+        h->table_img.swap(img);
+        h->cap.swap(cap);
+        h->host_len.swap(hl);
+        h->host_done.assign((size_t)n, 0);
+        ok = ok && hipMemcpyAsync(h->d_table(), h->table_img.data(), h->table_img.size() * 4, hipMemcpyHostToDevice, st) == hipSuccess;
+    } else {
+        // contiguous cache: the rows of sequence kept[i] move to slot i, in ascending i (kept[i] >= i and ascending, so a
+        // slot is never overwritten before it has been read); launches on one stream run in order
+        for (int i = 0; i < n; ++i)
+            launch_kv_move(h->kv, h->kv_i16 ? h->scales() : nullptr, h->area_elems(), 2 * h->s.n_layers, h->s.n_kv_heads, h->s.max_seq,
+                           h->s.head_dim, kept[i], i, lens[(size_t)kept[i]], st);
+    }
+    launch_compact_state(h->d_lens(), h->d_done(), tokens, h->d_kept(), n, st);
+    if (!ok || hipStreamSynchronize(st) != hipSuccess) { set_err(h, "rl_gen_compact: stream error"); return RL_GEN_E_HIP; }
+    int rc = check_hip(h, "rl_gen_compact");
+    if (rc != RL_GEN_OK) return rc;
+    h->B = n;
     return RL_GEN_OK;
 }
 

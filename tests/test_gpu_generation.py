@@ -822,6 +822,136 @@ def test_end_token_stops_a_sequence(graph):
     assert done[b_stop] == 1
 
 
+@pytest.mark.parametrize("graph", [False, True])
+@pytest.mark.parametrize("cache", ["contiguous", "paged"])
+def test_batch_compaction_after_the_end_token(cache, graph):
+    """rl_gen_compact: ended sequences leave the batch, the others move up (cache rows of a contiguous cache, page lists of
+    a paged one), later steps run on fewer rows -- and every sequence still produces exactly the tokens of the uncompacted
+    run, each of them the argmax of logits that are the oracle's (teacher-forced on those tokens) within the tolerance."""
+    from paper_2406_14088_amd import Generator, RlGenError
+    shape = ModelShape(2, 256, 4, 2, 64, 688, 48)                 # a small vocabulary: the end token comes up often
+    B, P, G, page = 14, 9, 20, 16
+    W = make_weights(shape, 61, device="cpu", std=0.05)
+    Wg = {k: ([t.to(DEV) for t in v] if isinstance(v, list) else v.to(DEV)) for k, v in W.items()}
+    prompts = make_prompts(Workload("t", 61, shape, B, P, G)).to(DEV)
+
+    def make():
+        if cache == "paged":
+            cap = [P + G] * B
+            n_pages = sum((c + page - 1) // page for c in cap)
+            gen = Generator(shape, Wg, B, P + G, page_size=page, n_pages=n_pages)
+            gen.set_block_table(_shuffled_pages(cap, page, n_pages, 62), cap)
+        else:
+            gen = Generator(shape, Wg, B, P + G)
+        gen.set_graph(graph)
+        return gen
+
+    # the free run picks the end token: what most sequences emit somewhere, at different steps
+    gen = make()
+    _, t = gen.prefill(prompts)
+    free = [t.clone()]
+    for _ in range(G - 1):
+        free.append(gen.decode_step(free[-1])[1].clone())
+    free = torch.stack(free).cpu().numpy()                         # [G, B]
+    gen.close()
+    first = {}
+    for v in range(shape.vocab):
+        hit = [int(np.nonzero(free[:, b] == v)[0][0]) if (free[:, b] == v).any() else -1 for b in range(B)]
+        first[v] = hit
+    eos = max(first, key=lambda v: (len({h for h in first[v] if h >= 0}), sum(h >= 0 for h in first[v])))
+    ends = first[eos]
+    assert sum(h >= 0 for h in ends) >= 4 and len({h for h in ends if h >= 0}) >= 3, ends
+    step(f"  end token {eos}: sequences end after {ends} tokens (-1: never)")
+
+    # uncompacted run with the end token
+    gen = make()
+    gen.set_eos(eos)
+    _, t = gen.prefill(prompts)
+    plain = [t.clone()]
+    for _ in range(G - 1):
+        plain.append(gen.decode_step(plain[-1])[1].clone())
+    plain = torch.stack(plain).cpu().numpy()
+    gen.close()
+
+    # compacted run: compaction after every second step; rows[i] = original sequence of batch row i
+    gen = make()
+    gen.set_eos(eos)
+    lg, t = gen.prefill(prompts)
+    rows = list(range(B))
+    tokens = {b: [] for b in range(B)}
+    logits = {b: [] for b in range(B)}
+    sizes = []
+    for g in range(G):
+        tn, ln = t.cpu().numpy(), np64(lg)
+        for i, b in enumerate(rows):
+            tokens[b].append(int(tn[i]))
+            logits[b].append(ln[i])
+        if g == G - 1 or not rows:
+            break
+        if g % 2 == 1:
+            kept = gen.compact(t)
+            rows = [rows[k] for k in kept]
+            assert gen.state()[0] == len(rows)
+            lens, done = gen.read_state()
+            assert done == [0] * len(rows) and lens == [P + len(tokens[b]) - 1 for b in rows]
+            t = t[: len(rows)].contiguous()
+        sizes.append(len(rows))
+        if not rows:
+            with pytest.raises(RlGenError):
+                gen.decode_step(torch.zeros((1,), dtype=torch.int32, device=DEV))
+            break
+        lg, t = gen.decode_step(t)
+    torch.cuda.synchronize()
+    gen.close()
+    assert sizes[-1] < B, sizes                                    # the batch did shrink
+    step(f"  batch sizes over the steps: {sizes}")
+
+    worst = 0.0
+    Wn = orc.weights_to_numpy(W)
+    for b in range(B):
+        n = len(tokens[b])
+        assert tokens[b] == [int(v) for v in plain[:n, b]], b      # the same tokens as without compaction ...
+        if n < G:
+            assert tokens[b][-1] == eos or ends[b] < 0             # ... and a sequence only leaves once it has ended
+            assert (plain[n:, b] == eos).all()
+        om = orc.OracleModel(shape, Wn, 1, P + G)
+        ol, _ = om.prefill(prompts[b: b + 1].cpu().numpy())
+        n = tokens[b].index(eos) + 1 if eos in tokens[b] else n    # what an ended sequence returns afterwards is not compared
+        for k in range(n):
+            worst = max(worst, np.abs(logits[b][k] - ol[0]).max())
+            assert tokens[b][k] == orc.argmax(logits[b][k])
+            if k + 1 < n:
+                ol, _ = om.decode_step(np.array([tokens[b][k]], np.int32))
+        om.close()
+    step(f"  max-abs logit error of the compacted run {worst:.3e}")
+    assert worst <= LOGIT_TOL
+
+
+def test_batch_compaction_when_nobody_or_everybody_has_ended():
+    from paper_2406_14088_amd import Generator, RlGenError
+    wl = PRESETS["tiny"]
+    W = make_weights(wl.shape, wl.index, device=DEV)
+    prompts = make_prompts(wl, device=DEV)[:1].contiguous()
+    gen = Generator(wl.shape, W, 1, wl.max_seq)
+    with pytest.raises(RlGenError):
+        gen.compact()                                              # no sequences yet
+    _, t = gen.prefill(prompts)
+    assert gen.compact(t) == [0] and gen.state() == (1, wl.prompt_len)        # nobody has ended: nothing changes
+    _, t2 = gen.decode_step(t)
+    gen.set_eos(int(t2.item()))                                    # what the sequence is about to repeat ends it
+    gen.reset()
+    _, t = gen.prefill(prompts)
+    _, t2 = gen.decode_step(t)
+    assert gen.read_state() == ([wl.prompt_len + 1], [1])
+    assert gen.compact(t2) == [] and gen.state() == (0, 0)         # everybody has ended: an empty generator
+    with pytest.raises(RlGenError):
+        gen.decode_step(t2)
+    gen.set_eos(-1)
+    _, t3 = gen.prefill(prompts)                                   # ... that takes a new batch
+    assert torch.equal(t3, t)
+    gen.close()
+
+
 def test_error_paths_on_device():
     from paper_2406_14088_amd import Generator, RlGenError
     wl = PRESETS["tiny"]
