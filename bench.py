@@ -66,11 +66,12 @@ def decode_kernel_models(shape, B, P, G, block_scaled, level):
         "gemm_o": {"bytes": d * qd * 2 + t_o * M * qd * 2 + M * d * 4, "flops": 2 * t_o * M * d * qd},
         "gemm_gate_up": {"bytes": 2 * F * d * 2 + t_ffn * M * d * 2 + t_act * M * F * 2, "flops": 2 * t_ffn * M * 2 * F * d},
         "gemm_down": {"bytes": d * F * 2 + t_act * M * F * 2 + M * d * 4, "flops": 2 * t_act * M * d * F},
-        "gemm_lm_head": {"bytes": V * d * 2 + t_ffn * M * d * 2 + M * V * 4, "flops": 2 * t_ffn * M * V * d},
+        # free-running greedy decode: the LM head leaves per-pass candidates (value + column per 128 columns) instead of logits
+        "gemm_lm_head": {"bytes": V * d * 2 + t_ffn * M * d * 2 + M * ((V + 127) // 128) * 8, "flops": 2 * t_ffn * M * V * d},
         "add_rmsnorm": {"bytes": M * d * (4 + 4 + 2 * 2), "flops": 0},
         "rope_append": {"bytes": M * nqkv * 4 + M * qd * 4 + 2 * M * Hkv * kv_row_bytes(shape, block_scaled), "flops": 0},
         "decode_attention": {"bytes": att, "flops": 0},
-        "argmax": {"bytes": M * V * 4, "flops": 0},
+        "argmax": {"bytes": M * ((V + 127) // 128) * 8 + M * 4, "flops": 0},
         "embed": {"bytes": M * d * (2 + 4), "flops": 0},
     }
 

@@ -102,6 +102,17 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
                       int64_t ldc, size_t split_stride, int32_t splits, int32_t epilogue, int32_t nb, int32_t rows_per_wg,
                       int32_t depth, uint16_t *out_lo, void *hip_stream);
 
+/* The LM head with the greedy choice fused into it (the last two steps of a decode step as the generator runs them):
+ * logits[M, V] = (A + A_lo) P^T as rl_op_gemm_packed computes it for one matrix, and next[m] = the column of the largest
+ * logit of row m -- lowest column on ties, -1 if the row holds a NaN -- i.e. exactly rl_op_argmax of those logits.  The
+ * projection's epilogue leaves the best logit of every pass of 128 columns in ws, a second small kernel picks among them:
+ * the logits are never re-read, and with logits == NULL never written.  A f16 [M, K] (row stride lda), A_lo f16 or NULL,
+ * P f16 fragment-order copy of the [V, K] matrix, logits fp32 (row stride ldc >= V) or NULL, next int32 [M], ws fp32
+ * [rl_op_lm_head_argmax_ws_floats(M, V)]; all DEVICE.  RL_GEN_E_SHAPE when the packed matrix reaches 3.75 GB. */
+size_t rl_op_lm_head_argmax_ws_floats(int32_t M, int32_t V);
+int rl_op_lm_head_argmax(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P, int32_t V, int32_t M, int32_t K,
+                         float *logits, int64_t ldc, float *ws, int32_t *next, void *hip_stream);
+
 /* Fused gate/up projection of few rows from fragment-order copies, the two 64-wide halves of every 128-wide K chunk on
  * separate wavefronts: out[M, F] (DEVICE half, row stride ldc) = silu(A Pg^T) * (A Pu^T), A DEVICE half [M, K] with row stride lda,
  * Pg and Pu = rl_op_pack_weights of the gate and up matrices [F, K].  The sums are formed in the order of rl_op_gemm's kernel 1 with

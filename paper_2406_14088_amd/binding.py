@@ -101,6 +101,8 @@ def lib():
         "rl_op_packed_weight_bytes": (sz, [i32, i32]),
         "rl_op_pack_weights": (C.c_int, [vp, vp, i32, i32, vp]),
         "rl_op_gemm_packed": (C.c_int, [vp, vp, i64, vp, vp, vp, i32, i32, i32, i32, i32, vp, i64, sz, i32, i32, i32, i32, i32, vp, vp]),
+        "rl_op_lm_head_argmax_ws_floats": (C.c_size_t, [i32, i32]),
+        "rl_op_lm_head_argmax": (C.c_int, [vp, vp, i64, vp, i32, i32, i32, vp, i64, vp, vp, vp]),
         "rl_op_build_rope_table": (C.c_int, [vp, i32, i32, f32]),
         "rl_op_rope_append": (C.c_int, [vp, i32, sz, i32, i32, i32, vp, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]),
         "rl_op_decode_attention": (C.c_int, [vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]),
@@ -128,7 +130,7 @@ EXPORTED_SYMBOLS = (
     "rl_gen_pack_weights", "rl_gen_prefill", "rl_gen_prefill_ragged", "rl_gen_set_eos", "rl_gen_read_state", "rl_gen_compact", "rl_gen_logprobs", "rl_gen_values",
     "rl_gen_decode_step", "rl_gen_generate", "rl_gen_set_graph", "rl_gen_set_qkv_terms", "rl_gen_set_sampling", "rl_gen_reset", "rl_gen_state", "rl_gen_destroy", "rl_gen_last_error",
     "rl_gen_profile", "rl_gen_profile_read", "rl_gen_kernel_class_name", "rl_op_embed", "rl_op_add_rmsnorm", "rl_op_gemm",
-    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_gemm_packed_swiglu_halves", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_noalloc", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
+    "rl_op_gemm_rope", "rl_op_gemm_tiled_packed", "rl_op_packed_weight_bytes", "rl_op_pack_weights", "rl_op_gemm_packed", "rl_op_lm_head_argmax_ws_floats", "rl_op_lm_head_argmax", "rl_op_gemm_packed_swiglu_halves", "rl_op_build_rope_table", "rl_op_rope_append", "rl_op_decode_attention", "rl_op_decode_attention_ws_floats", "rl_op_decode_attention_noalloc", "rl_op_decode_attention_paged", "rl_op_decode_attention_fused",
     "rl_op_prefill_attention", "rl_op_argmax", "rl_op_sample", "rl_op_logprob_gather", "rl_op_copy")
 
 
@@ -500,6 +502,18 @@ class _Ops:
         lda = A.stride(0) if lda is None else lda
         self._ck(lib().rl_op_gemm_packed(A.data_ptr(), _ptr(A_lo), lda, ptrs[0], ptrs[1], ptrs[2], rows[0], rows[1], rows[2], M, K,
                                          out.data_ptr(), ldc, split_stride, splits, epilogue, nb, rows_per_wg, depth, _ptr(out_lo), _stream()), "rl_op_gemm_packed")
+
+    def lm_head_argmax_ws_floats(self, M, V):
+        return int(lib().rl_op_lm_head_argmax_ws_floats(M, V))
+
+    def lm_head_argmax(self, A, P, V, K, nxt, logits=None, A_lo=None, ws=None):
+        import torch
+        M = A.shape[0]
+        if ws is None:
+            ws = torch.empty(max(int(lib().rl_op_lm_head_argmax_ws_floats(M, V)), 1), dtype=torch.float32, device=A.device)
+        self._ck(lib().rl_op_lm_head_argmax(A.data_ptr(), _ptr(A_lo), A.stride(0), P.data_ptr(), V, M, K, _ptr(logits),
+                                            logits.stride(0) if logits is not None else V, ws.data_ptr(), nxt.data_ptr(), _stream()),
+                 "rl_op_lm_head_argmax")
 
     def build_rope_table(self, tab, max_seq, head_dim, base):
         self._ck(lib().rl_op_build_rope_table(tab.data_ptr(), max_seq, head_dim, base), "rl_op_build_rope_table")

@@ -251,6 +251,37 @@ void launch_argmax(const float *logits, int B, int V, int32_t *next, int32_t *le
     argmax_kernel<<<B, AM_THREADS, 0, st>>>(logits, V, next, lens, done, eos);
 }
 
+// The greedy token from per-tile candidates (written by the LM-head projection's epilogue): one wavefront per row.
+__global__ __launch_bounds__(RL_WAVE) void argmax_merge_kernel(const float *__restrict__ cand_val, const int32_t *__restrict__ cand_idx,
+                                                               int tiles, int32_t *__restrict__ next, int32_t *lens, int32_t *done,
+                                                               int eos) {
+    const int b = blockIdx.x, t = threadIdx.x;
+    const float *cv = cand_val + (size_t)b * tiles;
+    const int32_t *ci = cand_idx + (size_t)b * tiles;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    int nan = 0;
+    for (int i = t; i < tiles; i += RL_WAVE) {
+        const float v = cv[i];
+        const int idx = ci[i];
+        nan |= (v != v);
+        if (v > bv || (v == bv && idx < bi)) { bv = v; bi = idx; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        nan |= __shfl_xor(nan, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (t == 0) next[b] = finish_token((nan || bi == 0x7fffffff) ? -1 : bi, b, lens, done, eos);
+}
+void launch_argmax_merge(const float *cand_val, const int32_t *cand_idx, int B, int tiles, int32_t *next, int32_t *lens, int32_t *done,
+                         int eos, hipStream_t st) {
+    if (B <= 0) return;
+    argmax_merge_kernel<<<B, RL_WAVE, 0, st>>>(cand_val, cand_idx, tiles, next, lens, done, eos);
+}
+
 // lens[b] = clamp(lens_in[b], 1, T) (T when lens_in is NULL), done[b] = 0: the sequence state a prefill leaves behind.
 __global__ void init_state_kernel(int32_t *lens, int32_t *done, int B, const int32_t *lens_in, int T) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;

@@ -97,6 +97,12 @@ struct PackedParams {
     f16_t *out_lo;       // SwiGLU epilogue, optional: second half term of the result, half(y - half(y)), same layout as out
     int64_t ldc;
     size_t split_stride;
+    // plain fp32 epilogue of a single matrix, optional (the LM head): per output row and per pass of 128 columns the largest
+    // value and its (lowest) column, NaN if the pass holds one -- cand_val / cand_idx [M][cand_tiles]; no_store: out is not written
+    float *cand_val;
+    int32_t *cand_idx;
+    int cand_tiles;
+    int no_store;
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t pk_rsrc(const void *p, uint32_t bytes) {
@@ -109,7 +115,9 @@ constexpr int pk_wgs_per_cu(int NB, int MT, int RC) { return pk_regs(NB, MT, RC)
 
 // SW: the weights are loaded non-temporally (one row block: every weight byte is used once).  A template parameter,
 // because the cache policy is an immediate of the load instruction and a branch per load would cut the loop into pieces.
-template <int NB, int TERMS, int MT, int RC, bool SW>
+// CAND: the plain-store epilogue also leaves the candidates of a greedy choice (PackedParams::cand_val); a template
+// parameter so that the projections that never ask for them keep their code and registers.
+template <int NB, int TERMS, int MT, int RC, bool SW, bool CAND = false>
 __global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_packed_kernel(PackedParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int BM = 32 * MT;               // activation rows per workgroup
@@ -311,11 +319,42 @@ __global__ __launch_bounds__(PK_THREADS, pk_wgs_per_cu(NB, MT, RC)) void gemm_pa
             __syncthreads();
             const int n_first = (ltile * NB + j) * 128;  // first weight row of this pass inside its matrix
             const int ncols = rows - n_first;             // valid columns (may exceed 128, may be <= 0)
+            if constexpr (CAND) {
+                // The greedy choice starts here: thread (row m, half hs) scans 64 of the row's 128 values of this pass in
+                // ascending columns, the two halves meet by one shuffle; the best value (lowest column on ties; NaN if the
+                // pass holds one) goes to the candidate list that argmax_merge finishes.
+                const int m = t >> 1, hs = t & 1;
+                float bv = -INFINITY;
+                int bi = 0x7fffffff;
+                int nan = 0;
+                if (m < BM) {
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int c = hs * 64 + 4 * k;
+                        const f32x4_t v = *reinterpret_cast<const f32x4_t *>(ct + m * PK_CT_STRIDE + c);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (c + e < ncols) {
+                                nan |= (v[e] != v[e]);
+                                if (v[e] > bv) { bv = v[e]; bi = n_first + c + e; }
+                            }
+                    }
+                }
+                const float ov = __shfl_xor(bv, 1, 64);
+                const int oi = __shfl_xor(bi, 1, 64);
+                nan |= __shfl_xor(nan, 1, 64);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                if (hs == 0 && m < Mloc) {
+                    const size_t at = (size_t)(m0 + m) * p.cand_tiles + (ltile * NB + j);
+                    p.cand_val[at] = nan ? __builtin_nanf("") : bv;
+                    p.cand_idx[at] = bi;
+                }
+            }
             // 32 lanes x float4 = one 512-byte output row; 8 rows per pass
 #pragma unroll
             for (int i = 0; i < BM / 8; ++i) {
                 int m = rr + 8 * i;
-                if (m < Mloc && c4 < ncols) {
+                if (m < Mloc && c4 < ncols && !(CAND && p.no_store)) {
                     f32x4_t v = *reinterpret_cast<const f32x4_t *>(ct + m * PK_CT_STRIDE + c4);
                     float *dst = out + (size_t)(m0 + m) * p.ldc + p.col_off[seg] + n_first + c4;
                     if (c4 + 4 <= ncols && ((reinterpret_cast<uintptr_t>(dst) & 15) == 0)) {
@@ -379,6 +418,18 @@ static void launch_p2(PackedParams &p, hipStream_t st) {
     }
     p.zblocks = ceil_div(p.M, BM);
     int ids = ceil_div(p.tiles * p.splits, 8) * 8 * p.zblocks;
+    if constexpr (NB == 1 && RC == 2) {
+        if (p.cand_val) {  // the LM head with a fused greedy choice
+            static bool cand_attr_set = false;
+            if (!cand_attr_set) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_packed_kernel<NB, TERMS, MT, RC, SW, true>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                cand_attr_set = true;
+            }
+            gemm_packed_kernel<NB, TERMS, MT, RC, SW, true><<<ids, PK_THREADS, lds, st>>>(p);
+            return;
+        }
+    }
     gemm_packed_kernel<NB, TERMS, MT, RC, SW><<<ids, PK_THREADS, lds, st>>>(p);
 }
 
@@ -668,6 +719,11 @@ void gemm_packed_plan(int N, int K, int M, int *nb, int *rows_per_wg, int *split
     *splits = s;
 }
 
+// whether launch_gemm_packed serves a matrix in one launch (what the fused greedy choice needs)
+bool gemm_packed_single_launch(int N, int K) {
+    return (size_t)ceil_div(N, 32) * 32 * ((size_t)ceil_div(K, 16) * 32) < PK_MAX_BYTES;
+}
+
 void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
     if (a.M <= 0) return;
     // 32-bit byte offsets inside the kernel: a packed matrix of PK_MAX_BYTES or more is walked in row slabs
@@ -713,6 +769,13 @@ void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st) {
     p.out_lo = a.epilogue == EPI_SWIGLU ? a.out_lo : nullptr;
     p.ldc = a.ldc;
     p.split_stride = a.split_stride;
+    // candidates of a fused greedy choice: one matrix, the plain store epilogue, no K split (the caller has checked)
+    const bool cand = a.cand_val && a.cand_idx && a.epilogue == EPI_F32 && p.splits == 1 && !a.P[1] && !a.P[2] && a.nb != 2 &&
+                      a.depth != 4;
+    p.cand_val = cand ? a.cand_val : nullptr;
+    p.cand_idx = cand ? a.cand_idx : nullptr;
+    p.cand_tiles = ceil_div(a.rows[0], 128);
+    p.no_store = cand && a.no_store ? 1 : 0;
     const bool swiglu = a.epilogue == EPI_SWIGLU;
     const int nb = swiglu ? 2 : (a.nb == 2 ? 2 : 1);
     int tiles = 0, col = 0;

@@ -34,6 +34,10 @@ int compact_state_max_batch();
 void launch_compact_state(int32_t *lens, int32_t *done, int32_t *tokens, const int32_t *kept, int n, hipStream_t st);
 void launch_kv_move(f16_t *kv, float *scales, size_t area_elems, int n_areas, int Hkv, int S, int hd, int src, int dst, int rows,
                     hipStream_t st);
+// Second half of the fused greedy choice: token of row b = column of the largest candidate (lowest column on ties, -1 if a
+// candidate is NaN), then the same end-token and length bookkeeping as launch_argmax.
+void launch_argmax_merge(const float *cand_val, const int32_t *cand_idx, int B, int tiles, int32_t *next, int32_t *lens, int32_t *done,
+                         int eos, hipStream_t st);
 void launch_gather_last_rows(const f16_t *h, const int32_t *lens, int b0, int nb, int T, int d, f16_t *out, hipStream_t st);
 // next[b] = smallest v with cumulative softmax(logits[b] / temperature) above u[b] (-1 on NaN); bookkeeping as launch_argmax.
 void launch_sample(const float *logits, int B, int V, float temperature, const float *u, int32_t *next, int32_t *lens,
@@ -125,7 +129,14 @@ struct PackedGemmArgs {
     int depth;            // weight chunks in flight per wavefront: 2 or 4 (0: 2)
     int rows_per_wg;      // activation rows per workgroup: 32, 64 or 128 (0: 128); the row blocks of one tile re-read its weights from L2
     f16_t *out_lo = nullptr;  // EPI_SWIGLU, optional: second half term of the result, half(y - half(y)), laid out like out
+    // EPI_F32 of one matrix without K split, optional (the LM head with a fused greedy choice): per row and per pass of 128
+    // columns the largest value and its lowest column (NaN if the pass holds a NaN), [M][ceil(rows[0] / 128)] each;
+    // launch_argmax_merge turns them into tokens.  no_store: the fp32 result itself is not written.
+    float *cand_val = nullptr;
+    int32_t *cand_idx = nullptr;
+    bool no_store = false;
 };
+bool gemm_packed_single_launch(int N, int K);  // the matrix is served by one launch (no row slabs): candidates are possible
 // M of any size (row blocks of 128 re-stream the weights; meant for M <= 256).
 void launch_gemm_packed(const PackedGemmArgs &a, hipStream_t st);
 // Fused gate/up projection (EPI_SWIGLU) of few rows from the copies, K halves on separate wavefronts: the sums are

@@ -497,7 +497,24 @@ bool run_layers(rl_gen *h, const int32_t *tokens, int nb, int T, int b0, bool de
 // (rows: optional compact [nb, hidden] rows to use instead -- the last valid position of ragged sequences)
 // lo: the rows behind the nb*T rows of h->h() hold the low term of the normalised rows (level 3); the kernel that reads the
 // fragment-order copy multiplies both terms, the row-major kernels use the high term alone.
-void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, const f16_t *rows = nullptr, bool lo = false) {
+// Fused greedy choice: the LM-head projection also leaves, per row and per pass of 128 vocabulary columns, its largest logit
+// and that logit's column (candidates), and a one-wavefront-per-row kernel picks the token from them: the [B, V] logits are
+// neither re-read nor, when the caller did not ask for them, written at all.  Applies when the projection runs from the
+// fragment-order copy in one launch with at most kSkinnyMaxM rows (every decode step and prefill chunk of the benchmark
+// shapes) and the token is chosen greedily; the candidates live in the internal logits area, which is idle exactly then
+// (the caller's buffer takes the logits, or nobody wants them).
+bool greedy_fusable(const rl_gen *h, int rows_per_call) {
+    return h->temperature <= 0.f && h->packed && rows_per_call <= kSkinnyMaxM && gemm_packed_single_launch(h->s.vocab, h->s.hidden) &&
+           (size_t)2 * ceil_div(h->s.vocab, 128) <= (size_t)h->s.vocab;
+}
+float *cand_val_of(const rl_gen *h) { return h->logits_ws(); }
+int32_t *cand_idx_of(const rl_gen *h) {
+    return reinterpret_cast<int32_t *>(h->logits_ws() + (size_t)h->s.max_batch * ceil_div(h->s.vocab, 128));
+}
+
+// fuse: 0 plain logits; 1 logits and candidates; 2 candidates only (the logits are not stored)
+void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, const f16_t *rows = nullptr, bool lo = false,
+             int fuse = 0) {
     const rl_gen_shape &s = h->s;
     GemmArgs a;
     a.A = h->h() + (size_t)(T - 1) * s.hidden; a.lda = (int64_t)T * s.hidden; a.M = nb; a.K = s.hidden;
@@ -514,17 +531,27 @@ void lm_head(rl_gen *h, int nb, int T, int b0, float *logits, hipStream_t st, co
         q.P[0] = h->p_lm_head; q.P[1] = nullptr; q.P[2] = nullptr;
         q.rows[0] = s.vocab; q.rows[1] = 0; q.rows[2] = 0;
         q.out = a.out; q.ldc = s.vocab; q.split_stride = 0; q.splits = 1; q.epilogue = EPI_F32; q.nb = 1; q.rows_per_wg = 128; q.depth = 2;
+        if (fuse) {
+            const size_t tiles = (size_t)ceil_div(s.vocab, 128);
+            q.cand_val = cand_val_of(h) + (size_t)b0 * tiles;
+            q.cand_idx = cand_idx_of(h) + (size_t)b0 * tiles;
+            q.no_store = fuse == 2;
+        }
         launch_gemm_packed(q, st);
     } else if (nb <= kSkinnyMaxM && !A_lo) launch_gemm_skinny(a, st);
     else { a.A_lo = A_lo; launch_gemm_tiled(a, st); }
 }
 
-void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, int32_t *next, hipStream_t st) {
+// logits: where the step's logits go (the caller's buffer or the internal one); wanted: the caller asked for them
+void enqueue_decode(rl_gen *h, const int32_t *tokens, float *logits, bool wanted, int32_t *next, hipStream_t st) {
     const bool lo = run_layers(h, tokens, h->B, 1, 0, true, st);
-    lm_head(h, h->B, 1, 0, logits, st, nullptr, lo);
+    const bool fused = greedy_fusable(h, h->B);
+    lm_head(h, h->B, 1, 0, logits, st, nullptr, lo, fused ? (wanted ? 1 : 2) : 0);
     Scope sc(h, RL_GEN_K_ARGMAX, st);
     if (h->temperature > 0.f)
         launch_sample(logits, h->B, h->s.vocab, h->temperature, h->sample_u, next, h->d_lens(), h->d_done(), h->eos, st);
+    else if (fused)
+        launch_argmax_merge(cand_val_of(h), cand_idx_of(h), h->B, ceil_div(h->s.vocab, 128), next, h->d_lens(), h->d_done(), h->eos, st);
     else
         launch_argmax(logits, h->B, h->s.vocab, next, h->d_lens(), h->d_done(), h->eos, st);
 }
@@ -902,6 +929,8 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
     }
     int per_chunk = h->wp.rows / T;  // whole sequences per pass through the layers
     if (per_chunk < 1) per_chunk = 1;
+    const bool fused = greedy_fusable(h, B < per_chunk ? B : per_chunk);
+    const int fuse = fused ? (logits ? 1 : 2) : 0;
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
         int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
         const bool lo = run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st, lens ? h->d_lens() : nullptr);
@@ -915,15 +944,16 @@ static int prefill_impl(rl_gen_t *h, const char *who, const int32_t *tokens, con
                     launch_gather_last_rows(h->h() + (size_t)nb * T * h->s.hidden, h->d_lens(), b0, nb, T, h->s.hidden,
                                             h->attn() + (size_t)nb * h->s.hidden, st);
             }
-            lm_head(h, nb, T, b0, lg, st, h->attn(), lo);
+            lm_head(h, nb, T, b0, lg, st, h->attn(), lo, fuse);
         } else {
-            lm_head(h, nb, T, b0, lg, st, nullptr, lo);
+            lm_head(h, nb, T, b0, lg, st, nullptr, lo, fuse);
         }
     }
     {
         Scope sc(h, RL_GEN_K_ARGMAX, st);
         // lengths were set by launch_init_state; here only the end flags follow from the first generated token
         if (h->temperature > 0.f) launch_sample(lg, B, h->s.vocab, h->temperature, h->sample_u, nx, nullptr, h->d_done(), h->eos, st);
+        else if (fused) launch_argmax_merge(cand_val_of(h), cand_idx_of(h), B, ceil_div(h->s.vocab, 128), nx, nullptr, h->d_done(), h->eos, st);
         else launch_argmax(lg, B, h->s.vocab, nx, nullptr, h->d_done(), h->eos, st);
     }
     int rc = check_hip(h, who);
@@ -1124,7 +1154,7 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
     int32_t *nx = next ? next : h->next_ws();
     bool use_graph = h->graph_on && !h->prof_on;
     if (!use_graph) {
-        enqueue_decode(h, tokens, lg, nx, st);
+        enqueue_decode(h, tokens, lg, logits != nullptr, nx, st);
     } else {
         GraphEntry *g = nullptr;
         for (auto &e : h->graphs)
@@ -1138,14 +1168,14 @@ int rl_gen_decode_step(rl_gen_t *h, const int32_t *tokens, float *logits, int32_
         if (g->exec) {
             if (hipGraphLaunch(g->exec, st) != hipSuccess) { set_err(h, "rl_gen_decode_step: hipGraphLaunch failed"); return RL_GEN_E_HIP; }
         } else if (g->calls == 1) {
-            enqueue_decode(h, tokens, lg, nx, st);  // first use: plain launches (also warms up lazy kernel attributes)
+            enqueue_decode(h, tokens, lg, logits != nullptr, nx, st);  // first use: plain launches (also warms up lazy kernel attributes)
         } else {
             hipGraph_t graph = nullptr;
             if (hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed) != hipSuccess) {
                 (void)hipGetLastError();
-                enqueue_decode(h, tokens, lg, nx, st);
+                enqueue_decode(h, tokens, lg, logits != nullptr, nx, st);
             } else {
-                enqueue_decode(h, tokens, lg, nx, st);
+                enqueue_decode(h, tokens, lg, logits != nullptr, nx, st);
                 hipError_t e = hipStreamEndCapture(st, &graph);
                 if (e != hipSuccess || !graph) { set_err(h, "rl_gen_decode_step: stream capture failed: %s", hipGetErrorString(e)); return RL_GEN_E_HIP; }
                 e = hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0);
@@ -1409,6 +1439,30 @@ int rl_op_gemm_packed(const uint16_t *A, const uint16_t *A_lo, int64_t lda, cons
     a.rows_per_wg = rows_per_wg;
     a.depth = depth;
     launch_gemm_packed(a, reinterpret_cast<hipStream_t>(st));
+    RL_OP_RETURN();
+}
+
+size_t rl_op_lm_head_argmax_ws_floats(int32_t M, int32_t V) {
+    return M > 0 && V > 0 ? (size_t)2 * M * ceil_div(V, 128) : 0;
+}
+
+int rl_op_lm_head_argmax(const uint16_t *A, const uint16_t *A_lo, int64_t lda, const uint16_t *P, int32_t V, int32_t M, int32_t K,
+                         float *logits, int64_t ldc, float *ws, int32_t *next, void *st) {
+    if (!A || !P || !ws || !next) return RL_GEN_E_NULL;
+    if (M < 0 || K <= 0 || K % 8 || lda % 8 || lda < K || V <= 0 || (logits && ldc < V)) return RL_GEN_E_SHAPE;
+    if (((uint64_t)M * (uint64_t)lda + (uint64_t)K) * 2 > 0xf0000000ull || !gemm_packed_single_launch(V, K)) return RL_GEN_E_SHAPE;
+    const int tiles = ceil_div(V, 128);
+    PackedGemmArgs a;
+    a.A = A; a.A_lo = A_lo; a.lda = lda; a.M = M; a.K = K;
+    a.P[0] = P; a.P[1] = nullptr; a.P[2] = nullptr;
+    a.rows[0] = V; a.rows[1] = 0; a.rows[2] = 0;
+    a.out = logits; a.ldc = logits ? ldc : V; a.split_stride = 0; a.splits = 1; a.epilogue = EPI_F32;
+    a.nb = 1; a.rows_per_wg = 128; a.depth = 2;
+    a.cand_val = ws;
+    a.cand_idx = reinterpret_cast<int32_t *>(ws + (size_t)M * tiles);
+    a.no_store = logits == nullptr;
+    launch_gemm_packed(a, reinterpret_cast<hipStream_t>(st));
+    launch_argmax_merge(a.cand_val, a.cand_idx, M, tiles, next, nullptr, nullptr, -1, reinterpret_cast<hipStream_t>(st));
     RL_OP_RETURN();
 }
 

@@ -266,6 +266,51 @@ def test_gemm_packed_f32(ops, M, K, rows, splits, nb, terms, rpw):
     assert np.abs(got - ref).max() <= tol, (np.abs(got - ref).max(), tol)
 
 
+@pytest.mark.parametrize("M,K,V,two", [(4, 256, 1000, False), (128, 512, 32000, False), (200, 256, 1024, True), (5, 136, 128256, False),
+                                       (130, 264, 3000, True)])
+def test_lm_head_with_fused_greedy_choice(ops, M, K, V, two):
+    """The LM-head projection whose epilogue starts the greedy choice: logits as the plain packed projection gives them (the
+    oracle's within fp32 accumulation), tokens exactly the lowest argmax of those logits -- with ties planted across
+    different 128-column passes, a NaN row (-1), a vocabulary that ends inside a pass -- and the same tokens when the
+    logits are not stored at all."""
+    step(f"lm head + greedy choice M={M} K={K} V={V} two-term={two}")
+    A = randn_f16((M, K), 70)
+    A_lo = (randn_f16((M, K), 71) * 2.0 ** -11).to(torch.float16) if two else None
+    W = randn_bf16((V, K), 72, std=0.05)
+    a = np64(A) + (np64(A_lo) if two else 0.0)
+    ref = orc.linear(bits(W), a)
+    # ties at the top: the weight row of a row's best column copied to a column 130 (or more) below or above it
+    planted = {}
+    for m in range(0, min(M, 4)):
+        c = int(np.argmax(ref[m]))
+        c2 = c - 130 - m if c - 130 - m >= 0 else c + 130 + m
+        W[c2] = W[c]
+        planted[m] = min(c, c2)
+    ref = orc.linear(bits(W), a)
+    if M > 4:
+        A[4] = float("nan")
+    P = pack(ops, W)
+    logits = torch.zeros((M, V), dtype=torch.float32, device=DEV)
+    nxt = torch.full((M,), -7, dtype=torch.int32, device=DEV)
+    nxt2 = torch.full((M,), -7, dtype=torch.int32, device=DEV)
+    ops.lm_head_argmax(A, P, V, K, nxt, logits=logits, A_lo=A_lo)
+    ops.lm_head_argmax(A, P, V, K, nxt2, logits=None, A_lo=A_lo)
+    torch.cuda.synchronize()
+    got, tok = np64(logits), nxt.cpu().numpy()
+    rows = [m for m in range(M) if m != 4]
+    tol = 2e-6 * np.sqrt(K) * (np.abs(ref[rows]).max() + 1.0)
+    assert np.abs(got[rows] - ref[rows]).max() <= tol
+    for m in range(M):
+        assert tok[m] == orc.argmax(got[m]), m                     # index work is exact (-1 for the NaN row)
+    if M > 4:
+        assert tok[4] == -1 and np.isnan(got[4]).all()
+    for m, c in planted.items():
+        if m != 4:
+            assert tok[m] == c and got[m, c] == got[m].max() and (got[m] == got[m].max()).sum() >= 2, m
+    assert np.array_equal(nxt2.cpu().numpy(), tok)
+    assert rows and ops.lm_head_argmax_ws_floats(M, V) == 2 * M * ((V + 127) // 128)
+
+
 @pytest.mark.parametrize("M,nb,rpw", [(4, 1, 0), (128, 2, 64), (200, 1, 32)])
 def test_gemm_packed_row_stride_and_accumulate(ops, M, nb, rpw):
     K, N, T = 256, 264, 3
