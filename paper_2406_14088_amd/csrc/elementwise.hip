@@ -359,23 +359,26 @@ void launch_logprob_gather(const float *logits, int64_t ld, int M, int V, const 
 
 // ------------------------------------------------------------------------------------------------
 // Scalar head: out[m] = sum_k h[m, k] * w[k] (h half, w bf16 or fp32, fp32 accumulation), one wavefront per row.
-__global__ __launch_bounds__(256) void rowdot_kernel(const f16_t *__restrict__ h, const void *__restrict__ w, int w_is_f32, int M,
-                                                     int d, float *__restrict__ out) {
+__global__ __launch_bounds__(256) void rowdot_kernel(const f16_t *__restrict__ h, const f16_t *__restrict__ h_lo,
+                                                     const void *__restrict__ w, int w_is_f32, int M, int d, float *__restrict__ out) {
     const int lane = threadIdx.x & 63;
     const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (m >= M) return;
     const f16_t *row = h + (size_t)m * d;
+    const f16_t *row_lo = h_lo ? h_lo + (size_t)m * d : nullptr;  // second half term of the rows (two-term activations)
     float acc = 0.f;
     for (int k = lane; k < d; k += 64) {
         float wk = w_is_f32 ? reinterpret_cast<const float *>(w)[k] : bf16_to_f32(reinterpret_cast<const bf16_t *>(w)[k]);
-        acc = fmaf(f16_to_f32(row[k]), wk, acc);
+        float x = f16_to_f32(row[k]);
+        if (row_lo) x += f16_to_f32(row_lo[k]);
+        acc = fmaf(x, wk, acc);
     }
     acc = wave_sum(acc);
     if (lane == 0) out[m] = acc;
 }
-void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st) {
+void launch_rowdot(const f16_t *h, const f16_t *h_lo, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st) {
     if (M <= 0) return;
-    rowdot_kernel<<<ceil_div(M, 4), 256, 0, st>>>(h, w, w_is_f32, M, d, out);
+    rowdot_kernel<<<ceil_div(M, 4), 256, 0, st>>>(h, h_lo, w, w_is_f32, M, d, out);
 }
 
 // ------------------------------------------------------------------------------------------------

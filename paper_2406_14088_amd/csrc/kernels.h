@@ -46,7 +46,7 @@ void launch_set_i32(int32_t *p, int32_t v, hipStream_t st);
 // dst[i * dst_stride] = src[i * src_stride] for i < n; 32-bit elements of any type, strides in elements
 void launch_copy_strided(const void *src, int64_t src_stride, void *dst, int64_t dst_stride, int n, hipStream_t st);
 // out[m] = sum_k h[m, k] * w[k]   (h half [M, d]; w bf16 or fp32 [d]; fp32 accumulation)
-void launch_rowdot(const f16_t *h, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st);
+void launch_rowdot(const f16_t *h, const f16_t *h_lo, const void *w, int w_is_f32, int M, int d, float *out, hipStream_t st);
 // Rows m_first .. m_first + M - 1 of a [n_seq * T] token grid: out[g] = log softmax(logits[g - m_first, :])[tokens[g + 1]],
 // 0 for the last position of a sequence.  logits fp32 [M, V] with row stride ld.
 void launch_logprob_gather(const float *logits, int64_t ld, int M, int V, const int32_t *tokens, int T, int64_t m_first,

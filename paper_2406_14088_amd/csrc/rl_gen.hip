@@ -1120,9 +1120,10 @@ int rl_gen_values(rl_gen_t *h, const int32_t *tokens, int32_t B, int32_t T, cons
     if (per_chunk < 1) per_chunk = 1;
     for (int b0 = 0; b0 < B; b0 += per_chunk) {
         int nb = B - b0 < per_chunk ? B - b0 : per_chunk;
-        run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
+        const bool lo = run_layers(h, tokens + (size_t)b0 * T, nb, T, b0, false, st);
         Scope sc(h, RL_GEN_K_MISC, st);
-        launch_rowdot(h->h(), head, h->s.weight_dtype == 0, nb * T, h->s.hidden, values + (size_t)b0 * T, st);
+        launch_rowdot(h->h(), lo ? h->h() + (size_t)nb * T * h->s.hidden : nullptr, head, h->s.weight_dtype == 0, nb * T, h->s.hidden,
+                      values + (size_t)b0 * T, st);
     }
     {
         Scope sc(h, RL_GEN_K_MISC, st);

@@ -243,8 +243,9 @@ def test_inference_call_logprobs(case):
     ref.close()
 
 
+@pytest.mark.parametrize("precision", [0, 3])
 @pytest.mark.parametrize("fp32_weights", [False, True])
-def test_inference_call_scalar_head(fp32_weights):
+def test_inference_call_scalar_head(fp32_weights, precision):
     """rl_gen_values: the Critic/Reward form of the inference call.  A scalar head w gives, at every position, what the LM
     head would give for a vocabulary row equal to w: the oracle runs the same decoder with w as row 0 of its LM head."""
     from paper_2406_14088_amd import Generator
@@ -257,11 +258,11 @@ def test_inference_call_scalar_head(fp32_weights):
     om = orc.OracleModel(shape, orc.weights_to_numpy(W, as_bf16_bits=not fp32_weights), B, T)
     want = om.forward_all(toks.numpy())[:, :, 0]
     om.close()
-    gen = Generator(shape, Wg, B, T)
+    gen = Generator(shape, Wg, B, T, precision=precision)
     got = np64(gen.values(toks.to(DEV), head.to(DEV)))
     torch.cuda.synchronize()
     err = np.abs(got - want).max()
-    step(f"  scalar head: max-abs error {err:.3e}")
+    step(f"  scalar head, level {precision}: max-abs error {err:.3e}")
     assert got.shape == (B, T) and err <= LOGIT_TOL and gen.state() == (B, T)
     gen.close()
 
