@@ -187,6 +187,16 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
         float ksc[DA_U], vsc[DA_U];
         int jj[DA_U];
         bool is_new[DA_U];
+        // Contiguous block-scaled rows: the RPW * DA_U scales of this trip are consecutive floats, so one load per
+        // wavefront (lane l takes the scale of row base + l mod rows-per-trip) fetches them all and a lane picks its rows'
+        // scales by shuffles -- a per-row load would add one memory request per row-load instruction.
+        float ks_l = 1.f, vs_l = 1.f;
+        if (I16 && !PAGED) {
+            const int j = base + lane % (RPW * DA_U);
+            const int jc = j < j1 ? j : j1 - 1;
+            ks_l = ksb[jc];
+            vs_l = vsb[jc];
+        }
 #pragma unroll
         for (int u = 0; u < DA_U; ++u) {
             int j = base + u * RPW + r;
@@ -198,8 +208,9 @@ __global__ __launch_bounds__(DA_THREADS) void decode_attention_kernel(
             // streaming of 8 GiB: 7.05 TB/s against 6.2 TB/s with ordinary loads)
             kr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(kb + row * HD));
             vr[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(vb + row * HD));
-            ksc[u] = I16 ? ksb[row] : 1.f;
-            vsc[u] = I16 ? vsb[row] : 1.f;
+            if (I16 && PAGED) { ksc[u] = ksb[row]; vsc[u] = vsb[row]; }
+            else if (I16) { ksc[u] = __shfl(ks_l, u * RPW + r, 64); vsc[u] = __shfl(vs_l, u * RPW + r, 64); }
+            else { ksc[u] = 1.f; vsc[u] = 1.f; }
         }
         if (PAGED) {
 #pragma unroll
