@@ -35,8 +35,8 @@ _PROGRESS = None
 
 
 def step(msg):
-    """Progress line of a long test: printed, and appended to gpurun_out/test_progress.log under the repository root so that a
-    runner that watches that folder sees the test is alive even when pytest captures the output."""
+    """Progress line of a long test: printed, and appended to a log file in the output folder under the repository root, so that
+    a runner that watches that folder sees the test is alive even when pytest captures the output."""
     global _PROGRESS
     print(msg, flush=True)
     try:
